@@ -1,0 +1,135 @@
+"""Seeded synthetic workloads shared by the CPU oracle's tests and the HIP path's tests.
+
+This module only *describes* networks and *draws* numbers: layer lists, initial
+weights, input batches and teacher-generated targets.  It contains none of the
+method's arithmetic (no delays, no learning-rate rescheduling, no correction, no
+optimizer, no forward/backward of the trained network): both the oracle and the
+HIP library compute those on their own from the integers and arrays given here.
+
+The paper trains on public image / translation datasets that are not available
+here; these generators stand in for them with the same tensor shapes.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Tuple
+
+import numpy as np
+
+__all__ = ["Layer", "Workload", "config", "init_params", "BatchStream", "n_params"]
+
+
+@dataclass(frozen=True)
+class Layer:
+    """One weight unit (weight matrix + bias), assigned to pipeline stage `stage` (1-based)."""
+    kind: str      # "linear"
+    n_in: int
+    n_out: int
+    act: str       # "none" | "relu" | "gelu"
+    stage: int
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    layers: Tuple[Layer, ...]
+    P: int                 # number of pipeline stages
+    N: int                 # microbatches per minibatch
+    loss: str              # "mse" | "xent"
+    dtype: str             # "f32" | "bf16" (bf16 compute, fp32 master)
+    microbatch: int
+    n_classes: int         # for "xent"; output width for "mse"
+    opt: dict = field(default_factory=dict)
+    steps: int = 0
+    seed_init: int = 2
+    seed_data: int = 0
+    seed_teacher: int = 1
+
+
+def n_params(layer: Layer) -> int:
+    return layer.n_out * layer.n_in + layer.n_out
+
+
+def _mlp(name, widths, acts, stages, **kw) -> Workload:
+    layers = tuple(Layer("linear", widths[j], widths[j + 1], acts[j], stages[j])
+                   for j in range(len(acts)))
+    return Workload(name=name, layers=layers, P=max(stages), **kw)
+
+
+def config(idx: int) -> Workload:
+    """Workloads by index.
+
+    0: tiny fp32 4-stage MLP (64-wide, ReLU, scalar regression head, MSE).
+    1: 16-stage MLP, 1024-wide, GELU, 10-class head sharing the last stage,
+       bf16 compute with fp32 master weights.
+    """
+    if idx == 0:
+        return _mlp("mlp4_f32", [64, 64, 64, 64, 1], ["relu", "relu", "relu", "none"], [1, 2, 3, 4],
+                    N=1, loss="mse", dtype="f32", microbatch=16, n_classes=1,
+                    opt=dict(kind="sgdm", lr=0.01, beta=0.9, D=0.9, K=20, weight_decay=0.0),
+                    steps=50)
+    if idx == 1:
+        widths = [1024] * 17 + [10]
+        acts = ["gelu"] * 16 + ["none"]
+        stages = list(range(1, 17)) + [16]
+        return _mlp("mlp16_bf16", widths, acts, stages,
+                    N=1, loss="xent", dtype="bf16", microbatch=128, n_classes=10,
+                    opt=dict(kind="sgdm", lr=0.01, beta=0.9, D=0.9, K=125, weight_decay=0.0),
+                    steps=500)
+    raise ValueError(f"unknown workload index {idx}")
+
+
+def small_mlp(width: int, depth: int, n_out: int, act: str, loss: str, dtype: str,
+              microbatch: int, layers_per_stage: int = 1, **opt) -> Workload:
+    """A free-form MLP for tests: `depth` hidden Linear+act layers then a head in the last stage."""
+    widths = [width] * (depth + 1) + [n_out]
+    acts = [act] * depth + ["none"]
+    stages = [j // layers_per_stage + 1 for j in range(depth)]
+    stages.append(stages[-1])
+    o = dict(kind="sgdm", lr=0.01, beta=0.9, D=0.9, K=10, weight_decay=0.0)
+    o.update(opt)
+    return _mlp(f"mlp{depth}x{width}_{dtype}", widths, acts, stages, N=1, loss=loss, dtype=dtype,
+                microbatch=microbatch, n_classes=n_out, opt=o, steps=0)
+
+
+def init_params(wl: Workload, seed: int | None = None) -> List[np.ndarray]:
+    """Initial parameters, one packed fp32 vector [W (n_out x n_in, row-major) | b (n_out)] per layer.
+
+    W ~ U(+-sqrt(6/fan_in)) behind ReLU/GELU (keeps activations O(1) through deep stacks),
+    U(+-sqrt(3/fan_in)) for a linear head; b ~ U(+-1/sqrt(fan_in)).
+    """
+    rng = np.random.default_rng(wl.seed_init if seed is None else seed)
+    out = []
+    for L in wl.layers:
+        bound = np.sqrt((6.0 if L.act in ("relu", "gelu") else 3.0) / L.n_in)
+        W = rng.uniform(-bound, bound, size=(L.n_out, L.n_in))
+        b = rng.uniform(-1.0, 1.0, size=(L.n_out,)) / np.sqrt(L.n_in)
+        out.append(np.concatenate([W.ravel(), b]).astype(np.float32))
+    return out
+
+
+class BatchStream:
+    """Deterministic stream of microbatches: x ~ N(0,1), targets from a fixed random teacher.
+
+    Teacher: 2-layer tanh network n_in -> 64 -> n_classes with N(0, 1/fan_in) weights.
+    "mse": y = teacher(x) as fp32 [M, n_classes];  "xent": y = argmax teacher(x) as int32 [M].
+    Batch `k` depends only on (seed_data, k), so any step can be regenerated.
+    """
+
+    def __init__(self, wl: Workload):
+        self.wl = wl
+        n_in = wl.layers[0].n_in
+        rng = np.random.default_rng(wl.seed_teacher)
+        self.T1 = rng.standard_normal((64, n_in)) / np.sqrt(n_in)
+        self.T2 = rng.standard_normal((wl.n_classes, 64)) / np.sqrt(64) * 2.0
+
+    def batch(self, k: int):
+        wl = self.wl
+        rng = np.random.default_rng([wl.seed_data, k])
+        x = rng.standard_normal((wl.microbatch, wl.layers[0].n_in)).astype(np.float32)
+        t = np.tanh(x.astype(np.float64) @ self.T1.T) @ self.T2.T
+        if wl.loss == "mse":
+            y = t.astype(np.float32)
+        else:
+            y = np.argmax(t, axis=1).astype(np.int32)
+        return x, y
