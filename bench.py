@@ -1,0 +1,160 @@
+#!/usr/bin/env python3
+"""Benchmark of the PipeMare hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one microbatch already resident in HBM: slot /
+step-size table, forward of all stages on tau_fwd-stale ring weights, loss, backward on corrected
+weights, fused update (T1 + optimizer + delta + ring / corrected-weight write-back).
+
+Workload at N=1: the 16-stage 1024-wide GELU MLP with a 10-class head, bf16 compute with fp32 master
+weights, microbatch 128, PipeMare delays tau_fwd,i = 2(P-i)+1, tau_bkwd = 0.
+
+Prints ONE JSON line.  `roofline` prices the dominant kernel (the fused update pass, HBM bound)
+with its algorithmic bytes: 32 B per parameter per step (read g, w, v, delta fp32; write w, v, delta
+fp32 + ring slot bf16 + corrected weights bf16).  `cpu_baseline` times the fp64 NumPy oracle on a
+bounded sample of the same workload on the host cores (a reference point, not a target).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
+BYTES_PER_PARAM = {("sgdm", "bf16"): 32, ("adamw", "bf16"): 40, ("sgdm", "f32"): 36, ("adamw", "f32"): 44}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, help="workload index (0: tiny fp32 MLP, 1: 16-stage bf16 MLP)")
+    ap.add_argument("--no-graph", action="store_true", help="launch every kernel eagerly instead of replaying a HIP graph")
+    ap.add_argument("--cpu-steps", type=int, default=24, help="oracle steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--pool", type=int, default=8, help="distinct device-resident microbatches cycled through")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_1910_05124_amd as pm
+    import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    w = wl.config(args.config)
+    o = w.opt
+    tau_fwd, tau_bkwd = pm.pm_delays(w.P, w.N, "pipemare")
+    params = wl.init_params(w)
+    n_params = int(sum(p.size for p in params))
+    stream_data = wl.BatchStream(w)
+    use_graph = not args.no_graph
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        sched = pm.make_sched(kind="const", base=o["lr"], K=o["K"])
+        opts = pm.make_opts(opt=o["kind"], beta1=o["beta"], D=o["D"], weight_decay=o["weight_decay"], t1=True, t2=True,
+                            N=w.N, dtype=w.dtype, loss=w.loss, microbatch=w.microbatch, use_graph=use_graph)
+        eng = pm.PipeMare(w.layers, w.P, tau_fwd, tau_bkwd, sched, opts, params, stream=side)
+        pool = [stream_data.batch(k) for k in range(args.pool)]
+        xs = [torch.from_numpy(x).cuda() for x, _ in pool]
+        ys = [torch.from_numpy(y).cuda() for _, y in pool]
+        # a captured graph is bound to its batch buffers: stage each microbatch device-to-device
+        x_in, y_in = torch.empty_like(xs[0]), torch.empty_like(ys[0])
+
+        def run(n, base):
+            for k in range(n):
+                i = (base + k) % args.pool
+                x_in.copy_(xs[i], non_blocking=True)
+                y_in.copy_(ys[i], non_blocking=True)
+                eng.step(x_in, y_in)
+
+        run(args.warmup, 0)
+        side.synchronize()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(args.steps, args.warmup)
+        side.synchronize()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        stats = eng.stats(param_norm=True)
+
+        # per-phase kernel time with HIP events on the engine's stream, same steps, eager launches
+        pm.pm_profile_begin(eng.ctx, args.steps)
+        run(args.steps, args.warmup + args.steps)
+        prof = pm.pm_profile_end(eng.ctx)
+        eng.close()
+
+    ms_per_step = dt / args.steps * 1e3
+    steps_per_s = args.steps / dt
+    bpp = BYTES_PER_PARAM[(o["kind"], w.dtype)]
+    upd_s = prof["update_ms"] * 1e-3
+    achieved = n_params * bpp / upd_s / 1e9 if upd_s > 0 else 0.0
+    gemm_flops = 6.0 * w.microbatch * sum(L.n_in * L.n_out for L in w.layers) - 2.0 * w.microbatch * w.layers[0].n_in * w.layers[0].n_out
+    gemm_s = (prof["fwd_ms"] + prof["bwd_ms"]) * 1e-3
+    out = {
+        "metric": "async pipeline train steps/s",
+        "value": round(steps_per_s, 2),
+        "unit": "steps/s",
+        "samples_per_s": round(steps_per_s * w.microbatch * w.N, 1),
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype if w.dtype != "f32" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.P}-stage MLP, {len(w.layers)} weight units, {n_params} params, "
+                               f"microbatch {w.microbatch}, PipeMare delays tau_fwd={tau_fwd[0]}..{tau_fwd[-1]}, tau_bkwd=0, "
+                               f"{o['kind']} beta {o['beta']}, T1 K={o['K']}, T2 D={o['D']}",
+                   "launch": "hip_graph" if use_graph else "eager", "final_loss": round(stats["loss"], 5)},
+        "roofline": {"kernel": "pm_fused_update_kernel", "bound": "hbm", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": None, "bytes_per_param": bpp, "params": n_params,
+                     "avg_kernel_ms": round(prof["update_ms"], 5), "launches_timed": prof["n"]},
+        "phases_ms": {"forward_loss": round(prof["fwd_ms"], 4), "backward": round(prof["bwd_ms"], 4),
+                      "update": round(prof["update_ms"], 4)},
+        "stage_gemms": {"algorithmic_tflop_per_step": round(gemm_flops / 1e12, 5),
+                        "achieved_tflops": round(gemm_flops / gemm_s / 1e12, 2) if gemm_s > 0 else None,
+                        "frac_of_bf16_mfma_peak": round(gemm_flops / gemm_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5) if gemm_s > 0 else None,
+                        "note": "includes loss, bias-gradient and launch gaps of the eager profiling pass"},
+    }
+    if args.cpu_steps > 0:
+        out["cpu_baseline"] = cpu_baseline(w, params, tau_fwd, tau_bkwd, args.cpu_steps)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(w, params, tau_fwd, tau_bkwd, n_steps):
+    """The fp64 NumPy oracle as it stands, timed on the host cores on the first n_steps of the workload."""
+    import workloads as wl
+    from pm_testutil import make_oracle
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    o = w.opt
+    orc = make_oracle(w, params, tau_fwd, tau_bkwd, opt=o["kind"], lr=o["lr"], beta=o["beta"], D=o["D"], K=o["K"],
+                      weight_decay=o["weight_decay"])
+    stream = wl.BatchStream(w)
+    batches = [stream.batch(k) for k in range(n_steps + 2)]
+    for k in range(2):
+        orc.step(batches[k])
+    t0 = time.perf_counter()
+    for k in range(2, n_steps + 2):
+        orc.step(batches[k])
+    dt = time.perf_counter() - t0
+    return {"value": round(n_steps / dt, 3), "unit": "steps/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n_steps} optimizer steps of the same workload (after 2 untimed), fp64 NumPy, explicit weight histories"}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,200 @@
+/*
+ * pipemare.h — C ABI of the MI355X (gfx950) PipeMare training-step library.
+ *
+ * One context executes asynchronous pipeline-parallel training of a chain of weight units
+ * (Linear + bias + activation) as a delay-faithful single-GPU run of all P pipeline stages:
+ * forward with weights that are tau_fwd,i optimizer steps old, read in place from a
+ * device-resident ring of weight versions; backward with discrepancy-corrected weights; one
+ * fused update pass (learning-rate rescheduling, optimizer, delta accumulator, ring and
+ * corrected-weight write-back).
+ *
+ * Conventions for every entry point
+ *   - "host" pointers are ordinary process memory, "device" pointers are HIP device memory on the
+ *     GPU that was current when pm_create was called.
+ *   - The library never allocates or frees device memory: the caller provides one arena
+ *     (pm_query_bytes tells how large) and owns it, the HIP stream and the batch buffers.
+ *   - All GPU work is enqueued on the stream given to pm_create.  Only pm_weights, pm_stats,
+ *     pm_device_step_table, pm_set_grads and pm_step with a non-NULL loss pointer wait for it.
+ *   - Errors are return codes (never exceptions, never abort); a NULL context gives PM_EINVAL.
+ *   - A context is not re-entrant: one thread, one stream.
+ */
+#ifndef PIPEMARE_H_
+#define PIPEMARE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pm_ctx pm_ctx;
+
+typedef enum {
+  PM_OK = 0,
+  PM_EINVAL = 1,    /* bad argument (shape chain, delays, NULL, misaligned pointer, ...) */
+  PM_ENOMEM = 2,    /* arena smaller than pm_query_bytes reports */
+  PM_EHIP = 3,      /* a HIP runtime call failed; pm_last_error() has the text */
+  PM_ESTATE = 4,    /* call not valid in the current state (e.g. mid-minibatch) */
+  PM_EDIVERGED = 5  /* a non-finite weight was produced (sticky; training can diverge by design
+                       of the experiment, cf. the stability analysis of Sec. 3.1) */
+} pm_status;
+
+typedef enum { PM_LINEAR = 0 } pm_layer_kind;
+typedef enum { PM_ACT_NONE = 0, PM_ACT_RELU = 1, PM_ACT_GELU = 2 /* exact erf form */ } pm_act;
+typedef enum { PM_METHOD_PIPEMARE = 0, PM_METHOD_PIPEDREAM = 1, PM_METHOD_GPIPE = 2 } pm_method;
+typedef enum { PM_LR_CONST = 0, PM_LR_STEP = 1, PM_LR_WARMUP_INVSQRT = 2 } pm_lr_kind;
+typedef enum { PM_OPT_SGDM = 0, PM_OPT_ADAMW = 1 } pm_opt_kind;
+typedef enum { PM_F32 = 0, PM_BF16 = 1 /* bf16 compute + ring, fp32 master/optimizer state */ } pm_dtype;
+typedef enum { PM_LOSS_MSE = 0, PM_LOSS_XENT = 1 } pm_loss_kind;
+
+/* One weight unit: y = act(x W^T + b), W is n_out x n_in row-major.  Weight and bias always share
+ * a pipeline stage (Sec. 4.1, "Pipeline Stages"); `stage` is 1-based and non-decreasing along the
+ * chain; several consecutive units may share a stage. */
+typedef struct {
+  int32_t kind;   /* pm_layer_kind */
+  int32_t n_in;
+  int32_t n_out;
+  int32_t act;    /* pm_act */
+  int32_t stage;  /* 1..P */
+} pm_layer_desc;
+
+/* Synchronous base schedule alpha_{k,base} (Sec. 3.1) and the T1 annealing length K (in steps).
+ *   CONST:           base
+ *   STEP:            base * factor^floor(k / interval)
+ *   WARMUP_INVSQRT:  linear init -> base over `interval` steps, then base * sqrt(interval / k)
+ * K = 0 disables the rescheduling exponent (p_k = 0). */
+typedef struct {
+  int32_t kind;       /* pm_lr_kind */
+  double base;
+  double init;
+  double factor;
+  int64_t interval;
+  int64_t K;
+} pm_lr_sched;
+
+typedef struct {
+  int32_t opt;               /* pm_opt_kind */
+  double beta1;              /* SGD momentum beta (App. B.3 form), or Adam beta1 */
+  double beta2;              /* Adam beta2 */
+  double eps;                /* Adam epsilon */
+  double weight_decay;       /* SGD: added to the gradient (L2); AdamW: decoupled */
+  double clip_norm;          /* > 0: scale gradients so their global L2 norm is at most this */
+  double D;                  /* T2 decay, gamma_i = D^(1/(tau_fwd,i - tau_bkwd,i)) (Sec. 3.2) */
+  const double* gamma_override; /* host, P entries or NULL: per-stage gamma_i given directly */
+  int32_t t1_enabled;        /* 0: every stage uses alpha_{k,base} */
+  int32_t t2_enabled;        /* 0: backward reads the plain version t - tau_bkwd,i */
+  int32_t n_microbatches;    /* N >= 1: pm_step accumulates N calls, then updates (Sec. 2.1) */
+  int32_t dtype;             /* pm_dtype */
+  int32_t loss;              /* pm_loss_kind */
+  int32_t microbatch;        /* rows M of every batch given to pm_step */
+  int32_t use_graph;         /* 1: replay the step as a captured HIP graph after the first call */
+} pm_opts;
+
+const char* pm_status_str(pm_status s);
+/* Text of the last failure on this thread ("" if none).  Host pointer owned by the library. */
+const char* pm_last_error(void);
+
+/* Per-stage delays of Table 1 for stages i = 1..P with N microbatches per minibatch:
+ * tau_fwd,i = ceil((2(P-i)+1)/N); tau_bkwd,i = 0 (PipeMare) | tau_fwd,i (PipeDream); both 0 for
+ * GPipe.  Host arrays of P entries each (index i-1).  PM_EINVAL if P < 1 or N < 1. */
+pm_status pm_delays(int32_t P, int32_t N, int32_t method, int32_t* tau_fwd, int32_t* tau_bkwd);
+
+/* Ring-slot arithmetic for one stage at optimizer step t (Sec. 2.1 delayed reads; the ring of
+ * R = tau_fwd + 1 slots is this library's stand-in for the paper's queue of stale weights):
+ * version read forward max(t - tau_fwd, 0), backward max(t - tau_bkwd, 0), written t + 1;
+ * slot = version mod R.  Pure host integer function. */
+pm_status pm_slots(int32_t tau_fwd, int32_t tau_bkwd, int64_t t,
+                   int32_t* fwd_slot, int32_t* bkwd_slot, int32_t* write_slot);
+
+/* T1 step size alpha_{k,i} = alpha_{k,base} / max(tau_i,1)^{p_k}, p_k = 1 - min(k/K,1) (Sec. 3.1),
+ * computed on the host in double precision. */
+pm_status pm_t1_lr(const pm_lr_sched* sched, int32_t tau, int64_t k, int32_t t1_enabled, double* lr);
+
+/* Bytes of device arena pm_create needs for this configuration. */
+pm_status pm_query_bytes(int32_t P, int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
+                         const pm_opts* opts, size_t* out_bytes);
+
+/* Build a context.
+ *   P, L               stages and weight units; layers[L] host
+ *   tau_fwd, tau_bkwd  host, P entries, 0 <= tau_bkwd,i <= tau_fwd,i
+ *   init_weights_host  L host pointers, unit l packed as [W (n_out*n_in) | b (n_out)] fp32
+ *   device_arena       device, 256-byte aligned, arena_bytes >= pm_query_bytes
+ *   hip_stream         hipStream_t (NULL = default stream)
+ * Every ring slot starts as w_0, delta_0 = v_0 = 0, corrected weights = w_0.
+ * On success *out owns only host memory; release with pm_destroy. */
+pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers,
+                    const int32_t* tau_fwd, const int32_t* tau_bkwd,
+                    const pm_lr_sched* sched, const pm_opts* opts,
+                    const float* const* init_weights_host,
+                    void* device_arena, size_t arena_bytes, void* hip_stream, pm_ctx** out);
+
+/* One microbatch through all stages (forward on stale weights, loss, backward on corrected
+ * weights); after the N-th microbatch of a minibatch also the fused update (Sec. 2.1 recurrence,
+ * T1, T2).  x_dev: device fp32 [microbatch, n_in of unit 0] row-major.  y_dev: device fp32
+ * [microbatch, n_out of last unit] (MSE) or int32 [microbatch] labels (cross-entropy).
+ * loss_out_host: NULL, or host float that receives this microbatch's mean loss (forces a
+ * stream synchronisation).  Returns PM_EDIVERGED once a non-finite weight has been seen by a
+ * synchronising call. */
+pm_status pm_step(pm_ctx* ctx, const void* x_dev, const void* y_dev, float* loss_out_host);
+
+/* fp32 master weights w_t of unit `layer` into host memory, packed [W | b]; n must equal
+ * n_out*n_in + n_out.  Synchronises the stream. */
+pm_status pm_weights(pm_ctx* ctx, int32_t layer, float* dst_host, size_t n);
+
+/* Same layout for the delta accumulator (which = 1), the optimizer's first state v or m
+ * (which = 2), the corrected backward weights currently stored (which = 3, widened to fp32) and
+ * the gradient buffer (which = 4). */
+pm_status pm_state(pm_ctx* ctx, int32_t which, int32_t layer, float* dst_host, size_t n);
+
+/* What the kernels of the most recent step actually used, read back from the device-resident
+ * step table: per unit the forward / backward / write slot and the step size.  Host arrays of L
+ * entries (any may be NULL); *t_used receives that step's index.  Synchronises. */
+pm_status pm_device_step_table(pm_ctx* ctx, int64_t* t_used, int32_t* fwd_slot, int32_t* bkwd_slot,
+                               int32_t* write_slot, float* lr);
+
+/* Running numbers: last loss, global gradient L2 norm of the last update (only when clipping is
+ * on, else 0), L2 norm of the master weights, number of completed optimizer steps.  Any output
+ * may be NULL.  Synchronises. */
+pm_status pm_stats(pm_ctx* ctx, double* loss, double* grad_norm, double* param_norm, int64_t* t);
+
+/* Testing / benchmarking of the update pass in isolation (the T1/T2/optimizer/write-back part of
+ * the step without a model): overwrite unit `layer`'s gradient buffer from host fp32 [W | b], and
+ * run exactly the update of one optimizer step on whatever the gradient buffers hold. */
+pm_status pm_set_grads(pm_ctx* ctx, int32_t layer, const float* src_host, size_t n);
+pm_status pm_apply_update(pm_ctx* ctx);
+
+/* Per-phase GPU timing of pm_step with HIP events recorded on the context's stream (host-side
+ * event objects; no device memory).  Between begin and end every pm_step runs eagerly (a captured
+ * graph is bypassed) and records four events: start, after forward + loss, after backward, after
+ * the fused update.  pm_profile_end synchronises and returns the mean milliseconds per step of
+ * the three phases over the steps recorded (at most max_steps).  n_microbatches must be 1. */
+pm_status pm_profile_begin(pm_ctx* ctx, int32_t max_steps);
+pm_status pm_profile_end(pm_ctx* ctx, double* fwd_ms, double* bwd_ms, double* update_ms, int32_t* n_steps);
+
+/* The three matrix products of one Linear unit as stand-alone primitives (the per-stage forward
+ * and the two halves of the per-stage backward of Sec. 2.1), on plain device matrices, for
+ * kernel-level tests and roofline measurement.  All matrices row-major and dense (leading
+ * dimension = width); element type bf16 (raw 16-bit) or fp32 per `dtype`; bf16 needs n_in and
+ * n_out to be multiples of 8 and 16-byte aligned pointers.  Asynchronous on `stream`.
+ *   fwd:        z = x W^T + b,  a = act(z)          x[M,n_in] W[n_out,n_in] b[n_out] -> z, a [M,n_out] (either may be NULL)
+ *   bwd_data:   dzprev = (dz W) * act_prev'(zprev)  dz[M,n_out] W[n_out,n_in] zprev[M,n_in] -> dzprev[M,n_in]
+ *   bwd_weight: dW = dz^T a, db = column sums of dz a[M,n_in] -> dW fp32 [n_out,n_in], db fp32 [n_out] (db may be NULL);
+ *               accumulate != 0 adds to the existing contents. */
+pm_status pm_linear_fwd(void* stream, int32_t dtype, int32_t M, int32_t n_in, int32_t n_out,
+                        const void* x_dev, const void* W_dev, const void* b_dev, int32_t act,
+                        void* z_dev, void* a_dev);
+pm_status pm_linear_bwd_data(void* stream, int32_t dtype, int32_t M, int32_t n_in, int32_t n_out,
+                             const void* dz_dev, const void* W_dev, const void* zprev_dev,
+                             int32_t act_prev, void* dzprev_dev);
+pm_status pm_linear_bwd_weight(void* stream, int32_t dtype, int32_t M, int32_t n_in, int32_t n_out,
+                               const void* dz_dev, const void* a_dev, float* dW_dev, float* db_dev,
+                               int32_t accumulate);
+
+/* Frees host state only; the arena stays the caller's. */
+void pm_destroy(pm_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIPEMARE_H_ */

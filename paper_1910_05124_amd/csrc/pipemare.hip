@@ -1,0 +1,753 @@
+// Host runtime and C ABI of the PipeMare step library (see include/pipemare.h).
+// gfx950 only.  The library owns no device memory: everything lives in the caller's arena.
+#include "../../include/pipemare.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "pm_common.hpp"
+#include "pm_elem.hpp"
+#include "pm_gemm_mfma.hpp"
+#include "pm_update.hpp"
+
+namespace {
+
+thread_local std::string g_err;
+
+pm_status fail(pm_status s, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return s;
+}
+
+#define PM_HIP(call)                                                                           \
+  do {                                                                                         \
+    hipError_t e_ = (call);                                                                    \
+    if (e_ != hipSuccess) return fail(PM_EHIP, "%s: %s", #call, hipGetErrorString(e_));        \
+  } while (0)
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+struct Unit {
+  pm_layer_desc d;
+  int64_t nw;        // n_out * n_in
+  int64_t boff;      // offset of the bias inside the unit (nw rounded up to 8 elements)
+  int64_t n;         // boff + n_out
+  int64_t n_pad;     // n rounded up to PM_CHUNK
+  int64_t off;       // element offset in the flat arrays
+  int64_t ring_off;  // element offset in the ring
+  int32_t tau_f, tau_b, R;
+  double gamma;
+  int32_t corr;      // tau_f - tau_b when T2 applies, else 0
+  int ld_in, ld_out; // leading dimensions of the activation matrices (multiples of 8)
+  // activation buffers (byte offsets into the arena)
+  size_t z_off, a_off, dz_off, z32_off;
+};
+
+struct Layout {
+  std::vector<Unit> units;
+  int64_t n_flat = 0;     // padded element count of the flat arrays
+  int64_t n_real = 0;     // true parameter count
+  int64_t ring_elems = 0;
+  int64_t n_chunks = 0;
+  size_t esz = 4;         // bytes per element of the compute dtype
+  // byte offsets
+  size_t w_off, g_off, v_off, s_off, d_off, ub_off, ring_off, chunk_off, ls_off, ld_off, hdr_off, x_off;
+  size_t act_begin, act_end, total;
+};
+
+pm_status validate(int32_t P, int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
+                   const int32_t* tau_bkwd, const pm_opts* o) {
+  if (P < 1 || L < 1 || !layers || !tau_fwd || !o) return fail(PM_EINVAL, "P, L >= 1 and non-NULL arrays required");
+  if (o->dtype != PM_F32 && o->dtype != PM_BF16) return fail(PM_EINVAL, "dtype must be PM_F32 or PM_BF16");
+  if (o->opt != PM_OPT_SGDM && o->opt != PM_OPT_ADAMW) return fail(PM_EINVAL, "unknown optimizer");
+  if (o->loss != PM_LOSS_MSE && o->loss != PM_LOSS_XENT) return fail(PM_EINVAL, "unknown loss");
+  if (o->microbatch < 1 || o->n_microbatches < 1) return fail(PM_EINVAL, "microbatch and n_microbatches must be >= 1");
+  if (!(o->D > 0.0 && o->D <= 1.0)) return fail(PM_EINVAL, "D must be in (0, 1]");
+  if (o->clip_norm < 0.0 || o->weight_decay < 0.0) return fail(PM_EINVAL, "clip_norm and weight_decay must be >= 0");
+  int prev_stage = 1;
+  for (int l = 0; l < L; ++l) {
+    const pm_layer_desc& d = layers[l];
+    if (d.kind != PM_LINEAR) return fail(PM_EINVAL, "unit %d: unknown kind", l);
+    if (d.n_in < 1 || d.n_out < 1) return fail(PM_EINVAL, "unit %d: sizes must be positive", l);
+    if (d.act < PM_ACT_NONE || d.act > PM_ACT_GELU) return fail(PM_EINVAL, "unit %d: unknown activation", l);
+    if (d.stage < 1 || d.stage > P) return fail(PM_EINVAL, "unit %d: stage %d outside 1..%d", l, d.stage, P);
+    if (d.stage < prev_stage) return fail(PM_EINVAL, "unit %d: stages must be non-decreasing along the chain", l);
+    prev_stage = d.stage;
+    if (l > 0 && layers[l - 1].n_out != d.n_in) return fail(PM_EINVAL, "unit %d: n_in %d does not chain with previous n_out %d", l, d.n_in, layers[l - 1].n_out);
+  }
+  for (int i = 0; i < P; ++i) {
+    if (tau_fwd[i] < 0) return fail(PM_EINVAL, "tau_fwd[%d] < 0", i);
+    if (tau_bkwd && (tau_bkwd[i] < 0 || tau_bkwd[i] > tau_fwd[i])) return fail(PM_EINVAL, "need 0 <= tau_bkwd[%d] <= tau_fwd[%d]", i, i);
+  }
+  return PM_OK;
+}
+
+void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd, const int32_t* tau_bkwd,
+                 const pm_opts* o, Layout& lay) {
+  lay.units.resize(L);
+  lay.esz = o->dtype == PM_BF16 ? 2 : 4;
+  int64_t off = 0, roff = 0, real = 0;
+  for (int l = 0; l < L; ++l) {
+    Unit& u = lay.units[l];
+    u.d = layers[l];
+    u.nw = (int64_t)u.d.n_out * u.d.n_in;
+    u.boff = round_up(u.nw, 8);
+    u.n = u.boff + u.d.n_out;
+    u.n_pad = round_up(u.n, PM_CHUNK);
+    u.off = off;
+    u.ring_off = roff;
+    u.tau_f = tau_fwd[u.d.stage - 1];
+    u.tau_b = tau_bkwd ? tau_bkwd[u.d.stage - 1] : 0;
+    u.R = u.tau_f + 1;
+    const int dd = u.tau_f - u.tau_b;
+    u.corr = (o->t2_enabled && dd > 0) ? dd : 0;
+    if (o->gamma_override) u.gamma = o->gamma_override[u.d.stage - 1];
+    else u.gamma = dd > 0 ? std::pow(o->D, 1.0 / dd) : 0.0;
+    u.ld_in = (int)round_up(u.d.n_in, 8);
+    u.ld_out = (int)round_up(u.d.n_out, 8);
+    off += u.n_pad;
+    roff += u.n_pad * u.R;
+    real += u.nw + u.d.n_out;
+  }
+  lay.n_flat = off;
+  lay.n_real = real;
+  lay.ring_elems = roff;
+  lay.n_chunks = off / PM_CHUNK;
+  size_t p = 0;
+  auto take = [&](size_t bytes) { size_t at = p; p = (size_t)round_up((int64_t)(p + bytes), PM_ALIGN); return at; };
+  lay.w_off = take(lay.n_flat * 4);
+  lay.g_off = take(lay.n_flat * 4);
+  lay.v_off = take(lay.n_flat * 4);
+  lay.s_off = take(o->opt == PM_OPT_ADAMW ? lay.n_flat * 4 : 0);
+  lay.d_off = take(lay.n_flat * 4);
+  lay.ub_off = take(lay.n_flat * lay.esz);
+  lay.ring_off = take(lay.ring_elems * lay.esz);
+  lay.chunk_off = take(lay.n_chunks * 4);
+  lay.ls_off = take(sizeof(PmLayerStatic) * L);
+  lay.ld_off = take(sizeof(PmLayerStep) * L);
+  lay.hdr_off = take(sizeof(PmStepHdr));
+  const int M = o->microbatch;
+  lay.act_begin = p;
+  lay.x_off = take((size_t)M * lay.units[0].ld_in * lay.esz);
+  for (int l = 0; l < L; ++l) {
+    Unit& u = lay.units[l];
+    const size_t e = (size_t)M * u.ld_out;
+    u.z_off = take(e * lay.esz);
+    u.a_off = take(e * lay.esz);
+    u.dz_off = take(e * lay.esz);
+    u.z32_off = (l == L - 1) ? take(e * 4) : 0;
+  }
+  lay.act_end = p;
+  lay.total = p;
+}
+
+}  // namespace
+
+struct pm_ctx {
+  int32_t P, L;
+  pm_opts o;
+  pm_lr_sched sched;
+  std::vector<double> gamma_override;
+  std::vector<int32_t> tau_f, tau_b;
+  Layout lay;
+  char* arena;
+  hipStream_t stream;
+  int64_t t_host = 0;      // completed optimizer steps
+  int32_t micro = 0;       // microbatches accumulated in the current minibatch
+  bool diverged = false;
+  float last_loss = 0.f;
+  // captured step
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t graph_exec = nullptr;
+  const void* graph_x = nullptr;
+  const void* graph_y = nullptr;
+  // optional per-phase timing (host-side event objects only)
+  std::vector<hipEvent_t> prof_ev;   // 4 per step: start, after forward+loss, after backward, after update
+  int32_t prof_cap = 0, prof_n = 0;
+  bool prof_on = false;
+
+  template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(arena + off); }
+  PmStepHdr* hdr() const { return at<PmStepHdr>(lay.hdr_off); }
+  PmLayerStatic* ls() const { return at<PmLayerStatic>(lay.ls_off); }
+  PmLayerStep* ld() const { return at<PmLayerStep>(lay.ld_off); }
+};
+
+namespace {
+
+PmSchedDev sched_dev(const pm_ctx* c) {
+  PmSchedDev s;
+  s.kind = c->sched.kind;
+  s.base = c->sched.base;
+  s.init = c->sched.init;
+  s.factor = c->sched.factor;
+  s.interval = c->sched.interval;
+  s.K = c->sched.K;
+  s.t1_enabled = c->o.t1_enabled;
+  s.beta1 = c->o.beta1;
+  s.beta2 = c->o.beta2;
+  s.gscale0 = 1.0 / c->o.n_microbatches;
+  return s;
+}
+
+inline void prof_mark(pm_ctx* c, int which) {
+  if (c->prof_on && c->prof_n < c->prof_cap) (void)hipEventRecord(c->prof_ev[(size_t)c->prof_n * 4 + which], c->stream);
+}
+
+// ---- kernel launches of one microbatch / one update, templated on the compute dtype -------------
+template <typename T>
+pm_status launch_update(pm_ctx* c) {
+  const Layout& lay = c->lay;
+  hipStream_t st = c->stream;
+  if (c->o.clip_norm > 0.0) {
+    int blocks = (int)std::min<int64_t>(2048, (lay.n_flat / 4 + 255) / 256);
+    hipLaunchKernelGGL(pm_sumsq_kernel, dim3(blocks), dim3(256), 0, st, c->at<float>(lay.g_off), lay.n_flat,
+                       &c->hdr()->gnorm2);
+    hipLaunchKernelGGL(pm_clip_scale_kernel, dim3(1), dim3(1), 0, st, c->hdr(), (float)c->o.clip_norm);
+  }
+  prof_mark(c, 2);
+  PmUpdArgs<T> a;
+  a.g = c->at<float>(lay.g_off);
+  a.w = c->at<float>(lay.w_off);
+  a.v = c->at<float>(lay.v_off);
+  a.s = c->at<float>(lay.s_off);
+  a.d = c->at<float>(lay.d_off);
+  a.ring = c->at<T>(lay.ring_off);
+  a.ub = c->at<T>(lay.ub_off);
+  a.chunk_layer = c->at<int32_t>(lay.chunk_off);
+  a.ls = c->ls();
+  a.ld = c->ld();
+  a.hdr = c->hdr();
+  a.beta1 = (float)c->o.beta1;
+  a.beta2 = (float)c->o.beta2;
+  a.eps = (float)c->o.eps;
+  a.wd = (float)c->o.weight_decay;
+  if (c->o.opt == PM_OPT_SGDM)
+    hipLaunchKernelGGL((pm_fused_update_kernel<T, 0>), dim3((unsigned)lay.n_chunks), dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL((pm_fused_update_kernel<T, 1>), dim3((unsigned)lay.n_chunks), dim3(256), 0, st, a);
+  prof_mark(c, 3);
+  PM_HIP(hipGetLastError());
+  return PM_OK;
+}
+
+void launch_prologue(pm_ctx* c) {
+  hipLaunchKernelGGL(pm_prologue_kernel, dim3(1), dim3(256), 0, c->stream, c->hdr(), c->ls(), c->ld(), c->L,
+                     sched_dev(c));
+}
+
+template <typename T, class Epi>
+void launch_gemm_on(hipStream_t st, int I, int J, int K, const T* A, int64_t sai, int64_t sak, PmWLoc<T> B, int64_t sbj,
+                    int64_t sbk, const Epi& epi) {
+  if constexpr (sizeof(T) == 2) {
+    if (pm_mfma_gemm_try(st, I, J, K, A, sai, sak, B, sbj, sbk, epi)) return;
+  }
+  dim3 grid((J + 15) / 16, (I + 15) / 16);
+  hipLaunchKernelGGL((pm_gemm_plain_kernel<T, T, Epi>), grid, dim3(256), 0, st, I, J, K, A, sai, sak, B, sbj, sbk, epi);
+}
+
+template <typename T, class Epi>
+void launch_gemm(pm_ctx* c, int I, int J, int K, const T* A, int64_t sai, int64_t sak, PmWLoc<T> B, int64_t sbj,
+                 int64_t sbk, const Epi& epi) {
+  launch_gemm_on<T>(c->stream, I, J, K, A, sai, sak, B, sbj, sbk, epi);
+}
+
+// Forward on the tau_fwd-stale ring slots, loss, backward on the corrected weights.
+template <typename T>
+pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int accumulate) {
+  const Layout& lay = c->lay;
+  hipStream_t st = c->stream;
+  const int M = c->o.microbatch, L = c->L;
+  T* ring = c->at<T>(lay.ring_off);
+  T* ub = c->at<T>(lay.ub_off);
+  float* g = c->at<float>(lay.g_off);
+  const Unit& u0 = lay.units[0];
+  prof_mark(c, 0);
+  {
+    const int64_t tot = (int64_t)M * u0.ld_in;
+    hipLaunchKernelGGL((pm_stage_input_kernel<T>), dim3((unsigned)std::min<int64_t>(1024, (tot + 255) / 256)), dim3(256),
+                       0, st, (const float*)x_dev, c->at<T>(lay.x_off), M, u0.d.n_in, u0.ld_in, c->hdr());
+  }
+  // ---- forward: unit l reads W (and b) of version max(t - tau_fwd, 0) in place from its ring slot
+  for (int l = 0; l < L; ++l) {
+    const Unit& u = lay.units[l];
+    const T* a_in = l == 0 ? c->at<T>(lay.x_off) : c->at<T>(lay.units[l - 1].a_off);
+    PmWLoc<T> W{ring + u.ring_off, &c->ld()[l].fwd_slot, u.n_pad};
+    PmEpiFwd<T> epi;
+    epi.bias = PmWLoc<T>{ring + u.ring_off + u.boff, &c->ld()[l].fwd_slot, u.n_pad};
+    epi.z = (l == L - 1) ? nullptr : c->at<T>(u.z_off);
+    epi.a = (l == L - 1) ? nullptr : c->at<T>(u.a_off);
+    epi.z32 = (l == L - 1) ? c->at<float>(u.z32_off) : nullptr;
+    epi.ld = u.ld_out;
+    epi.act = u.d.act;
+    epi.b_ = nullptr;
+    // Z[M, n_out] = A[M, n_in] . W[n_out, n_in]^T
+    launch_gemm<T>(c, M, u.d.n_out, u.d.n_in, a_in, u.ld_in, 1, W, u.d.n_in, 1, epi);
+  }
+  // ---- loss and d(loss)/d(z_last)   (the last unit's activation must be PM_ACT_NONE)
+  {
+    const Unit& u = lay.units[L - 1];
+    if (c->o.loss == PM_LOSS_XENT)
+      hipLaunchKernelGGL((pm_xent_kernel<T>), dim3((M + 3) / 4), dim3(256), 0, st, c->at<float>(u.z32_off),
+                         (const int32_t*)y_dev, c->at<T>(u.dz_off), M, u.d.n_out, u.ld_out, c->hdr());
+    else {
+      const int64_t tot = (int64_t)M * u.ld_out;
+      hipLaunchKernelGGL((pm_mse_kernel<T>), dim3((unsigned)std::min<int64_t>(256, (tot + 255) / 256)), dim3(256), 0, st,
+                         c->at<float>(u.z32_off), (const float*)y_dev, c->at<T>(u.dz_off), M, u.d.n_out, u.ld_out,
+                         c->hdr());
+    }
+  }
+  prof_mark(c, 1);
+  // ---- backward
+  for (int l = L - 1; l >= 0; --l) {
+    const Unit& u = lay.units[l];
+    const T* a_in = l == 0 ? c->at<T>(lay.x_off) : c->at<T>(lay.units[l - 1].a_off);
+    const T* dz = c->at<T>(u.dz_off);
+    // weight gradient from the stored forward activations: dW[n_out, n_in] = dz^T . a_in
+    PmEpiBwdWeight ew{g + u.off, u.d.n_in, accumulate};
+    launch_gemm<T>(c, u.d.n_out, u.d.n_in, M, dz, 1, u.ld_out, PmWLoc<T>{a_in, nullptr, 0}, 1, u.ld_in, ew);
+    hipLaunchKernelGGL((pm_bias_grad_kernel<T>), dim3((u.d.n_out + 63) / 64), dim3(256), 0, st, dz, g + u.off + u.boff,
+                       M, u.d.n_out, u.ld_out, accumulate);
+    if (l == 0) break;   // the first unit's backward weights never enter any gradient
+    // data gradient through the backward weights: da_in[M, n_in] = dz . W_bkwd, fused with act'(z_prev).
+    // W_bkwd = corrected buffer when the T2 coefficient is non-zero, else version max(t - tau_bkwd, 0).
+    const Unit& up = lay.units[l - 1];
+    PmWLoc<T> Wb = u.corr ? PmWLoc<T>{ub + u.off, nullptr, 0}
+                          : PmWLoc<T>{ring + u.ring_off, &c->ld()[l].bkwd_slot, u.n_pad};
+    PmEpiBwdData<T> ed{c->at<T>(up.z_off), c->at<T>(up.dz_off), up.ld_out, up.d.act};
+    launch_gemm<T>(c, M, u.d.n_in, u.d.n_out, dz, u.ld_out, 1, Wb, 1, u.d.n_in, ed);
+  }
+  PM_HIP(hipGetLastError());
+  return PM_OK;
+}
+
+template <typename T>
+pm_status enqueue_step(pm_ctx* c, const void* x, const void* y, bool first_micro, bool last_micro) {
+  if (first_micro) launch_prologue(c);
+  pm_status s = launch_fwd_bwd<T>(c, x, y, first_micro ? 0 : 1);
+  if (s != PM_OK) return s;
+  if (last_micro) {
+    s = launch_update<T>(c);
+    if (c->prof_on && c->prof_n < c->prof_cap) c->prof_n += 1;
+  }
+  return s;
+}
+
+pm_status enqueue_step_dt(pm_ctx* c, const void* x, const void* y, bool first_micro, bool last_micro) {
+  return c->o.dtype == PM_BF16 ? enqueue_step<bf16_t>(c, x, y, first_micro, last_micro)
+                               : enqueue_step<float>(c, x, y, first_micro, last_micro);
+}
+
+pm_status check_unit(pm_ctx* c, int32_t layer, size_t n) {
+  if (!c) return fail(PM_EINVAL, "NULL context");
+  if (layer < 0 || layer >= c->L) return fail(PM_EINVAL, "unit index %d outside 0..%d", layer, c->L - 1);
+  const Unit& u = c->lay.units[layer];
+  if ((int64_t)n != u.nw + u.d.n_out) return fail(PM_EINVAL, "unit %d holds %lld values, caller said %zu", layer, (long long)(u.nw + u.d.n_out), n);
+  return PM_OK;
+}
+
+}  // namespace
+
+namespace {
+template <typename T>
+pm_status linear_fwd_t(hipStream_t st, int M, int n_in, int n_out, const void* x, const void* W, const void* b, int act,
+                       void* z, void* a) {
+  PmEpiFwd<T> epi;
+  epi.bias = PmWLoc<T>{(const T*)b, nullptr, 0};
+  epi.z = (T*)z; epi.a = (T*)a; epi.z32 = nullptr; epi.ld = n_out; epi.act = act; epi.b_ = nullptr;
+  launch_gemm_on<T>(st, M, n_out, n_in, (const T*)x, n_in, 1, PmWLoc<T>{(const T*)W, nullptr, 0}, n_in, 1, epi);
+  PM_HIP(hipGetLastError());
+  return PM_OK;
+}
+template <typename T>
+pm_status linear_bwd_data_t(hipStream_t st, int M, int n_in, int n_out, const void* dz, const void* W, const void* zprev,
+                            int act_prev, void* dzprev) {
+  PmEpiBwdData<T> epi{(const T*)zprev, (T*)dzprev, n_in, act_prev};
+  launch_gemm_on<T>(st, M, n_in, n_out, (const T*)dz, n_out, 1, PmWLoc<T>{(const T*)W, nullptr, 0}, 1, n_in, epi);
+  PM_HIP(hipGetLastError());
+  return PM_OK;
+}
+template <typename T>
+pm_status linear_bwd_weight_t(hipStream_t st, int M, int n_in, int n_out, const void* dz, const void* a, float* dW,
+                              float* db, int accumulate) {
+  PmEpiBwdWeight epi{dW, n_in, accumulate};
+  launch_gemm_on<T>(st, n_out, n_in, M, (const T*)dz, 1, n_out, PmWLoc<T>{(const T*)a, nullptr, 0}, 1, n_in, epi);
+  if (db)
+    hipLaunchKernelGGL((pm_bias_grad_kernel<T>), dim3((n_out + 63) / 64), dim3(256), 0, st, (const T*)dz, db, M, n_out,
+                       n_out, accumulate);
+  PM_HIP(hipGetLastError());
+  return PM_OK;
+}
+pm_status check_linear(int32_t dtype, int32_t M, int32_t n_in, int32_t n_out, int32_t act) {
+  if (dtype != PM_F32 && dtype != PM_BF16) return fail(PM_EINVAL, "dtype must be PM_F32 or PM_BF16");
+  if (M < 1 || n_in < 1 || n_out < 1) return fail(PM_EINVAL, "sizes must be positive");
+  if (act < PM_ACT_NONE || act > PM_ACT_GELU) return fail(PM_EINVAL, "unknown activation");
+  if (dtype == PM_BF16 && ((n_in | n_out) & 7)) return fail(PM_EINVAL, "bf16 primitives need n_in and n_out to be multiples of 8");
+  return PM_OK;
+}
+}  // namespace
+
+extern "C" {
+
+const char* pm_status_str(pm_status s) {
+  switch (s) {
+    case PM_OK: return "PM_OK";
+    case PM_EINVAL: return "PM_EINVAL";
+    case PM_ENOMEM: return "PM_ENOMEM";
+    case PM_EHIP: return "PM_EHIP";
+    case PM_ESTATE: return "PM_ESTATE";
+    case PM_EDIVERGED: return "PM_EDIVERGED";
+  }
+  return "PM_?";
+}
+
+const char* pm_last_error(void) { return g_err.c_str(); }
+
+pm_status pm_delays(int32_t P, int32_t N, int32_t method, int32_t* tau_fwd, int32_t* tau_bkwd) {
+  if (P < 1 || N < 1 || !tau_fwd || !tau_bkwd) return fail(PM_EINVAL, "P, N >= 1 and output arrays required");
+  if (method < PM_METHOD_PIPEMARE || method > PM_METHOD_GPIPE) return fail(PM_EINVAL, "unknown method");
+  for (int32_t i = 1; i <= P; ++i) {
+    const int32_t num = 2 * (P - i) + 1;
+    const int32_t tf = method == PM_METHOD_GPIPE ? 0 : (num + N - 1) / N;
+    tau_fwd[i - 1] = tf;
+    tau_bkwd[i - 1] = method == PM_METHOD_PIPEDREAM ? tf : 0;
+  }
+  return PM_OK;
+}
+
+pm_status pm_slots(int32_t tau_fwd, int32_t tau_bkwd, int64_t t, int32_t* fwd_slot, int32_t* bkwd_slot,
+                   int32_t* write_slot) {
+  if (tau_fwd < 0 || tau_bkwd < 0 || tau_bkwd > tau_fwd || t < 0) return fail(PM_EINVAL, "need 0 <= tau_bkwd <= tau_fwd and t >= 0");
+  const int64_t R = (int64_t)tau_fwd + 1;
+  const int64_t vf = t - tau_fwd > 0 ? t - tau_fwd : 0;
+  const int64_t vb = t - tau_bkwd > 0 ? t - tau_bkwd : 0;
+  if (fwd_slot) *fwd_slot = (int32_t)(vf % R);
+  if (bkwd_slot) *bkwd_slot = (int32_t)(vb % R);
+  if (write_slot) *write_slot = (int32_t)((t + 1) % R);
+  return PM_OK;
+}
+
+pm_status pm_t1_lr(const pm_lr_sched* s, int32_t tau, int64_t k, int32_t t1_enabled, double* lr) {
+  if (!s || !lr || k < 0 || tau < 0) return fail(PM_EINVAL, "bad argument");
+  double a;
+  switch (s->kind) {
+    case PM_LR_CONST: a = s->base; break;
+    case PM_LR_STEP:
+      if (s->interval < 1) return fail(PM_EINVAL, "interval must be >= 1");
+      a = s->base * std::pow(s->factor, (double)(k / s->interval));
+      break;
+    case PM_LR_WARMUP_INVSQRT:
+      if (s->interval < 1) return fail(PM_EINVAL, "warmup length must be >= 1");
+      if (k < s->interval) a = s->init + (s->base - s->init) * ((double)k / (double)s->interval);
+      else a = s->base * std::sqrt((double)s->interval / (double)k);
+      break;
+    default: return fail(PM_EINVAL, "unknown schedule kind");
+  }
+  double p = 0.0;
+  if (s->K > 0) p = 1.0 - std::fmin((double)k / (double)s->K, 1.0);
+  if (t1_enabled && p > 0.0) a /= std::pow((double)(tau > 1 ? tau : 1), p);
+  *lr = a;
+  return PM_OK;
+}
+
+pm_status pm_query_bytes(int32_t P, int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
+                         const pm_opts* opts, size_t* out_bytes) {
+  if (!out_bytes) return fail(PM_EINVAL, "out_bytes is NULL");
+  pm_status s = validate(P, L, layers, tau_fwd, nullptr, opts);
+  if (s != PM_OK) return s;
+  Layout lay;
+  make_layout(L, layers, tau_fwd, nullptr, opts, lay);
+  *out_bytes = lay.total;
+  return PM_OK;
+}
+
+pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
+                    const int32_t* tau_bkwd, const pm_lr_sched* sched, const pm_opts* opts,
+                    const float* const* init_weights_host, void* device_arena, size_t arena_bytes,
+                    void* hip_stream, pm_ctx** out) {
+  if (!out) return fail(PM_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (!tau_bkwd || !sched || !init_weights_host || !device_arena) return fail(PM_EINVAL, "NULL argument");
+  pm_status s = validate(P, L, layers, tau_fwd, tau_bkwd, opts);
+  if (s != PM_OK) return s;
+  if (layers[L - 1].act != PM_ACT_NONE) return fail(PM_EINVAL, "the last unit feeds the loss and must have no activation");
+  if (sched->kind < PM_LR_CONST || sched->kind > PM_LR_WARMUP_INVSQRT) return fail(PM_EINVAL, "unknown schedule kind");
+  if (sched->kind != PM_LR_CONST && sched->interval < 1) return fail(PM_EINVAL, "schedule interval must be >= 1");
+  if (sched->K < 0) return fail(PM_EINVAL, "K must be >= 0");
+  if (((uintptr_t)device_arena) % PM_ALIGN) return fail(PM_EINVAL, "arena must be %d-byte aligned", PM_ALIGN);
+  for (int l = 0; l < L; ++l)
+    if (!init_weights_host[l]) return fail(PM_EINVAL, "init_weights_host[%d] is NULL", l);
+  if (L > 65535) return fail(PM_EINVAL, "too many units");
+
+  pm_ctx* c = new pm_ctx();
+  c->P = P;
+  c->L = L;
+  c->o = *opts;
+  c->sched = *sched;
+  if (opts->gamma_override) {
+    c->gamma_override.assign(opts->gamma_override, opts->gamma_override + P);
+    c->o.gamma_override = c->gamma_override.data();
+  }
+  c->tau_f.assign(tau_fwd, tau_fwd + P);
+  c->tau_b.assign(tau_bkwd, tau_bkwd + P);
+  make_layout(L, layers, tau_fwd, tau_bkwd, &c->o, c->lay);
+  const Layout& lay = c->lay;
+  if (arena_bytes < lay.total) {
+    delete c;
+    return fail(PM_ENOMEM, "arena has %zu bytes, %zu needed", arena_bytes, lay.total);
+  }
+  c->arena = (char*)device_arena;
+  c->stream = (hipStream_t)hip_stream;
+
+  // host images of the static tables and the packed initial weights
+  std::vector<float> w0((size_t)lay.n_flat, 0.f);
+  std::vector<int32_t> chunk_layer((size_t)lay.n_chunks);
+  std::vector<PmLayerStatic> ls(L);
+  for (int l = 0; l < L; ++l) {
+    const Unit& u = lay.units[l];
+    std::memcpy(&w0[u.off], init_weights_host[l], sizeof(float) * u.nw);
+    std::memcpy(&w0[u.off + u.boff], init_weights_host[l] + u.nw, sizeof(float) * u.d.n_out);
+    for (int64_t ch = u.off / PM_CHUNK; ch < (u.off + u.n_pad) / PM_CHUNK; ++ch) chunk_layer[ch] = l;
+    PmLayerStatic& S = ls[l];
+    S.off = u.off; S.n_pad = u.n_pad; S.ring_off = u.ring_off; S.R = u.R; S.tau_f = u.tau_f; S.tau_b = u.tau_b;
+    S.stage = u.d.stage; S.gamma = (float)u.gamma; S.corr = (float)u.corr;
+  }
+  hipStream_t st = c->stream;
+  auto bail = [&](hipError_t e, const char* what) {
+    delete c;
+    return fail(PM_EHIP, "%s: %s", what, hipGetErrorString(e));
+  };
+  hipError_t e;
+  // zero everything except the ring (which the init kernel fills): optimizer state, delta, grads,
+  // tables, header, activations (their pad columns must stay zero)
+  if ((e = hipMemsetAsync(c->arena + lay.g_off, 0, lay.ub_off - lay.g_off, st)) != hipSuccess) return bail(e, "memset state");
+  if ((e = hipMemsetAsync(c->arena + lay.chunk_off, 0, lay.total - lay.chunk_off, st)) != hipSuccess) return bail(e, "memset tables");
+  if ((e = hipMemcpyAsync(c->arena + lay.w_off, w0.data(), w0.size() * 4, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy weights");
+  if ((e = hipMemcpyAsync(c->arena + lay.chunk_off, chunk_layer.data(), chunk_layer.size() * 4, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy chunk table");
+  if ((e = hipMemcpyAsync(c->arena + lay.ls_off, ls.data(), ls.size() * sizeof(PmLayerStatic), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy unit table");
+  if (c->o.dtype == PM_BF16)
+    hipLaunchKernelGGL((pm_init_ring_kernel<bf16_t>), dim3((unsigned)lay.n_chunks), dim3(256), 0, st,
+                       c->at<float>(lay.w_off), c->at<bf16_t>(lay.ring_off), c->at<bf16_t>(lay.ub_off),
+                       c->at<int32_t>(lay.chunk_off), c->ls());
+  else
+    hipLaunchKernelGGL((pm_init_ring_kernel<float>), dim3((unsigned)lay.n_chunks), dim3(256), 0, st,
+                       c->at<float>(lay.w_off), c->at<float>(lay.ring_off), c->at<float>(lay.ub_off),
+                       c->at<int32_t>(lay.chunk_off), c->ls());
+  if ((e = hipGetLastError()) != hipSuccess) return bail(e, "init kernel");
+  if ((e = hipStreamSynchronize(st)) != hipSuccess) return bail(e, "synchronise after init");   // host images go out of scope
+  *out = c;
+  return PM_OK;
+}
+
+pm_status pm_step(pm_ctx* c, const void* x_dev, const void* y_dev, float* loss_out_host) {
+  if (!c || !x_dev || !y_dev) return fail(PM_EINVAL, "NULL argument");
+  if (c->diverged) return fail(PM_EDIVERGED, "a non-finite weight was produced at an earlier step");
+  const bool first = c->micro == 0;
+  const bool last = c->micro + 1 == c->o.n_microbatches;
+  pm_status s = PM_OK;
+  if (c->o.use_graph && c->o.n_microbatches == 1 && !c->prof_on) {
+    if (!c->graph_exec || c->graph_x != x_dev || c->graph_y != y_dev) {
+      // (re)capture: all slot and step-size values are read from the device table inside the
+      // kernels, so one graph serves every step as long as the batch pointers stay the same
+      if (c->graph_exec) { (void)hipGraphExecDestroy(c->graph_exec); c->graph_exec = nullptr; }
+      if (c->graph) { (void)hipGraphDestroy(c->graph); c->graph = nullptr; }
+      PM_HIP(hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+      s = enqueue_step_dt(c, x_dev, y_dev, true, true);
+      hipError_t e = hipStreamEndCapture(c->stream, &c->graph);
+      if (s != PM_OK) return s;
+      if (e != hipSuccess) return fail(PM_EHIP, "hipStreamEndCapture: %s", hipGetErrorString(e));
+      PM_HIP(hipGraphInstantiate(&c->graph_exec, c->graph, nullptr, nullptr, 0));
+      c->graph_x = x_dev;
+      c->graph_y = y_dev;
+    }
+    PM_HIP(hipGraphLaunch(c->graph_exec, c->stream));
+  } else {
+    s = enqueue_step_dt(c, x_dev, y_dev, first, last);
+    if (s != PM_OK) return s;
+  }
+  if (last) { c->micro = 0; c->t_host += 1; } else c->micro += 1;
+  if (loss_out_host) {
+    PmStepHdr h;
+    PM_HIP(hipMemcpyAsync(&h, c->hdr(), sizeof h, hipMemcpyDeviceToHost, c->stream));
+    PM_HIP(hipStreamSynchronize(c->stream));
+    *loss_out_host = c->last_loss = h.loss;
+    if (h.diverged) { c->diverged = true; return fail(PM_EDIVERGED, "non-finite weight after step %lld", (long long)h.t_used); }
+  }
+  return PM_OK;
+}
+
+pm_status pm_weights(pm_ctx* c, int32_t layer, float* dst_host, size_t n) { return pm_state(c, 0, layer, dst_host, n); }
+
+pm_status pm_state(pm_ctx* c, int32_t which, int32_t layer, float* dst, size_t n) {
+  pm_status s = check_unit(c, layer, n);
+  if (s != PM_OK) return s;
+  if (!dst) return fail(PM_EINVAL, "dst is NULL");
+  const Layout& lay = c->lay;
+  const Unit& u = lay.units[layer];
+  size_t base;
+  switch (which) {
+    case 0: base = lay.w_off; break;
+    case 1: base = lay.d_off; break;
+    case 2: base = lay.v_off; break;
+    case 3: base = lay.ub_off; break;
+    case 4: base = lay.g_off; break;
+    default: return fail(PM_EINVAL, "unknown state selector %d", which);
+  }
+  if (which == 3 && c->o.dtype == PM_BF16) {
+    std::vector<bf16_t> tmp((size_t)u.n);
+    PM_HIP(hipMemcpyAsync(tmp.data(), c->at<bf16_t>(base) + u.off, tmp.size() * 2, hipMemcpyDeviceToHost, c->stream));
+    PM_HIP(hipStreamSynchronize(c->stream));
+    auto widen = [](bf16_t h) { uint32_t b = (uint32_t)h << 16; float f; std::memcpy(&f, &b, 4); return f; };
+    for (int64_t i = 0; i < u.nw; ++i) dst[i] = widen(tmp[i]);
+    for (int64_t i = 0; i < u.d.n_out; ++i) dst[u.nw + i] = widen(tmp[u.boff + i]);
+    return PM_OK;
+  }
+  const float* src = c->at<float>(base) + u.off;
+  PM_HIP(hipMemcpyAsync(dst, src, sizeof(float) * u.nw, hipMemcpyDeviceToHost, c->stream));
+  PM_HIP(hipMemcpyAsync(dst + u.nw, src + u.boff, sizeof(float) * u.d.n_out, hipMemcpyDeviceToHost, c->stream));
+  PM_HIP(hipStreamSynchronize(c->stream));
+  return PM_OK;
+}
+
+pm_status pm_device_step_table(pm_ctx* c, int64_t* t_used, int32_t* fwd_slot, int32_t* bkwd_slot,
+                               int32_t* write_slot, float* lr) {
+  if (!c) return fail(PM_EINVAL, "NULL context");
+  std::vector<PmLayerStep> ld(c->L);
+  PmStepHdr h;
+  PM_HIP(hipMemcpyAsync(ld.data(), c->ld(), sizeof(PmLayerStep) * c->L, hipMemcpyDeviceToHost, c->stream));
+  PM_HIP(hipMemcpyAsync(&h, c->hdr(), sizeof h, hipMemcpyDeviceToHost, c->stream));
+  PM_HIP(hipStreamSynchronize(c->stream));
+  if (t_used) *t_used = h.t_used;
+  for (int l = 0; l < c->L; ++l) {
+    if (fwd_slot) fwd_slot[l] = ld[l].fwd_slot;
+    if (bkwd_slot) bkwd_slot[l] = ld[l].bkwd_slot;
+    if (write_slot) write_slot[l] = ld[l].write_slot;
+    if (lr) lr[l] = ld[l].lr;
+  }
+  return PM_OK;
+}
+
+pm_status pm_stats(pm_ctx* c, double* loss, double* grad_norm, double* param_norm, int64_t* t) {
+  if (!c) return fail(PM_EINVAL, "NULL context");
+  const Layout& lay = c->lay;
+  if (param_norm) {
+    PM_HIP(hipMemsetAsync(&c->hdr()->pnorm2, 0, sizeof(float), c->stream));
+    int blocks = (int)std::min<int64_t>(2048, (lay.n_flat / 4 + 255) / 256);
+    hipLaunchKernelGGL(pm_sumsq_kernel, dim3(blocks), dim3(256), 0, c->stream, c->at<float>(lay.w_off), lay.n_flat,
+                       &c->hdr()->pnorm2);
+  }
+  PmStepHdr h;
+  PM_HIP(hipMemcpyAsync(&h, c->hdr(), sizeof h, hipMemcpyDeviceToHost, c->stream));
+  PM_HIP(hipStreamSynchronize(c->stream));
+  if (loss) *loss = h.loss;
+  if (grad_norm) *grad_norm = c->o.clip_norm > 0.0 ? std::sqrt((double)h.gnorm2) / c->o.n_microbatches : 0.0;
+  if (param_norm) *param_norm = std::sqrt((double)h.pnorm2);
+  if (t) *t = h.t_next;
+  if (h.diverged) { c->diverged = true; return fail(PM_EDIVERGED, "non-finite weight after step %lld", (long long)h.t_used); }
+  return PM_OK;
+}
+
+pm_status pm_set_grads(pm_ctx* c, int32_t layer, const float* src, size_t n) {
+  pm_status s = check_unit(c, layer, n);
+  if (s != PM_OK) return s;
+  if (!src) return fail(PM_EINVAL, "src is NULL");
+  const Unit& u = c->lay.units[layer];
+  float* g = c->at<float>(c->lay.g_off) + u.off;
+  PM_HIP(hipMemcpyAsync(g, src, sizeof(float) * u.nw, hipMemcpyHostToDevice, c->stream));
+  PM_HIP(hipMemcpyAsync(g + u.boff, src + u.nw, sizeof(float) * u.d.n_out, hipMemcpyHostToDevice, c->stream));
+  PM_HIP(hipStreamSynchronize(c->stream));
+  return PM_OK;
+}
+
+pm_status pm_apply_update(pm_ctx* c) {
+  if (!c) return fail(PM_EINVAL, "NULL context");
+  if (c->micro != 0) return fail(PM_ESTATE, "a minibatch is in progress");
+  if (c->diverged) return fail(PM_EDIVERGED, "a non-finite weight was produced at an earlier step");
+  launch_prologue(c);
+  pm_status s = c->o.dtype == PM_BF16 ? launch_update<bf16_t>(c) : launch_update<float>(c);
+  if (s == PM_OK) c->t_host += 1;
+  return s;
+}
+
+
+pm_status pm_linear_fwd(void* stream, int32_t dtype, int32_t M, int32_t n_in, int32_t n_out, const void* x_dev,
+                        const void* W_dev, const void* b_dev, int32_t act, void* z_dev, void* a_dev) {
+  pm_status s = check_linear(dtype, M, n_in, n_out, act);
+  if (s != PM_OK) return s;
+  if (!x_dev || !W_dev || !b_dev || (!z_dev && !a_dev)) return fail(PM_EINVAL, "NULL argument");
+  return dtype == PM_BF16 ? linear_fwd_t<bf16_t>((hipStream_t)stream, M, n_in, n_out, x_dev, W_dev, b_dev, act, z_dev, a_dev)
+                          : linear_fwd_t<float>((hipStream_t)stream, M, n_in, n_out, x_dev, W_dev, b_dev, act, z_dev, a_dev);
+}
+
+pm_status pm_linear_bwd_data(void* stream, int32_t dtype, int32_t M, int32_t n_in, int32_t n_out, const void* dz_dev,
+                             const void* W_dev, const void* zprev_dev, int32_t act_prev, void* dzprev_dev) {
+  pm_status s = check_linear(dtype, M, n_in, n_out, act_prev);
+  if (s != PM_OK) return s;
+  if (!dz_dev || !W_dev || !zprev_dev || !dzprev_dev) return fail(PM_EINVAL, "NULL argument");
+  return dtype == PM_BF16 ? linear_bwd_data_t<bf16_t>((hipStream_t)stream, M, n_in, n_out, dz_dev, W_dev, zprev_dev, act_prev, dzprev_dev)
+                          : linear_bwd_data_t<float>((hipStream_t)stream, M, n_in, n_out, dz_dev, W_dev, zprev_dev, act_prev, dzprev_dev);
+}
+
+pm_status pm_linear_bwd_weight(void* stream, int32_t dtype, int32_t M, int32_t n_in, int32_t n_out, const void* dz_dev,
+                               const void* a_dev, float* dW_dev, float* db_dev, int32_t accumulate) {
+  pm_status s = check_linear(dtype, M, n_in, n_out, 0);
+  if (s != PM_OK) return s;
+  if (!dz_dev || !a_dev || !dW_dev) return fail(PM_EINVAL, "NULL argument");
+  return dtype == PM_BF16 ? linear_bwd_weight_t<bf16_t>((hipStream_t)stream, M, n_in, n_out, dz_dev, a_dev, dW_dev, db_dev, accumulate)
+                          : linear_bwd_weight_t<float>((hipStream_t)stream, M, n_in, n_out, dz_dev, a_dev, dW_dev, db_dev, accumulate);
+}
+
+pm_status pm_profile_begin(pm_ctx* c, int32_t max_steps) {
+  if (!c || max_steps < 1 || max_steps > 65536) return fail(PM_EINVAL, "need a context and 1 <= max_steps <= 65536");
+  if (c->o.n_microbatches != 1) return fail(PM_ESTATE, "phase timing supports n_microbatches = 1 only");
+  for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
+  c->prof_ev.assign((size_t)max_steps * 4, nullptr);
+  for (auto& e : c->prof_ev) PM_HIP(hipEventCreate(&e));
+  c->prof_cap = max_steps;
+  c->prof_n = 0;
+  c->prof_on = true;
+  return PM_OK;
+}
+
+pm_status pm_profile_end(pm_ctx* c, double* fwd_ms, double* bwd_ms, double* update_ms, int32_t* n_steps) {
+  if (!c) return fail(PM_EINVAL, "NULL context");
+  if (!c->prof_on) return fail(PM_ESTATE, "pm_profile_begin was not called");
+  PM_HIP(hipStreamSynchronize(c->stream));
+  double acc[3] = {0, 0, 0};
+  for (int i = 0; i < c->prof_n; ++i)
+    for (int k = 0; k < 3; ++k) {
+      float ms = 0.f;
+      PM_HIP(hipEventElapsedTime(&ms, c->prof_ev[(size_t)i * 4 + k], c->prof_ev[(size_t)i * 4 + k + 1]));
+      acc[k] += ms;
+    }
+  const double inv = c->prof_n ? 1.0 / c->prof_n : 0.0;
+  if (fwd_ms) *fwd_ms = acc[0] * inv;
+  if (bwd_ms) *bwd_ms = acc[1] * inv;
+  if (update_ms) *update_ms = acc[2] * inv;
+  if (n_steps) *n_steps = c->prof_n;
+  for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
+  c->prof_ev.clear();
+  c->prof_on = false;
+  c->prof_cap = c->prof_n = 0;
+  return PM_OK;
+}
+
+void pm_destroy(pm_ctx* c) {
+  if (!c) return;
+  for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
+  if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
+  if (c->graph) (void)hipGraphDestroy(c->graph);
+  delete c;
+}
+
+}  // extern "C"

@@ -1,0 +1,101 @@
+// Shared device-side types of the PipeMare step library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef unsigned short bf16_t;   // raw bfloat16 bits
+
+constexpr int PM_CHUNK = 2048;   // elements of the flat parameter space handled by one update block
+constexpr int PM_ALIGN = 256;    // byte alignment of every arena region
+
+// Static per-unit description, written once by pm_create.
+struct PmLayerStatic {
+  int64_t off;       // element offset of the unit in the flat fp32 arrays (multiple of PM_CHUNK)
+  int64_t n_pad;     // padded element count (multiple of PM_CHUNK) = ring slot stride
+  int64_t ring_off;  // element offset of slot 0 of this unit in the ring
+  int32_t R;         // ring slots = tau_fwd + 1
+  int32_t tau_f;
+  int32_t tau_b;
+  int32_t stage;
+  float gamma;       // decay of the delta accumulator (T2)
+  float corr;        // tau_fwd - tau_bkwd if the correction is active, else 0
+};
+
+// Per-step values for a unit, rewritten by the prologue kernel from the device step counter.
+struct PmLayerStep {
+  int32_t fwd_slot;    // (max(t - tau_fwd, 0)) mod R
+  int32_t bkwd_slot;   // (max(t - tau_bkwd, 0)) mod R
+  int32_t write_slot;  // (t + 1) mod R
+  int32_t ub_slot;     // (max(t + 1 - tau_bkwd, 0)) mod R : base of the next corrected weights
+  float lr;            // alpha_{t,i}
+  int32_t pad_[3];
+};
+
+struct PmStepHdr {
+  long long t_next;    // optimizer steps completed = index of the next step
+  long long t_used;    // index of the step the tables were last computed for
+  float loss;          // accumulated by the loss kernel
+  float gnorm2;        // sum of squares of the accumulated gradients (clipping only)
+  float gscale;        // factor applied to the gradient buffer inside the update
+  float bc1, bc2;      // Adam bias corrections 1/(1-beta^(t+1))
+  int32_t diverged;    // set when a non-finite weight is written
+  float pnorm2;        // scratch for pm_stats
+  int32_t pad_;
+};
+
+struct PmSchedDev {
+  int32_t kind;
+  double base, init, factor;
+  long long interval, K;
+  int32_t t1_enabled;
+  double beta1, beta2;
+  double gscale0;      // 1 / N (mean over microbatches)
+};
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// round-to-nearest-even, NaN kept quiet
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float ldf(const float* p) { return *p; }
+__device__ __forceinline__ float ldf(const bf16_t* p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ void stf(float* p, float v) { *p = v; }
+__device__ __forceinline__ void stf(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// Where a weight matrix lives this step: base + slot * stride (slot read from the device step
+// table so that a captured graph stays valid from step to step); slot == nullptr -> base.
+template <typename T>
+struct PmWLoc {
+  const T* base;
+  const int32_t* slot;
+  int64_t stride;
+  __device__ __forceinline__ const T* get() const { return slot ? base + (int64_t)(*slot) * stride : base; }
+};
+
+__device__ __forceinline__ float pm_act_fwd(float z, int act) {
+  if (act == 1) return z > 0.f ? z : 0.f;
+  if (act == 2) return 0.5f * z * (1.f + erff(z * 0.70710678118654752f));
+  return z;
+}
+__device__ __forceinline__ float pm_act_bwd(float z, int act) {
+  if (act == 1) return z > 0.f ? 1.f : 0.f;
+  if (act == 2)
+    return 0.5f * (1.f + erff(z * 0.70710678118654752f)) + z * __expf(-0.5f * z * z) * 0.39894228040143268f;
+  return 1.f;
+}
+
+__device__ __forceinline__ float pm_wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float pm_wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}

@@ -1,0 +1,152 @@
+// Input staging, loss kernels, bias gradient and the plain (non-MFMA) GEMM used for fp32 contexts.
+#pragma once
+#include "pm_common.hpp"
+
+// x (fp32 [M, n]) -> compute dtype [M, ld]; pad columns zeroed.  Also clears the loss accumulator
+// of the microbatch (first kernel of every microbatch).
+template <typename T>
+__global__ __launch_bounds__(256) void pm_stage_input_kernel(const float* __restrict__ x, T* __restrict__ out,
+                                                             int M, int n, int ld, PmStepHdr* hdr) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) hdr->loss = 0.f;
+  const int64_t total = (int64_t)M * ld;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int m = (int)(i / ld), c = (int)(i % ld);
+    stf(out + i, c < n ? x[(int64_t)m * n + c] : 0.f);
+  }
+}
+
+// Softmax cross-entropy, mean over rows.  One wavefront per row; logits fp32 [M, ld].
+// Writes dz = (softmax - onehot)/M in the compute dtype (pad columns zero) and adds the row's
+// loss / M to hdr->loss.
+template <typename T>
+__global__ __launch_bounds__(256) void pm_xent_kernel(const float* __restrict__ logits, const int32_t* __restrict__ y,
+                                                      T* __restrict__ dz, int M, int C, int ld, PmStepHdr* hdr) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= M) return;
+  const float* z = logits + (int64_t)row * ld;
+  float mx = -3.0e38f;
+  for (int c = lane; c < C; c += 64) mx = fmaxf(mx, z[c]);
+  mx = pm_wave_max(mx);
+  float se = 0.f;
+  for (int c = lane; c < C; c += 64) se += __expf(z[c] - mx);
+  se = pm_wave_sum(se);
+  const int label = y[row];
+  const bool label_ok = label >= 0 && label < C;      // an out-of-range label contributes nothing
+  const float inv = 1.f / se, invM = 1.f / (float)M;
+  for (int c = lane; c < ld; c += 64) {
+    float v = 0.f;
+    if (c < C) v = (__expf(z[c] - mx) * inv - (c == label ? 1.f : 0.f)) * invM;
+    stf(dz + (int64_t)row * ld + c, v);
+  }
+  if (lane == 0 && label_ok) atomicAdd(&hdr->loss, (logf(se) + mx - z[label]) * invM);
+}
+
+// Mean squared error over all M*C outputs: dz = 2 (out - y) / (M C).
+template <typename T>
+__global__ __launch_bounds__(256) void pm_mse_kernel(const float* __restrict__ out, const float* __restrict__ y,
+                                                     T* __restrict__ dz, int M, int C, int ld, PmStepHdr* hdr) {
+  const int64_t total = (int64_t)M * ld;
+  const float inv = 1.f / ((float)M * (float)C);
+  float acc = 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int m = (int)(i / ld), c = (int)(i % ld);
+    float v = 0.f;
+    if (c < C) {
+      const float diff = out[i] - y[(int64_t)m * C + c];
+      acc += diff * diff;
+      v = 2.f * diff * inv;
+    }
+    stf(dz + i, v);
+  }
+  acc = pm_wave_sum(acc);
+  if ((threadIdx.x & 63) == 0 && acc != 0.f) atomicAdd(&hdr->loss, acc * inv);
+}
+
+// Bias gradient db[n] = sum_m dz[m, n] into the fp32 gradient buffer (optionally accumulating).
+// One wavefront per 64 columns would idle for narrow layers, so: block = 256 threads =
+// 64 columns x 4 row groups, reduced through LDS.
+template <typename T>
+__global__ __launch_bounds__(256) void pm_bias_grad_kernel(const T* __restrict__ dz, float* __restrict__ db,
+                                                           int M, int N, int ld, int accumulate) {
+  const int col = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int rg = threadIdx.x >> 6;
+  float acc = 0.f;
+  if (col < N)
+    for (int m = rg; m < M; m += 4) acc += ldf(dz + (int64_t)m * ld + col);
+  __shared__ float part[4][64];
+  part[rg][threadIdx.x & 63] = acc;
+  __syncthreads();
+  if (rg == 0 && col < N) {
+    const float s = part[0][threadIdx.x] + part[1][threadIdx.x] + part[2][threadIdx.x] + part[3][threadIdx.x];
+    db[col] = accumulate ? db[col] + s : s;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Epilogues shared by the plain and the MFMA GEMMs.  acc is the fp32 contraction result for
+// output element (i, j).
+// ---------------------------------------------------------------------------------------------
+// forward: z = acc + b[j]; stores z (compute dtype and/or fp32) and a = act(z)
+template <typename T>
+struct PmEpiFwd {
+  PmWLoc<T> bias;   // the bias lives in the same ring slot as its weight matrix
+  T* z; T* a; float* z32; int ld; int act;
+  const T* b_;
+  __device__ __forceinline__ void begin() { b_ = bias.get(); }
+  __device__ __forceinline__ void operator()(int i, int j, float acc) const {
+    const float zz = acc + ldf(b_ + j);
+    const int64_t o = (int64_t)i * ld + j;
+    if (z) stf(z + o, zz);
+    if (z32) z32[o] = zz;
+    if (a) stf(a + o, pm_act_fwd(zz, act));
+  }
+};
+// backward data: dz_prev = acc * act'(z_prev)
+template <typename T>
+struct PmEpiBwdData {
+  const T* zprev; T* dzprev; int ld; int act;
+  __device__ __forceinline__ void begin() {}
+  __device__ __forceinline__ void operator()(int i, int j, float acc) const {
+    const int64_t o = (int64_t)i * ld + j;
+    stf(dzprev + o, acc * pm_act_bwd(ldf(zprev + o), act));
+  }
+};
+// backward weight: g[i, j] (+)= acc, fp32
+struct PmEpiBwdWeight {
+  float* g; int ld; int accumulate;
+  __device__ __forceinline__ void begin() {}
+  __device__ __forceinline__ void operator()(int i, int j, float acc) const {
+    const int64_t o = (int64_t)i * ld + j;
+    g[o] = accumulate ? g[o] + acc : acc;
+  }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Plain tiled GEMM  C[i, j] = sum_k A(i, k) * B(j, k)  with arbitrary strides; fp32 FMA.
+// Used for fp32 contexts (tiny layers where launch latency dominates) and for any bf16 shape the
+// MFMA kernel's alignment rules exclude.  16x16 outputs per block, K staged 16 at a time.
+// ---------------------------------------------------------------------------------------------
+template <typename TA, typename TB, class Epi>
+__global__ __launch_bounds__(256) void pm_gemm_plain_kernel(int I, int J, int K,
+                                                            const TA* __restrict__ A, int64_t sai, int64_t sak,
+                                                            PmWLoc<TB> bloc, int64_t sbj, int64_t sbk,
+                                                            Epi epi) {
+  __shared__ float sA[16][17], sB[16][17];
+  const TB* B = bloc.get();
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  const int i0 = blockIdx.y * 16, j0 = blockIdx.x * 16;
+  float acc = 0.f;
+  for (int k0 = 0; k0 < K; k0 += 16) {
+    const int ia = i0 + ty, jb = j0 + ty, kk = k0 + tx;
+    sA[ty][tx] = (ia < I && kk < K) ? ldf(A + ia * sai + kk * sak) : 0.f;
+    sB[ty][tx] = (jb < J && kk < K) ? ldf(B + jb * sbj + kk * sbk) : 0.f;
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) acc += sA[ty][k] * sB[tx][k];
+    __syncthreads();
+  }
+  const int i = i0 + ty, j = j0 + tx;
+  epi.begin();
+  if (i < I && j < J) epi(i, j, acc);
+}

@@ -1,0 +1,229 @@
+// bf16 MFMA GEMM for the stage forward / backward-data / backward-weight products (gfx950).
+//
+//   C[i, j] = sum_k A(i, k) * B(j, k),   fp32 accumulation on v_mfma_f32_32x32x16_bf16.
+//
+// Each operand is either "KC" (contraction index contiguous in memory: X[r * ld + k]) or "RC"
+// (row index contiguous: X[k * ld + r]).  The three products of a Linear unit map to
+//   forward          Z = A W^T      A: KC (activations)   B: KC (W[n_out, n_in])
+//   backward data    dA = dZ W      A: KC (dZ)            B: RC (W read along n_in)
+//   backward weight  dW = dZ^T A    A: RC (dZ)            B: RC (activations)
+// Global -> LDS is always a straight 16-byte copy of the tile as it lies in memory; an RC tile
+// is transposed on the LDS -> register side (eight 2-byte reads along k, consecutive lanes on
+// consecutive addresses, so no bank conflicts), a KC tile is read with one 16-byte load per
+// fragment.  LDS rows are padded by 8 elements so the 16-byte fragment reads of 16 lanes cover
+// all banks once.
+//
+// Block = WI x WJ x WK wavefronts.  WI x WJ waves tile the BI x BJ output block in 32x32 MFMA
+// tiles; WK > 1 additionally splits every 64-wide K slab across waves (for skinny problems such
+// as 128 x 1024 x 1024 where output tiles alone cannot fill 256 CUs) and the partial
+// accumulators are summed through LDS before the epilogue.
+//
+// Requirements (checked by the dispatcher, which otherwise declines): leading dimensions and
+// base pointers multiples of 8 elements; memory readable up to the next multiple of 8 along the
+// contiguous index, holding zeros beyond the logical extent.
+#pragma once
+#include "pm_common.hpp"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 pm_bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float pm_f32x16;
+
+constexpr int PM_BK = 64;
+
+template <int ROWS, bool KC>
+struct PmTileShape {                       // how a (ROWS x PM_BK) operand tile lies in LDS
+  static constexpr int lds_rows = KC ? ROWS : PM_BK;
+  static constexpr int lds_cols = KC ? PM_BK : ROWS;
+  static constexpr int stride = lds_cols + 8;
+  static constexpr int elems = lds_rows * stride;
+  static constexpr int chunks = lds_rows * lds_cols / 8;    // 16-byte pieces
+};
+
+template <int ROWS, bool KC, int NT>
+struct PmTileLoader {
+  using S = PmTileShape<ROWS, KC>;
+  static constexpr int PER = (S::chunks + NT - 1) / NT;
+  uint4 r[PER];
+  // r0: first row of the tile, k0: first contraction index; R / K logical extents
+  __device__ __forceinline__ void load(const bf16_t* __restrict__ X, int64_t ld, int r0, int k0, int R, int K) {
+    const int R8 = (R + 7) & ~7, K8 = (K + 7) & ~7;
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      const int c = p * NT + threadIdx.x;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (S::chunks % NT == 0 || c < S::chunks) {
+        const int lr = c / (S::lds_cols / 8), lc = (c % (S::lds_cols / 8)) * 8;
+        if (KC) {
+          const int row = r0 + lr, k = k0 + lc;
+          if (row < R && k < K8) v = *reinterpret_cast<const uint4*>(X + (int64_t)row * ld + k);
+        } else {
+          const int k = k0 + lr, row = r0 + lc;
+          if (k < K && row < R8) v = *reinterpret_cast<const uint4*>(X + (int64_t)k * ld + row);
+        }
+      }
+      r[p] = v;
+    }
+  }
+  __device__ __forceinline__ void store(bf16_t* s) const {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      const int c = p * NT + threadIdx.x;
+      if (S::chunks % NT == 0 || c < S::chunks) {
+        const int lr = c / (S::lds_cols / 8), lc = (c % (S::lds_cols / 8)) * 8;
+        *reinterpret_cast<uint4*>(s + lr * S::stride + lc) = r[p];
+      }
+    }
+  }
+};
+
+// MFMA operand fragment for tile row `row` (0..ROWS-1), k-group kg (8 consecutive k from kbase)
+template <int ROWS, bool KC>
+__device__ __forceinline__ pm_bf16x8 pm_read_frag(const bf16_t* s, int row, int kbase) {
+  using S = PmTileShape<ROWS, KC>;
+  if (KC) {
+    return *reinterpret_cast<const pm_bf16x8*>(s + row * S::stride + kbase);
+  } else {
+    union { pm_bf16x8 v; bf16_t h[8]; } u;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) u.h[e] = s[(kbase + e) * S::stride + row];
+    return u.v;
+  }
+}
+
+template <int BI, int BJ, int WI, int WJ, int WK, bool AKC, bool BKC, class Epi>
+__global__ __launch_bounds__(WI * WJ * WK * 64) void pm_gemm_mfma_kernel(int I, int J, int K,
+                                                                         const bf16_t* __restrict__ A, int64_t lda,
+                                                                         PmWLoc<bf16_t> bloc, int64_t ldb, Epi epi) {
+  constexpr int NT = WI * WJ * WK * 64;
+  constexpr int TI = BI / WI / 32, TJ = BJ / WJ / 32;     // 32x32 MFMA tiles per wave
+  constexpr int KS = PM_BK / 16 / WK;                     // k-steps of 16 per wave per slab
+  static_assert(BI % (WI * 32) == 0 && BJ % (WJ * 32) == 0 && (PM_BK / 16) % WK == 0, "tile shape");
+  using SA = PmTileShape<BI, AKC>;
+  using SB = PmTileShape<BJ, BKC>;
+  constexpr int LDS_AB = (SA::elems + SB::elems) * 2;
+  constexpr int LDS_RED = WK > 1 ? WK * WI * WJ * TI * TJ * 1024 * 4 : 0;
+  constexpr int LDS_BYTES = LDS_AB > LDS_RED ? LDS_AB : LDS_RED;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem);
+  bf16_t* sB = sA + SA::elems;
+
+  const bf16_t* __restrict__ B = bloc.get();
+  const int i0 = blockIdx.y * BI, j0 = blockIdx.x * BJ;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wk = wave % WK, wj = (wave / WK) % WJ, wi = wave / (WK * WJ);
+  const int lr = lane & 31, kg = lane >> 5;
+
+  pm_f32x16 acc[TI][TJ];
+#pragma unroll
+  for (int a = 0; a < TI; ++a)
+#pragma unroll
+    for (int b = 0; b < TJ; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  PmTileLoader<BI, AKC, NT> la;
+  PmTileLoader<BJ, BKC, NT> lb;
+  const int nk = (K + PM_BK - 1) / PM_BK;
+  la.load(A, lda, i0, 0, I, K);
+  lb.load(B, ldb, j0, 0, J, K);
+  for (int kt = 0; kt < nk; ++kt) {
+    la.store(sA);
+    lb.store(sB);
+    __syncthreads();
+    if (kt + 1 < nk) {
+      la.load(A, lda, i0, (kt + 1) * PM_BK, I, K);
+      lb.load(B, ldb, j0, (kt + 1) * PM_BK, J, K);
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int kbase = (wk * KS + ks) * 16 + kg * 8;
+      pm_bf16x8 fa[TI], fb[TJ];
+#pragma unroll
+      for (int a = 0; a < TI; ++a) fa[a] = pm_read_frag<BI, AKC>(sA, (wi * TI + a) * 32 + lr, kbase);
+#pragma unroll
+      for (int b = 0; b < TJ; ++b) fb[b] = pm_read_frag<BJ, BKC>(sB, (wj * TJ + b) * 32 + lr, kbase);
+#pragma unroll
+      for (int a = 0; a < TI; ++a)
+#pragma unroll
+        for (int b = 0; b < TJ; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  epi.begin();
+  if (WK == 1) {
+    // accumulator layout of the 32x32 tile: value v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32
+#pragma unroll
+    for (int a = 0; a < TI; ++a)
+#pragma unroll
+      for (int b = 0; b < TJ; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int i = i0 + (wi * TI + a) * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+          const int j = j0 + (wj * TJ + b) * 32 + lr;
+          if (i < I && j < J) epi(i, j, acc[a][b][v]);
+        }
+  } else {
+    // sum the WK partial tiles through LDS; afterwards thread -> element mapping is row-major over
+    // the block so the epilogue's stores are contiguous along j
+    float* red = reinterpret_cast<float*>(smem);
+#pragma unroll
+    for (int a = 0; a < TI; ++a)
+#pragma unroll
+      for (int b = 0; b < TJ; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int li = (wi * TI + a) * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+          const int lj = (wj * TJ + b) * 32 + lr;
+          red[(wk * BI + li) * BJ + lj] = acc[a][b][v];
+        }
+    __syncthreads();
+    for (int e = threadIdx.x; e < BI * BJ; e += NT) {
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < WK; ++w) sum += red[w * BI * BJ + e];
+      const int i = i0 + e / BJ, j = j0 + e % BJ;
+      if (i < I && j < J) epi(i, j, sum);
+    }
+  }
+}
+
+template <int BI, int BJ, int WI, int WJ, int WK, bool AKC, bool BKC, class Epi>
+inline void pm_mfma_launch(hipStream_t st, int I, int J, int K, const bf16_t* A, int64_t lda, PmWLoc<bf16_t> B,
+                           int64_t ldb, const Epi& epi) {
+  dim3 grid((J + BJ - 1) / BJ, (I + BI - 1) / BI);
+  hipLaunchKernelGGL((pm_gemm_mfma_kernel<BI, BJ, WI, WJ, WK, AKC, BKC, Epi>), grid, dim3(WI * WJ * WK * 64), 0, st, I,
+                     J, K, A, lda, B, ldb, epi);
+}
+
+template <bool AKC, bool BKC, class Epi>
+inline void pm_mfma_pick(hipStream_t st, int I, int J, int K, const bf16_t* A, int64_t lda, PmWLoc<bf16_t> B,
+                         int64_t ldb, const Epi& epi) {
+  const long tiles128 = (long)((I + 127) / 128) * ((J + 127) / 128);
+  const long tiles64 = (long)((I + 63) / 64) * ((J + 63) / 64);
+  if (tiles128 >= 512) pm_mfma_launch<128, 128, 2, 2, 1, AKC, BKC>(st, I, J, K, A, lda, B, ldb, epi);
+  else if (tiles64 >= 192 || K <= 256) pm_mfma_launch<64, 64, 2, 2, 1, AKC, BKC>(st, I, J, K, A, lda, B, ldb, epi);
+  else pm_mfma_launch<32, 32, 1, 1, 4, AKC, BKC>(st, I, J, K, A, lda, B, ldb, epi);
+}
+
+// Try to run the product on MFMA.  Strides are in elements; exactly one of (sxr, sxk) must be 1
+// per operand.  Returns false (nothing launched) when the alignment rules do not fit, in which
+// case the caller uses the plain kernel.
+template <class Epi>
+inline bool pm_mfma_gemm_try(hipStream_t st, int I, int J, int K, const bf16_t* A, int64_t sai, int64_t sak,
+                             PmWLoc<bf16_t> B, int64_t sbj, int64_t sbk, const Epi& epi) {
+  const bool akc = sak == 1, bkc = sbk == 1;
+  if (!akc && sai != 1) return false;
+  if (!bkc && sbj != 1) return false;
+  const int64_t lda = akc ? sai : sak, ldb = bkc ? sbj : sbk;
+  if ((lda & 7) || (ldb & 7) || (B.stride & 7)) return false;
+  if (((uintptr_t)A & 15) || ((uintptr_t)B.base & 15)) return false;
+  // the contiguous index is read in whole groups of 8: the row must be that long
+  if (lda < ((akc ? K : I) + 7) / 8 * 8) return false;
+  if (ldb < ((bkc ? K : J) + 7) / 8 * 8) return false;
+  if (akc && bkc) pm_mfma_pick<true, true>(st, I, J, K, A, lda, B, ldb, epi);
+  else if (akc && !bkc) pm_mfma_pick<true, false>(st, I, J, K, A, lda, B, ldb, epi);
+  else if (!akc && bkc) pm_mfma_pick<false, true>(st, I, J, K, A, lda, B, ldb, epi);
+  else pm_mfma_pick<false, false>(st, I, J, K, A, lda, B, ldb, epi);
+  return true;
+}

@@ -1,0 +1,204 @@
+// Prologue (slot / step-size table), gradient norm and the fused PipeMare update pass.
+#pragma once
+#include "pm_common.hpp"
+
+// ---------------------------------------------------------------------------------------------
+// Prologue: one launch per optimizer step.  Reads the device step counter t, writes per unit the
+// ring slots of the delayed reads (Sec. 2.1: versions t - tau_fwd,i and t - tau_bkwd,i, clamped
+// to 0 during pipeline fill) and the rescheduled step size (Sec. 3.1, T1), then advances t.
+// A single block so that the counter update is ordered after every table entry.
+// ---------------------------------------------------------------------------------------------
+__global__ void pm_prologue_kernel(PmStepHdr* hdr, const PmLayerStatic* ls, PmLayerStep* ld, int L,
+                                   PmSchedDev sc) {
+  const long long t = hdr->t_next;
+  double a_base;
+  if (sc.kind == 0) {
+    a_base = sc.base;
+  } else if (sc.kind == 1) {
+    a_base = sc.base * pow(sc.factor, (double)(t / sc.interval));
+  } else {
+    if (t < sc.interval) a_base = sc.init + (sc.base - sc.init) * ((double)t / (double)sc.interval);
+    else a_base = t > 0 ? sc.base * sqrt((double)sc.interval / (double)t) : sc.base;
+  }
+  double p = 0.0;
+  if (sc.K > 0) {
+    double f = (double)t / (double)sc.K;
+    p = 1.0 - (f < 1.0 ? f : 1.0);
+  }
+  for (int l = threadIdx.x; l < L; l += blockDim.x) {
+    const PmLayerStatic S = ls[l];
+    PmLayerStep D;
+    const long long vf = t - S.tau_f > 0 ? t - S.tau_f : 0;
+    const long long vb = t - S.tau_b > 0 ? t - S.tau_b : 0;
+    const long long vu = t + 1 - S.tau_b > 0 ? t + 1 - S.tau_b : 0;
+    D.fwd_slot = (int32_t)(vf % S.R);
+    D.bkwd_slot = (int32_t)(vb % S.R);
+    D.write_slot = (int32_t)((t + 1) % S.R);
+    D.ub_slot = (int32_t)(vu % S.R);
+    double lr = a_base;
+    if (sc.t1_enabled && p > 0.0) {
+      const int tau = S.tau_f > 1 ? S.tau_f : 1;
+      lr = a_base / pow((double)tau, p);
+    }
+    D.lr = (float)lr;
+    D.pad_[0] = D.pad_[1] = D.pad_[2] = 0;
+    ld[l] = D;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    hdr->t_used = t;
+    hdr->t_next = t + 1;
+    hdr->gnorm2 = 0.f;
+    hdr->gscale = (float)sc.gscale0;
+    hdr->bc1 = (float)(1.0 / (1.0 - pow(sc.beta1, (double)(t + 1))));
+    hdr->bc2 = (float)(1.0 / (1.0 - pow(sc.beta2, (double)(t + 1))));
+  }
+}
+
+__global__ void pm_zero_loss_kernel(PmStepHdr* hdr) { hdr->loss = 0.f; }
+
+// ---------------------------------------------------------------------------------------------
+// Sum of squares over a flat fp32 array (global gradient norm for clipping, parameter norm for
+// the divergence monitor): wavefront shuffles, one LDS stage, one atomic per block.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pm_sumsq_kernel(const float* __restrict__ x, int64_t n, float* out) {
+  float acc = 0.f;
+  const int64_t n4 = n >> 2;
+  const float4* x4 = reinterpret_cast<const float4*>(x);
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x) {
+    const float4 v = x4[i];
+    acc += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  acc = pm_wave_sum(acc);
+  __shared__ float part[4];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) atomicAdd(out, part[0] + part[1] + part[2] + part[3]);
+}
+
+// gscale <- (1/N) * min(1, clip / ||g/N||)
+__global__ void pm_clip_scale_kernel(PmStepHdr* hdr, float clip) {
+  const float gn = sqrtf(hdr->gnorm2) * hdr->gscale;
+  if (gn > clip) hdr->gscale *= clip / gn;
+}
+
+// ---------------------------------------------------------------------------------------------
+// The fused update: ONE launch over the flat parameter space of all units.
+//   g' = gscale * g (+ wd * w for SGD)
+//   SGD momentum (App. B.3 form)  v <- beta v - lr_i g' ;  w <- w + v
+//   AdamW                         m,s moments with bias correction; w <- w - lr_i (mhat/(sqrt(shat)+eps) + wd w)
+//   delta <- gamma_i delta + (1 - gamma_i)(w_new - w)                 (Sec. 3.2, T2 accumulator)
+//   ring[(t+1) mod R_i] <- round(w_new)                               (the version the forward reads later)
+//   ub <- round(base - (tau_fwd,i - tau_bkwd,i) delta_new)            (Sec. 3.2, corrected backward weights
+//        of the NEXT step; base = w_new when tau_bkwd = 0, else the stored version t+1-tau_bkwd)
+// Each block owns PM_CHUNK consecutive elements, all of one unit (units are padded to the chunk),
+// so the per-unit scalars are wave-uniform; each thread owns 8 consecutive elements: two 16-byte
+// loads per fp32 stream, one 16-byte store per bf16 stream.
+// ---------------------------------------------------------------------------------------------
+template <typename RT>
+struct PmUpdArgs {
+  const float* g;
+  float* w;
+  float* v;   // momentum, or Adam m
+  float* s;   // Adam second moment
+  float* d;   // delta
+  RT* ring;
+  RT* ub;
+  const int32_t* chunk_layer;
+  const PmLayerStatic* ls;
+  const PmLayerStep* ld;
+  PmStepHdr* hdr;
+  float beta1, beta2, eps, wd;
+};
+
+__device__ __forceinline__ void pm_store8(float* p, const float* x) {
+  reinterpret_cast<float4*>(p)[0] = make_float4(x[0], x[1], x[2], x[3]);
+  reinterpret_cast<float4*>(p)[1] = make_float4(x[4], x[5], x[6], x[7]);
+}
+__device__ __forceinline__ void pm_store8(bf16_t* p, const float* x) {
+  uint4 o;
+  o.x = (uint32_t)f32_to_bf16(x[0]) | ((uint32_t)f32_to_bf16(x[1]) << 16);
+  o.y = (uint32_t)f32_to_bf16(x[2]) | ((uint32_t)f32_to_bf16(x[3]) << 16);
+  o.z = (uint32_t)f32_to_bf16(x[4]) | ((uint32_t)f32_to_bf16(x[5]) << 16);
+  o.w = (uint32_t)f32_to_bf16(x[6]) | ((uint32_t)f32_to_bf16(x[7]) << 16);
+  *reinterpret_cast<uint4*>(p) = o;
+}
+__device__ __forceinline__ void pm_load8(const float* p, float* x) {
+  const float4 a = reinterpret_cast<const float4*>(p)[0];
+  const float4 b = reinterpret_cast<const float4*>(p)[1];
+  x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+__device__ __forceinline__ void pm_load8(const bf16_t* p, float* x) {
+  const uint4 a = *reinterpret_cast<const uint4*>(p);
+  x[0] = __uint_as_float(a.x << 16); x[1] = __uint_as_float(a.x & 0xffff0000u);
+  x[2] = __uint_as_float(a.y << 16); x[3] = __uint_as_float(a.y & 0xffff0000u);
+  x[4] = __uint_as_float(a.z << 16); x[5] = __uint_as_float(a.z & 0xffff0000u);
+  x[6] = __uint_as_float(a.w << 16); x[7] = __uint_as_float(a.w & 0xffff0000u);
+}
+
+template <typename RT, int OPT>
+__global__ __launch_bounds__(256) void pm_fused_update_kernel(PmUpdArgs<RT> a) {
+  const int c = blockIdx.x;
+  const int l = a.chunk_layer[c];
+  const PmLayerStatic S = a.ls[l];
+  const PmLayerStep D = a.ld[l];
+  const float lr = D.lr, gam = S.gamma, corr = S.corr;
+  const float gs = a.hdr->gscale;
+  const int64_t e = (int64_t)c * PM_CHUNK + threadIdx.x * 8;
+  const int64_t rel = e - S.off;
+
+  float g[8], w[8], v[8], d[8], s[8], wn[8], ubv[8];
+  pm_load8(a.g + e, g);
+  pm_load8(a.w + e, w);
+  pm_load8(a.v + e, v);
+  pm_load8(a.d + e, d);
+  if (OPT == 1) pm_load8(a.s + e, s);
+  const bool ub_from_ring = (corr != 0.f) && (S.tau_b > 0);
+  if (ub_from_ring) pm_load8(a.ring + S.ring_off + (int64_t)D.ub_slot * S.n_pad + rel, ubv);
+
+  bool bad = false;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    float gj = g[j] * gs;
+    float dw;   // w_{t+1} - w_t, kept as computed (not re-derived by subtraction) so delta keeps its low bits
+    if (OPT == 0) {
+      gj += a.wd * w[j];
+      v[j] = a.beta1 * v[j] - lr * gj;
+      dw = v[j];
+    } else {
+      v[j] = a.beta1 * v[j] + (1.f - a.beta1) * gj;
+      s[j] = a.beta2 * s[j] + (1.f - a.beta2) * gj * gj;
+      const float mh = v[j] * a.hdr->bc1;
+      const float sh = s[j] * a.hdr->bc2;
+      dw = -lr * (mh / (sqrtf(sh) + a.eps) + a.wd * w[j]);
+    }
+    wn[j] = w[j] + dw;
+    d[j] = gam * d[j] + (1.f - gam) * dw;
+    bad |= !(fabsf(wn[j]) <= 3.0e38f);
+  }
+  pm_store8(a.w + e, wn);
+  pm_store8(a.v + e, v);
+  pm_store8(a.d + e, d);
+  if (OPT == 1) pm_store8(a.s + e, s);
+  pm_store8(a.ring + S.ring_off + (int64_t)D.write_slot * S.n_pad + rel, wn);
+  if (corr != 0.f) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ubv[j] = (ub_from_ring ? ubv[j] : wn[j]) - corr * d[j];
+    pm_store8(a.ub + e, ubv);
+  }
+  if (bad) a.hdr->diverged = 1;
+}
+
+// Fill every ring slot and the corrected-weight buffer of all units with the initial weights.
+template <typename RT>
+__global__ __launch_bounds__(256) void pm_init_ring_kernel(const float* __restrict__ w, RT* ring, RT* ub,
+                                                           const int32_t* chunk_layer,
+                                                           const PmLayerStatic* ls) {
+  const int c = blockIdx.x;
+  const PmLayerStatic S = ls[chunk_layer[c]];
+  const int64_t e = (int64_t)c * PM_CHUNK + threadIdx.x * 8;
+  float x[8];
+  pm_load8(w + e, x);
+  pm_store8(ub + e, x);
+  for (int r = 0; r < S.R; ++r) pm_store8(ring + S.ring_off + (int64_t)r * S.n_pad + (e - S.off), x);
+}

@@ -44,6 +44,7 @@ class Workload:
     seed_init: int = 2
     seed_data: int = 0
     seed_teacher: int = 1
+    init: str = "fan_in"   # "fan_in": W ~ U(+-1/sqrt(fan_in));  "he": W ~ U(+-sqrt(6/fan_in)) behind ReLU/GELU
 
 
 def n_params(layer: Layer) -> int:
@@ -75,12 +76,12 @@ def config(idx: int) -> Workload:
         return _mlp("mlp16_bf16", widths, acts, stages,
                     N=1, loss="xent", dtype="bf16", microbatch=128, n_classes=10,
                     opt=dict(kind="sgdm", lr=0.01, beta=0.9, D=0.9, K=125, weight_decay=0.0),
-                    steps=500)
+                    steps=500, init="he")
     raise ValueError(f"unknown workload index {idx}")
 
 
 def small_mlp(width: int, depth: int, n_out: int, act: str, loss: str, dtype: str,
-              microbatch: int, layers_per_stage: int = 1, **opt) -> Workload:
+              microbatch: int, layers_per_stage: int = 1, init: str = "fan_in", **opt) -> Workload:
     """A free-form MLP for tests: `depth` hidden Linear+act layers then a head in the last stage."""
     widths = [width] * (depth + 1) + [n_out]
     acts = [act] * depth + ["none"]
@@ -89,19 +90,24 @@ def small_mlp(width: int, depth: int, n_out: int, act: str, loss: str, dtype: st
     o = dict(kind="sgdm", lr=0.01, beta=0.9, D=0.9, K=10, weight_decay=0.0)
     o.update(opt)
     return _mlp(f"mlp{depth}x{width}_{dtype}", widths, acts, stages, N=1, loss=loss, dtype=dtype,
-                microbatch=microbatch, n_classes=n_out, opt=o, steps=0)
+                microbatch=microbatch, n_classes=n_out, opt=o, steps=0, init=init)
 
 
 def init_params(wl: Workload, seed: int | None = None) -> List[np.ndarray]:
     """Initial parameters, one packed fp32 vector [W (n_out x n_in, row-major) | b (n_out)] per layer.
 
-    W ~ U(+-sqrt(6/fan_in)) behind ReLU/GELU (keeps activations O(1) through deep stacks),
-    U(+-sqrt(3/fan_in)) for a linear head; b ~ U(+-1/sqrt(fan_in)).
+    init "fan_in": W ~ U(+-1/sqrt(fan_in)) everywhere.
+    init "he":     W ~ U(+-sqrt(6/fan_in)) behind ReLU/GELU (keeps activations O(1) through deep
+                   stacks), U(+-sqrt(3/fan_in)) for a linear head.
+    b ~ U(+-1/sqrt(fan_in)) in both.
     """
     rng = np.random.default_rng(wl.seed_init if seed is None else seed)
     out = []
     for L in wl.layers:
-        bound = np.sqrt((6.0 if L.act in ("relu", "gelu") else 3.0) / L.n_in)
+        if wl.init == "he":
+            bound = np.sqrt((6.0 if L.act in ("relu", "gelu") else 3.0) / L.n_in)
+        else:
+            bound = 1.0 / np.sqrt(L.n_in)
         W = rng.uniform(-bound, bound, size=(L.n_out, L.n_in))
         b = rng.uniform(-1.0, 1.0, size=(L.n_out,)) / np.sqrt(L.n_in)
         out.append(np.concatenate([W.ravel(), b]).astype(np.float32))
