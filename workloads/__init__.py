@@ -75,7 +75,7 @@ def config(idx: int) -> Workload:
         stages = list(range(1, 17)) + [16]
         return _mlp("mlp16_bf16", widths, acts, stages,
                     N=1, loss="xent", dtype="bf16", microbatch=128, n_classes=10,
-                    opt=dict(kind="sgdm", lr=0.01, beta=0.9, D=0.9, K=125, weight_decay=0.0),
+                    opt=dict(kind="sgdm", lr=0.001, beta=0.9, D=0.9, K=125, weight_decay=0.0),
                     steps=500, init="he")
     raise ValueError(f"unknown workload index {idx}")
 
