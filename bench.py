@@ -36,7 +36,10 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload index (0: tiny fp32 MLP, 1: 16-stage bf16 MLP)")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel eagerly instead of replaying a HIP graph")
     ap.add_argument("--cpu-steps", type=int, default=24, help="oracle steps timed for cpu_baseline (0 = skip)")
-    ap.add_argument("--pool", type=int, default=8, help="distinct device-resident microbatches cycled through")
+    ap.add_argument("--pool", type=int, default=64, help="distinct device-resident microbatches cycled through")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run three plain device-to-device copies of this many MiB after the timed region "
+                         "(a kernel of known traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -90,6 +93,12 @@ def main():
         run(args.steps, args.warmup + args.steps)
         prof = pm.pm_profile_end(eng.ctx)
         eng.close()
+        if args.calib_copy_mib > 0:
+            src = torch.ones(args.calib_copy_mib << 20, dtype=torch.uint8, device="cuda")
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
+            side.synchronize()
 
     ms_per_step = dt / args.steps * 1e3
     steps_per_s = args.steps / dt
@@ -118,7 +127,8 @@ def main():
                    "launch": "hip_graph" if use_graph else "eager", "final_loss": round(stats["loss"], 5)},
         "roofline": {"kernel": "pm_fused_update_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": None, "bytes_per_param": bpp, "params": n_params,
+                     "traffic": measured_traffic(w.name), "algorithmic_bytes": n_params * bpp,
+                     "bytes_per_param": bpp, "params": n_params,
                      "avg_kernel_ms": round(prof["update_ms"], 5), "launches_timed": prof["n"]},
         "phases_ms": {"forward_loss": round(prof["fwd_ms"], 4), "backward": round(prof["bwd_ms"], 4),
                       "update": round(prof["update_ms"], 4)},
@@ -130,6 +140,20 @@ def main():
     if args.cpu_steps > 0:
         out["cpu_baseline"] = cpu_baseline(w, params, tau_fwd, tau_bkwd, args.cpu_steps)
     print(json.dumps(out), flush=True)
+
+
+def measured_traffic(workload_name):
+    """HBM bytes per launch of the update kernel from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a plain copy), or None."""
+    path = os.path.join(ROOT, "profiles", f"update_traffic_{workload_name}.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch pm_fused_update_kernel:"):
+                    return int(float(line.split(":")[1]))
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(w, params, tau_fwd, tau_bkwd, n_steps):

@@ -62,7 +62,7 @@ struct Layout {
   int64_t n_chunks = 0;
   size_t esz = 4;         // bytes per element of the compute dtype
   // byte offsets
-  size_t w_off, g_off, v_off, s_off, d_off, ub_off, ring_off, chunk_off, ls_off, ld_off, hdr_off, x_off;
+  size_t w_off, g_off, v_off, s_off, d_off, ub_off, ring_off, chunk_off, ls_off, ld_off, hdr_off, probs_off, x_off;
   size_t act_begin, act_end, total;
 };
 
@@ -137,6 +137,7 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
   lay.ls_off = take(sizeof(PmLayerStatic) * L);
   lay.ld_off = take(sizeof(PmLayerStep) * L);
   lay.hdr_off = take(sizeof(PmStepHdr));
+  lay.probs_off = take(sizeof(PmGemmProb<PmEpiBwdWeight>) * 2 * L);
   const int M = o->microbatch;
   lay.act_begin = p;
   lay.x_off = take((size_t)M * lay.units[0].ld_in * lay.esz);
@@ -172,6 +173,9 @@ struct pm_ctx {
   hipGraphExec_t graph_exec = nullptr;
   const void* graph_x = nullptr;
   const void* graph_y = nullptr;
+  // all weight-gradient products as one grouped MFMA launch (problem tables live in the arena)
+  bool dw_grouped = false;
+  int dw_maxI = 0, dw_maxJ = 0;
   // optional per-phase timing (host-side event objects only)
   std::vector<hipEvent_t> prof_ev;   // 4 per step: start, after forward+loss, after backward, after update
   int32_t prof_cap = 0, prof_n = 0;
@@ -274,9 +278,11 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
   const Unit& u0 = lay.units[0];
   prof_mark(c, 0);
   {
+    // one launch: block 0 also refreshes the slot / step-size table at the start of a minibatch
     const int64_t tot = (int64_t)M * u0.ld_in;
-    hipLaunchKernelGGL((pm_stage_input_kernel<T>), dim3((unsigned)std::min<int64_t>(1024, (tot + 255) / 256)), dim3(256),
-                       0, st, (const float*)x_dev, c->at<T>(lay.x_off), M, u0.d.n_in, u0.ld_in, c->hdr());
+    hipLaunchKernelGGL((pm_begin_step_kernel<T>), dim3((unsigned)std::min<int64_t>(1024, (tot + 255) / 256)), dim3(256),
+                       0, st, (const float*)x_dev, c->at<T>(lay.x_off), M, u0.d.n_in, u0.ld_in, c->hdr(), c->ls(),
+                       c->ld(), accumulate ? 0 : L, sched_dev(c));
   }
   // ---- forward: unit l reads W (and b) of version max(t - tau_fwd, 0) in place from its ring slot
   for (int l = 0; l < L; ++l) {
@@ -308,24 +314,45 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
     }
   }
   prof_mark(c, 1);
-  // ---- backward
-  for (int l = L - 1; l >= 0; --l) {
+  // ---- backward, data-gradient chain: da_in[M, n_in] = dz . W_bkwd, fused with act'(z_prev).
+  // W_bkwd = corrected buffer when the T2 coefficient is non-zero, else version max(t - tau_bkwd, 0).
+  // The first unit needs none (its backward weights never enter any gradient).
+  for (int l = L - 1; l >= 1; --l) {
     const Unit& u = lay.units[l];
-    const T* a_in = l == 0 ? c->at<T>(lay.x_off) : c->at<T>(lay.units[l - 1].a_off);
-    const T* dz = c->at<T>(u.dz_off);
-    // weight gradient from the stored forward activations: dW[n_out, n_in] = dz^T . a_in
-    PmEpiBwdWeight ew{g + u.off, u.d.n_in, accumulate};
-    launch_gemm<T>(c, u.d.n_out, u.d.n_in, M, dz, 1, u.ld_out, PmWLoc<T>{a_in, nullptr, 0}, 1, u.ld_in, ew);
-    hipLaunchKernelGGL((pm_bias_grad_kernel<T>), dim3((u.d.n_out + 63) / 64), dim3(256), 0, st, dz, g + u.off + u.boff,
-                       M, u.d.n_out, u.ld_out, accumulate);
-    if (l == 0) break;   // the first unit's backward weights never enter any gradient
-    // data gradient through the backward weights: da_in[M, n_in] = dz . W_bkwd, fused with act'(z_prev).
-    // W_bkwd = corrected buffer when the T2 coefficient is non-zero, else version max(t - tau_bkwd, 0).
     const Unit& up = lay.units[l - 1];
+    const T* dz = c->at<T>(u.dz_off);
     PmWLoc<T> Wb = u.corr ? PmWLoc<T>{ub + u.off, nullptr, 0}
                           : PmWLoc<T>{ring + u.ring_off, &c->ld()[l].bkwd_slot, u.n_pad};
     PmEpiBwdData<T> ed{c->at<T>(up.z_off), c->at<T>(up.dz_off), up.ld_out, up.d.act};
     launch_gemm<T>(c, M, u.d.n_in, u.d.n_out, dz, u.ld_out, 1, Wb, 1, u.d.n_in, ed);
+  }
+  // ---- weight gradients from the stored forward activations: dW[n_out, n_in] = dz^T . a_in,
+  // db = column sums of dz.  They depend only on stored tensors, so all units go out as ONE
+  // grouped launch (bias gradients fused) when every unit fits the MFMA kernel.
+  bool grouped = false;
+  if constexpr (sizeof(T) == 2) {
+    if (c->dw_grouped) {
+      const auto* tab = c->at<PmGemmProb<PmEpiBwdWeight>>(lay.probs_off) + (accumulate ? L : 0);
+      dim3 grid((c->dw_maxJ + 63) / 64, (c->dw_maxI + 63) / 64, L);
+      if (M <= 128)
+        hipLaunchKernelGGL((pm_gemm_mfma_grouped_kernel<PmCfgShortK, false, false, PmEpiBwdWeight>), grid, dim3(256), 0,
+                           st, tab);
+      else
+        hipLaunchKernelGGL((pm_gemm_mfma_grouped_kernel<PmCfgMid, false, false, PmEpiBwdWeight>), grid, dim3(256), 0, st,
+                           tab);
+      grouped = true;
+    }
+  }
+  if (!grouped) {
+    for (int l = L - 1; l >= 0; --l) {
+      const Unit& u = lay.units[l];
+      const T* a_in = l == 0 ? c->at<T>(lay.x_off) : c->at<T>(lay.units[l - 1].a_off);
+      const T* dz = c->at<T>(u.dz_off);
+      PmEpiBwdWeight ew{g + u.off, u.d.n_in, accumulate, nullptr};
+      launch_gemm<T>(c, u.d.n_out, u.d.n_in, M, dz, 1, u.ld_out, PmWLoc<T>{a_in, nullptr, 0}, 1, u.ld_in, ew);
+      hipLaunchKernelGGL((pm_bias_grad_kernel<T>), dim3((u.d.n_out + 63) / 64), dim3(256), 0, st, dz,
+                         g + u.off + u.boff, M, u.d.n_out, u.ld_out, accumulate);
+    }
   }
   PM_HIP(hipGetLastError());
   return PM_OK;
@@ -333,7 +360,6 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
 
 template <typename T>
 pm_status enqueue_step(pm_ctx* c, const void* x, const void* y, bool first_micro, bool last_micro) {
-  if (first_micro) launch_prologue(c);
   pm_status s = launch_fwd_bwd<T>(c, x, y, first_micro ? 0 : 1);
   if (s != PM_OK) return s;
   if (last_micro) {
@@ -380,7 +406,7 @@ pm_status linear_bwd_data_t(hipStream_t st, int M, int n_in, int n_out, const vo
 template <typename T>
 pm_status linear_bwd_weight_t(hipStream_t st, int M, int n_in, int n_out, const void* dz, const void* a, float* dW,
                               float* db, int accumulate) {
-  PmEpiBwdWeight epi{dW, n_in, accumulate};
+  PmEpiBwdWeight epi{dW, n_in, accumulate, nullptr};
   launch_gemm_on<T>(st, n_out, n_in, M, (const T*)dz, 1, n_out, PmWLoc<T>{(const T*)a, nullptr, 0}, 1, n_in, epi);
   if (db)
     hipLaunchKernelGGL((pm_bias_grad_kernel<T>), dim3((n_out + 63) / 64), dim3(256), 0, st, (const T*)dz, db, M, n_out,
@@ -535,6 +561,30 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
   if ((e = hipMemcpyAsync(c->arena + lay.w_off, w0.data(), w0.size() * 4, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy weights");
   if ((e = hipMemcpyAsync(c->arena + lay.chunk_off, chunk_layer.data(), chunk_layer.size() * 4, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy chunk table");
   if ((e = hipMemcpyAsync(c->arena + lay.ls_off, ls.data(), ls.size() * sizeof(PmLayerStatic), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy unit table");
+  std::vector<PmGemmProb<PmEpiBwdWeight>> probs;
+  if (c->o.dtype == PM_BF16) {
+    // weight-gradient problem tables (first microbatch: overwrite, later ones: accumulate)
+    const int M = c->o.microbatch;
+    float* g = c->at<float>(lay.g_off);
+    bool fits = true;
+    probs.resize((size_t)2 * L);
+    for (int acc = 0; acc < 2; ++acc)
+      for (int l = 0; l < L; ++l) {
+        const Unit& u = lay.units[l];
+        const bf16_t* a_in = l == 0 ? c->at<bf16_t>(lay.x_off) : c->at<bf16_t>(lay.units[l - 1].a_off);
+        const bf16_t* dz = c->at<bf16_t>(u.dz_off);
+        fits = fits && pm_mfma_fits(u.d.n_out, u.d.n_in, M, dz, 1, u.ld_out, a_in, 0, 1, u.ld_in);
+        PmGemmProb<PmEpiBwdWeight>& pr = probs[(size_t)acc * L + l];
+        pr.I = u.d.n_out; pr.J = u.d.n_in; pr.K = M;
+        pr.A = dz; pr.lda = u.ld_out;
+        pr.B = PmWLoc<bf16_t>{a_in, nullptr, 0}; pr.ldb = u.ld_in;
+        pr.epi = PmEpiBwdWeight{g + u.off, u.d.n_in, acc, g + u.off + u.boff};
+        c->dw_maxI = std::max(c->dw_maxI, (int)u.d.n_out);
+        c->dw_maxJ = std::max(c->dw_maxJ, (int)u.d.n_in);
+      }
+    c->dw_grouped = fits;
+    if ((e = hipMemcpyAsync(c->arena + lay.probs_off, probs.data(), probs.size() * sizeof(probs[0]), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy problem table");
+  }
   if (c->o.dtype == PM_BF16)
     hipLaunchKernelGGL((pm_init_ring_kernel<bf16_t>), dim3((unsigned)lay.n_chunks), dim3(256), 0, st,
                        c->at<float>(lay.w_off), c->at<bf16_t>(lay.ring_off), c->at<bf16_t>(lay.ub_off),

@@ -90,6 +90,9 @@ __global__ __launch_bounds__(256) void pm_bias_grad_kernel(const T* __restrict__
 // forward: z = acc + b[j]; stores z (compute dtype and/or fp32) and a = act(z)
 template <typename T>
 struct PmEpiFwd {
+  static constexpr bool kColSumA = false;
+  __device__ __forceinline__ bool wants_colsum() const { return false; }
+  __device__ __forceinline__ void colsum(int, float) const {}
   PmWLoc<T> bias;   // the bias lives in the same ring slot as its weight matrix
   T* z; T* a; float* z32; int ld; int act;
   const T* b_;
@@ -105,6 +108,9 @@ struct PmEpiFwd {
 // backward data: dz_prev = acc * act'(z_prev)
 template <typename T>
 struct PmEpiBwdData {
+  static constexpr bool kColSumA = false;
+  __device__ __forceinline__ bool wants_colsum() const { return false; }
+  __device__ __forceinline__ void colsum(int, float) const {}
   const T* zprev; T* dzprev; int ld; int act;
   __device__ __forceinline__ void begin() {}
   __device__ __forceinline__ void operator()(int i, int j, float acc) const {
@@ -112,9 +118,13 @@ struct PmEpiBwdData {
     stf(dzprev + o, acc * pm_act_bwd(ldf(zprev + o), act));
   }
 };
-// backward weight: g[i, j] (+)= acc, fp32
+// backward weight: g[i, j] (+)= acc, fp32; db[i] (+)= column sum of the A operand (MFMA path only)
 struct PmEpiBwdWeight {
+  static constexpr bool kColSumA = true;
   float* g; int ld; int accumulate;
+  float* db;   // bias gradient, or nullptr when a separate kernel produces it
+  __device__ __forceinline__ bool wants_colsum() const { return db != nullptr; }
+  __device__ __forceinline__ void colsum(int i, float s) const { db[i] = accumulate ? db[i] + s : s; }
   __device__ __forceinline__ void begin() {}
   __device__ __forceinline__ void operator()(int i, int j, float acc) const {
     const int64_t o = (int64_t)i * ld + j;

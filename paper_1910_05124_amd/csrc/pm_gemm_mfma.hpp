@@ -14,9 +14,16 @@
 // all banks once.
 //
 // Block = WI x WJ x WK wavefronts.  WI x WJ waves tile the BI x BJ output block in 32x32 MFMA
-// tiles; WK > 1 additionally splits every 64-wide K slab across waves (for skinny problems such
-// as 128 x 1024 x 1024 where output tiles alone cannot fill 256 CUs) and the partial
-// accumulators are summed through LDS before the epilogue.
+// tiles; WK > 1 additionally splits every K slab across waves (for skinny problems such as
+// 128 x 1024 x 1024 where output tiles alone cannot fill 256 CUs) and the partial accumulators
+// are summed through LDS before the epilogue.  The slab depth BK is a template parameter: the
+// skinny shapes are bound by memory latency, not MFMA rate, so they use deep slabs (many
+// 16-byte loads in flight per thread, few serialised round trips).
+//
+// A launch covers either one problem (passed by value) or a table of problems in device memory
+// indexed by blockIdx.z (all weight-gradient products of a step go out as one launch).  The
+// weight-gradient epilogue can also emit the bias gradient: column sums of the (RC) A tile,
+// accumulated by the blocks of the first column of tiles while the tile sits in LDS.
 //
 // Requirements (checked by the dispatcher, which otherwise declines): leading dimensions and
 // base pointers multiples of 8 elements; memory readable up to the next multiple of 8 along the
@@ -27,20 +34,18 @@
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 pm_bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float pm_f32x16;
 
-constexpr int PM_BK = 64;
-
-template <int ROWS, bool KC>
-struct PmTileShape {                       // how a (ROWS x PM_BK) operand tile lies in LDS
-  static constexpr int lds_rows = KC ? ROWS : PM_BK;
-  static constexpr int lds_cols = KC ? PM_BK : ROWS;
+template <int ROWS, bool KC, int BK>
+struct PmTileShape {                       // how a (ROWS x BK) operand tile lies in LDS
+  static constexpr int lds_rows = KC ? ROWS : BK;
+  static constexpr int lds_cols = KC ? BK : ROWS;
   static constexpr int stride = lds_cols + 8;
   static constexpr int elems = lds_rows * stride;
   static constexpr int chunks = lds_rows * lds_cols / 8;    // 16-byte pieces
 };
 
-template <int ROWS, bool KC, int NT>
+template <int ROWS, bool KC, int BK, int NT>
 struct PmTileLoader {
-  using S = PmTileShape<ROWS, KC>;
+  using S = PmTileShape<ROWS, KC, BK>;
   static constexpr int PER = (S::chunks + NT - 1) / NT;
   uint4 r[PER];
   // r0: first row of the tile, k0: first contraction index; R / K logical extents
@@ -75,10 +80,10 @@ struct PmTileLoader {
   }
 };
 
-// MFMA operand fragment for tile row `row` (0..ROWS-1), k-group kg (8 consecutive k from kbase)
-template <int ROWS, bool KC>
+// MFMA operand fragment for tile row `row` (0..ROWS-1): 8 consecutive k from kbase
+template <int ROWS, bool KC, int BK>
 __device__ __forceinline__ pm_bf16x8 pm_read_frag(const bf16_t* s, int row, int kbase) {
-  using S = PmTileShape<ROWS, KC>;
+  using S = PmTileShape<ROWS, KC, BK>;
   if (KC) {
     return *reinterpret_cast<const pm_bf16x8*>(s + row * S::stride + kbase);
   } else {
@@ -89,25 +94,46 @@ __device__ __forceinline__ pm_bf16x8 pm_read_frag(const bf16_t* s, int row, int 
   }
 }
 
-template <int BI, int BJ, int WI, int WJ, int WK, bool AKC, bool BKC, class Epi>
-__global__ __launch_bounds__(WI * WJ * WK * 64) void pm_gemm_mfma_kernel(int I, int J, int K,
-                                                                         const bf16_t* __restrict__ A, int64_t lda,
-                                                                         PmWLoc<bf16_t> bloc, int64_t ldb, Epi epi) {
-  constexpr int NT = WI * WJ * WK * 64;
+template <class Epi>
+struct PmGemmProb {
+  int I, J, K;
+  const bf16_t* A;
+  int64_t lda;
+  PmWLoc<bf16_t> B;
+  int64_t ldb;
+  Epi epi;
+};
+
+template <int BI_, int BJ_, int WI_, int WJ_, int WK_, int BK_>
+struct PmGemmCfg {
+  static constexpr int BI = BI_, BJ = BJ_, WI = WI_, WJ = WJ_, WK = WK_, BK = BK_;
+  static constexpr int NT = WI * WJ * WK * 64;
+};
+
+template <class Cfg, bool AKC, bool BKC>
+struct PmGemmLds {
+  using SA = PmTileShape<Cfg::BI, AKC, Cfg::BK>;
+  using SB = PmTileShape<Cfg::BJ, BKC, Cfg::BK>;
+  static constexpr int ab = (SA::elems + SB::elems) * 2;
+  static constexpr int red = Cfg::WK > 1 ? Cfg::WK * Cfg::BI * Cfg::BJ * 4 : 0;
+  static constexpr int bytes = ab > red ? ab : red;
+};
+
+template <class Cfg, bool AKC, bool BKC, class Epi>
+__device__ __forceinline__ void pm_gemm_body(const PmGemmProb<Epi>& pr, Epi epi, int bx, int by, unsigned char* smem) {
+  constexpr int BI = Cfg::BI, BJ = Cfg::BJ, WI = Cfg::WI, WJ = Cfg::WJ, WK = Cfg::WK, BK = Cfg::BK, NT = Cfg::NT;
   constexpr int TI = BI / WI / 32, TJ = BJ / WJ / 32;     // 32x32 MFMA tiles per wave
-  constexpr int KS = PM_BK / 16 / WK;                     // k-steps of 16 per wave per slab
-  static_assert(BI % (WI * 32) == 0 && BJ % (WJ * 32) == 0 && (PM_BK / 16) % WK == 0, "tile shape");
-  using SA = PmTileShape<BI, AKC>;
-  using SB = PmTileShape<BJ, BKC>;
-  constexpr int LDS_AB = (SA::elems + SB::elems) * 2;
-  constexpr int LDS_RED = WK > 1 ? WK * WI * WJ * TI * TJ * 1024 * 4 : 0;
-  constexpr int LDS_BYTES = LDS_AB > LDS_RED ? LDS_AB : LDS_RED;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
+  constexpr int KS = BK / 16 / WK;                        // k-steps of 16 per wave per slab
+  static_assert(BI % (WI * 32) == 0 && BJ % (WJ * 32) == 0 && (BK / 16) % WK == 0, "tile shape");
+  using SA = PmTileShape<BI, AKC, BK>;
+  const int I = pr.I, J = pr.J, K = pr.K;
+  const int i0 = by * BI, j0 = bx * BJ;
+  if (i0 >= I || j0 >= J) return;                         // grouped launch: grid sized for the largest problem
   bf16_t* sA = reinterpret_cast<bf16_t*>(smem);
   bf16_t* sB = sA + SA::elems;
-
-  const bf16_t* __restrict__ B = bloc.get();
-  const int i0 = blockIdx.y * BI, j0 = blockIdx.x * BJ;
+  const bf16_t* __restrict__ A = pr.A;
+  const bf16_t* __restrict__ B = pr.B.get();
+  const int64_t lda = pr.lda, ldb = pr.ldb;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wk = wave % WK, wj = (wave / WK) % WJ, wi = wave / (WK * WJ);
   const int lr = lane & 31, kg = lane >> 5;
@@ -119,10 +145,12 @@ __global__ __launch_bounds__(WI * WJ * WK * 64) void pm_gemm_mfma_kernel(int I, 
     for (int b = 0; b < TJ; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+  float colsum = 0.f;                                     // bias gradient (weight-gradient epilogue only)
+  const bool do_colsum = Epi::kColSumA && !AKC && bx == 0 && epi.wants_colsum();
 
-  PmTileLoader<BI, AKC, NT> la;
-  PmTileLoader<BJ, BKC, NT> lb;
-  const int nk = (K + PM_BK - 1) / PM_BK;
+  PmTileLoader<BI, AKC, BK, NT> la;
+  PmTileLoader<BJ, BKC, BK, NT> lb;
+  const int nk = (K + BK - 1) / BK;
   la.load(A, lda, i0, 0, I, K);
   lb.load(B, ldb, j0, 0, J, K);
   for (int kt = 0; kt < nk; ++kt) {
@@ -130,17 +158,23 @@ __global__ __launch_bounds__(WI * WJ * WK * 64) void pm_gemm_mfma_kernel(int I, 
     lb.store(sB);
     __syncthreads();
     if (kt + 1 < nk) {
-      la.load(A, lda, i0, (kt + 1) * PM_BK, I, K);
-      lb.load(B, ldb, j0, (kt + 1) * PM_BK, J, K);
+      la.load(A, lda, i0, (kt + 1) * BK, I, K);
+      lb.load(B, ldb, j0, (kt + 1) * BK, J, K);
+    }
+    if (Epi::kColSumA && !AKC) {
+      if (do_colsum && threadIdx.x < BI) {
+#pragma unroll 8
+        for (int k = 0; k < BK; ++k) colsum += bf16_to_f32(sA[k * SA::stride + threadIdx.x]);
+      }
     }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const int kbase = (wk * KS + ks) * 16 + kg * 8;
       pm_bf16x8 fa[TI], fb[TJ];
 #pragma unroll
-      for (int a = 0; a < TI; ++a) fa[a] = pm_read_frag<BI, AKC>(sA, (wi * TI + a) * 32 + lr, kbase);
+      for (int a = 0; a < TI; ++a) fa[a] = pm_read_frag<BI, AKC, BK>(sA, (wi * TI + a) * 32 + lr, kbase);
 #pragma unroll
-      for (int b = 0; b < TJ; ++b) fb[b] = pm_read_frag<BJ, BKC>(sB, (wj * TJ + b) * 32 + lr, kbase);
+      for (int b = 0; b < TJ; ++b) fb[b] = pm_read_frag<BJ, BKC, BK>(sB, (wj * TJ + b) * 32 + lr, kbase);
 #pragma unroll
       for (int a = 0; a < TI; ++a)
 #pragma unroll
@@ -151,6 +185,9 @@ __global__ __launch_bounds__(WI * WJ * WK * 64) void pm_gemm_mfma_kernel(int I, 
   }
 
   epi.begin();
+  if (Epi::kColSumA && !AKC) {
+    if (do_colsum && threadIdx.x < BI && i0 + (int)threadIdx.x < I) epi.colsum(i0 + threadIdx.x, colsum);
+  }
   if (WK == 1) {
     // accumulator layout of the 32x32 tile: value v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32
 #pragma unroll
@@ -188,42 +225,75 @@ __global__ __launch_bounds__(WI * WJ * WK * 64) void pm_gemm_mfma_kernel(int I, 
   }
 }
 
-template <int BI, int BJ, int WI, int WJ, int WK, bool AKC, bool BKC, class Epi>
-inline void pm_mfma_launch(hipStream_t st, int I, int J, int K, const bf16_t* A, int64_t lda, PmWLoc<bf16_t> B,
-                           int64_t ldb, const Epi& epi) {
-  dim3 grid((J + BJ - 1) / BJ, (I + BI - 1) / BI);
-  hipLaunchKernelGGL((pm_gemm_mfma_kernel<BI, BJ, WI, WJ, WK, AKC, BKC, Epi>), grid, dim3(WI * WJ * WK * 64), 0, st, I,
-                     J, K, A, lda, B, ldb, epi);
+// one problem, passed by value
+template <class Cfg, bool AKC, bool BKC, class Epi>
+__global__ __launch_bounds__(Cfg::NT) void pm_gemm_mfma_kernel(PmGemmProb<Epi> pr) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[PmGemmLds<Cfg, AKC, BKC>::bytes];
+  pm_gemm_body<Cfg, AKC, BKC, Epi>(pr, pr.epi, blockIdx.x, blockIdx.y, smem);
 }
+
+// a table of problems in device memory, one per blockIdx.z
+template <class Cfg, bool AKC, bool BKC, class Epi>
+__global__ __launch_bounds__(Cfg::NT) void pm_gemm_mfma_grouped_kernel(const PmGemmProb<Epi>* __restrict__ probs) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[PmGemmLds<Cfg, AKC, BKC>::bytes];
+  const PmGemmProb<Epi>& pr = probs[blockIdx.z];
+  pm_gemm_body<Cfg, AKC, BKC, Epi>(pr, pr.epi, blockIdx.x, blockIdx.y, smem);
+}
+
+template <class Cfg, bool AKC, bool BKC, class Epi>
+inline void pm_mfma_launch(hipStream_t st, const PmGemmProb<Epi>& pr) {
+  dim3 grid((pr.J + Cfg::BJ - 1) / Cfg::BJ, (pr.I + Cfg::BI - 1) / Cfg::BI);
+  hipLaunchKernelGGL((pm_gemm_mfma_kernel<Cfg, AKC, BKC, Epi>), grid, dim3(Cfg::NT), 0, st, pr);
+}
+
+using PmCfgBig = PmGemmCfg<128, 128, 2, 2, 1, 64>;      // MFMA-bound shapes
+using PmCfgMid = PmGemmCfg<64, 64, 2, 2, 1, 64>;
+using PmCfgShortK = PmGemmCfg<64, 64, 2, 2, 1, 128>;    // K <= 128 (weight gradient of a small microbatch): one slab
+// few output tiles, long K: bound by memory latency, so the slab is as deep as registers and LDS
+// allow (all loads of up to 1024 k in flight at once: 128 staging VGPRs, 132 KB LDS, one block per CU)
+using PmCfgSkinny256 = PmGemmCfg<32, 32, 1, 1, 4, 256>;
+using PmCfgSkinny512 = PmGemmCfg<32, 32, 1, 1, 4, 512>;
+using PmCfgSkinny1K = PmGemmCfg<32, 32, 1, 1, 4, 1024>;
 
 template <bool AKC, bool BKC, class Epi>
-inline void pm_mfma_pick(hipStream_t st, int I, int J, int K, const bf16_t* A, int64_t lda, PmWLoc<bf16_t> B,
-                         int64_t ldb, const Epi& epi) {
-  const long tiles128 = (long)((I + 127) / 128) * ((J + 127) / 128);
-  const long tiles64 = (long)((I + 63) / 64) * ((J + 63) / 64);
-  if (tiles128 >= 512) pm_mfma_launch<128, 128, 2, 2, 1, AKC, BKC>(st, I, J, K, A, lda, B, ldb, epi);
-  else if (tiles64 >= 192 || K <= 256) pm_mfma_launch<64, 64, 2, 2, 1, AKC, BKC>(st, I, J, K, A, lda, B, ldb, epi);
-  else pm_mfma_launch<32, 32, 1, 1, 4, AKC, BKC>(st, I, J, K, A, lda, B, ldb, epi);
+inline void pm_mfma_pick(hipStream_t st, const PmGemmProb<Epi>& pr) {
+  const long tiles128 = (long)((pr.I + 127) / 128) * ((pr.J + 127) / 128);
+  const long tiles64 = (long)((pr.I + 63) / 64) * ((pr.J + 63) / 64);
+  if (tiles128 >= 512) pm_mfma_launch<PmCfgBig, AKC, BKC>(st, pr);
+  else if (pr.K <= 128) pm_mfma_launch<PmCfgShortK, AKC, BKC>(st, pr);
+  else if (tiles64 >= 192 || pr.K <= 256) pm_mfma_launch<PmCfgMid, AKC, BKC>(st, pr);
+  else if (pr.K >= 768) pm_mfma_launch<PmCfgSkinny1K, AKC, BKC>(st, pr);
+  else if (pr.K >= 384) pm_mfma_launch<PmCfgSkinny512, AKC, BKC>(st, pr);
+  else pm_mfma_launch<PmCfgSkinny256, AKC, BKC>(st, pr);
 }
 
-// Try to run the product on MFMA.  Strides are in elements; exactly one of (sxr, sxk) must be 1
-// per operand.  Returns false (nothing launched) when the alignment rules do not fit, in which
-// case the caller uses the plain kernel.
-template <class Epi>
-inline bool pm_mfma_gemm_try(hipStream_t st, int I, int J, int K, const bf16_t* A, int64_t sai, int64_t sak,
-                             PmWLoc<bf16_t> B, int64_t sbj, int64_t sbk, const Epi& epi) {
+// Alignment rules of the MFMA path for one problem given element strides (exactly one of
+// (sxr, sxk) must be 1 per operand).
+inline bool pm_mfma_fits(int I, int J, int K, const void* A, int64_t sai, int64_t sak, const void* Bbase, int64_t Bstride,
+                         int64_t sbj, int64_t sbk) {
   const bool akc = sak == 1, bkc = sbk == 1;
   if (!akc && sai != 1) return false;
   if (!bkc && sbj != 1) return false;
   const int64_t lda = akc ? sai : sak, ldb = bkc ? sbj : sbk;
-  if ((lda & 7) || (ldb & 7) || (B.stride & 7)) return false;
-  if (((uintptr_t)A & 15) || ((uintptr_t)B.base & 15)) return false;
+  if ((lda & 7) || (ldb & 7) || (Bstride & 7)) return false;
+  if (((uintptr_t)A & 15) || ((uintptr_t)Bbase & 15)) return false;
   // the contiguous index is read in whole groups of 8: the row must be that long
   if (lda < ((akc ? K : I) + 7) / 8 * 8) return false;
   if (ldb < ((bkc ? K : J) + 7) / 8 * 8) return false;
-  if (akc && bkc) pm_mfma_pick<true, true>(st, I, J, K, A, lda, B, ldb, epi);
-  else if (akc && !bkc) pm_mfma_pick<true, false>(st, I, J, K, A, lda, B, ldb, epi);
-  else if (!akc && bkc) pm_mfma_pick<false, true>(st, I, J, K, A, lda, B, ldb, epi);
-  else pm_mfma_pick<false, false>(st, I, J, K, A, lda, B, ldb, epi);
+  return true;
+}
+
+// Try to run the product on MFMA.  Returns false (nothing launched) when the alignment rules do
+// not fit, in which case the caller uses the plain kernel.
+template <class Epi>
+inline bool pm_mfma_gemm_try(hipStream_t st, int I, int J, int K, const bf16_t* A, int64_t sai, int64_t sak,
+                             PmWLoc<bf16_t> B, int64_t sbj, int64_t sbk, const Epi& epi) {
+  if (!pm_mfma_fits(I, J, K, A, sai, sak, B.base, B.stride, sbj, sbk)) return false;
+  const bool akc = sak == 1, bkc = sbk == 1;
+  PmGemmProb<Epi> pr{I, J, K, A, akc ? sai : sak, B, bkc ? sbj : sbk, epi};
+  if (akc && bkc) pm_mfma_pick<true, true>(st, pr);
+  else if (akc && !bkc) pm_mfma_pick<true, false>(st, pr);
+  else if (!akc && bkc) pm_mfma_pick<false, true>(st, pr);
+  else pm_mfma_pick<false, false>(st, pr);
   return true;
 }

@@ -8,8 +8,8 @@
 // to 0 during pipeline fill) and the rescheduled step size (Sec. 3.1, T1), then advances t.
 // A single block so that the counter update is ordered after every table entry.
 // ---------------------------------------------------------------------------------------------
-__global__ void pm_prologue_kernel(PmStepHdr* hdr, const PmLayerStatic* ls, PmLayerStep* ld, int L,
-                                   PmSchedDev sc) {
+__device__ __forceinline__ void pm_prologue_block(PmStepHdr* hdr, const PmLayerStatic* ls, PmLayerStep* ld, int L,
+                                                  const PmSchedDev& sc) {
   const long long t = hdr->t_next;
   double a_base;
   if (sc.kind == 0) {
@@ -55,7 +55,27 @@ __global__ void pm_prologue_kernel(PmStepHdr* hdr, const PmLayerStatic* ls, PmLa
   }
 }
 
-__global__ void pm_zero_loss_kernel(PmStepHdr* hdr) { hdr->loss = 0.f; }
+__global__ void pm_prologue_kernel(PmStepHdr* hdr, const PmLayerStatic* ls, PmLayerStep* ld, int L, PmSchedDev sc) {
+  pm_prologue_block(hdr, ls, ld, L, sc);
+}
+
+// First kernel of every microbatch: stages the fp32 input batch into the compute dtype (pad columns
+// zero), clears the loss accumulator, and - in block 0, when L > 0, i.e. at the start of a
+// minibatch - refreshes the step table (so the step costs one launch less).
+template <typename T>
+__global__ __launch_bounds__(256) void pm_begin_step_kernel(const float* __restrict__ x, T* __restrict__ out, int M,
+                                                            int n, int ld_x, PmStepHdr* hdr, const PmLayerStatic* ls,
+                                                            PmLayerStep* ld, int L, PmSchedDev sc) {
+  if (blockIdx.x == 0) {
+    if (L > 0) pm_prologue_block(hdr, ls, ld, L, sc);
+    if (threadIdx.x == 0) hdr->loss = 0.f;
+  }
+  const int64_t total = (int64_t)M * ld_x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int m = (int)(i / ld_x), c = (int)(i % ld_x);
+    stf(out + i, c < n ? x[(int64_t)m * n + c] : 0.f);
+  }
+}
 
 // ---------------------------------------------------------------------------------------------
 // Sum of squares over a flat fp32 array (global gradient norm for clipping, parameter norm for
