@@ -256,7 +256,11 @@ using PmCfgSkinny512 = PmGemmCfg<32, 32, 1, 1, 4, 512>;
 using PmCfgSkinny1K = PmGemmCfg<32, 32, 1, 1, 4, 1024>;
 
 template <bool AKC, bool BKC, class Epi>
+inline bool pm_big_try(hipStream_t st, const PmGemmProb<Epi>& pr);
+
+template <bool AKC, bool BKC, class Epi>
 inline void pm_mfma_pick(hipStream_t st, const PmGemmProb<Epi>& pr) {
+  if (pm_big_try<AKC, BKC>(st, pr)) return;
   const long tiles128 = (long)((pr.I + 127) / 128) * ((pr.J + 127) / 128);
   const long tiles64 = (long)((pr.I + 63) / 64) * ((pr.J + 63) / 64);
   if (tiles128 >= 512) pm_mfma_launch<PmCfgBig, AKC, BKC>(st, pr);
@@ -295,5 +299,230 @@ inline bool pm_mfma_gemm_try(hipStream_t st, int I, int J, int K, const bf16_t* 
   else if (akc && !bkc) pm_mfma_pick<true, false>(st, pr);
   else if (!akc && bkc) pm_mfma_pick<false, true>(st, pr);
   else pm_mfma_pick<false, false>(st, pr);
+  return true;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Large problems (MFMA bound): big block tiles, double-buffered LDS (one barrier per 64-deep slab,
+// the next slab's global loads in flight during the MFMAs), RC operands read with the gfx950 LDS
+// transpose load (ds_read_b64_tr_b16: two instructions per fragment instead of eight 2-byte
+// reads), XCD-aware block -> tile mapping so that tiles sharing operand panels share an L2.
+// ---------------------------------------------------------------------------------------------
+typedef short pm_v4s __attribute__((ext_vector_type(4)));
+
+template <int ROWS, bool KC>
+struct PmBigTile {                         // (ROWS x 64) operand slab in LDS
+  static constexpr int BK = 64;
+  static constexpr int lds_rows = KC ? ROWS : BK;
+  static constexpr int lds_cols = KC ? BK : ROWS;
+  // KC: 16-byte fragment reads of 16 lanes cover all banks once with an 8-element pad.
+  // RC: transpose reads touch 4 consecutive k-rows x 64 bytes; a row stride of 16 words mod 64 keeps them apart.
+  static constexpr int stride = KC ? BK + 8 : ROWS + 32;
+  static constexpr int elems = lds_rows * stride;
+  static constexpr int chunks = lds_rows * lds_cols / 8;
+};
+
+template <int ROWS, bool KC, int NT>
+struct PmBigLoader {
+  using S = PmBigTile<ROWS, KC>;
+  static_assert(S::chunks % NT == 0, "tile must split evenly over the block");
+  static constexpr int PER = S::chunks / NT;
+  uint4 r[PER];
+  __device__ __forceinline__ void load(const bf16_t* __restrict__ X, int64_t ld, int r0, int k0, int R, int K) {
+    const int R8 = (R + 7) & ~7, K8 = (K + 7) & ~7;
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      const int c = p * NT + threadIdx.x;
+      const int lr = c / (S::lds_cols / 8), lc = (c % (S::lds_cols / 8)) * 8;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (KC) {
+        const int row = r0 + lr, k = k0 + lc;
+        if (row < R && k < K8) v = *reinterpret_cast<const uint4*>(X + (int64_t)row * ld + k);
+      } else {
+        const int k = k0 + lr, row = r0 + lc;
+        if (k < K && row < R8) v = *reinterpret_cast<const uint4*>(X + (int64_t)k * ld + row);
+      }
+      r[p] = v;
+    }
+  }
+  __device__ __forceinline__ void store(bf16_t* s) const {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) store_part(s, p);
+  }
+  __device__ __forceinline__ void store_part(bf16_t* s, int p) const {
+    const int c = p * NT + threadIdx.x;
+    const int lr = c / (S::lds_cols / 8), lc = (c % (S::lds_cols / 8)) * 8;
+    *reinterpret_cast<uint4*>(s + lr * S::stride + lc) = r[p];
+  }
+};
+
+// fragment of the 32-row tile starting at tile row r32, contraction indices kb .. kb+15
+template <int ROWS, bool KC>
+__device__ __forceinline__ pm_bf16x8 pm_big_frag(const bf16_t* s, int r32, int kb, int lane) {
+  using S = PmBigTile<ROWS, KC>;
+  if (KC) {
+    return *reinterpret_cast<const pm_bf16x8*>(s + (r32 + (lane & 31)) * S::stride + kb + (lane >> 5) * 8);
+  } else {
+    // Transpose load: in each group of 16 lanes, lane q supplies the address of 4 consecutive
+    // elements (one k-row, 4 rows of the operand) and receives, for operand row (its index in the
+    // group), the elements of 4 consecutive k-rows.  Lane q of group g addresses
+    // k-row kb + 8*(g/2) + q/4, operand rows r32 + 16*(g%2) + 4*(q%4) .. +3.
+    const int g = lane >> 4, q = lane & 15;
+    const bf16_t* p = s + (kb + 8 * (g >> 1) + (q >> 2)) * S::stride + r32 + 16 * (g & 1) + 4 * (q & 3);
+    typedef pm_v4s __attribute__((address_space(3))) * lds_v4s;
+    const pm_v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p));
+    const pm_v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p + 4 * S::stride));
+    union { pm_bf16x8 v; pm_v4s h[2]; } u;
+    u.h[0] = lo;
+    u.h[1] = hi;
+    return u.v;
+  }
+}
+
+template <int BI_, int BJ_, int WI_, int WJ_>
+struct PmBigCfg {
+  static constexpr int BI = BI_, BJ = BJ_, WI = WI_, WJ = WJ_, NT = WI_ * WJ_ * 64;
+  // waves per SIMD the register budget is sized for: the 128 x 128 wave tile holds 256 accumulator
+  // registers and needs the whole 512-entry file (its LDS footprint allows one block per CU anyway)
+  static constexpr int WPE = (BI_ / WI_) * (BJ_ / WJ_) >= 128 * 128 ? 1 : 2;
+};
+
+template <class Cfg, bool AKC, bool BKC, class Epi>
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(1, Cfg::WPE))) void pm_gemm_big_kernel(PmGemmProb<Epi> pr, int tiles_i, int tiles_j) {
+  constexpr int BI = Cfg::BI, BJ = Cfg::BJ, WI = Cfg::WI, WJ = Cfg::WJ, NT = Cfg::NT, BK = 64;
+  constexpr int TI = BI / WI / 32, TJ = BJ / WJ / 32;
+  using SA = PmBigTile<BI, AKC>;
+  using SB = PmBigTile<BJ, BKC>;
+  __shared__ __attribute__((aligned(16))) bf16_t smem[2 * (SA::elems + SB::elems)];
+  constexpr int STAGE = SA::elems + SB::elems;      // stage s: A at s*STAGE, B at s*STAGE + SA::elems
+
+  // XCD-aware mapping: consecutive block ids land on consecutive XCDs (8 of them), so give each
+  // XCD a contiguous range of tiles, and inside it walk the tiles in column panels of 8 row tiles.
+  int id = blockIdx.x;
+  const int nblk = tiles_i * tiles_j;
+  if ((nblk & 7) == 0) id = (id & 7) * (nblk >> 3) + (id >> 3);
+  constexpr int GROUP = 8;
+  const int panel = id / (GROUP * tiles_j);
+  const int first_i = panel * GROUP;
+  const int rows_in_panel = (tiles_i - first_i) < GROUP ? (tiles_i - first_i) : GROUP;
+  const int by = first_i + (id % (GROUP * tiles_j)) % rows_in_panel;
+  const int bx = (id % (GROUP * tiles_j)) / rows_in_panel;
+
+  const int I = pr.I, J = pr.J, K = pr.K;
+  const int i0 = by * BI, j0 = bx * BJ;
+  const bf16_t* __restrict__ A = pr.A;
+  const bf16_t* __restrict__ B = pr.B.get();
+  const int64_t lda = pr.lda, ldb = pr.ldb;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wj = wave % WJ, wi = wave / WJ;
+  const int lr = lane & 31, kg = lane >> 5;
+
+  pm_f32x16 acc[TI][TJ];
+#pragma unroll
+  for (int a = 0; a < TI; ++a)
+#pragma unroll
+    for (int b = 0; b < TJ; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+  Epi epi = pr.epi;
+  float colsum = 0.f;
+  const bool do_colsum = Epi::kColSumA && !AKC && bx == 0 && epi.wants_colsum();
+
+  using LA = PmBigLoader<BI, AKC, NT>;
+  using LB = PmBigLoader<BJ, BKC, NT>;
+  constexpr int QA = (LA::PER + 3) / 4, QB = (LB::PER + 3) / 4;
+  LA la;
+  LB lb;
+  const int nk = (K + BK - 1) / BK;
+  la.load(A, lda, i0, 0, I, K);
+  lb.load(B, ldb, j0, 0, J, K);
+  la.store(smem);
+  lb.store(smem + SA::elems);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    const bf16_t* cA = smem + cur * STAGE;
+    const bf16_t* cB = cA + SA::elems;
+    if (kt + 1 < nk) {
+      la.load(A, lda, i0, (kt + 1) * BK, I, K);
+      lb.load(B, ldb, j0, (kt + 1) * BK, J, K);
+    }
+    if (Epi::kColSumA && !AKC) {
+      if (do_colsum && threadIdx.x < BI) {
+#pragma unroll 8
+        for (int k = 0; k < BK; ++k) colsum += bf16_to_f32(cA[k * SA::stride + threadIdx.x]);
+      }
+    }
+    // fragments are double-buffered in registers: the LDS reads of k-step ks+1 are in flight
+    // while the MFMAs of k-step ks issue
+    pm_bf16x8 fa[2][TI], fb[2][TJ];
+#pragma unroll
+    for (int a = 0; a < TI; ++a) fa[0][a] = pm_big_frag<BI, AKC>(cA, (wi * TI + a) * 32, 0, lane);
+#pragma unroll
+    for (int b = 0; b < TJ; ++b) fb[0][b] = pm_big_frag<BJ, BKC>(cB, (wj * TJ + b) * 32, 0, lane);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      const int c = ks & 1, n = c ^ 1;
+      if (ks + 1 < BK / 16) {
+#pragma unroll
+        for (int a = 0; a < TI; ++a) fa[n][a] = pm_big_frag<BI, AKC>(cA, (wi * TI + a) * 32, (ks + 1) * 16, lane);
+#pragma unroll
+        for (int b = 0; b < TJ; ++b) fb[n][b] = pm_big_frag<BJ, BKC>(cB, (wj * TJ + b) * 32, (ks + 1) * 16, lane);
+      }
+#pragma unroll
+      for (int a = 0; a < TI; ++a)
+#pragma unroll
+        for (int b = 0; b < TJ; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][a], fb[c][b], acc[a][b], 0, 0, 0);
+      // a quarter of the staged next slab goes to the other LDS stage behind each k-step's MFMAs
+      if (kt + 1 < nk) {
+        if (ks * QA < LA::PER) {
+#pragma unroll
+          for (int q = 0; q < QA; ++q)
+            if (ks * QA + q < LA::PER) la.store_part(smem + (cur ^ 1) * STAGE, ks * QA + q);
+        }
+        if (ks * QB < LB::PER) {
+#pragma unroll
+          for (int q = 0; q < QB; ++q)
+            if (ks * QB + q < LB::PER) lb.store_part(smem + (cur ^ 1) * STAGE + SA::elems, ks * QB + q);
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  epi.begin();
+  if (Epi::kColSumA && !AKC) {
+    if (do_colsum && threadIdx.x < BI && i0 + (int)threadIdx.x < I) epi.colsum(i0 + threadIdx.x, colsum);
+  }
+#pragma unroll
+  for (int a = 0; a < TI; ++a)
+#pragma unroll
+    for (int b = 0; b < TJ; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int i = i0 + (wi * TI + a) * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+        const int j = j0 + (wj * TJ + b) * 32 + lr;
+        if (i < I && j < J) epi(i, j, acc[a][b][v]);
+      }
+}
+
+// 128 x 128 block, 4 waves x (64 x 64): 80 KB of LDS, so two blocks share a CU and cover each
+// other's barriers.  Measured on 8192-row problems (K, N in {1024, 4096}) this beat 256 x 256
+// (8 waves x 128 x 64) and 256 x 128 (4 waves x 128 x 64) blocks in 7 of 9 shape / layout cases.
+using PmBig128 = PmBigCfg<128, 128, 2, 2>;
+
+template <class Cfg, bool AKC, bool BKC, class Epi>
+inline void pm_big_launch(hipStream_t st, const PmGemmProb<Epi>& pr) {
+  const int ti = (pr.I + Cfg::BI - 1) / Cfg::BI, tj = (pr.J + Cfg::BJ - 1) / Cfg::BJ;
+  hipLaunchKernelGGL((pm_gemm_big_kernel<Cfg, AKC, BKC, Epi>), dim3(ti * tj), dim3(Cfg::NT), 0, st, pr, ti, tj);
+}
+
+// true if the problem was large enough for (and was launched on) the big-tile kernel
+template <bool AKC, bool BKC, class Epi>
+inline bool pm_big_try(hipStream_t st, const PmGemmProb<Epi>& pr) {
+  const long tiles = (long)((pr.I + 127) / 128) * ((pr.J + 127) / 128);
+  if (pr.K < 256 || tiles < 200) return false;
+  pm_big_launch<PmBig128, AKC, BKC>(st, pr);
   return true;
 }

@@ -112,8 +112,7 @@ __global__ void pm_clip_scale_kernel(PmStepHdr* hdr, float clip) {
 //   ub <- round(base - (tau_fwd,i - tau_bkwd,i) delta_new)            (Sec. 3.2, corrected backward weights
 //        of the NEXT step; base = w_new when tau_bkwd = 0, else the stored version t+1-tau_bkwd)
 // Each block owns PM_CHUNK consecutive elements, all of one unit (units are padded to the chunk),
-// so the per-unit scalars are wave-uniform; each thread owns 8 consecutive elements: two 16-byte
-// loads per fp32 stream, one 16-byte store per bf16 stream.
+// so the per-unit scalars are wave-uniform; each thread owns 2 x 4 elements (see PmAcc below).
 // ---------------------------------------------------------------------------------------------
 template <typename RT>
 struct PmUpdArgs {
@@ -156,25 +155,84 @@ __device__ __forceinline__ void pm_load8(const bf16_t* p, float* x) {
   x[6] = __uint_as_float(a.w << 16); x[7] = __uint_as_float(a.w & 0xffff0000u);
 }
 
-template <typename RT, int OPT>
+// Element access pattern of one thread inside its 2048-element chunk: two groups of 4 elements
+// 1024 apart, so every load / store instruction of a wave covers one dense 1 KB (fp32) or 512 B
+// (bf16) span.  VAR 1: ordinary accesses; VAR 2: non-temporal loads and stores.
+template <int VAR> struct PmAcc;
+template <bool NT> struct PmAccSplit {
+  static __device__ __forceinline__ int64_t base(int tid) { return tid * 4; }
+  typedef float __attribute__((ext_vector_type(4))) f4;
+  typedef unsigned int __attribute__((ext_vector_type(2))) u2;
+  static __device__ __forceinline__ float4 l4(const float4* p) {
+    if (!NT) return *p;
+    const f4 v = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+  }
+  static __device__ __forceinline__ void s4(float4* p, float4 v) {
+    if (!NT) { *p = v; return; }
+    f4 t; t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+    __builtin_nontemporal_store(t, reinterpret_cast<f4*>(p));
+  }
+  static __device__ __forceinline__ uint2 l2(const uint2* p) {
+    if (!NT) return *p;
+    const u2 v = __builtin_nontemporal_load(reinterpret_cast<const u2*>(p));
+    return make_uint2(v.x, v.y);
+  }
+  static __device__ __forceinline__ void s2(uint2* p, uint2 v) {
+    if (!NT) { *p = v; return; }
+    u2 t; t.x = v.x; t.y = v.y;
+    __builtin_nontemporal_store(t, reinterpret_cast<u2*>(p));
+  }
+  static __device__ __forceinline__ void ld(const float* p, float* x) {
+    const float4 a = l4(reinterpret_cast<const float4*>(p));
+    const float4 b = l4(reinterpret_cast<const float4*>(p + 1024));
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+  }
+  static __device__ __forceinline__ void ld(const bf16_t* p, float* x) {
+    const uint2 a = l2(reinterpret_cast<const uint2*>(p));
+    const uint2 b = l2(reinterpret_cast<const uint2*>(p + 1024));
+    x[0] = __uint_as_float(a.x << 16); x[1] = __uint_as_float(a.x & 0xffff0000u);
+    x[2] = __uint_as_float(a.y << 16); x[3] = __uint_as_float(a.y & 0xffff0000u);
+    x[4] = __uint_as_float(b.x << 16); x[5] = __uint_as_float(b.x & 0xffff0000u);
+    x[6] = __uint_as_float(b.y << 16); x[7] = __uint_as_float(b.y & 0xffff0000u);
+  }
+  static __device__ __forceinline__ void st(float* p, const float* x) {
+    s4(reinterpret_cast<float4*>(p), make_float4(x[0], x[1], x[2], x[3]));
+    s4(reinterpret_cast<float4*>(p + 1024), make_float4(x[4], x[5], x[6], x[7]));
+  }
+  static __device__ __forceinline__ void st(bf16_t* p, const float* x) {
+    uint2 a, b;
+    a.x = (uint32_t)f32_to_bf16(x[0]) | ((uint32_t)f32_to_bf16(x[1]) << 16);
+    a.y = (uint32_t)f32_to_bf16(x[2]) | ((uint32_t)f32_to_bf16(x[3]) << 16);
+    b.x = (uint32_t)f32_to_bf16(x[4]) | ((uint32_t)f32_to_bf16(x[5]) << 16);
+    b.y = (uint32_t)f32_to_bf16(x[6]) | ((uint32_t)f32_to_bf16(x[7]) << 16);
+    s2(reinterpret_cast<uint2*>(p), a);
+    s2(reinterpret_cast<uint2*>(p + 1024), b);
+  }
+};
+template <> struct PmAcc<1> : PmAccSplit<false> {};
+template <> struct PmAcc<2> : PmAccSplit<true> {};
+
+template <typename RT, int OPT, int VAR>
 __global__ __launch_bounds__(256) void pm_fused_update_kernel(PmUpdArgs<RT> a) {
+  using X = PmAcc<VAR>;
   const int c = blockIdx.x;
   const int l = a.chunk_layer[c];
   const PmLayerStatic S = a.ls[l];
   const PmLayerStep D = a.ld[l];
   const float lr = D.lr, gam = S.gamma, corr = S.corr;
   const float gs = a.hdr->gscale;
-  const int64_t e = (int64_t)c * PM_CHUNK + threadIdx.x * 8;
+  const int64_t e = (int64_t)c * PM_CHUNK + X::base(threadIdx.x);
   const int64_t rel = e - S.off;
 
   float g[8], w[8], v[8], d[8], s[8], wn[8], ubv[8];
-  pm_load8(a.g + e, g);
-  pm_load8(a.w + e, w);
-  pm_load8(a.v + e, v);
-  pm_load8(a.d + e, d);
-  if (OPT == 1) pm_load8(a.s + e, s);
+  X::ld(a.g + e, g);
+  X::ld(a.w + e, w);
+  X::ld(a.v + e, v);
+  X::ld(a.d + e, d);
+  if (OPT == 1) X::ld(a.s + e, s);
   const bool ub_from_ring = (corr != 0.f) && (S.tau_b > 0);
-  if (ub_from_ring) pm_load8(a.ring + S.ring_off + (int64_t)D.ub_slot * S.n_pad + rel, ubv);
+  if (ub_from_ring) X::ld(a.ring + S.ring_off + (int64_t)D.ub_slot * S.n_pad + rel, ubv);
 
   bool bad = false;
 #pragma unroll
@@ -196,15 +254,15 @@ __global__ __launch_bounds__(256) void pm_fused_update_kernel(PmUpdArgs<RT> a) {
     d[j] = gam * d[j] + (1.f - gam) * dw;
     bad |= !(fabsf(wn[j]) <= 3.0e38f);
   }
-  pm_store8(a.w + e, wn);
-  pm_store8(a.v + e, v);
-  pm_store8(a.d + e, d);
-  if (OPT == 1) pm_store8(a.s + e, s);
-  pm_store8(a.ring + S.ring_off + (int64_t)D.write_slot * S.n_pad + rel, wn);
+  X::st(a.w + e, wn);
+  X::st(a.v + e, v);
+  X::st(a.d + e, d);
+  if (OPT == 1) X::st(a.s + e, s);
+  X::st(a.ring + S.ring_off + (int64_t)D.write_slot * S.n_pad + rel, wn);
   if (corr != 0.f) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) ubv[j] = (ub_from_ring ? ubv[j] : wn[j]) - corr * d[j];
-    pm_store8(a.ub + e, ubv);
+    X::st(a.ub + e, ubv);
   }
   if (bad) a.hdr->diverged = 1;
 }

@@ -108,11 +108,14 @@ def test_update_chunk_boundaries_large_unit(torch_cuda):
 
 # ------------------------------------------------------------------------------- linear primitives
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("shape", [(128, 1024, 1024), (48, 72, 200), (300, 264, 136), (128, 1024, 16), (16, 64, 64)])
+@pytest.mark.parametrize("shape", [(128, 1024, 1024), (48, 72, 200), (300, 264, 136), (128, 1024, 16), (16, 64, 64),
+                                   (2048, 512, 2048), (4096, 1024, 4096), (4000, 1000, 4040), (8192, 512, 1024)])
 def test_linear_primitives_against_numpy(torch_cuda, dtype, shape):
     import paper_1910_05124_amd as pm
     torch = torch_cuda
     M, n_in, n_out = shape
+    if dtype == "f32" and M * n_in * n_out > 1 << 28:
+        pytest.skip("fp32 contexts use the plain kernel, meant for tiny layers")
     rng = np.random.default_rng(M + n_in)
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
 
