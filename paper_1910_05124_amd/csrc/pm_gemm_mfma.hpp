@@ -236,7 +236,7 @@ __global__ __launch_bounds__(Cfg::NT) void pm_gemm_mfma_kernel(PmGemmProb<Epi> p
 template <class Cfg, bool AKC, bool BKC, class Epi>
 __global__ __launch_bounds__(Cfg::NT) void pm_gemm_mfma_grouped_kernel(const PmGemmProb<Epi>* __restrict__ probs) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[PmGemmLds<Cfg, AKC, BKC>::bytes];
-  const PmGemmProb<Epi>& pr = probs[blockIdx.z];
+  const PmGemmProb<Epi> pr = probs[blockIdx.z];   // by value: the fields become wave-uniform registers
   pm_gemm_body<Cfg, AKC, BKC, Epi>(pr, pr.epi, blockIdx.x, blockIdx.y, smem);
 }
 
