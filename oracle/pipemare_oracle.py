@@ -233,7 +233,10 @@ class PipeMareOracle:
     tau_fwd/bkwd   per-stage delays, index i-1 for stage i
     opt            dict: kind "sgdm" | "adamw"; beta (sgdm); beta1, beta2, eps (adamw);
                    weight_decay; clip_norm (0 = off); D; gamma_override (list per stage or None);
-                   K; t1 (bool); t2 (bool); sched (dict for base_lr); N (microbatches)
+                   K; t1 (bool); t2 (bool); sched (dict for base_lr); N (microbatches);
+                   sync_warmup (int E_w >= 0): the first E_w steps run synchronously (all delays 0,
+                   base step size: "PipeMareW", Sec. 4), after which the delays apply and the T1
+                   counter starts at 0; delta keeps accumulating during the warm-up
     keep_history   True keeps every version; False drops versions no delay can reach any more
                    (still indexed by absolute version number).
     """
@@ -249,7 +252,7 @@ class PipeMareOracle:
                 raise ValueError("need 0 <= tau_bkwd <= tau_fwd")
         o = dict(kind="sgdm", beta=0.0, beta1=0.9, beta2=0.98, eps=1e-8, weight_decay=0.0,
                  clip_norm=0.0, D=1.0, gamma_override=None, K=0, t1=True, t2=True,
-                 sched=dict(kind="const", base=0.1), N=1)
+                 sched=dict(kind="const", base=0.1), N=1, sync_warmup=0)
         o.update(opt)
         self.opt = o
         self.keep_history = keep_history
@@ -277,8 +280,11 @@ class PipeMareOracle:
         return self.hist[u][self.t]
 
     def read_versions(self, t=None):
-        """(forward version, backward version) per unit at step t: max(t - tau, 0)."""
+        """(forward version, backward version) per unit at step t: max(t - tau, 0); the current
+        version t for both during the synchronous warm-up."""
         t = self.t if t is None else t
+        if t < self.opt["sync_warmup"]:
+            return [(t, t)] * self.U
         return [(max(t - self._tf(u), 0), max(t - self._tb(u), 0)) for u in range(self.U)]
 
     # -- one optimizer step
@@ -286,6 +292,7 @@ class PipeMareOracle:
         """One minibatch.  `batch` is a single microbatch, or a list of N microbatches whose
         gradients are averaged (all computed with the same delayed weights, Sec. 2.1)."""
         o, t = self.opt, self.t
+        warm = t < o["sync_warmup"]
         vers = self.read_versions(t)
         self.last_versions = vers
         u_fwd = [self.hist[u][vers[u][0]] for u in range(self.U)]
@@ -293,7 +300,7 @@ class PipeMareOracle:
         for u in range(self.U):
             base = self.hist[u][vers[u][1]]
             d = self._tf(u) - self._tb(u)
-            if o["t2"] and d > 0:
+            if o["t2"] and d > 0 and not warm:
                 base = base - d * self.delta[u]
             u_bkwd.append(base)
 
@@ -313,7 +320,7 @@ class PipeMareOracle:
         a_base = base_lr(o["sched"], t)
         for u in range(self.U):
             w = self.hist[u][t]
-            lr = t1_lr(a_base, self._tf(u), t, o["K"]) if o["t1"] else a_base
+            lr = t1_lr(a_base, self._tf(u), t - o["sync_warmup"], o["K"]) if (o["t1"] and not warm) else a_base
             self.last_lr[u] = lr
             g = grads[u]
             if o["kind"] == "sgdm":

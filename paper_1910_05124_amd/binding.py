@@ -58,7 +58,8 @@ class pm_opts(C.Structure):
                 ("weight_decay", C.c_double), ("clip_norm", C.c_double), ("D", C.c_double),
                 ("gamma_override", C.POINTER(C.c_double)), ("t1_enabled", C.c_int32),
                 ("t2_enabled", C.c_int32), ("n_microbatches", C.c_int32), ("dtype", C.c_int32),
-                ("loss", C.c_int32), ("microbatch", C.c_int32), ("use_graph", C.c_int32)]
+                ("loss", C.c_int32), ("microbatch", C.c_int32), ("use_graph", C.c_int32),
+                ("sync_warmup_steps", C.c_int64)]
 
 
 class PmError(RuntimeError):
@@ -229,9 +230,9 @@ def make_sched(kind="const", base=0.01, init=0.0, factor=1.0, interval=1, K=0) -
 
 def make_opts(opt="sgdm", beta1=0.9, beta2=0.98, eps=1e-8, weight_decay=0.0, clip_norm=0.0, D=1.0,
               gamma_override=None, t1=True, t2=True, N=1, dtype="f32", loss="mse", microbatch=1,
-              use_graph=False) -> pm_opts:
+              use_graph=False, sync_warmup=0) -> pm_opts:
     o = pm_opts(PM_OPT[opt], beta1, beta2, eps, weight_decay, clip_norm, D, None, int(t1), int(t2), N,
-                PM_DTYPE[dtype], PM_LOSS[loss], microbatch, int(use_graph))
+                PM_DTYPE[dtype], PM_LOSS[loss], microbatch, int(use_graph), int(sync_warmup))
     if gamma_override is not None:
         arr = (C.c_double * len(gamma_override))(*gamma_override)
         o._keep = arr

@@ -75,6 +75,7 @@ pm_status validate(int32_t P, int32_t L, const pm_layer_desc* layers, const int3
   if (o->loss != PM_LOSS_MSE && o->loss != PM_LOSS_XENT) return fail(PM_EINVAL, "unknown loss");
   if (o->microbatch < 1 || o->n_microbatches < 1) return fail(PM_EINVAL, "microbatch and n_microbatches must be >= 1");
   if (!(o->D > 0.0 && o->D <= 1.0)) return fail(PM_EINVAL, "D must be in (0, 1]");
+  if (o->sync_warmup_steps < 0) return fail(PM_EINVAL, "sync_warmup_steps must be >= 0");
   if (o->clip_norm < 0.0 || o->weight_decay < 0.0) return fail(PM_EINVAL, "clip_norm and weight_decay must be >= 0");
   int prev_stage = 1;
   for (int l = 0; l < L; ++l) {
@@ -202,6 +203,7 @@ PmSchedDev sched_dev(const pm_ctx* c) {
   s.beta1 = c->o.beta1;
   s.beta2 = c->o.beta2;
   s.gscale0 = 1.0 / c->o.n_microbatches;
+  s.sync_warmup = c->o.sync_warmup_steps;
   return s;
 }
 

@@ -28,7 +28,8 @@ struct PmLayerStep {
   int32_t write_slot;  // (t + 1) mod R
   int32_t ub_slot;     // (max(t + 1 - tau_bkwd, 0)) mod R : base of the next corrected weights
   float lr;            // alpha_{t,i}
-  int32_t pad_[3];
+  float corr_next;     // T2 coefficient of the NEXT step's corrected weights (0 during synchronous warm-up)
+  int32_t pad_[2];
 };
 
 struct PmStepHdr {
@@ -50,6 +51,7 @@ struct PmSchedDev {
   int32_t t1_enabled;
   double beta1, beta2;
   double gscale0;      // 1 / N (mean over microbatches)
+  long long sync_warmup;  // E_w: steps t < E_w run with all delays 0 and the base step size
 };
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }

@@ -11,6 +11,9 @@
 __device__ __forceinline__ void pm_prologue_block(PmStepHdr* hdr, const PmLayerStatic* ls, PmLayerStep* ld, int L,
                                                   const PmSchedDev& sc) {
   const long long t = hdr->t_next;
+  const bool warm = t < sc.sync_warmup;            // synchronous warm-up (PipeMareW): no delays, no T1/T2
+  const bool warm_next = t + 1 < sc.sync_warmup;
+  const long long k = warm ? 0 : t - sc.sync_warmup;   // T1 counts from the switch
   double a_base;
   if (sc.kind == 0) {
     a_base = sc.base;
@@ -21,16 +24,17 @@ __device__ __forceinline__ void pm_prologue_block(PmStepHdr* hdr, const PmLayerS
     else a_base = t > 0 ? sc.base * sqrt((double)sc.interval / (double)t) : sc.base;
   }
   double p = 0.0;
-  if (sc.K > 0) {
-    double f = (double)t / (double)sc.K;
+  if (sc.K > 0 && !warm) {
+    double f = (double)k / (double)sc.K;
     p = 1.0 - (f < 1.0 ? f : 1.0);
   }
   for (int l = threadIdx.x; l < L; l += blockDim.x) {
     const PmLayerStatic S = ls[l];
     PmLayerStep D;
-    const long long vf = t - S.tau_f > 0 ? t - S.tau_f : 0;
-    const long long vb = t - S.tau_b > 0 ? t - S.tau_b : 0;
-    const long long vu = t + 1 - S.tau_b > 0 ? t + 1 - S.tau_b : 0;
+    const long long tf = warm ? 0 : S.tau_f, tb = warm ? 0 : S.tau_b, tbn = warm_next ? 0 : S.tau_b;
+    const long long vf = t - tf > 0 ? t - tf : 0;
+    const long long vb = t - tb > 0 ? t - tb : 0;
+    const long long vu = t + 1 - tbn > 0 ? t + 1 - tbn : 0;
     D.fwd_slot = (int32_t)(vf % S.R);
     D.bkwd_slot = (int32_t)(vb % S.R);
     D.write_slot = (int32_t)((t + 1) % S.R);
@@ -41,7 +45,8 @@ __device__ __forceinline__ void pm_prologue_block(PmStepHdr* hdr, const PmLayerS
       lr = a_base / pow((double)tau, p);
     }
     D.lr = (float)lr;
-    D.pad_[0] = D.pad_[1] = D.pad_[2] = 0;
+    D.corr_next = warm_next ? 0.f : S.corr;
+    D.pad_[0] = D.pad_[1] = 0;
     ld[l] = D;
   }
   __syncthreads();
@@ -220,7 +225,10 @@ __global__ __launch_bounds__(256) void pm_fused_update_kernel(PmUpdArgs<RT> a) {
   const int l = a.chunk_layer[c];
   const PmLayerStatic S = a.ls[l];
   const PmLayerStep D = a.ld[l];
-  const float lr = D.lr, gam = S.gamma, corr = S.corr;
+  // S.corr != 0 says the backward reads the corrected buffer at all; D.corr_next is the coefficient
+  // of the step that will read it (0 while that step is still in the synchronous warm-up)
+  const float lr = D.lr, gam = S.gamma, corr = D.corr_next;
+  const bool has_ub = S.corr != 0.f;
   const float gs = a.hdr->gscale;
   const int64_t e = (int64_t)c * PM_CHUNK + X::base(threadIdx.x);
   const int64_t rel = e - S.off;
@@ -259,7 +267,7 @@ __global__ __launch_bounds__(256) void pm_fused_update_kernel(PmUpdArgs<RT> a) {
   X::st(a.d + e, d);
   if (OPT == 1) X::st(a.s + e, s);
   X::st(a.ring + S.ring_off + (int64_t)D.write_slot * S.n_pad + rel, wn);
-  if (corr != 0.f) {
+  if (has_ub) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) ubv[j] = (ub_from_ring ? ubv[j] : wn[j]) - corr * d[j];
     X::st(a.ub + e, ubv);

@@ -173,11 +173,11 @@ def test_config0_fp32_mlp_50_steps(torch_cuda):
 
 
 @pytest.mark.parametrize("case", ["pipemare", "t2_off", "pipedream", "gpipe", "adamw_clip", "microbatches", "graph",
-                                  "gamma_override", "ragged_bf16"])
+                                  "gamma_override", "ragged_bf16", "sync_warmup", "sync_warmup_bf16"])
 def test_modes_small(torch_cuda, case):
     """Every mode of the step on a small MLP (several stages share units; odd widths hit the
     non-MFMA kernel, multiples of 8 the MFMA kernel)."""
-    dtype = "bf16" if case in ("ragged_bf16", "graph", "pipemare") else "f32"
+    dtype = "bf16" if case in ("ragged_bf16", "graph", "pipemare", "sync_warmup_bf16") else "f32"
     width = 72 if case != "ragged_bf16" else 50
     w = wl.small_mlp(width, 5, 6, "gelu", "xent", dtype, 24, layers_per_stage=2)
     # bf16 contexts: a smaller step keeps 14 steps of rounding noise (activations, ring and
@@ -199,6 +199,8 @@ def test_modes_small(torch_cuda, case):
         gpu_kw = dict(use_graph=True)
     elif case == "gamma_override":
         kw["gamma_override"] = [0.9, 0.8, 0.7]
+    elif case.startswith("sync_warmup"):
+        kw["sync_warmup"] = 5            # PipeMareW: 5 synchronous steps, then 9 asynchronous ones
     steps = 14
     if case == "graph":
         # a captured graph is bound to the batch buffers: feed every step through the same two tensors

@@ -460,3 +460,31 @@ def test_microbatch_accumulation_is_mean_gradient():
     o2.step((np.concatenate([x0, x1]), np.concatenate([y0, y1])))
     for u in range(len(params)):
         assert np.allclose(o.weights(u), o2.weights(u), rtol=0, atol=1e-15)
+
+
+def test_sync_warmup_then_switch():
+    """PipeMareW (Sec. 4): E_w synchronous steps equal a zero-delay run with T1/T2 off; afterwards the
+    delayed recurrence applies with the T1 counter restarted, reading versions produced during warm-up."""
+    w, params, stream = _mlp_setup("mse", "relu", width=8, depth=3, n_out=1, M=4)
+    tf, tb = po.pipeline_delays(w.P, 1)
+    stage = [L.stage for L in w.layers]
+    model = po.MLPModel(w.layers, w.loss)
+    Ew = 6
+    o = po.PipeMareOracle(model, params, stage, tf, tb, dict(sched=dict(kind="const", base=0.05), beta=0.9, K=5, D=0.5,
+                                                             sync_warmup=Ew), keep_history=True)
+    sync = po.PipeMareOracle(model, params, stage, [0] * w.P, [0] * w.P,
+                             dict(sched=dict(kind="const", base=0.05), beta=0.9, t1=False, t2=False), keep_history=True)
+    for k in range(Ew):
+        assert o.read_versions() == [(k, k)] * len(params)
+        o.step(stream.batch(k)); sync.step(stream.batch(k))
+        assert all(lr == 0.05 for lr in o.last_lr)
+    for u in range(len(params)):
+        assert np.array_equal(o.weights(u), sync.weights(u))
+    # first asynchronous step: delayed versions come from the warm-up history, T1 exponent is 1
+    assert o.read_versions() == [(max(Ew - tf[s - 1], 0), Ew) for s in stage]
+    o.step(stream.batch(Ew))
+    for u, s in enumerate(stage):
+        assert o.last_lr[u] == pytest.approx(0.05 / max(tf[s - 1], 1))
+    o.step(stream.batch(Ew + 1))
+    for u, s in enumerate(stage):
+        assert o.last_lr[u] == pytest.approx(0.05 / max(tf[s - 1], 1) ** (1 - 1 / 5))
