@@ -13,8 +13,10 @@
  *     GPU that was current when pm_create was called.
  *   - The library never allocates or frees device memory: the caller provides one arena
  *     (pm_query_bytes tells how large) and owns it, the HIP stream and the batch buffers.
- *   - All GPU work is enqueued on the stream given to pm_create.  Only pm_weights, pm_stats,
- *     pm_device_step_table, pm_set_grads and pm_step with a non-NULL loss pointer wait for it.
+ *   - All GPU work is enqueued on the stream given to pm_create (plus, with overlap_update, the
+ *     fused update on a second stream the library creates).  Only pm_weights, pm_state, pm_stats,
+ *     pm_device_step_table, pm_set_grads, pm_synchronize, pm_profile_end and pm_step with a
+ *     non-NULL loss pointer wait for it.
  *   - Errors are return codes (never exceptions, never abort); a NULL context gives PM_EINVAL.
  *   - A context is not re-entrant: one thread, one stream.
  */
@@ -92,6 +94,12 @@ typedef struct {
   int64_t sync_warmup_steps; /* E_w >= 0: the first E_w optimizer steps run synchronously (all delays 0,
                                 base step size, no correction: the warm-up of PipeMareW, Sec. 4), then
                                 the delays apply and the T1 step counter starts from 0 */
+  int32_t overlap_update;    /* 1: run the fused update of step t on a second stream owned by the library,
+                                concurrently with the forward of step t+1 (which, with tau_fwd >= 1
+                                everywhere, reads only versions <= t-1: the method's own asynchrony).
+                                Ignored with use_graph.  The caller's stream being idle then no longer
+                                implies the last update has finished: pm_synchronize or any read-back
+                                call waits for it. */
 } pm_opts;
 
 const char* pm_status_str(pm_status s);
@@ -193,6 +201,10 @@ pm_status pm_linear_bwd_data(void* stream, int32_t dtype, int32_t M, int32_t n_i
 pm_status pm_linear_bwd_weight(void* stream, int32_t dtype, int32_t M, int32_t n_in, int32_t n_out,
                                const void* dz_dev, const void* a_dev, float* dW_dev, float* db_dev,
                                int32_t accumulate);
+
+/* Waits for everything the context has enqueued, on the caller's stream and on the library's
+ * second stream (overlap_update). */
+pm_status pm_synchronize(pm_ctx* ctx);
 
 /* Frees host state only; the arena stays the caller's. */
 void pm_destroy(pm_ctx* ctx);

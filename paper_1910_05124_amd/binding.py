@@ -17,7 +17,8 @@ __all__ = [
     "lib", "PmError", "pm_layer_desc", "pm_lr_sched", "pm_opts",
     "pm_delays", "pm_slots", "pm_t1_lr", "pm_query_bytes", "pm_create", "pm_step", "pm_weights",
     "pm_state", "pm_device_step_table", "pm_stats", "pm_set_grads", "pm_apply_update", "pm_destroy",
-    "pm_linear_fwd", "pm_linear_bwd_data", "pm_linear_bwd_weight", "pm_profile_begin", "pm_profile_end", "PipeMare",
+    "pm_linear_fwd", "pm_linear_bwd_data", "pm_linear_bwd_weight", "pm_profile_begin", "pm_profile_end",
+    "pm_synchronize", "PipeMare",
     "PM_LINEAR", "PM_ACT", "PM_METHOD", "PM_LR", "PM_OPT", "PM_DTYPE", "PM_LOSS", "EXPORTS",
 ]
 
@@ -40,7 +41,7 @@ _STATUS = {0: "PM_OK", 1: "PM_EINVAL", 2: "PM_ENOMEM", 3: "PM_EHIP", 4: "PM_ESTA
 EXPORTS = ["pm_status_str", "pm_last_error", "pm_delays", "pm_slots", "pm_t1_lr", "pm_query_bytes",
            "pm_create", "pm_step", "pm_weights", "pm_state", "pm_device_step_table", "pm_stats",
            "pm_set_grads", "pm_apply_update", "pm_profile_begin", "pm_profile_end", "pm_linear_fwd", "pm_linear_bwd_data",
-           "pm_linear_bwd_weight", "pm_destroy"]
+           "pm_linear_bwd_weight", "pm_synchronize", "pm_destroy"]
 
 
 class pm_layer_desc(C.Structure):
@@ -59,7 +60,7 @@ class pm_opts(C.Structure):
                 ("gamma_override", C.POINTER(C.c_double)), ("t1_enabled", C.c_int32),
                 ("t2_enabled", C.c_int32), ("n_microbatches", C.c_int32), ("dtype", C.c_int32),
                 ("loss", C.c_int32), ("microbatch", C.c_int32), ("use_graph", C.c_int32),
-                ("sync_warmup_steps", C.c_int64)]
+                ("sync_warmup_steps", C.c_int64), ("overlap_update", C.c_int32)]
 
 
 class PmError(RuntimeError):
@@ -92,6 +93,7 @@ lib.pm_profile_end.argtypes = [_vp, C.POINTER(C.c_double), C.POINTER(C.c_double)
 lib.pm_linear_fwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _i32, _vp, _vp]
 lib.pm_linear_bwd_data.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _i32, _vp]
 lib.pm_linear_bwd_weight.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _i32]
+lib.pm_synchronize.argtypes = [_vp]
 lib.pm_destroy.argtypes = [_vp]
 lib.pm_destroy.restype = None
 for _n in EXPORTS:
@@ -208,6 +210,10 @@ def pm_profile_end(ctx: int):
     return dict(fwd_ms=f.value, bwd_ms=b.value, update_ms=u.value, n=n.value)
 
 
+def pm_synchronize(ctx: int):
+    _check(lib.pm_synchronize(ctx))
+
+
 def pm_destroy(ctx: int):
     lib.pm_destroy(ctx)
 
@@ -230,9 +236,9 @@ def make_sched(kind="const", base=0.01, init=0.0, factor=1.0, interval=1, K=0) -
 
 def make_opts(opt="sgdm", beta1=0.9, beta2=0.98, eps=1e-8, weight_decay=0.0, clip_norm=0.0, D=1.0,
               gamma_override=None, t1=True, t2=True, N=1, dtype="f32", loss="mse", microbatch=1,
-              use_graph=False, sync_warmup=0) -> pm_opts:
+              use_graph=False, sync_warmup=0, overlap_update=False) -> pm_opts:
     o = pm_opts(PM_OPT[opt], beta1, beta2, eps, weight_decay, clip_norm, D, None, int(t1), int(t2), N,
-                PM_DTYPE[dtype], PM_LOSS[loss], microbatch, int(use_graph), int(sync_warmup))
+                PM_DTYPE[dtype], PM_LOSS[loss], microbatch, int(use_graph), int(sync_warmup), int(overlap_update))
     if gamma_override is not None:
         arr = (C.c_double * len(gamma_override))(*gamma_override)
         o._keep = arr
@@ -282,6 +288,9 @@ class PipeMare:
 
     def step_table(self):
         return pm_device_step_table(self.ctx, self.L)
+
+    def synchronize(self):
+        pm_synchronize(self.ctx)
 
     def stats(self, param_norm=False):
         return pm_stats(self.ctx, param_norm)

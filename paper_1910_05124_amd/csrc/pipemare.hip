@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -137,7 +138,7 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
   lay.ring_off = take(lay.ring_elems * lay.esz);
   lay.chunk_off = take(lay.n_chunks * 4);
   lay.ls_off = take(sizeof(PmLayerStatic) * L);
-  lay.ld_off = take(sizeof(PmLayerStep) * L);
+  lay.ld_off = take(sizeof(PmLayerStep) * L * 2);
   lay.hdr_off = take(sizeof(PmStepHdr));
   lay.probs_off = take(sizeof(PmGemmProb<PmEpiBwdWeight>) * 2 * L);
   const int M = o->microbatch;
@@ -178,6 +179,13 @@ struct pm_ctx {
   // all weight-gradient products as one grouped MFMA launch (problem tables live in the arena)
   bool dw_grouped = false;
   int dw_maxI = 0, dw_maxJ = 0;
+  // overlap of the update of step t with the forward of step t+1 (second stream owned by the library)
+  bool overlap = false;
+  int32_t min_tau_f = 0;
+  hipStream_t stream_b = nullptr;
+  hipEvent_t ev_bwd = nullptr, ev_upd = nullptr;
+  bool upd_pending = false;    // an update is (possibly) still running on stream_b
+  int last_par = 0;            // step-table set used by the most recent step
   // optional per-phase timing (host-side event objects only)
   std::vector<hipEvent_t> prof_ev;   // 4 per step: start, after forward+loss, after backward, after update
   int32_t prof_cap = 0, prof_n = 0;
@@ -186,7 +194,8 @@ struct pm_ctx {
   template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(arena + off); }
   PmStepHdr* hdr() const { return at<PmStepHdr>(lay.hdr_off); }
   PmLayerStatic* ls() const { return at<PmLayerStatic>(lay.ls_off); }
-  PmLayerStep* ld() const { return at<PmLayerStep>(lay.ld_off); }
+  PmLayerStep* ld(int par) const { return at<PmLayerStep>(lay.ld_off) + (size_t)par * L; }
+  int par() const { return overlap ? (int)(t_host & 1) : 0; }   // which step-table set the current step uses
 };
 
 namespace {
@@ -213,14 +222,13 @@ inline void prof_mark(pm_ctx* c, int which) {
 
 // ---- kernel launches of one microbatch / one update, templated on the compute dtype -------------
 template <typename T>
-pm_status launch_update(pm_ctx* c) {
+pm_status launch_update(pm_ctx* c, hipStream_t st, int par) {
   const Layout& lay = c->lay;
-  hipStream_t st = c->stream;
   if (c->o.clip_norm > 0.0) {
     int blocks = (int)std::min<int64_t>(2048, (lay.n_flat / 4 + 255) / 256);
     hipLaunchKernelGGL(pm_sumsq_kernel, dim3(blocks), dim3(256), 0, st, c->at<float>(lay.g_off), lay.n_flat,
-                       &c->hdr()->gnorm2);
-    hipLaunchKernelGGL(pm_clip_scale_kernel, dim3(1), dim3(1), 0, st, c->hdr(), (float)c->o.clip_norm);
+                       &c->hdr()->gnorm2[par]);
+    hipLaunchKernelGGL(pm_clip_scale_kernel, dim3(1), dim3(1), 0, st, c->hdr(), (float)c->o.clip_norm, par);
   }
   prof_mark(c, 2);
   PmUpdArgs<T> a;
@@ -233,8 +241,9 @@ pm_status launch_update(pm_ctx* c) {
   a.ub = c->at<T>(lay.ub_off);
   a.chunk_layer = c->at<int32_t>(lay.chunk_off);
   a.ls = c->ls();
-  a.ld = c->ld();
+  a.ld = c->ld(par);
   a.hdr = c->hdr();
+  a.par = par;
   a.beta1 = (float)c->o.beta1;
   a.beta2 = (float)c->o.beta2;
   a.eps = (float)c->o.eps;
@@ -257,9 +266,18 @@ pm_status launch_update(pm_ctx* c) {
   return PM_OK;
 }
 
-void launch_prologue(pm_ctx* c) {
-  hipLaunchKernelGGL(pm_prologue_kernel, dim3(1), dim3(256), 0, c->stream, c->hdr(), c->ls(), c->ld(), c->L,
-                     sched_dev(c));
+void launch_prologue(pm_ctx* c, int par) {
+  hipLaunchKernelGGL(pm_prologue_kernel, dim3(1), dim3(256), 0, c->stream, c->hdr(), c->ls(), c->ld(par), c->L,
+                     sched_dev(c), par);
+}
+
+// Make the caller's stream wait for an update that may still run on the library's second stream.
+pm_status quiesce(pm_ctx* c) {
+  if (c->upd_pending) {
+    PM_HIP(hipStreamWaitEvent(c->stream, c->ev_upd, 0));
+    c->upd_pending = false;
+  }
+  return PM_OK;
 }
 
 template <typename T, class Epi>
@@ -280,7 +298,7 @@ void launch_gemm(pm_ctx* c, int I, int J, int K, const T* A, int64_t sai, int64_
 
 // Forward on the tau_fwd-stale ring slots, loss, backward on the corrected weights.
 template <typename T>
-pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int accumulate) {
+pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int accumulate, int par) {
   const Layout& lay = c->lay;
   hipStream_t st = c->stream;
   const int M = c->o.microbatch, L = c->L;
@@ -294,15 +312,15 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
     const int64_t tot = (int64_t)M * u0.ld_in;
     hipLaunchKernelGGL((pm_begin_step_kernel<T>), dim3((unsigned)std::min<int64_t>(1024, (tot + 255) / 256)), dim3(256),
                        0, st, (const float*)x_dev, c->at<T>(lay.x_off), M, u0.d.n_in, u0.ld_in, c->hdr(), c->ls(),
-                       c->ld(), accumulate ? 0 : L, sched_dev(c));
+                       c->ld(par), accumulate ? 0 : L, sched_dev(c), par);
   }
   // ---- forward: unit l reads W (and b) of version max(t - tau_fwd, 0) in place from its ring slot
   for (int l = 0; l < L; ++l) {
     const Unit& u = lay.units[l];
     const T* a_in = l == 0 ? c->at<T>(lay.x_off) : c->at<T>(lay.units[l - 1].a_off);
-    PmWLoc<T> W{ring + u.ring_off, &c->ld()[l].fwd_slot, u.n_pad};
+    PmWLoc<T> W{ring + u.ring_off, &c->ld(par)[l].fwd_slot, u.n_pad};
     PmEpiFwd<T> epi;
-    epi.bias = PmWLoc<T>{ring + u.ring_off + u.boff, &c->ld()[l].fwd_slot, u.n_pad};
+    epi.bias = PmWLoc<T>{ring + u.ring_off + u.boff, &c->ld(par)[l].fwd_slot, u.n_pad};
     epi.z = (l == L - 1) ? nullptr : c->at<T>(u.z_off);
     epi.a = (l == L - 1) ? nullptr : c->at<T>(u.a_off);
     epi.z32 = (l == L - 1) ? c->at<float>(u.z32_off) : nullptr;
@@ -326,6 +344,12 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
     }
   }
   prof_mark(c, 1);
+  // The backward needs what the previous step's update produced (corrected weights, or version t
+  // itself when tau_bkwd = 0) and will overwrite the gradient buffer that update reads.
+  {
+    pm_status qs = quiesce(c);
+    if (qs != PM_OK) return qs;
+  }
   // ---- backward, data-gradient chain: da_in[M, n_in] = dz . W_bkwd, fused with act'(z_prev).
   // W_bkwd = corrected buffer when the T2 coefficient is non-zero, else version max(t - tau_bkwd, 0).
   // The first unit needs none (its backward weights never enter any gradient).
@@ -334,7 +358,7 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
     const Unit& up = lay.units[l - 1];
     const T* dz = c->at<T>(u.dz_off);
     PmWLoc<T> Wb = u.corr ? PmWLoc<T>{ub + u.off, nullptr, 0}
-                          : PmWLoc<T>{ring + u.ring_off, &c->ld()[l].bkwd_slot, u.n_pad};
+                          : PmWLoc<T>{ring + u.ring_off, &c->ld(par)[l].bkwd_slot, u.n_pad};
     PmEpiBwdData<T> ed{c->at<T>(up.z_off), c->at<T>(up.dz_off), up.ld_out, up.d.act};
     launch_gemm<T>(c, M, u.d.n_in, u.d.n_out, dz, u.ld_out, 1, Wb, 1, u.d.n_in, ed);
   }
@@ -372,10 +396,29 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
 
 template <typename T>
 pm_status enqueue_step(pm_ctx* c, const void* x, const void* y, bool first_micro, bool last_micro) {
-  pm_status s = launch_fwd_bwd<T>(c, x, y, first_micro ? 0 : 1);
+  const int par = c->par();
+  c->last_par = par;
+  // The forward of step t reads versions <= t - 1 when every effective tau_fwd is >= 1, i.e. nothing
+  // the still-running update of step t-1 (which writes version t) touches: that asynchrony of the
+  // method is what lets the two overlap.  A zero delay (GPipe mode, synchronous warm-up) needs
+  // version t itself, so then the forward waits.
+  const bool fwd_independent = c->min_tau_f >= 1 && c->t_host >= c->o.sync_warmup_steps;
+  if (!fwd_independent) {
+    pm_status qs = quiesce(c);
+    if (qs != PM_OK) return qs;
+  }
+  pm_status s = launch_fwd_bwd<T>(c, x, y, first_micro ? 0 : 1, par);
   if (s != PM_OK) return s;
   if (last_micro) {
-    s = launch_update<T>(c);
+    if (c->overlap && !c->prof_on) {
+      PM_HIP(hipEventRecord(c->ev_bwd, c->stream));
+      PM_HIP(hipStreamWaitEvent(c->stream_b, c->ev_bwd, 0));
+      s = launch_update<T>(c, c->stream_b, par);
+      PM_HIP(hipEventRecord(c->ev_upd, c->stream_b));
+      c->upd_pending = true;
+    } else {
+      s = launch_update<T>(c, c->stream, par);
+    }
     if (c->prof_on && c->prof_n < c->prof_cap) c->prof_n += 1;
   }
   return s;
@@ -549,6 +592,19 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
   }
   c->arena = (char*)device_arena;
   c->stream = (hipStream_t)hip_stream;
+  c->min_tau_f = *std::min_element(c->tau_f.begin(), c->tau_f.end());
+  c->overlap = opts->overlap_update != 0 && opts->use_graph == 0;
+  if (c->overlap) {
+    // host-side objects only; default priority
+    if (hipStreamCreateWithFlags(&c->stream_b, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_bwd, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_upd, hipEventDisableTiming) != hipSuccess) {
+      if (c->ev_bwd) (void)hipEventDestroy(c->ev_bwd);
+      if (c->stream_b) (void)hipStreamDestroy(c->stream_b);
+      delete c;
+      return fail(PM_EHIP, "could not create the second stream for overlap_update");
+    }
+  }
 
   // host images of the static tables and the packed initial weights
   std::vector<float> w0((size_t)lay.n_flat, 0.f);
@@ -657,6 +713,7 @@ pm_status pm_state(pm_ctx* c, int32_t which, int32_t layer, float* dst, size_t n
   pm_status s = check_unit(c, layer, n);
   if (s != PM_OK) return s;
   if (!dst) return fail(PM_EINVAL, "dst is NULL");
+  if ((s = quiesce(c)) != PM_OK) return s;
   const Layout& lay = c->lay;
   const Unit& u = lay.units[layer];
   size_t base;
@@ -687,9 +744,11 @@ pm_status pm_state(pm_ctx* c, int32_t which, int32_t layer, float* dst, size_t n
 pm_status pm_device_step_table(pm_ctx* c, int64_t* t_used, int32_t* fwd_slot, int32_t* bkwd_slot,
                                int32_t* write_slot, float* lr) {
   if (!c) return fail(PM_EINVAL, "NULL context");
+  pm_status qs = quiesce(c);
+  if (qs != PM_OK) return qs;
   std::vector<PmLayerStep> ld(c->L);
   PmStepHdr h;
-  PM_HIP(hipMemcpyAsync(ld.data(), c->ld(), sizeof(PmLayerStep) * c->L, hipMemcpyDeviceToHost, c->stream));
+  PM_HIP(hipMemcpyAsync(ld.data(), c->ld(c->last_par), sizeof(PmLayerStep) * c->L, hipMemcpyDeviceToHost, c->stream));
   PM_HIP(hipMemcpyAsync(&h, c->hdr(), sizeof h, hipMemcpyDeviceToHost, c->stream));
   PM_HIP(hipStreamSynchronize(c->stream));
   if (t_used) *t_used = h.t_used;
@@ -704,6 +763,8 @@ pm_status pm_device_step_table(pm_ctx* c, int64_t* t_used, int32_t* fwd_slot, in
 
 pm_status pm_stats(pm_ctx* c, double* loss, double* grad_norm, double* param_norm, int64_t* t) {
   if (!c) return fail(PM_EINVAL, "NULL context");
+  pm_status qs = quiesce(c);
+  if (qs != PM_OK) return qs;
   const Layout& lay = c->lay;
   if (param_norm) {
     PM_HIP(hipMemsetAsync(&c->hdr()->pnorm2, 0, sizeof(float), c->stream));
@@ -715,7 +776,7 @@ pm_status pm_stats(pm_ctx* c, double* loss, double* grad_norm, double* param_nor
   PM_HIP(hipMemcpyAsync(&h, c->hdr(), sizeof h, hipMemcpyDeviceToHost, c->stream));
   PM_HIP(hipStreamSynchronize(c->stream));
   if (loss) *loss = h.loss;
-  if (grad_norm) *grad_norm = c->o.clip_norm > 0.0 ? std::sqrt((double)h.gnorm2) / c->o.n_microbatches : 0.0;
+  if (grad_norm) *grad_norm = c->o.clip_norm > 0.0 ? std::sqrt((double)h.gnorm2[c->last_par]) / c->o.n_microbatches : 0.0;
   if (param_norm) *param_norm = std::sqrt((double)h.pnorm2);
   if (t) *t = h.t_next;
   if (h.diverged) { c->diverged = true; return fail(PM_EDIVERGED, "non-finite weight after step %lld", (long long)h.t_used); }
@@ -726,6 +787,7 @@ pm_status pm_set_grads(pm_ctx* c, int32_t layer, const float* src, size_t n) {
   pm_status s = check_unit(c, layer, n);
   if (s != PM_OK) return s;
   if (!src) return fail(PM_EINVAL, "src is NULL");
+  if ((s = quiesce(c)) != PM_OK) return s;
   const Unit& u = c->lay.units[layer];
   float* g = c->at<float>(c->lay.g_off) + u.off;
   PM_HIP(hipMemcpyAsync(g, src, sizeof(float) * u.nw, hipMemcpyHostToDevice, c->stream));
@@ -738,8 +800,12 @@ pm_status pm_apply_update(pm_ctx* c) {
   if (!c) return fail(PM_EINVAL, "NULL context");
   if (c->micro != 0) return fail(PM_ESTATE, "a minibatch is in progress");
   if (c->diverged) return fail(PM_EDIVERGED, "a non-finite weight was produced at an earlier step");
-  launch_prologue(c);
-  pm_status s = c->o.dtype == PM_BF16 ? launch_update<bf16_t>(c) : launch_update<float>(c);
+  pm_status s = quiesce(c);
+  if (s != PM_OK) return s;
+  const int par = c->par();
+  c->last_par = par;
+  launch_prologue(c, par);
+  s = c->o.dtype == PM_BF16 ? launch_update<bf16_t>(c, c->stream, par) : launch_update<float>(c, c->stream, par);
   if (s == PM_OK) c->t_host += 1;
   return s;
 }
@@ -775,6 +841,10 @@ pm_status pm_linear_bwd_weight(void* stream, int32_t dtype, int32_t M, int32_t n
 pm_status pm_profile_begin(pm_ctx* c, int32_t max_steps) {
   if (!c || max_steps < 1 || max_steps > 65536) return fail(PM_EINVAL, "need a context and 1 <= max_steps <= 65536");
   if (c->o.n_microbatches != 1) return fail(PM_ESTATE, "phase timing supports n_microbatches = 1 only");
+  {
+    pm_status qs = quiesce(c);
+    if (qs != PM_OK) return qs;
+  }
   for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
   c->prof_ev.assign((size_t)max_steps * 4, nullptr);
   for (auto& e : c->prof_ev) PM_HIP(hipEventCreate(&e));
@@ -807,8 +877,22 @@ pm_status pm_profile_end(pm_ctx* c, double* fwd_ms, double* bwd_ms, double* upda
   return PM_OK;
 }
 
+pm_status pm_synchronize(pm_ctx* c) {
+  if (!c) return fail(PM_EINVAL, "NULL context");
+  PM_HIP(hipStreamSynchronize(c->stream));
+  if (c->stream_b) PM_HIP(hipStreamSynchronize(c->stream_b));
+  c->upd_pending = false;
+  return PM_OK;
+}
+
 void pm_destroy(pm_ctx* c) {
   if (!c) return;
+  if (c->stream_b) {
+    (void)hipStreamSynchronize(c->stream_b);
+    (void)hipStreamDestroy(c->stream_b);
+  }
+  if (c->ev_bwd) (void)hipEventDestroy(c->ev_bwd);
+  if (c->ev_upd) (void)hipEventDestroy(c->ev_upd);
   for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
   if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
   if (c->graph) (void)hipGraphDestroy(c->graph);

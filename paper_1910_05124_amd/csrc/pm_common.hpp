@@ -32,16 +32,19 @@ struct PmLayerStep {
   int32_t pad_[2];
 };
 
+// The step table and the per-step scalars exist twice (index = step parity): the update of step t,
+// which may run on the library's second stream, reads set t&1 while the first kernel of step t+1
+// already writes set (t+1)&1.
 struct PmStepHdr {
   long long t_next;    // optimizer steps completed = index of the next step
   long long t_used;    // index of the step the tables were last computed for
   float loss;          // accumulated by the loss kernel
-  float gnorm2;        // sum of squares of the accumulated gradients (clipping only)
-  float gscale;        // factor applied to the gradient buffer inside the update
-  float bc1, bc2;      // Adam bias corrections 1/(1-beta^(t+1))
   int32_t diverged;    // set when a non-finite weight is written
   float pnorm2;        // scratch for pm_stats
   int32_t pad_;
+  float gnorm2[2];     // sum of squares of the accumulated gradients (clipping only)
+  float gscale[2];     // factor applied to the gradient buffer inside the update
+  float bc1[2], bc2[2];  // Adam bias corrections 1/(1-beta^(t+1))
 };
 
 struct PmSchedDev {

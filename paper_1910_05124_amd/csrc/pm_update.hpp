@@ -9,7 +9,7 @@
 // A single block so that the counter update is ordered after every table entry.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ void pm_prologue_block(PmStepHdr* hdr, const PmLayerStatic* ls, PmLayerStep* ld, int L,
-                                                  const PmSchedDev& sc) {
+                                                  const PmSchedDev& sc, int par) {
   const long long t = hdr->t_next;
   const bool warm = t < sc.sync_warmup;            // synchronous warm-up (PipeMareW): no delays, no T1/T2
   const bool warm_next = t + 1 < sc.sync_warmup;
@@ -53,15 +53,16 @@ __device__ __forceinline__ void pm_prologue_block(PmStepHdr* hdr, const PmLayerS
   if (threadIdx.x == 0) {
     hdr->t_used = t;
     hdr->t_next = t + 1;
-    hdr->gnorm2 = 0.f;
-    hdr->gscale = (float)sc.gscale0;
-    hdr->bc1 = (float)(1.0 / (1.0 - pow(sc.beta1, (double)(t + 1))));
-    hdr->bc2 = (float)(1.0 / (1.0 - pow(sc.beta2, (double)(t + 1))));
+    hdr->gnorm2[par] = 0.f;
+    hdr->gscale[par] = (float)sc.gscale0;
+    hdr->bc1[par] = (float)(1.0 / (1.0 - pow(sc.beta1, (double)(t + 1))));
+    hdr->bc2[par] = (float)(1.0 / (1.0 - pow(sc.beta2, (double)(t + 1))));
   }
 }
 
-__global__ void pm_prologue_kernel(PmStepHdr* hdr, const PmLayerStatic* ls, PmLayerStep* ld, int L, PmSchedDev sc) {
-  pm_prologue_block(hdr, ls, ld, L, sc);
+__global__ void pm_prologue_kernel(PmStepHdr* hdr, const PmLayerStatic* ls, PmLayerStep* ld, int L, PmSchedDev sc,
+                                   int par) {
+  pm_prologue_block(hdr, ls, ld, L, sc, par);
 }
 
 // First kernel of every microbatch: stages the fp32 input batch into the compute dtype (pad columns
@@ -70,9 +71,9 @@ __global__ void pm_prologue_kernel(PmStepHdr* hdr, const PmLayerStatic* ls, PmLa
 template <typename T>
 __global__ __launch_bounds__(256) void pm_begin_step_kernel(const float* __restrict__ x, T* __restrict__ out, int M,
                                                             int n, int ld_x, PmStepHdr* hdr, const PmLayerStatic* ls,
-                                                            PmLayerStep* ld, int L, PmSchedDev sc) {
+                                                            PmLayerStep* ld, int L, PmSchedDev sc, int par) {
   if (blockIdx.x == 0) {
-    if (L > 0) pm_prologue_block(hdr, ls, ld, L, sc);
+    if (L > 0) pm_prologue_block(hdr, ls, ld, L, sc, par);
     if (threadIdx.x == 0) hdr->loss = 0.f;
   }
   const int64_t total = (int64_t)M * ld_x;
@@ -102,9 +103,9 @@ __global__ __launch_bounds__(256) void pm_sumsq_kernel(const float* __restrict__
 }
 
 // gscale <- (1/N) * min(1, clip / ||g/N||)
-__global__ void pm_clip_scale_kernel(PmStepHdr* hdr, float clip) {
-  const float gn = sqrtf(hdr->gnorm2) * hdr->gscale;
-  if (gn > clip) hdr->gscale *= clip / gn;
+__global__ void pm_clip_scale_kernel(PmStepHdr* hdr, float clip, int par) {
+  const float gn = sqrtf(hdr->gnorm2[par]) * hdr->gscale[par];
+  if (gn > clip) hdr->gscale[par] *= clip / gn;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -132,6 +133,7 @@ struct PmUpdArgs {
   const PmLayerStatic* ls;
   const PmLayerStep* ld;
   PmStepHdr* hdr;
+  int par;    // which set of step scalars (step parity)
   float beta1, beta2, eps, wd;
 };
 
@@ -229,7 +231,7 @@ __global__ __launch_bounds__(256) void pm_fused_update_kernel(PmUpdArgs<RT> a) {
   // of the step that will read it (0 while that step is still in the synchronous warm-up)
   const float lr = D.lr, gam = S.gamma, corr = D.corr_next;
   const bool has_ub = S.corr != 0.f;
-  const float gs = a.hdr->gscale;
+  const float gs = a.hdr->gscale[a.par];
   const int64_t e = (int64_t)c * PM_CHUNK + X::base(threadIdx.x);
   const int64_t rel = e - S.off;
 
@@ -254,8 +256,8 @@ __global__ __launch_bounds__(256) void pm_fused_update_kernel(PmUpdArgs<RT> a) {
     } else {
       v[j] = a.beta1 * v[j] + (1.f - a.beta1) * gj;
       s[j] = a.beta2 * s[j] + (1.f - a.beta2) * gj * gj;
-      const float mh = v[j] * a.hdr->bc1;
-      const float sh = s[j] * a.hdr->bc2;
+      const float mh = v[j] * a.hdr->bc1[a.par];
+      const float sh = s[j] * a.hdr->bc2[a.par];
       dw = -lr * (mh / (sqrtf(sh) + a.eps) + a.wd * w[j]);
     }
     wn[j] = w[j] + dw;

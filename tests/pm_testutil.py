@@ -26,14 +26,15 @@ def make_oracle(w, params, tau_fwd, tau_bkwd, *, opt="sgdm", lr=0.01, beta=0.9, 
 
 def make_gpu(w, params, tau_fwd, tau_bkwd, *, opt="sgdm", lr=0.01, beta=0.9, beta2=0.98, eps=1e-8,
              weight_decay=0.0, clip_norm=0.0, D=0.9, K=0, t1=True, t2=True, N=1, sched=None,
-             gamma_override=None, use_graph=False, dtype=None, stream=None, sync_warmup=0):
+             gamma_override=None, use_graph=False, dtype=None, stream=None, sync_warmup=0, overlap_update=False):
     import paper_1910_05124_amd as pm
     s = sched or dict(kind="const", base=lr)
     sc = pm.make_sched(kind=s["kind"], base=s["base"], init=s.get("init", 0.0), factor=s.get("factor", 1.0),
                        interval=s.get("interval", s.get("warmup", 1)), K=K)
     o = pm.make_opts(opt=opt, beta1=beta, beta2=beta2, eps=eps, weight_decay=weight_decay, clip_norm=clip_norm,
                      D=D, gamma_override=gamma_override, t1=t1, t2=t2, N=N, dtype=dtype or w.dtype, loss=w.loss,
-                     microbatch=w.microbatch, use_graph=use_graph, sync_warmup=sync_warmup)
+                     microbatch=w.microbatch, use_graph=use_graph, sync_warmup=sync_warmup,
+                     overlap_update=overlap_update)
     return pm.PipeMare(w.layers, w.P, tau_fwd, tau_bkwd, sc, o, params, stream=stream)
 
 

@@ -19,7 +19,8 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.timeout(1500)
-def test_config1_bf16_mlp16_500_steps():
+@pytest.mark.parametrize("launch", ["graph", "overlap"])
+def test_config1_bf16_mlp16_500_steps(launch):
     import torch
     w = wl.config(1)
     o_ = w.opt
@@ -34,7 +35,8 @@ def test_config1_bf16_mlp16_500_steps():
     report = {}
     t0 = time.time()
     with torch.cuda.stream(side):
-        g = make_gpu(w, params, tf, tb, use_graph=True, stream=side, **kw)
+        g = make_gpu(w, params, tf, tb, use_graph=(launch == "graph"), overlap_update=(launch == "overlap"),
+                     stream=side, **kw)
         x0, y0 = stream.batch(0)
         xd, yd = torch.from_numpy(x0).cuda(), torch.from_numpy(y0).cuda()
         for k in range(w.steps):

@@ -24,8 +24,9 @@ def torch_cuda():
     return torch
 
 
-def run_pair(torch, w, steps, tau=None, check_tables=False, N=1, gpu_kw=None, **kw):
-    """Step oracle and GPU side by side; returns (gpu ctx, oracle, losses)."""
+def run_pair(torch, w, steps, tau=None, check_tables=False, N=1, gpu_kw=None, free_running=False, **kw):
+    """Step oracle and GPU side by side; returns (gpu ctx, oracle, losses).  free_running: no
+    per-step read-backs, so consecutive steps really overlap on the device."""
     params = wl.init_params(w)
     tf, tb = tau if tau is not None else po.pipeline_delays(w.P, N)
     stream = wl.BatchStream(w)
@@ -39,7 +40,11 @@ def run_pair(torch, w, steps, tau=None, check_tables=False, N=1, gpu_kw=None, **
         for x, y in mbs:
             xd = torch.from_numpy(x).cuda()
             yd = torch.from_numpy(y).cuda()
-            lg += g.step(xd, yd, want_loss=True) / N
+            if free_running and k + 1 < steps:
+                g.step(xd, yd)
+                lg = lo
+            else:
+                lg += g.step(xd, yd, want_loss=True) / N
         losses.append((lo, lg))
         if check_tables:
             t_used, fs, bs, ws, lrs = g.step_table()
@@ -173,11 +178,13 @@ def test_config0_fp32_mlp_50_steps(torch_cuda):
 
 
 @pytest.mark.parametrize("case", ["pipemare", "t2_off", "pipedream", "gpipe", "adamw_clip", "microbatches", "graph",
-                                  "gamma_override", "ragged_bf16", "sync_warmup", "sync_warmup_bf16"])
+                                  "gamma_override", "ragged_bf16", "sync_warmup", "sync_warmup_bf16",
+                                  "overlap", "overlap_free", "overlap_gpipe", "overlap_warmup", "overlap_clip_f32"])
 def test_modes_small(torch_cuda, case):
     """Every mode of the step on a small MLP (several stages share units; odd widths hit the
     non-MFMA kernel, multiples of 8 the MFMA kernel)."""
-    dtype = "bf16" if case in ("ragged_bf16", "graph", "pipemare", "sync_warmup_bf16") else "f32"
+    dtype = "bf16" if case in ("ragged_bf16", "graph", "pipemare", "sync_warmup_bf16", "overlap", "overlap_free",
+                               "overlap_gpipe", "overlap_warmup") else "f32"
     width = 72 if case != "ragged_bf16" else 50
     w = wl.small_mlp(width, 5, 6, "gelu", "xent", dtype, 24, layers_per_stage=2)
     # bf16 contexts: a smaller step keeps 14 steps of rounding noise (activations, ring and
@@ -201,6 +208,17 @@ def test_modes_small(torch_cuda, case):
         kw["gamma_override"] = [0.9, 0.8, 0.7]
     elif case.startswith("sync_warmup"):
         kw["sync_warmup"] = 5            # PipeMareW: 5 synchronous steps, then 9 asynchronous ones
+    free = False
+    if case.startswith("overlap"):
+        # update of step t on the library's second stream, concurrent with the forward of step t+1
+        gpu_kw = dict(overlap_update=True)
+        free = case != "overlap"
+        if case == "overlap_gpipe":
+            tau = po.pipeline_delays(w.P, 1, "gpipe")       # zero delays: the forward must wait for the update
+        elif case == "overlap_warmup":
+            kw["sync_warmup"] = 5
+        elif case == "overlap_clip_f32":
+            kw = dict(opt="adamw", lr=2e-3, beta=0.9, beta2=0.98, weight_decay=0.01, clip_norm=0.5, D=0.3, K=8)
     steps = 14
     if case == "graph":
         # a captured graph is bound to the batch buffers: feed every step through the same two tensors
@@ -226,7 +244,8 @@ def test_modes_small(torch_cuda, case):
                     R = tf[L.stage - 1] + 1
                     assert (fs[u], ws[u]) == (o.last_versions[u][0] % R, (k + 1) % R)
     else:
-        g, o, losses = run_pair(torch_cuda, w, steps, tau=tau, check_tables=True, N=N, gpu_kw=gpu_kw, **kw)
+        g, o, losses = run_pair(torch_cuda, w, steps, tau=tau, check_tables=not free, N=N, gpu_kw=gpu_kw,
+                                free_running=free, **kw)
         for lo, lg in losses:
             assert lg == pytest.approx(lo, rel=3e-2 if dtype == "bf16" else 1e-4)
     err, errs = max_rel_err(g.weights(), o.weights())
