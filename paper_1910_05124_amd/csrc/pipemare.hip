@@ -290,6 +290,18 @@ void launch_gemm_on(hipStream_t st, int I, int J, int K, const T* A, int64_t sai
   hipLaunchKernelGGL((pm_gemm_plain_kernel<T, T, Epi>), grid, dim3(256), 0, st, I, J, K, A, sai, sak, B, sbj, sbk, epi);
 }
 
+// Bias gradient db = column sums of dz as its own launch (when the GEMM does not fuse it).
+template <typename T>
+void launch_bias_grad(hipStream_t st, const T* dz, float* db, int M, int N, int ld, int accumulate) {
+  if (M > 512) {
+    if (!accumulate) hipLaunchKernelGGL(pm_zero_f32_kernel, dim3((N + 255) / 256), dim3(256), 0, st, db, (int64_t)N);
+    hipLaunchKernelGGL((pm_bias_grad_chunked_kernel<T>), dim3((N + 63) / 64, (M + 255) / 256), dim3(256), 0, st, dz, db,
+                       M, N, ld);
+  } else {
+    hipLaunchKernelGGL((pm_bias_grad_kernel<T>), dim3((N + 63) / 64), dim3(256), 0, st, dz, db, M, N, ld, accumulate);
+  }
+}
+
 template <typename T, class Epi>
 void launch_gemm(pm_ctx* c, int I, int J, int K, const T* A, int64_t sai, int64_t sak, PmWLoc<T> B, int64_t sbj,
                  int64_t sbk, const Epi& epi) {
@@ -386,8 +398,7 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
       const T* dz = c->at<T>(u.dz_off);
       PmEpiBwdWeight ew{g + u.off, u.d.n_in, accumulate, nullptr};
       launch_gemm<T>(c, u.d.n_out, u.d.n_in, M, dz, 1, u.ld_out, PmWLoc<T>{a_in, nullptr, 0}, 1, u.ld_in, ew);
-      hipLaunchKernelGGL((pm_bias_grad_kernel<T>), dim3((u.d.n_out + 63) / 64), dim3(256), 0, st, dz,
-                         g + u.off + u.boff, M, u.d.n_out, u.ld_out, accumulate);
+      launch_bias_grad<T>(st, dz, g + u.off + u.boff, M, u.d.n_out, u.ld_out, accumulate);
     }
   }
   PM_HIP(hipGetLastError());
@@ -462,13 +473,13 @@ template <typename T>
 pm_status linear_bwd_weight_t(hipStream_t st, int M, int n_in, int n_out, const void* dz, const void* a, float* dW,
                               float* db, int accumulate) {
   // the MFMA kernels produce the bias gradient themselves (column sums of the dz tile in LDS)
+  // (for few rows; with many rows the column sums would sit on the critical path of the blocks
+  // that own them, and a chunked reduction over the whole chip is faster)
   bool fused_db = false;
-  if constexpr (sizeof(T) == 2) fused_db = pm_mfma_fits(n_out, n_in, M, dz, 1, n_out, a, 0, 1, n_in);
+  if constexpr (sizeof(T) == 2) fused_db = M <= 512 && pm_mfma_fits(n_out, n_in, M, dz, 1, n_out, a, 0, 1, n_in);
   PmEpiBwdWeight epi{dW, n_in, accumulate, fused_db ? db : nullptr};
   launch_gemm_on<T>(st, n_out, n_in, M, (const T*)dz, 1, n_out, PmWLoc<T>{(const T*)a, nullptr, 0}, 1, n_in, epi);
-  if (db && !fused_db)
-    hipLaunchKernelGGL((pm_bias_grad_kernel<T>), dim3((n_out + 63) / 64), dim3(256), 0, st, (const T*)dz, db, M, n_out,
-                       n_out, accumulate);
+  if (db && !fused_db) launch_bias_grad<T>(st, (const T*)dz, db, M, n_out, n_out, accumulate);
   PM_HIP(hipGetLastError());
   return PM_OK;
 }

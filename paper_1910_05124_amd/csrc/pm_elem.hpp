@@ -83,6 +83,29 @@ __global__ __launch_bounds__(256) void pm_bias_grad_kernel(const T* __restrict__
   }
 }
 
+// Bias gradient for many rows (token-rich microbatches): the rows are cut into chunks of 256 so
+// that the whole chip reads dz once at full bandwidth; partial column sums meet in fp32 atomics
+// (db must be zero, or hold the value to accumulate onto, when the kernel starts).
+template <typename T>
+__global__ __launch_bounds__(256) void pm_bias_grad_chunked_kernel(const T* __restrict__ dz, float* __restrict__ db,
+                                                                   int M, int N, int ld) {
+  const int col = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int rg = threadIdx.x >> 6;
+  const int m0 = blockIdx.y * 256, m1 = m0 + 256 < M ? m0 + 256 : M;
+  float acc = 0.f;
+  if (col < N)
+    for (int m = m0 + rg; m < m1; m += 4) acc += ldf(dz + (int64_t)m * ld + col);
+  __shared__ float part[4][64];
+  part[rg][threadIdx.x & 63] = acc;
+  __syncthreads();
+  if (rg == 0 && col < N)
+    atomicAdd(db + col, part[0][threadIdx.x] + part[1][threadIdx.x] + part[2][threadIdx.x] + part[3][threadIdx.x]);
+}
+
+__global__ __launch_bounds__(256) void pm_zero_f32_kernel(float* p, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0.f;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Epilogues shared by the plain and the MFMA GEMMs.  acc is the fp32 contraction result for
 // output element (i, j).
@@ -104,6 +127,20 @@ struct PmEpiFwd {
     if (z32) z32[o] = zz;
     if (a) stf(a + o, pm_act_fwd(zz, act));
   }
+  // eight consecutive columns j .. j+7 (j a multiple of 8) of row i: 16-byte accesses
+  __device__ __forceinline__ void op8(int i, int j, const float* acc) const {
+    float bb[8], zz[8], aa[8];
+    pm_ld8(b_ + j, bb);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      zz[e] = acc[e] + bb[e];
+      aa[e] = pm_act_fwd(zz[e], act);
+    }
+    const int64_t o = (int64_t)i * ld + j;
+    if (z) pm_st8(z + o, zz);
+    if (z32) pm_st8(z32 + o, zz);
+    if (a) pm_st8(a + o, aa);
+  }
 };
 // backward data: dz_prev = acc * act'(z_prev)
 template <typename T>
@@ -117,6 +154,14 @@ struct PmEpiBwdData {
     const int64_t o = (int64_t)i * ld + j;
     stf(dzprev + o, acc * pm_act_bwd(ldf(zprev + o), act));
   }
+  __device__ __forceinline__ void op8(int i, int j, const float* acc) const {
+    const int64_t o = (int64_t)i * ld + j;
+    float zp[8], out[8];
+    pm_ld8(zprev + o, zp);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) out[e] = acc[e] * pm_act_bwd(zp[e], act);
+    pm_st8(dzprev + o, out);
+  }
 };
 // backward weight: g[i, j] (+)= acc, fp32; db[i] (+)= column sum of the A operand (MFMA path only)
 struct PmEpiBwdWeight {
@@ -129,6 +174,19 @@ struct PmEpiBwdWeight {
   __device__ __forceinline__ void operator()(int i, int j, float acc) const {
     const int64_t o = (int64_t)i * ld + j;
     g[o] = accumulate ? g[o] + acc : acc;
+  }
+  __device__ __forceinline__ void op8(int i, int j, const float* acc) const {
+    const int64_t o = (int64_t)i * ld + j;
+    float out[8];
+    if (accumulate) {
+      pm_ld8(g + o, out);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) out[e] += acc[e];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) out[e] = acc[e];
+    }
+    pm_st8(g + o, out);
   }
 };
 

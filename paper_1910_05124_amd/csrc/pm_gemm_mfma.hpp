@@ -30,6 +30,7 @@
 // contiguous index, holding zeros beyond the logical extent.
 #pragma once
 #include "pm_common.hpp"
+#include "pm_elem.hpp"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 pm_bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float pm_f32x16;
@@ -495,16 +496,36 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(1, Cfg:
   if (Epi::kColSumA && !AKC) {
     if (do_colsum && threadIdx.x < BI && i0 + (int)threadIdx.x < I) epi.colsum(i0 + threadIdx.x, colsum);
   }
+  // Epilogue through LDS (the operand stages are dead after the last barrier): each wave parks its
+  // fp32 tile row-major in a private region, then every lane takes 8 consecutive columns of a row,
+  // so global accesses are 16-byte pieces of full 128-byte row segments instead of 2-byte scatters.
+  constexpr int WT_I = TI * 32, WT_J = TJ * 32, ES = WT_J + 4;          // wave tile and its padded row stride
+  static_assert(sizeof(smem) >= (size_t)WI * WJ * WT_I * ES * 4, "epilogue staging does not fit the operand stages");
+  float* es = reinterpret_cast<float*>(smem) + (size_t)wave * WT_I * ES;
 #pragma unroll
   for (int a = 0; a < TI; ++a)
 #pragma unroll
     for (int b = 0; b < TJ; ++b)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int i = i0 + (wi * TI + a) * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-        const int j = j0 + (wj * TJ + b) * 32 + lr;
-        if (i < I && j < J) epi(i, j, acc[a][b][v]);
-      }
+      for (int v = 0; v < 16; ++v)
+        es[(a * 32 + 8 * (v >> 2) + 4 * kg + (v & 3)) * ES + b * 32 + lr] = acc[a][b][v];
+  const int wi0 = i0 + wi * WT_I, wj0 = j0 + wj * WT_J;
+#pragma unroll 4
+  for (int c = lane; c < WT_I * (WT_J / 8); c += 64) {
+    const int r = c / (WT_J / 8), c8 = (c % (WT_J / 8)) * 8;
+    const int i = wi0 + r, j = wj0 + c8;
+    if (i >= I || j >= J) continue;
+    float vals[8];
+    const float4 v0 = *reinterpret_cast<const float4*>(es + r * ES + c8);
+    const float4 v1 = *reinterpret_cast<const float4*>(es + r * ES + c8 + 4);
+    vals[0] = v0.x; vals[1] = v0.y; vals[2] = v0.z; vals[3] = v0.w;
+    vals[4] = v1.x; vals[5] = v1.y; vals[6] = v1.z; vals[7] = v1.w;
+    if (j + 8 <= J) {
+      epi.op8(i, j, vals);
+    } else {
+      for (int e = 0; e < 8 && j + e < J; ++e) epi(i, j + e, vals[e]);
+    }
+  }
 }
 
 // 128 x 128 block, 4 waves x (64 x 64): 80 KB of LDS, so two blocks share a CU and cover each
@@ -522,7 +543,11 @@ inline void pm_big_launch(hipStream_t st, const PmGemmProb<Epi>& pr) {
 template <bool AKC, bool BKC, class Epi>
 inline bool pm_big_try(hipStream_t st, const PmGemmProb<Epi>& pr) {
   const long tiles = (long)((pr.I + 127) / 128) * ((pr.J + 127) / 128);
-  if (pr.K < 256 || tiles < 200) return false;
+  if (pr.K < 256) return false;
+  // enough tiles to fill the chip, or fewer tiles with a long contraction (the weight gradient of a
+  // token-rich microbatch: the deep software pipeline matters more than idle CUs; splitting K
+  // over blocks with fp32 atomics was measured slower than leaving 3/4 of the CUs idle)
+  if (tiles < 200 && !(tiles >= 32 && pr.K >= 2048)) return false;
   pm_big_launch<PmBig128, AKC, BKC>(st, pr);
   return true;
 }

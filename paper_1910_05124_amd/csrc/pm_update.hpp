@@ -137,31 +137,6 @@ struct PmUpdArgs {
   float beta1, beta2, eps, wd;
 };
 
-__device__ __forceinline__ void pm_store8(float* p, const float* x) {
-  reinterpret_cast<float4*>(p)[0] = make_float4(x[0], x[1], x[2], x[3]);
-  reinterpret_cast<float4*>(p)[1] = make_float4(x[4], x[5], x[6], x[7]);
-}
-__device__ __forceinline__ void pm_store8(bf16_t* p, const float* x) {
-  uint4 o;
-  o.x = (uint32_t)f32_to_bf16(x[0]) | ((uint32_t)f32_to_bf16(x[1]) << 16);
-  o.y = (uint32_t)f32_to_bf16(x[2]) | ((uint32_t)f32_to_bf16(x[3]) << 16);
-  o.z = (uint32_t)f32_to_bf16(x[4]) | ((uint32_t)f32_to_bf16(x[5]) << 16);
-  o.w = (uint32_t)f32_to_bf16(x[6]) | ((uint32_t)f32_to_bf16(x[7]) << 16);
-  *reinterpret_cast<uint4*>(p) = o;
-}
-__device__ __forceinline__ void pm_load8(const float* p, float* x) {
-  const float4 a = reinterpret_cast<const float4*>(p)[0];
-  const float4 b = reinterpret_cast<const float4*>(p)[1];
-  x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-}
-__device__ __forceinline__ void pm_load8(const bf16_t* p, float* x) {
-  const uint4 a = *reinterpret_cast<const uint4*>(p);
-  x[0] = __uint_as_float(a.x << 16); x[1] = __uint_as_float(a.x & 0xffff0000u);
-  x[2] = __uint_as_float(a.y << 16); x[3] = __uint_as_float(a.y & 0xffff0000u);
-  x[4] = __uint_as_float(a.z << 16); x[5] = __uint_as_float(a.z & 0xffff0000u);
-  x[6] = __uint_as_float(a.w << 16); x[7] = __uint_as_float(a.w & 0xffff0000u);
-}
-
 // Element access pattern of one thread inside its 2048-element chunk: two groups of 4 elements
 // 1024 apart, so every load / store instruction of a wave covers one dense 1 KB (fp32) or 512 B
 // (bf16) span.  VAR 1: ordinary accesses; VAR 2: non-temporal loads and stores.
@@ -286,7 +261,7 @@ __global__ __launch_bounds__(256) void pm_init_ring_kernel(const float* __restri
   const PmLayerStatic S = ls[chunk_layer[c]];
   const int64_t e = (int64_t)c * PM_CHUNK + threadIdx.x * 8;
   float x[8];
-  pm_load8(w + e, x);
-  pm_store8(ub + e, x);
-  for (int r = 0; r < S.R; ++r) pm_store8(ring + S.ring_off + (int64_t)r * S.n_pad + (e - S.off), x);
+  pm_ld8(w + e, x);
+  pm_st8(ub + e, x);
+  for (int r = 0; r < S.R; ++r) pm_st8(ring + S.ring_off + (int64_t)r * S.n_pad + (e - S.off), x);
 }
