@@ -16,13 +16,13 @@ from typing import List, Tuple
 
 import numpy as np
 
-__all__ = ["Layer", "Workload", "config", "init_params", "BatchStream", "n_params"]
+__all__ = ["Layer", "Workload", "config", "init_params", "BatchStream", "n_params", "transformer", "TokenStream"]
 
 
 @dataclass(frozen=True)
 class Layer:
     """One weight unit (weight matrix + bias), assigned to pipeline stage `stage` (1-based)."""
-    kind: str      # "linear"
+    kind: str      # "linear" | "embed" (n_in = vocab, n_out = width, no bias) | "layernorm" (gain + bias of width n_out)
     n_in: int
     n_out: int
     act: str       # "none" | "relu" | "gelu"
@@ -45,9 +45,14 @@ class Workload:
     seed_data: int = 0
     seed_teacher: int = 1
     init: str = "fan_in"   # "fan_in": W ~ U(+-1/sqrt(fan_in));  "he": W ~ U(+-sqrt(6/fan_in)) behind ReLU/GELU
+    arch: dict = field(default_factory=dict)   # {} = plain chain; transformer: n_layers, d_model, n_heads, d_ff, vocab, seq
 
 
 def n_params(layer: Layer) -> int:
+    if layer.kind == "embed":
+        return layer.n_in * layer.n_out
+    if layer.kind == "layernorm":
+        return 2 * layer.n_out
     return layer.n_out * layer.n_in + layer.n_out
 
 
@@ -104,6 +109,14 @@ def init_params(wl: Workload, seed: int | None = None) -> List[np.ndarray]:
     rng = np.random.default_rng(wl.seed_init if seed is None else seed)
     out = []
     for L in wl.layers:
+        if L.kind == "embed":          # E ~ N(0, 1/width)
+            out.append((rng.standard_normal((L.n_in, L.n_out)) / np.sqrt(L.n_out)).ravel().astype(np.float32))
+            continue
+        if L.kind == "layernorm":      # gain 1 + U(+-0.1), bias U(+-0.1): off the trivial point so every use of them shows
+            g = 1.0 + rng.uniform(-0.1, 0.1, size=L.n_out)
+            b = rng.uniform(-0.1, 0.1, size=L.n_out)
+            out.append(np.concatenate([g, b]).astype(np.float32))
+            continue
         if wl.init == "he":
             bound = np.sqrt((6.0 if L.act in ("relu", "gelu") else 3.0) / L.n_in)
         else:
@@ -139,3 +152,55 @@ class BatchStream:
         else:
             y = np.argmax(t, axis=1).astype(np.int32)
         return x, y
+
+
+def transformer(n_layers: int, d_model: int, n_heads: int, d_ff: int, vocab: int, seq: int, microbatch: int,
+                dtype: str = "bf16", name: str | None = None, steps: int = 0, **opt) -> Workload:
+    """Fine-grained pre-LN causal Transformer: one pipeline stage per weight matrix (a LayerNorm rides
+    in the stage of the matrix that consumes it).  Units in topological order:
+    embed | per layer: ln1, Wq, Wk, Wv, Wo, ln2, W1, W2 | final ln, head.
+    Stages: embed = 1, then Wq, Wk, Wv, Wo, W1, W2 of every layer, head last: P = 6 * n_layers + 2."""
+    layers = [Layer("embed", vocab, d_model, "none", 1)]
+    st = 1
+    for _ in range(n_layers):
+        layers.append(Layer("layernorm", d_model, d_model, "none", st + 1))
+        for _w in range(3):
+            st += 1
+            layers.append(Layer("linear", d_model, d_model, "none", st))
+        st += 1
+        layers.append(Layer("linear", d_model, d_model, "none", st))
+        layers.append(Layer("layernorm", d_model, d_model, "none", st + 1))
+        st += 1
+        layers.append(Layer("linear", d_model, d_ff, "relu", st))
+        st += 1
+        layers.append(Layer("linear", d_ff, d_model, "none", st))
+    st += 1
+    layers.append(Layer("layernorm", d_model, d_model, "none", st))
+    layers.append(Layer("linear", d_model, vocab, "none", st))
+    o = dict(kind="adamw", lr=5e-4, beta=0.9, beta2=0.98, eps=1e-8, D=0.1, K=0, weight_decay=0.0,
+             sched=dict(kind="warmup_invsqrt", base=5e-4, init=1e-7, warmup=40))
+    o.update(opt)
+    return Workload(name=name or f"tfm{n_layers}x{d_model}_{dtype}", layers=tuple(layers), P=st, N=1, loss="xent",
+                    dtype=dtype, microbatch=microbatch, n_classes=vocab, opt=o, steps=steps,
+                    arch=dict(kind="transformer", n_layers=n_layers, d_model=d_model, n_heads=n_heads, d_ff=d_ff,
+                              vocab=vocab, seq=seq))
+
+
+class TokenStream:
+    """Deterministic token microbatches: ids ~ Zipf(1.1) truncated to the vocabulary (inverse CDF of a
+    uniform draw), sequences of seq+1 tokens; inputs are the first seq, targets the next token.
+    Stands in for tokenised translation corpora (same shapes; rank-frequency law of natural text)."""
+
+    def __init__(self, wl: Workload, exponent: float = 1.1):
+        self.wl = wl
+        V = wl.arch["vocab"]
+        p = 1.0 / np.power(np.arange(1, V + 1, dtype=np.float64), exponent)
+        self.cdf = np.cumsum(p / p.sum())
+
+    def batch(self, k: int):
+        wl = self.wl
+        S, V = wl.arch["seq"], wl.arch["vocab"]
+        rng = np.random.default_rng([wl.seed_data, k])
+        u = rng.random((wl.microbatch, S + 1))
+        ids = np.minimum(np.searchsorted(self.cdf, u), V - 1).astype(np.int32)
+        return np.ascontiguousarray(ids[:, :S]), np.ascontiguousarray(ids[:, 1:])
