@@ -1,8 +1,9 @@
 /*
  * pipemare.h — C ABI of the MI355X (gfx950) PipeMare training-step library.
  *
- * One context executes asynchronous pipeline-parallel training of a chain of weight units
- * (Linear + bias + activation) as a delay-faithful single-GPU run of all P pipeline stages:
+ * One context executes asynchronous pipeline-parallel training of a network of weight units
+ * (a chain of Linear + bias + activation units, or a fine-grained pre-LN causal Transformer made of
+ * embedding, LayerNorm and Linear units) as a delay-faithful single-GPU run of all P pipeline stages:
  * forward with weights that are tau_fwd,i optimizer steps old, read in place from a
  * device-resident ring of weight versions; backward with discrepancy-corrected weights; one
  * fused update pass (learning-rate rescheduling, optimizer, delta accumulator, ring and
@@ -42,7 +43,15 @@ typedef enum {
                        of the experiment, cf. the stability analysis of Sec. 3.1) */
 } pm_status;
 
-typedef enum { PM_LINEAR = 0 } pm_layer_kind;
+typedef enum {
+  PM_LINEAR = 0,     /* W [n_out, n_in] row-major + bias [n_out] */
+  PM_EMBED = 1,      /* table E [n_in = vocabulary, n_out = width], no bias */
+  PM_LAYERNORM = 2   /* gain [n_out] + bias [n_out] over rows of width n_in = n_out, eps 1e-5 */
+} pm_layer_kind;
+typedef enum {
+  PM_ARCH_CHAIN = 0,       /* Linear units in sequence, unit l feeds unit l+1 */
+  PM_ARCH_TRANSFORMER = 1  /* embed | per layer: ln1, Wq, Wk, Wv, Wo, ln2, W1, W2 | final ln, head (see pm_opts) */
+} pm_arch;
 typedef enum { PM_ACT_NONE = 0, PM_ACT_RELU = 1, PM_ACT_GELU = 2 /* exact erf form */ } pm_act;
 typedef enum { PM_METHOD_PIPEMARE = 0, PM_METHOD_PIPEDREAM = 1, PM_METHOD_GPIPE = 2 } pm_method;
 typedef enum { PM_LR_CONST = 0, PM_LR_STEP = 1, PM_LR_WARMUP_INVSQRT = 2 } pm_lr_kind;
@@ -50,9 +59,12 @@ typedef enum { PM_OPT_SGDM = 0, PM_OPT_ADAMW = 1 } pm_opt_kind;
 typedef enum { PM_F32 = 0, PM_BF16 = 1 /* bf16 compute + ring, fp32 master/optimizer state */ } pm_dtype;
 typedef enum { PM_LOSS_MSE = 0, PM_LOSS_XENT = 1 } pm_loss_kind;
 
-/* One weight unit: y = act(x W^T + b), W is n_out x n_in row-major.  Weight and bias always share
- * a pipeline stage (Sec. 4.1, "Pipeline Stages"); `stage` is 1-based and non-decreasing along the
- * chain; several consecutive units may share a stage. */
+/* One weight unit.  Linear: y = act(x W^T + b), W is n_out x n_in row-major.  Weight and bias always
+ * share a pipeline stage (Sec. 4.1, "Pipeline Stages"); `stage` is 1-based and non-decreasing in
+ * topological order; several consecutive units may share a stage (a LayerNorm normally rides in the
+ * stage of the matrix that consumes it).  Packed host layout of a unit's values, used by
+ * init_weights_host, pm_weights, pm_state and pm_set_grads: [W | b] (Linear), [E] (embedding),
+ * [gain | bias] (LayerNorm). */
 typedef struct {
   int32_t kind;   /* pm_layer_kind */
   int32_t n_in;
@@ -100,6 +112,15 @@ typedef struct {
                                 Ignored with use_graph.  The caller's stream being idle then no longer
                                 implies the last update has finished: pm_synchronize or any read-back
                                 call waits for it. */
+  int32_t arch;              /* pm_arch.  PM_ARCH_TRANSFORMER: the L = 8*n_layers + 3 units must be, in order,
+                                EMBED(vocab, d) | n_layers x { LAYERNORM(d), LINEAR(d,d) q, LINEAR(d,d) k, LINEAR(d,d) v,
+                                LINEAR(d,d) o, LAYERNORM(d), LINEAR(d,d_ff) with act, LINEAR(d_ff,d) } | LAYERNORM(d),
+                                LINEAR(d,vocab).  Pre-LN residual blocks, causal attention, fixed sinusoidal positions,
+                                untied output head, mean token cross-entropy (loss must be PM_LOSS_XENT).  `microbatch`
+                                counts sequences; pm_step takes int32 token ids [microbatch, seq_len] as x and the
+                                int32 next-token targets of the same shape as y. */
+  int32_t n_heads;           /* Transformer: attention heads (d % n_heads == 0) */
+  int32_t seq_len;           /* Transformer: tokens per sequence */
 } pm_opts;
 
 const char* pm_status_str(pm_status s);
@@ -129,7 +150,7 @@ pm_status pm_query_bytes(int32_t P, int32_t L, const pm_layer_desc* layers, cons
 /* Build a context.
  *   P, L               stages and weight units; layers[L] host
  *   tau_fwd, tau_bkwd  host, P entries, 0 <= tau_bkwd,i <= tau_fwd,i
- *   init_weights_host  L host pointers, unit l packed as [W (n_out*n_in) | b (n_out)] fp32
+ *   init_weights_host  L host pointers, unit l in its packed layout (see pm_layer_desc), fp32
  *   device_arena       device, 256-byte aligned, arena_bytes >= pm_query_bytes
  *   hip_stream         hipStream_t (NULL = default stream)
  * Every ring slot starts as w_0, delta_0 = v_0 = 0, corrected weights = w_0.
@@ -142,15 +163,17 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers,
 
 /* One microbatch through all stages (forward on stale weights, loss, backward on corrected
  * weights); after the N-th microbatch of a minibatch also the fused update (Sec. 2.1 recurrence,
- * T1, T2).  x_dev: device fp32 [microbatch, n_in of unit 0] row-major.  y_dev: device fp32
+ * T1, T2).  Chain: x_dev device fp32 [microbatch, n_in of unit 0] row-major, y_dev device fp32
  * [microbatch, n_out of last unit] (MSE) or int32 [microbatch] labels (cross-entropy).
+ * Transformer: x_dev, y_dev device int32 [microbatch, seq_len] (ids outside the vocabulary are
+ * clamped on input and contribute no loss as targets).
  * loss_out_host: NULL, or host float that receives this microbatch's mean loss (forces a
  * stream synchronisation).  Returns PM_EDIVERGED once a non-finite weight has been seen by a
  * synchronising call. */
 pm_status pm_step(pm_ctx* ctx, const void* x_dev, const void* y_dev, float* loss_out_host);
 
-/* fp32 master weights w_t of unit `layer` into host memory, packed [W | b]; n must equal
- * n_out*n_in + n_out.  Synchronises the stream. */
+/* fp32 master weights w_t of unit `layer` into host memory in the unit's packed layout; n must
+ * equal the unit's value count.  Synchronises the stream. */
 pm_status pm_weights(pm_ctx* ctx, int32_t layer, float* dst_host, size_t n);
 
 /* Same layout for the delta accumulator (which = 1), the optimizer's first state v or m
@@ -201,6 +224,30 @@ pm_status pm_linear_bwd_data(void* stream, int32_t dtype, int32_t M, int32_t n_i
 pm_status pm_linear_bwd_weight(void* stream, int32_t dtype, int32_t M, int32_t n_in, int32_t n_out,
                                const void* dz_dev, const void* a_dev, float* dW_dev, float* db_dev,
                                int32_t accumulate);
+
+/* Weight-free and vector-weight operators of the Transformer stages as stand-alone primitives for
+ * kernel-level tests and measurement.  rows = tokens, row r = sequence r / S, position r % S.
+ * Element type of the "T" matrices per `dtype` (bf16 raw 16-bit, or fp32); d a multiple of 8.
+ *   layernorm_fwd: y = (x - mean) * rstd * gain + bias        x fp32 [rows,d], gain/bias T [d] -> y T [rows,d],
+ *                  mean, rstd fp32 [rows]
+ *   layernorm_bwd: dx = (dx_res or 0) + rstd (dxh - mean(dxh) - xhat mean(dxh xhat)), dxh = dy * gain_bkwd
+ *                  (the gain of the BACKWARD weights, Sec. 2.1); dgain += sum dy xhat, dbias += sum dy
+ *                  dy fp32 [rows,d]; dx fp32 (may alias dx_res); dx_t T copy of dx or NULL; dgain, dbias fp32 [d]
+ *                  are added to (caller zeroes them)
+ *   attention_fwd: causal softmax(q k^T / sqrt(dh)) v per (sequence, head); q, k, v, o T [B*S, H*dh], head h in
+ *                  columns h*dh..; lse fp32 [B, H, S] receives log-sum-exp of the scaled scores
+ *   attention_bwd: gradients dq, dk, dv T [B*S, H*dh] from do, recomputing probabilities from q, k, lse */
+pm_status pm_layernorm_fwd(void* stream, int32_t dtype, int32_t rows, int32_t d, const float* x_dev,
+                           const void* gain_dev, const void* bias_dev, void* y_dev, float* mean_dev, float* rstd_dev);
+pm_status pm_layernorm_bwd(void* stream, int32_t dtype, int32_t rows, int32_t d, const float* dy_dev,
+                           const float* x_dev, const float* mean_dev, const float* rstd_dev,
+                           const void* gain_bkwd_dev, const float* dx_res_dev, float* dx_dev, void* dx_t_dev,
+                           float* dgain_dev, float* dbias_dev);
+pm_status pm_attention_fwd(void* stream, int32_t dtype, int32_t B, int32_t S, int32_t H, int32_t dh,
+                           const void* q_dev, const void* k_dev, const void* v_dev, void* o_dev, float* lse_dev);
+pm_status pm_attention_bwd(void* stream, int32_t dtype, int32_t B, int32_t S, int32_t H, int32_t dh,
+                           const void* q_dev, const void* k_dev, const void* v_dev, const void* o_dev,
+                           const void* do_dev, const float* lse_dev, void* dq_dev, void* dk_dev, void* dv_dev);
 
 /* Waits for everything the context has enqueued, on the caller's stream and on the library's
  * second stream (overlap_update). */

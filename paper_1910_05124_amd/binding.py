@@ -18,8 +18,8 @@ __all__ = [
     "pm_delays", "pm_slots", "pm_t1_lr", "pm_query_bytes", "pm_create", "pm_step", "pm_weights",
     "pm_state", "pm_device_step_table", "pm_stats", "pm_set_grads", "pm_apply_update", "pm_destroy",
     "pm_linear_fwd", "pm_linear_bwd_data", "pm_linear_bwd_weight", "pm_profile_begin", "pm_profile_end",
-    "pm_synchronize", "PipeMare",
-    "PM_LINEAR", "PM_ACT", "PM_METHOD", "PM_LR", "PM_OPT", "PM_DTYPE", "PM_LOSS", "EXPORTS",
+    "pm_synchronize", "PipeMare", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
+    "PM_LINEAR", "PM_KIND", "PM_ARCH", "PM_ACT", "PM_METHOD", "PM_LR", "PM_OPT", "PM_DTYPE", "PM_LOSS", "EXPORTS",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -30,6 +30,8 @@ if not os.path.exists(_LIB_PATH):
 lib = C.CDLL(_LIB_PATH)
 
 PM_LINEAR = 0
+PM_KIND = {"linear": 0, "embed": 1, "layernorm": 2}
+PM_ARCH = {"chain": 0, "transformer": 1}
 PM_ACT = {"none": 0, "relu": 1, "gelu": 2}
 PM_METHOD = {"pipemare": 0, "pipedream": 1, "gpipe": 2}
 PM_LR = {"const": 0, "step": 1, "warmup_invsqrt": 2}
@@ -41,7 +43,8 @@ _STATUS = {0: "PM_OK", 1: "PM_EINVAL", 2: "PM_ENOMEM", 3: "PM_EHIP", 4: "PM_ESTA
 EXPORTS = ["pm_status_str", "pm_last_error", "pm_delays", "pm_slots", "pm_t1_lr", "pm_query_bytes",
            "pm_create", "pm_step", "pm_weights", "pm_state", "pm_device_step_table", "pm_stats",
            "pm_set_grads", "pm_apply_update", "pm_profile_begin", "pm_profile_end", "pm_linear_fwd", "pm_linear_bwd_data",
-           "pm_linear_bwd_weight", "pm_synchronize", "pm_destroy"]
+           "pm_linear_bwd_weight", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
+           "pm_synchronize", "pm_destroy"]
 
 
 class pm_layer_desc(C.Structure):
@@ -60,7 +63,8 @@ class pm_opts(C.Structure):
                 ("gamma_override", C.POINTER(C.c_double)), ("t1_enabled", C.c_int32),
                 ("t2_enabled", C.c_int32), ("n_microbatches", C.c_int32), ("dtype", C.c_int32),
                 ("loss", C.c_int32), ("microbatch", C.c_int32), ("use_graph", C.c_int32),
-                ("sync_warmup_steps", C.c_int64), ("overlap_update", C.c_int32)]
+                ("sync_warmup_steps", C.c_int64), ("overlap_update", C.c_int32), ("arch", C.c_int32),
+                ("n_heads", C.c_int32), ("seq_len", C.c_int32)]
 
 
 class PmError(RuntimeError):
@@ -93,6 +97,10 @@ lib.pm_profile_end.argtypes = [_vp, C.POINTER(C.c_double), C.POINTER(C.c_double)
 lib.pm_linear_fwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _i32, _vp, _vp]
 lib.pm_linear_bwd_data.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _i32, _vp]
 lib.pm_linear_bwd_weight.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _i32]
+lib.pm_layernorm_fwd.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.pm_layernorm_bwd.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.pm_attention_fwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
+lib.pm_attention_bwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.pm_synchronize.argtypes = [_vp]
 lib.pm_destroy.argtypes = [_vp]
 lib.pm_destroy.restype = None
@@ -136,7 +144,7 @@ def pm_t1_lr(sched: pm_lr_sched, tau: int, k: int, t1_enabled: bool = True) -> f
 def _layer_array(layers):
     arr = (pm_layer_desc * len(layers))()
     for i, L in enumerate(layers):
-        arr[i] = pm_layer_desc(PM_LINEAR, L.n_in, L.n_out, PM_ACT[L.act], L.stage)
+        arr[i] = pm_layer_desc(PM_KIND[getattr(L, "kind", "linear")], L.n_in, L.n_out, PM_ACT[L.act], L.stage)
     return arr
 
 
@@ -230,20 +238,47 @@ def pm_linear_bwd_weight(stream, dtype, M, n_in, n_out, dz, a, dW, db, accumulat
     _check(lib.pm_linear_bwd_weight(_vp(stream), PM_DTYPE[dtype], M, n_in, n_out, dz, a, dW, db, int(accumulate)))
 
 
+def pm_layernorm_fwd(stream, dtype, rows, d, x, gain, bias, y, mean, rstd):
+    _check(lib.pm_layernorm_fwd(_vp(stream), PM_DTYPE[dtype], rows, d, x, gain, bias, y, mean, rstd))
+
+
+def pm_layernorm_bwd(stream, dtype, rows, d, dy, x, mean, rstd, gain_bkwd, dx_res, dx, dx_t, dgain, dbias):
+    _check(lib.pm_layernorm_bwd(_vp(stream), PM_DTYPE[dtype], rows, d, dy, x, mean, rstd, gain_bkwd, dx_res, dx, dx_t,
+                                dgain, dbias))
+
+
+def pm_attention_fwd(stream, dtype, B, S, H, dh, q, k, v, o, lse):
+    _check(lib.pm_attention_fwd(_vp(stream), PM_DTYPE[dtype], B, S, H, dh, q, k, v, o, lse))
+
+
+def pm_attention_bwd(stream, dtype, B, S, H, dh, q, k, v, o, do, lse, dq, dk, dv):
+    _check(lib.pm_attention_bwd(_vp(stream), PM_DTYPE[dtype], B, S, H, dh, q, k, v, o, do, lse, dq, dk, dv))
+
+
 def make_sched(kind="const", base=0.01, init=0.0, factor=1.0, interval=1, K=0) -> pm_lr_sched:
     return pm_lr_sched(PM_LR[kind], base, init, factor, interval, K)
 
 
 def make_opts(opt="sgdm", beta1=0.9, beta2=0.98, eps=1e-8, weight_decay=0.0, clip_norm=0.0, D=1.0,
               gamma_override=None, t1=True, t2=True, N=1, dtype="f32", loss="mse", microbatch=1,
-              use_graph=False, sync_warmup=0, overlap_update=False) -> pm_opts:
+              use_graph=False, sync_warmup=0, overlap_update=False, arch="chain", n_heads=0, seq_len=0) -> pm_opts:
     o = pm_opts(PM_OPT[opt], beta1, beta2, eps, weight_decay, clip_norm, D, None, int(t1), int(t2), N,
-                PM_DTYPE[dtype], PM_LOSS[loss], microbatch, int(use_graph), int(sync_warmup), int(overlap_update))
+                PM_DTYPE[dtype], PM_LOSS[loss], microbatch, int(use_graph), int(sync_warmup), int(overlap_update),
+                PM_ARCH[arch], int(n_heads), int(seq_len))
     if gamma_override is not None:
         arr = (C.c_double * len(gamma_override))(*gamma_override)
         o._keep = arr
         o.gamma_override = C.cast(arr, C.POINTER(C.c_double))
     return o
+
+
+def _unit_size(L) -> int:
+    kind = getattr(L, "kind", "linear")
+    if kind == "embed":
+        return L.n_in * L.n_out
+    if kind == "layernorm":
+        return 2 * L.n_out
+    return L.n_out * L.n_in + L.n_out
 
 
 class PipeMare:
@@ -255,7 +290,7 @@ class PipeMare:
         self.torch = torch
         self.layers = list(layers)
         self.L = len(self.layers)
-        self.sizes = [L.n_out * L.n_in + L.n_out for L in self.layers]
+        self.sizes = [_unit_size(L) for L in self.layers]
         self.device = torch.device(device)
         nbytes = pm_query_bytes(P, self.layers, tau_fwd, opts)
         with torch.cuda.device(self.device):
@@ -268,7 +303,7 @@ class PipeMare:
         self.arena_bytes = nbytes
 
     def step(self, x, y, want_loss=False):
-        """x: cuda fp32 [M, n_in]; y: cuda fp32 [M, n_out] or int32 [M]."""
+        """Chain: x cuda fp32 [M, n_in]; y cuda fp32 [M, n_out] or int32 [M].  Transformer: x, y cuda int32 [M, S]."""
         return pm_step(self.ctx, x.data_ptr(), y.data_ptr(), want_loss)
 
     def weights(self, layer=None):

@@ -17,6 +17,7 @@
 #include "pm_elem.hpp"
 #include "pm_gemm_mfma.hpp"
 #include "pm_update.hpp"
+#include "pm_transformer.hpp"
 
 namespace {
 
@@ -42,9 +43,10 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 struct Unit {
   pm_layer_desc d;
-  int64_t nw;        // n_out * n_in
-  int64_t boff;      // offset of the bias inside the unit (nw rounded up to 8 elements)
-  int64_t n;         // boff + n_out
+  int64_t nw;        // values of the first part: W (n_out * n_in), embedding table, or LayerNorm gain
+  int64_t nb;        // values of the second part (bias); 0 for an embedding
+  int64_t boff;      // offset of the second part inside the unit (nw rounded up to 8 elements)
+  int64_t n;         // boff + nb
   int64_t n_pad;     // n rounded up to PM_CHUNK
   int64_t off;       // element offset in the flat arrays
   int64_t ring_off;  // element offset in the ring
@@ -66,6 +68,16 @@ struct Layout {
   // byte offsets
   size_t w_off, g_off, v_off, s_off, d_off, ub_off, ring_off, chunk_off, ls_off, ld_off, hdr_off, probs_off, x_off;
   size_t act_begin, act_end, total;
+  // Transformer activations (byte offsets; see launch_tfm).  Per layer: index [layer]
+  struct TfmLayer {
+    size_t x, mu1, rs1, n1, q, k, v, lse, o, h, mu2, rs2, n2, z1, f;
+  };
+  std::vector<TfmLayer> tl;
+  size_t t_xf, t_muf, t_rsf, t_nf, t_logits, t_dlogits;      // final LayerNorm and head
+  size_t t_dx, t_dxt, t_dn, t_dff, t_do, t_dq, t_dk, t_dv;   // backward scratch, reused by every layer
+  size_t t_pos, t_zero;                                      // positions fp32 [S, d]; zero-region table
+  int n_zero = 0;
+  int64_t zero_max = 0;
 };
 
 pm_status validate(int32_t P, int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
@@ -78,16 +90,46 @@ pm_status validate(int32_t P, int32_t L, const pm_layer_desc* layers, const int3
   if (!(o->D > 0.0 && o->D <= 1.0)) return fail(PM_EINVAL, "D must be in (0, 1]");
   if (o->sync_warmup_steps < 0) return fail(PM_EINVAL, "sync_warmup_steps must be >= 0");
   if (o->clip_norm < 0.0 || o->weight_decay < 0.0) return fail(PM_EINVAL, "clip_norm and weight_decay must be >= 0");
+  if (o->arch != PM_ARCH_CHAIN && o->arch != PM_ARCH_TRANSFORMER) return fail(PM_EINVAL, "unknown architecture");
   int prev_stage = 1;
   for (int l = 0; l < L; ++l) {
     const pm_layer_desc& d = layers[l];
-    if (d.kind != PM_LINEAR) return fail(PM_EINVAL, "unit %d: unknown kind", l);
+    if (d.kind < PM_LINEAR || d.kind > PM_LAYERNORM) return fail(PM_EINVAL, "unit %d: unknown kind", l);
+    if (o->arch == PM_ARCH_CHAIN && d.kind != PM_LINEAR) return fail(PM_EINVAL, "unit %d: a chain holds Linear units only", l);
     if (d.n_in < 1 || d.n_out < 1) return fail(PM_EINVAL, "unit %d: sizes must be positive", l);
     if (d.act < PM_ACT_NONE || d.act > PM_ACT_GELU) return fail(PM_EINVAL, "unit %d: unknown activation", l);
     if (d.stage < 1 || d.stage > P) return fail(PM_EINVAL, "unit %d: stage %d outside 1..%d", l, d.stage, P);
     if (d.stage < prev_stage) return fail(PM_EINVAL, "unit %d: stages must be non-decreasing along the chain", l);
     prev_stage = d.stage;
-    if (l > 0 && layers[l - 1].n_out != d.n_in) return fail(PM_EINVAL, "unit %d: n_in %d does not chain with previous n_out %d", l, d.n_in, layers[l - 1].n_out);
+    if (o->arch == PM_ARCH_CHAIN && l > 0 && layers[l - 1].n_out != d.n_in) return fail(PM_EINVAL, "unit %d: n_in %d does not chain with previous n_out %d", l, d.n_in, layers[l - 1].n_out);
+  }
+  if (o->arch == PM_ARCH_TRANSFORMER) {
+    if (o->loss != PM_LOSS_XENT) return fail(PM_EINVAL, "the Transformer is trained with token cross-entropy (PM_LOSS_XENT)");
+    if (L < 11 || (L - 3) % 8) return fail(PM_EINVAL, "a Transformer has 8 * n_layers + 3 units, got %d", L);
+    if (o->n_heads < 1 || o->seq_len < 1) return fail(PM_EINVAL, "n_heads and seq_len must be >= 1");
+    const int V = layers[0].n_in, d = layers[0].n_out, nl = (L - 3) / 8;
+    auto is = [&](int l, int kind, int n_in, int n_out) {
+      return layers[l].kind == kind && layers[l].n_in == n_in && layers[l].n_out == n_out;
+    };
+    if (layers[0].kind != PM_EMBED) return fail(PM_EINVAL, "unit 0 must be the embedding");
+    if (d % o->n_heads || (d & 7)) return fail(PM_EINVAL, "width %d must be a multiple of 8 and of n_heads %d", d, o->n_heads);
+    const int dff = layers[7].n_out;
+    if (dff & 7) return fail(PM_EINVAL, "feed-forward width %d must be a multiple of 8", dff);
+    for (int b = 0; b < nl; ++b) {
+      const int u = 1 + 8 * b;
+      const bool ok = is(u, PM_LAYERNORM, d, d) && is(u + 1, PM_LINEAR, d, d) && is(u + 2, PM_LINEAR, d, d) &&
+                      is(u + 3, PM_LINEAR, d, d) && is(u + 4, PM_LINEAR, d, d) && is(u + 5, PM_LAYERNORM, d, d) &&
+                      is(u + 6, PM_LINEAR, d, dff) && is(u + 7, PM_LINEAR, dff, d);
+      if (!ok) return fail(PM_EINVAL, "layer %d: units must be ln1, Wq, Wk, Wv, Wo, ln2, W1 (d -> d_ff), W2 (d_ff -> d)", b);
+      for (int j = 0; j < 8; ++j)
+        if (j != 6 && layers[u + j].act != PM_ACT_NONE) return fail(PM_EINVAL, "unit %d: only the first feed-forward matrix has an activation", u + j);
+    }
+    if (!is(L - 2, PM_LAYERNORM, d, d) || !is(L - 1, PM_LINEAR, d, V)) return fail(PM_EINVAL, "the last two units must be the final LayerNorm and the output head (d -> vocabulary)");
+    if (d > 1024) return fail(PM_EINVAL, "LayerNorm kernels support widths up to 1024");
+    const int dh = d / o->n_heads;
+    const bool mfma_attn = o->dtype == PM_BF16 && pm_attn_mfma_fits(o->seq_len, dh);
+    if (!mfma_attn && !pm_attn_plain_fits(o->seq_len, dh))
+      return fail(PM_EINVAL, "attention: outside bf16 / head size 64 / seq_len multiple of 32, the head size must be 4, 8, 16, 32 or 64 and seq_len * (head size + 1) <= 8192");
   }
   for (int i = 0; i < P; ++i) {
     if (tau_fwd[i] < 0) return fail(PM_EINVAL, "tau_fwd[%d] < 0", i);
@@ -104,9 +146,11 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
   for (int l = 0; l < L; ++l) {
     Unit& u = lay.units[l];
     u.d = layers[l];
-    u.nw = (int64_t)u.d.n_out * u.d.n_in;
+    if (u.d.kind == PM_LAYERNORM) { u.nw = u.d.n_out; u.nb = u.d.n_out; }
+    else if (u.d.kind == PM_EMBED) { u.nw = (int64_t)u.d.n_in * u.d.n_out; u.nb = 0; }
+    else { u.nw = (int64_t)u.d.n_out * u.d.n_in; u.nb = u.d.n_out; }
     u.boff = round_up(u.nw, 8);
-    u.n = u.boff + u.d.n_out;
+    u.n = u.boff + u.nb;
     u.n_pad = round_up(u.n, PM_CHUNK);
     u.off = off;
     u.ring_off = roff;
@@ -114,14 +158,15 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
     u.tau_b = tau_bkwd ? tau_bkwd[u.d.stage - 1] : 0;
     u.R = u.tau_f + 1;
     const int dd = u.tau_f - u.tau_b;
-    u.corr = (o->t2_enabled && dd > 0) ? dd : 0;
+    // nothing flows through an embedding to earlier units: its backward weights are never read
+    u.corr = (o->t2_enabled && dd > 0 && u.d.kind != PM_EMBED) ? dd : 0;
     if (o->gamma_override) u.gamma = o->gamma_override[u.d.stage - 1];
     else u.gamma = dd > 0 ? std::pow(o->D, 1.0 / dd) : 0.0;
     u.ld_in = (int)round_up(u.d.n_in, 8);
     u.ld_out = (int)round_up(u.d.n_out, 8);
     off += u.n_pad;
     roff += u.n_pad * u.R;
-    real += u.nw + u.d.n_out;
+    real += u.nw + u.nb;
   }
   lay.n_flat = off;
   lay.n_real = real;
@@ -143,14 +188,42 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
   lay.probs_off = take(sizeof(PmGemmProb<PmEpiBwdWeight>) * 2 * L);
   const int M = o->microbatch;
   lay.act_begin = p;
-  lay.x_off = take((size_t)M * lay.units[0].ld_in * lay.esz);
-  for (int l = 0; l < L; ++l) {
-    Unit& u = lay.units[l];
-    const size_t e = (size_t)M * u.ld_out;
-    u.z_off = take(e * lay.esz);
-    u.a_off = take(e * lay.esz);
-    u.dz_off = take(e * lay.esz);
-    u.z32_off = (l == L - 1) ? take(e * 4) : 0;
+  if (o->arch == PM_ARCH_TRANSFORMER) {
+    const size_t Tk = (size_t)M * o->seq_len, d = lay.units[0].d.n_out, dff = lay.units[7].d.n_out;
+    const size_t ldV = (size_t)round_up(lay.units[0].d.n_in, 8), e = lay.esz;
+    const int nl = (L - 3) / 8;
+    lay.x_off = 0;
+    lay.tl.resize(nl);
+    for (auto& b : lay.tl) {
+      b.x = take(Tk * d * 4); b.mu1 = take(Tk * 4); b.rs1 = take(Tk * 4); b.n1 = take(Tk * d * e);
+      b.q = take(Tk * d * e); b.k = take(Tk * d * e); b.v = take(Tk * d * e);
+      b.lse = take(Tk * o->n_heads * 4); b.o = take(Tk * d * e);
+      b.h = take(Tk * d * 4); b.mu2 = take(Tk * 4); b.rs2 = take(Tk * 4); b.n2 = take(Tk * d * e);
+      b.z1 = take(Tk * dff * e); b.f = take(Tk * dff * e);
+    }
+    lay.t_xf = take(Tk * d * 4); lay.t_muf = take(Tk * 4); lay.t_rsf = take(Tk * 4); lay.t_nf = take(Tk * d * e);
+    lay.t_logits = take(Tk * ldV * 4); lay.t_dlogits = take(Tk * ldV * e);
+    lay.t_dx = take(Tk * d * 4); lay.t_dxt = take(Tk * d * e); lay.t_dn = take(Tk * d * 4);
+    lay.t_dff = take(Tk * dff * e); lay.t_do = take(Tk * d * e);
+    lay.t_dq = take(Tk * d * e); lay.t_dk = take(Tk * d * e); lay.t_dv = take(Tk * d * e);
+    lay.t_pos = take((size_t)o->seq_len * d * 4);
+    // gradient regions that are accumulated with atomics and therefore cleared at the start of a
+    // minibatch: the embedding table and every LayerNorm
+    lay.n_zero = 0;
+    lay.zero_max = 0;
+    for (int l = 0; l < L; ++l)
+      if (lay.units[l].d.kind != PM_LINEAR) { lay.n_zero += 1; lay.zero_max = std::max(lay.zero_max, lay.units[l].n_pad); }
+    lay.t_zero = take(sizeof(int64_t) * 2 * lay.n_zero);
+  } else {
+    lay.x_off = take((size_t)M * lay.units[0].ld_in * lay.esz);
+    for (int l = 0; l < L; ++l) {
+      Unit& u = lay.units[l];
+      const size_t e = (size_t)M * u.ld_out;
+      u.z_off = take(e * lay.esz);
+      u.a_off = take(e * lay.esz);
+      u.dz_off = take(e * lay.esz);
+      u.z32_off = (l == L - 1) ? take(e * 4) : 0;
+    }
   }
   lay.act_end = p;
   lay.total = p;
@@ -405,6 +478,156 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
   return PM_OK;
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Fine-grained pre-LN causal Transformer: one microbatch forward on the tau_fwd-stale ring slots,
+// token cross-entropy, backward on the corrected weights.  Residual stream and its gradient fp32;
+// GEMM operands in the compute dtype.  A backward kernel reads a weight only where a gradient
+// flows through it (Linear: dz . W; LayerNorm: dy * gain); weight gradients use stored forward
+// activations (Sec. 2.1).
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumulate, int par) {
+  const Layout& lay = c->lay;
+  hipStream_t st = c->stream;
+  const int L = c->L, nl = (L - 3) / 8;
+  const int B = c->o.microbatch, S = c->o.seq_len, H = c->o.n_heads;
+  const int Tk = B * S, V = lay.units[0].d.n_in, d = lay.units[0].d.n_out, dff = lay.units[7].d.n_out, dh = d / H;
+  const int ldV = (int)round_up(V, 8);
+  T* ring = c->at<T>(lay.ring_off);
+  T* ub = c->at<T>(lay.ub_off);
+  float* g = c->at<float>(lay.g_off);
+  PmLayerStep* tab = c->ld(par);
+  const int32_t* tokens = (const int32_t*)x_dev;
+  auto U = [&](int u) -> const Unit& { return lay.units[u]; };
+  auto Wf = [&](int u, int64_t extra) { return PmWLoc<T>{ring + U(u).ring_off + extra, &tab[u].fwd_slot, U(u).n_pad}; };
+  auto Wb = [&](int u, int64_t extra) {
+    return U(u).corr ? PmWLoc<T>{ub + U(u).off + extra, nullptr, 0}
+                     : PmWLoc<T>{ring + U(u).ring_off + extra, &tab[u].bkwd_slot, U(u).n_pad};
+  };
+  // z = a_in W_fwd^T + b (optional), a = act(z)
+  auto lin_fwd = [&](int u, const T* a_in, int n_in, int n_out, T* z, T* a, int act) {
+    PmEpiFwd<T> epi;
+    epi.bias = Wf(u, U(u).boff);
+    epi.z = z; epi.a = a; epi.z32 = nullptr; epi.ld = n_out; epi.act = act; epi.b_ = nullptr;
+    launch_gemm<T>(c, Tk, n_out, n_in, a_in, n_in, 1, Wf(u, 0), n_in, 1, epi);
+  };
+  // out = res + a_in W_fwd^T + b   (fp32 residual stream)
+  auto lin_fwd_res = [&](int u, const T* a_in, int n_in, int n_out, const float* res, float* out) {
+    PmEpiFwdRes<T> epi;
+    epi.bias = Wf(u, U(u).boff);
+    epi.res = res; epi.out = out; epi.ld = n_out; epi.b_ = nullptr;
+    launch_gemm<T>(c, Tk, n_out, n_in, a_in, n_in, 1, Wf(u, 0), n_in, 1, epi);
+  };
+  // dW = dz^T a_in, db = column sums of dz
+  auto wgrad = [&](int u, const T* dz, int ld_dz, const T* a_in, int n_out, int n_in) {
+    PmEpiBwdWeight ew{g + U(u).off, n_in, accumulate, nullptr};
+    launch_gemm<T>(c, n_out, n_in, Tk, dz, 1, ld_dz, PmWLoc<T>{a_in, nullptr, 0}, 1, n_in, ew);
+    launch_bias_grad<T>(st, dz, g + U(u).off + U(u).boff, Tk, n_out, ld_dz, accumulate);
+  };
+  // fp32 out (+)= dz W_bkwd
+  auto dgrad_f32 = [&](int u, const T* dz, int ld_dz, int n_out, int n_in, float* out, int acc) {
+    PmEpiF32 e{out, n_in, acc};
+    launch_gemm<T>(c, Tk, n_in, n_out, dz, ld_dz, 1, Wb(u, 0), 1, n_in, e);
+  };
+  // out = (dz W_bkwd) * act'(zprev) in the compute dtype
+  auto dgrad_t = [&](int u, const T* dz, int n_out, int n_in, const T* zprev, int act, T* out) {
+    PmEpiBwdData<T> e{zprev, out, n_in, act};
+    launch_gemm<T>(c, Tk, n_in, n_out, dz, n_out, 1, Wb(u, 0), 1, n_in, e);
+  };
+  auto ln_fwd = [&](int u, const float* x, T* out, float* mu, float* rs) {
+    pm_ln_fwd_launch<T>(st, x, Wf(u, 0), (int)U(u).boff, out, mu, rs, Tk, d);
+  };
+  auto ln_bwd = [&](int u, const float* dy, const float* x, const float* mu, const float* rs, const float* dx_res,
+                    float* dx_out, T* dx_t) {
+    pm_ln_bwd_launch<T>(st, dy, x, mu, rs, Wb(u, 0), dx_res, dx_out, dx_t, g + U(u).off, g + U(u).off + U(u).boff, Tk, d);
+  };
+  auto F = [&](size_t off) { return c->at<float>(off); };
+  auto TT = [&](size_t off) { return c->at<T>(off); };
+
+  prof_mark(c, 0);
+  hipLaunchKernelGGL(pm_begin_tokens_kernel, dim3(1), dim3(256), 0, st, c->hdr(), c->ls(), tab, accumulate ? 0 : L,
+                     sched_dev(c), par);
+  // ---- forward
+  float* x0 = F(nl ? lay.tl[0].x : lay.t_xf);
+  {
+    const int64_t tot = (int64_t)Tk * d;
+    hipLaunchKernelGGL((pm_embed_fwd_kernel<T>), dim3((unsigned)std::min<int64_t>(4096, (tot + 255) / 256)), dim3(256), 0,
+                       st, tokens, Wf(0, 0), F(lay.t_pos), x0, Tk, S, d, V);
+  }
+  for (int l = 0; l < nl; ++l) {
+    const Layout::TfmLayer& b = lay.tl[l];
+    const int u = 1 + 8 * l;
+    float* x = F(b.x);
+    float* y = F(l + 1 < nl ? lay.tl[l + 1].x : lay.t_xf);
+    ln_fwd(u, x, TT(b.n1), F(b.mu1), F(b.rs1));
+    lin_fwd(u + 1, TT(b.n1), d, d, nullptr, TT(b.q), PM_ACT_NONE);
+    lin_fwd(u + 2, TT(b.n1), d, d, nullptr, TT(b.k), PM_ACT_NONE);
+    lin_fwd(u + 3, TT(b.n1), d, d, nullptr, TT(b.v), PM_ACT_NONE);
+    if (!pm_attn_fwd_launch<T>(st, B, S, H, dh, TT(b.q), TT(b.k), TT(b.v), TT(b.o), F(b.lse)))
+      return fail(PM_EINVAL, "attention shape not supported");
+    lin_fwd_res(u + 4, TT(b.o), d, d, x, F(b.h));
+    ln_fwd(u + 5, F(b.h), TT(b.n2), F(b.mu2), F(b.rs2));
+    lin_fwd(u + 6, TT(b.n2), d, dff, TT(b.z1), TT(b.f), U(u + 6).d.act);
+    lin_fwd_res(u + 7, TT(b.f), dff, d, F(b.h), y);
+  }
+  ln_fwd(L - 2, F(lay.t_xf), TT(lay.t_nf), F(lay.t_muf), F(lay.t_rsf));
+  {
+    PmEpiFwd<T> epi;
+    epi.bias = Wf(L - 1, U(L - 1).boff);
+    epi.z = nullptr; epi.a = nullptr; epi.z32 = F(lay.t_logits); epi.ld = ldV; epi.act = PM_ACT_NONE; epi.b_ = nullptr;
+    launch_gemm<T>(c, Tk, V, d, TT(lay.t_nf), d, 1, Wf(L - 1, 0), d, 1, epi);
+  }
+  hipLaunchKernelGGL((pm_xent_kernel<T>), dim3((Tk + 3) / 4), dim3(256), 0, st, F(lay.t_logits), (const int32_t*)y_dev,
+                     TT(lay.t_dlogits), Tk, V, ldV, c->hdr());
+  prof_mark(c, 1);
+  {
+    pm_status qs = quiesce(c);
+    if (qs != PM_OK) return qs;
+  }
+  // ---- backward
+  if (!accumulate && lay.n_zero > 0) {
+    const unsigned bx = (unsigned)std::max<int64_t>(1, std::min<int64_t>(1024, lay.zero_max / 4 / 256));
+    hipLaunchKernelGGL(pm_zero_regions_kernel, dim3(bx, lay.n_zero), dim3(256), 0, st, g, c->at<int64_t>(lay.t_zero));
+  }
+  float* dx = F(lay.t_dx);
+  float* dn = F(lay.t_dn);
+  T* dxt = TT(lay.t_dxt);
+  wgrad(L - 1, TT(lay.t_dlogits), ldV, TT(lay.t_nf), V, d);
+  dgrad_f32(L - 1, TT(lay.t_dlogits), ldV, V, d, dn, 0);
+  ln_bwd(L - 2, dn, F(lay.t_xf), F(lay.t_muf), F(lay.t_rsf), nullptr, dx, dxt);
+  for (int l = nl - 1; l >= 0; --l) {
+    const Layout::TfmLayer& b = lay.tl[l];
+    const int u = 1 + 8 * l;
+    // y = h + f W2^T + b2
+    wgrad(u + 7, dxt, d, TT(b.f), d, dff);
+    dgrad_t(u + 7, dxt, d, dff, TT(b.z1), U(u + 6).d.act, TT(lay.t_dff));
+    wgrad(u + 6, TT(lay.t_dff), dff, TT(b.n2), dff, d);
+    dgrad_f32(u + 6, TT(lay.t_dff), dff, dff, d, dn, 0);
+    ln_bwd(u + 5, dn, F(b.h), F(b.mu2), F(b.rs2), dx, dx, dxt);          // dx is now d loss / d h
+    // h = x + o Wo^T + bo
+    wgrad(u + 4, dxt, d, TT(b.o), d, d);
+    dgrad_t(u + 4, dxt, d, d, nullptr, PM_ACT_NONE, TT(lay.t_do));
+    if (!pm_attn_bwd_launch<T>(st, B, S, H, dh, TT(b.q), TT(b.k), TT(b.v), TT(b.o), TT(lay.t_do), F(b.lse), TT(lay.t_dq),
+                               TT(lay.t_dk), TT(lay.t_dv)))
+      return fail(PM_EINVAL, "attention shape not supported");
+    wgrad(u + 1, TT(lay.t_dq), d, TT(b.n1), d, d);
+    wgrad(u + 2, TT(lay.t_dk), d, TT(b.n1), d, d);
+    wgrad(u + 3, TT(lay.t_dv), d, TT(b.n1), d, d);
+    dgrad_f32(u + 1, TT(lay.t_dq), d, d, d, dn, 0);
+    dgrad_f32(u + 2, TT(lay.t_dk), d, d, d, dn, 1);
+    dgrad_f32(u + 3, TT(lay.t_dv), d, d, d, dn, 1);
+    ln_bwd(u, dn, F(b.x), F(b.mu1), F(b.rs1), dx, dx, dxt);              // dx is now d loss / d x
+  }
+  {
+    const int64_t tot = (int64_t)Tk * d;
+    hipLaunchKernelGGL(pm_embed_bwd_kernel, dim3((unsigned)std::min<int64_t>(4096, (tot + 255) / 256)), dim3(256), 0, st,
+                       tokens, dx, g + U(0).off, Tk, d, V);
+  }
+  PM_HIP(hipGetLastError());
+  return PM_OK;
+}
+
 template <typename T>
 pm_status enqueue_step(pm_ctx* c, const void* x, const void* y, bool first_micro, bool last_micro) {
   const int par = c->par();
@@ -418,7 +641,8 @@ pm_status enqueue_step(pm_ctx* c, const void* x, const void* y, bool first_micro
     pm_status qs = quiesce(c);
     if (qs != PM_OK) return qs;
   }
-  pm_status s = launch_fwd_bwd<T>(c, x, y, first_micro ? 0 : 1, par);
+  pm_status s = c->o.arch == PM_ARCH_TRANSFORMER ? launch_tfm<T>(c, x, y, first_micro ? 0 : 1, par)
+                                                 : launch_fwd_bwd<T>(c, x, y, first_micro ? 0 : 1, par);
   if (s != PM_OK) return s;
   if (last_micro) {
     if (c->overlap && !c->prof_on) {
@@ -444,7 +668,7 @@ pm_status check_unit(pm_ctx* c, int32_t layer, size_t n) {
   if (!c) return fail(PM_EINVAL, "NULL context");
   if (layer < 0 || layer >= c->L) return fail(PM_EINVAL, "unit index %d outside 0..%d", layer, c->L - 1);
   const Unit& u = c->lay.units[layer];
-  if ((int64_t)n != u.nw + u.d.n_out) return fail(PM_EINVAL, "unit %d holds %lld values, caller said %zu", layer, (long long)(u.nw + u.d.n_out), n);
+  if ((int64_t)n != u.nw + u.nb) return fail(PM_EINVAL, "unit %d holds %lld values, caller said %zu", layer, (long long)(u.nw + u.nb), n);
   return PM_OK;
 }
 
@@ -624,7 +848,7 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
   for (int l = 0; l < L; ++l) {
     const Unit& u = lay.units[l];
     std::memcpy(&w0[u.off], init_weights_host[l], sizeof(float) * u.nw);
-    std::memcpy(&w0[u.off + u.boff], init_weights_host[l] + u.nw, sizeof(float) * u.d.n_out);
+    if (u.nb) std::memcpy(&w0[u.off + u.boff], init_weights_host[l] + u.nw, sizeof(float) * u.nb);
     for (int64_t ch = u.off / PM_CHUNK; ch < (u.off + u.n_pad) / PM_CHUNK; ++ch) chunk_layer[ch] = l;
     PmLayerStatic& S = ls[l];
     S.off = u.off; S.n_pad = u.n_pad; S.ring_off = u.ring_off; S.R = u.R; S.tau_f = u.tau_f; S.tau_b = u.tau_b;
@@ -644,7 +868,23 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
   if ((e = hipMemcpyAsync(c->arena + lay.chunk_off, chunk_layer.data(), chunk_layer.size() * 4, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy chunk table");
   if ((e = hipMemcpyAsync(c->arena + lay.ls_off, ls.data(), ls.size() * sizeof(PmLayerStatic), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy unit table");
   std::vector<PmGemmProb<PmEpiBwdWeight>> probs;
-  if (c->o.dtype == PM_BF16) {
+  std::vector<float> pos;
+  std::vector<int64_t> zero_tab;
+  if (c->o.arch == PM_ARCH_TRANSFORMER) {
+    // fixed sinusoidal positions pos[s, 2i] = sin(s / 10000^(2i/d)), pos[s, 2i+1] = cos(same)
+    const int S = c->o.seq_len, d = lay.units[0].d.n_out;
+    pos.resize((size_t)S * d);
+    for (int sidx = 0; sidx < S; ++sidx)
+      for (int j = 0; j < d; ++j) {
+        const double ang = (double)sidx / std::pow(10000.0, (double)(j & ~1) / (double)d);
+        pos[(size_t)sidx * d + j] = (float)((j & 1) ? std::cos(ang) : std::sin(ang));
+      }
+    for (int l = 0; l < L; ++l)
+      if (lay.units[l].d.kind != PM_LINEAR) { zero_tab.push_back(lay.units[l].off); zero_tab.push_back(lay.units[l].n_pad); }
+    if ((e = hipMemcpyAsync(c->arena + lay.t_pos, pos.data(), pos.size() * 4, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy positions");
+    if ((e = hipMemcpyAsync(c->arena + lay.t_zero, zero_tab.data(), zero_tab.size() * 8, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy region table");
+  }
+  if (c->o.dtype == PM_BF16 && c->o.arch == PM_ARCH_CHAIN) {
     // weight-gradient problem tables (first microbatch: overwrite, later ones: accumulate)
     const int M = c->o.microbatch;
     float* g = c->at<float>(lay.g_off);
@@ -742,12 +982,12 @@ pm_status pm_state(pm_ctx* c, int32_t which, int32_t layer, float* dst, size_t n
     PM_HIP(hipStreamSynchronize(c->stream));
     auto widen = [](bf16_t h) { uint32_t b = (uint32_t)h << 16; float f; std::memcpy(&f, &b, 4); return f; };
     for (int64_t i = 0; i < u.nw; ++i) dst[i] = widen(tmp[i]);
-    for (int64_t i = 0; i < u.d.n_out; ++i) dst[u.nw + i] = widen(tmp[u.boff + i]);
+    for (int64_t i = 0; i < u.nb; ++i) dst[u.nw + i] = widen(tmp[u.boff + i]);
     return PM_OK;
   }
   const float* src = c->at<float>(base) + u.off;
   PM_HIP(hipMemcpyAsync(dst, src, sizeof(float) * u.nw, hipMemcpyDeviceToHost, c->stream));
-  PM_HIP(hipMemcpyAsync(dst + u.nw, src + u.boff, sizeof(float) * u.d.n_out, hipMemcpyDeviceToHost, c->stream));
+  if (u.nb) PM_HIP(hipMemcpyAsync(dst + u.nw, src + u.boff, sizeof(float) * u.nb, hipMemcpyDeviceToHost, c->stream));
   PM_HIP(hipStreamSynchronize(c->stream));
   return PM_OK;
 }
@@ -802,7 +1042,7 @@ pm_status pm_set_grads(pm_ctx* c, int32_t layer, const float* src, size_t n) {
   const Unit& u = c->lay.units[layer];
   float* g = c->at<float>(c->lay.g_off) + u.off;
   PM_HIP(hipMemcpyAsync(g, src, sizeof(float) * u.nw, hipMemcpyHostToDevice, c->stream));
-  PM_HIP(hipMemcpyAsync(g + u.boff, src + u.nw, sizeof(float) * u.d.n_out, hipMemcpyHostToDevice, c->stream));
+  if (u.nb) PM_HIP(hipMemcpyAsync(g + u.boff, src + u.nw, sizeof(float) * u.nb, hipMemcpyHostToDevice, c->stream));
   PM_HIP(hipStreamSynchronize(c->stream));
   return PM_OK;
 }
@@ -847,6 +1087,74 @@ pm_status pm_linear_bwd_weight(void* stream, int32_t dtype, int32_t M, int32_t n
   if (!dz_dev || !a_dev || !dW_dev) return fail(PM_EINVAL, "NULL argument");
   return dtype == PM_BF16 ? linear_bwd_weight_t<bf16_t>((hipStream_t)stream, M, n_in, n_out, dz_dev, a_dev, dW_dev, db_dev, accumulate)
                           : linear_bwd_weight_t<float>((hipStream_t)stream, M, n_in, n_out, dz_dev, a_dev, dW_dev, db_dev, accumulate);
+}
+
+pm_status pm_layernorm_fwd(void* stream, int32_t dtype, int32_t rows, int32_t d, const float* x_dev, const void* gain_dev,
+                           const void* bias_dev, void* y_dev, float* mean_dev, float* rstd_dev) {
+  if (dtype != PM_F32 && dtype != PM_BF16) return fail(PM_EINVAL, "dtype must be PM_F32 or PM_BF16");
+  if (rows < 1 || d < 1 || d > 1024) return fail(PM_EINVAL, "need rows >= 1 and 1 <= d <= 1024");
+  if (!x_dev || !gain_dev || !bias_dev || !y_dev || !mean_dev || !rstd_dev) return fail(PM_EINVAL, "NULL argument");
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == PM_BF16) {
+    const bf16_t* gp = (const bf16_t*)gain_dev;
+    pm_ln_fwd_launch<bf16_t>(st, x_dev, PmWLoc<bf16_t>{gp, nullptr, 0}, (int)((const bf16_t*)bias_dev - gp), (bf16_t*)y_dev,
+                             mean_dev, rstd_dev, rows, d);
+  } else {
+    const float* gp = (const float*)gain_dev;
+    pm_ln_fwd_launch<float>(st, x_dev, PmWLoc<float>{gp, nullptr, 0}, (int)((const float*)bias_dev - gp), (float*)y_dev,
+                            mean_dev, rstd_dev, rows, d);
+  }
+  PM_HIP(hipGetLastError());
+  return PM_OK;
+}
+
+pm_status pm_layernorm_bwd(void* stream, int32_t dtype, int32_t rows, int32_t d, const float* dy_dev, const float* x_dev,
+                           const float* mean_dev, const float* rstd_dev, const void* gain_bkwd_dev,
+                           const float* dx_res_dev, float* dx_dev, void* dx_t_dev, float* dgain_dev, float* dbias_dev) {
+  if (dtype != PM_F32 && dtype != PM_BF16) return fail(PM_EINVAL, "dtype must be PM_F32 or PM_BF16");
+  if (rows < 1 || d < 1 || d > 1024) return fail(PM_EINVAL, "need rows >= 1 and 1 <= d <= 1024");
+  if (!dy_dev || !x_dev || !mean_dev || !rstd_dev || !gain_bkwd_dev || !dx_dev || !dgain_dev || !dbias_dev)
+    return fail(PM_EINVAL, "NULL argument");
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == PM_BF16)
+    pm_ln_bwd_launch<bf16_t>(st, dy_dev, x_dev, mean_dev, rstd_dev, PmWLoc<bf16_t>{(const bf16_t*)gain_bkwd_dev, nullptr, 0},
+                             dx_res_dev, dx_dev, (bf16_t*)dx_t_dev, dgain_dev, dbias_dev, rows, d);
+  else
+    pm_ln_bwd_launch<float>(st, dy_dev, x_dev, mean_dev, rstd_dev, PmWLoc<float>{(const float*)gain_bkwd_dev, nullptr, 0},
+                            dx_res_dev, dx_dev, (float*)dx_t_dev, dgain_dev, dbias_dev, rows, d);
+  PM_HIP(hipGetLastError());
+  return PM_OK;
+}
+
+pm_status pm_attention_fwd(void* stream, int32_t dtype, int32_t B, int32_t S, int32_t H, int32_t dh, const void* q_dev,
+                           const void* k_dev, const void* v_dev, void* o_dev, float* lse_dev) {
+  if (dtype != PM_F32 && dtype != PM_BF16) return fail(PM_EINVAL, "dtype must be PM_F32 or PM_BF16");
+  if (B < 1 || S < 1 || H < 1 || dh < 1) return fail(PM_EINVAL, "sizes must be positive");
+  if (!q_dev || !k_dev || !v_dev || !o_dev || !lse_dev) return fail(PM_EINVAL, "NULL argument");
+  hipStream_t st = (hipStream_t)stream;
+  const bool ok = dtype == PM_BF16
+      ? pm_attn_fwd_launch<bf16_t>(st, B, S, H, dh, (const bf16_t*)q_dev, (const bf16_t*)k_dev, (const bf16_t*)v_dev, (bf16_t*)o_dev, lse_dev)
+      : pm_attn_fwd_launch<float>(st, B, S, H, dh, (const float*)q_dev, (const float*)k_dev, (const float*)v_dev, (float*)o_dev, lse_dev);
+  if (!ok) return fail(PM_EINVAL, "attention shape (S %d, head size %d) not supported for this dtype", S, dh);
+  PM_HIP(hipGetLastError());
+  return PM_OK;
+}
+
+pm_status pm_attention_bwd(void* stream, int32_t dtype, int32_t B, int32_t S, int32_t H, int32_t dh, const void* q_dev,
+                           const void* k_dev, const void* v_dev, const void* o_dev, const void* do_dev,
+                           const float* lse_dev, void* dq_dev, void* dk_dev, void* dv_dev) {
+  if (dtype != PM_F32 && dtype != PM_BF16) return fail(PM_EINVAL, "dtype must be PM_F32 or PM_BF16");
+  if (B < 1 || S < 1 || H < 1 || dh < 1) return fail(PM_EINVAL, "sizes must be positive");
+  if (!q_dev || !k_dev || !v_dev || !o_dev || !do_dev || !lse_dev || !dq_dev || !dk_dev || !dv_dev) return fail(PM_EINVAL, "NULL argument");
+  hipStream_t st = (hipStream_t)stream;
+  const bool ok = dtype == PM_BF16
+      ? pm_attn_bwd_launch<bf16_t>(st, B, S, H, dh, (const bf16_t*)q_dev, (const bf16_t*)k_dev, (const bf16_t*)v_dev, (const bf16_t*)o_dev,
+                                   (const bf16_t*)do_dev, lse_dev, (bf16_t*)dq_dev, (bf16_t*)dk_dev, (bf16_t*)dv_dev)
+      : pm_attn_bwd_launch<float>(st, B, S, H, dh, (const float*)q_dev, (const float*)k_dev, (const float*)v_dev, (const float*)o_dev,
+                                  (const float*)do_dev, lse_dev, (float*)dq_dev, (float*)dk_dev, (float*)dv_dev);
+  if (!ok) return fail(PM_EINVAL, "attention shape (S %d, head size %d) not supported for this dtype", S, dh);
+  PM_HIP(hipGetLastError());
+  return PM_OK;
 }
 
 pm_status pm_profile_begin(pm_ctx* c, int32_t max_steps) {

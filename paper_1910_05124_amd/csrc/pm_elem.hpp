@@ -142,7 +142,7 @@ struct PmEpiFwd {
     if (a) pm_st8(a + o, aa);
   }
 };
-// backward data: dz_prev = acc * act'(z_prev)
+// backward data: dz_prev = acc * act'(z_prev)   (act == 0: dz_prev = acc, z_prev is not read)
 template <typename T>
 struct PmEpiBwdData {
   static constexpr bool kColSumA = false;
@@ -152,14 +152,19 @@ struct PmEpiBwdData {
   __device__ __forceinline__ void begin() {}
   __device__ __forceinline__ void operator()(int i, int j, float acc) const {
     const int64_t o = (int64_t)i * ld + j;
-    stf(dzprev + o, acc * pm_act_bwd(ldf(zprev + o), act));
+    stf(dzprev + o, act ? acc * pm_act_bwd(ldf(zprev + o), act) : acc);
   }
   __device__ __forceinline__ void op8(int i, int j, const float* acc) const {
     const int64_t o = (int64_t)i * ld + j;
     float zp[8], out[8];
-    pm_ld8(zprev + o, zp);
+    if (act) {
+      pm_ld8(zprev + o, zp);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) out[e] = acc[e] * pm_act_bwd(zp[e], act);
+      for (int e = 0; e < 8; ++e) out[e] = acc[e] * pm_act_bwd(zp[e], act);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) out[e] = acc[e];
+    }
     pm_st8(dzprev + o, out);
   }
 };

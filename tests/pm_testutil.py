@@ -16,7 +16,13 @@ def sched_dict(kind="const", base=0.01, init=0.0, factor=1.0, interval=1):
 def make_oracle(w, params, tau_fwd, tau_bkwd, *, opt="sgdm", lr=0.01, beta=0.9, beta2=0.98, eps=1e-8,
                 weight_decay=0.0, clip_norm=0.0, D=0.9, K=0, t1=True, t2=True, N=1, sched=None,
                 gamma_override=None, model=None, keep_history=False, sync_warmup=0):
-    model = model or po.MLPModel(w.layers, w.loss)
+    if model is None:
+        if w.arch.get("kind") == "transformer":
+            from oracle.transformer_oracle import TransformerModel
+            a = w.arch
+            model = TransformerModel(a["n_layers"], a["d_model"], a["n_heads"], a["d_ff"], a["vocab"], a["seq"])
+        else:
+            model = po.MLPModel(w.layers, w.loss)
     o = dict(kind=opt, beta=beta, beta1=beta, beta2=beta2, eps=eps, weight_decay=weight_decay,
              clip_norm=clip_norm, D=D, K=K, t1=t1, t2=t2, N=N, gamma_override=gamma_override,
              sched=sched or dict(kind="const", base=lr), sync_warmup=sync_warmup)
@@ -34,16 +40,37 @@ def make_gpu(w, params, tau_fwd, tau_bkwd, *, opt="sgdm", lr=0.01, beta=0.9, bet
     o = pm.make_opts(opt=opt, beta1=beta, beta2=beta2, eps=eps, weight_decay=weight_decay, clip_norm=clip_norm,
                      D=D, gamma_override=gamma_override, t1=t1, t2=t2, N=N, dtype=dtype or w.dtype, loss=w.loss,
                      microbatch=w.microbatch, use_graph=use_graph, sync_warmup=sync_warmup,
-                     overlap_update=overlap_update)
+                     overlap_update=overlap_update, arch=w.arch.get("kind", "chain"),
+                     n_heads=w.arch.get("n_heads", 0), seq_len=w.arch.get("seq", 0))
     return pm.PipeMare(w.layers, w.P, tau_fwd, tau_bkwd, sc, o, params, stream=stream)
 
 
-def max_rel_err(gpu_weights, oracle_weights):
-    """Per unit ||w_gpu - w_oracle||_inf / ||w_oracle||_inf; returns the max over units and the list."""
+def max_rel_err(gpu_weights, oracle_weights, skip=None):
+    """Per unit ||w_gpu - w_oracle||_inf / ||w_oracle||_inf; returns the max over units and the list.
+    skip: {unit: slice} of entries left out of the difference (see key_bias_entries)."""
     errs = []
-    for a, b in zip(gpu_weights, oracle_weights):
-        errs.append(float(np.max(np.abs(a.astype(np.float64) - b)) / np.max(np.abs(b))))
+    for u, (a, b) in enumerate(zip(gpu_weights, oracle_weights)):
+        diff = np.abs(a.astype(np.float64) - b)
+        if skip and u in skip:
+            diff = diff.copy()
+            diff[skip[u]] = 0.0
+        errs.append(float(np.max(diff) / np.max(np.abs(b))))
     return max(errs), errs
+
+
+def key_bias_entries(w):
+    """Entries whose gradient is identically zero in exact arithmetic: the bias of every attention key
+    projection (adding a constant vector to all keys of a head shifts each query's scores by one
+    constant, which the softmax removes).  Under Adam, which normalises the gradient's magnitude
+    away, such an entry follows the rounding noise of whatever precision computed it - fp64 noise
+    (~1e-17, far below Adam's eps) in the oracle, fp32 / bf16 noise (above eps) on the GPU - so its
+    trajectory is not a property of the method and it is left out of the weight comparison.  It has no
+    effect on any other value (the same invariance).  tests/test_oracle_transformer.py pins that the
+    oracle's gradient there is zero to rounding."""
+    if w.arch.get("kind") != "transformer":
+        return {}
+    d = w.arch["d_model"]
+    return {1 + 8 * l + 2: slice(d * d, d * d + d) for l in range(w.arch["n_layers"])}
 
 
 class GivenGrads:

@@ -114,6 +114,27 @@ def test_two_weight_gradient_equals_autograd_construction():
     assert all(np.array_equal(a, b) for a, b in zip(grads, g2))
 
 
+def test_key_bias_gradient_is_zero_to_rounding():
+    """Softmax shift invariance: the bias of a key projection cannot change the loss, so its gradient
+    vanishes identically (the GPU parity tests leave these entries out of the weight comparison)."""
+    w, params, model, toks, tgt = _setup(seed=2)
+    rng = np.random.default_rng(3)
+    Fw = [p + 0.05 * rng.standard_normal(p.shape) for p in params]
+    Bw = [p + 0.05 * rng.standard_normal(p.shape) for p in params]
+    l0, grads = model.loss_and_grads(Fw, Bw, (toks, tgt))
+    d = model.d
+    for l in range(model.nl):
+        u = 1 + 8 * l + 2
+        gk = grads[u]
+        assert np.max(np.abs(gk[d * d:])) <= 1e-15 * max(1.0, np.max(np.abs(gk[:d * d])) * 1e3)
+        assert np.max(np.abs(gk[:d * d])) > 1e-6            # the matrix itself does matter
+        # and the loss really does not depend on it
+        F2 = [p.copy() for p in Fw]
+        F2[u][d * d:] += rng.standard_normal(d)
+        l1, _ = model.loss_and_grads(F2, Bw, (toks, tgt))
+        assert l1 == pytest.approx(l0, rel=1e-12)
+
+
 def test_causality():
     """Changing a later token must not change the loss terms of earlier positions."""
     w, params, model, toks, tgt = _setup()
