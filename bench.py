@@ -33,7 +33,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=1, help="workload index (0: tiny fp32 MLP, 1: 16-stage bf16 MLP)")
+    ap.add_argument("--config", type=int, default=1,
+                    help="workload index (0: tiny fp32 MLP, 1: 16-stage bf16 MLP (default, the headline workload), "
+                         "2: 6-layer Transformer, 4: 12-layer Transformer)")
     ap.add_argument("--launch", choices=["graph", "eager", "overlap"], default="graph",
                     help="overlap: eager launches, the update of step t on the library's second stream concurrent "
                          "with the forward of step t+1; graph: replay a captured HIP graph; eager: one stream")
@@ -60,15 +62,20 @@ def main():
     tau_fwd, tau_bkwd = pm.pm_delays(w.P, w.N, "pipemare")
     params = wl.init_params(w)
     n_params = int(sum(p.size for p in params))
-    stream_data = wl.BatchStream(w)
+    stream_data = wl.batch_stream(w)
+    is_tfm = w.arch.get("kind") == "transformer"
     launch = "eager" if args.no_graph else args.launch
     use_graph = launch == "graph"
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):
-        sched = pm.make_sched(kind="const", base=o["lr"], K=o["K"])
-        opts = pm.make_opts(opt=o["kind"], beta1=o["beta"], D=o["D"], weight_decay=o["weight_decay"], t1=True, t2=True,
+        sd = o.get("sched") or dict(kind="const", base=o["lr"])
+        sched = pm.make_sched(kind=sd["kind"], base=sd["base"], init=sd.get("init", 0.0), factor=sd.get("factor", 1.0),
+                              interval=sd.get("interval", sd.get("warmup", 1)), K=o["K"])
+        opts = pm.make_opts(opt=o["kind"], beta1=o["beta"], beta2=o.get("beta2", 0.98), eps=o.get("eps", 1e-8), D=o["D"],
+                            weight_decay=o["weight_decay"], t1=True, t2=True,
                             N=w.N, dtype=w.dtype, loss=w.loss, microbatch=w.microbatch, use_graph=use_graph,
-                            overlap_update=(launch == "overlap"))
+                            overlap_update=(launch == "overlap"), arch=w.arch.get("kind", "chain"),
+                            n_heads=w.arch.get("n_heads", 0), seq_len=w.arch.get("seq", 0))
         eng = pm.PipeMare(w.layers, w.P, tau_fwd, tau_bkwd, sched, opts, params, stream=side)
         pool = [stream_data.batch(k) for k in range(args.pool)]
         xs = [torch.from_numpy(x).cuda() for x, _ in pool]
@@ -110,14 +117,30 @@ def main():
     steps_per_s = args.steps / dt
     bpp = BYTES_PER_PARAM[(o["kind"], w.dtype)]
     upd_s = prof["update_ms"] * 1e-3
-    achieved = n_params * bpp / upd_s / 1e9 if upd_s > 0 else 0.0
-    gemm_flops = 6.0 * w.microbatch * sum(L.n_in * L.n_out for L in w.layers) - 2.0 * w.microbatch * w.layers[0].n_in * w.layers[0].n_out
+    # an embedding has no corrected backward weights (nothing flows through it): one 2- or 4-byte stream less
+    esz = 2 if w.dtype == "bf16" else 4
+    alg_bytes = sum(wl.n_params(L) * (bpp - (esz if L.kind == "embed" else 0)) for L in w.layers)
+    achieved = alg_bytes / upd_s / 1e9 if upd_s > 0 else 0.0
+    lin = [L for L in w.layers if L.kind == "linear"]
+    if is_tfm:
+        a = w.arch
+        tokens = w.microbatch * a["seq"]
+        # every Linear: forward, data gradient, weight gradient (2 M n_in n_out each); causal attention core:
+        # 2 products forward, 4 backward, each S^2 dh flops per (sequence, head) when only the lower triangle counts
+        gemm_flops = 6.0 * tokens * sum(L.n_in * L.n_out for L in lin)
+        attn_flops = 6.0 * a["seq"] ** 2 * (a["d_model"] // a["n_heads"]) * w.microbatch * a["n_heads"] * a["n_layers"]
+        gemm_flops += attn_flops
+        samples = tokens
+    else:
+        gemm_flops = 6.0 * w.microbatch * sum(L.n_in * L.n_out for L in lin) - 2.0 * w.microbatch * lin[0].n_in * lin[0].n_out
+        samples = w.microbatch
     gemm_s = (prof["fwd_ms"] + prof["bwd_ms"]) * 1e-3
     out = {
         "metric": "async pipeline train steps/s",
         "value": round(steps_per_s, 2),
         "unit": "steps/s",
-        "samples_per_s": round(steps_per_s * w.microbatch * w.N, 1),
+        "samples_per_s": round(steps_per_s * samples * w.N, 1),
+        "samples_unit": "tokens" if is_tfm else "rows",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -127,13 +150,14 @@ def main():
         "vs_baseline": None,
         "dtype": w.dtype if w.dtype != "f32" else "f32",
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.P}-stage MLP, {len(w.layers)} weight units, {n_params} params, "
-                               f"microbatch {w.microbatch}, PipeMare delays tau_fwd={tau_fwd[0]}..{tau_fwd[-1]}, tau_bkwd=0, "
+        "config": {"workload": f"{w.name}: {w.P}-stage {'Transformer' if is_tfm else 'MLP'}, {len(w.layers)} weight units, {n_params} params, "
+                               f"microbatch {w.microbatch}{' x ' + str(w.arch['seq']) + ' tokens' if is_tfm else ''}, "
+                               f"PipeMare delays tau_fwd={tau_fwd[0]}..{tau_fwd[-1]}, tau_bkwd=0, "
                                f"{o['kind']} beta {o['beta']}, T1 K={o['K']}, T2 D={o['D']}",
                    "launch": launch, "final_loss": round(stats["loss"], 5)},
         "roofline": {"kernel": "pm_fused_update_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic(w.name), "algorithmic_bytes": n_params * bpp,
+                     "traffic": measured_traffic(w.name), "algorithmic_bytes": alg_bytes,
                      "bytes_per_param": bpp, "params": n_params,
                      "avg_kernel_ms": round(prof["update_ms"], 5), "launches_timed": prof["n"]},
         "phases_ms": {"forward_loss": round(prof["fwd_ms"], 4), "backward": round(prof["bwd_ms"], 4),
@@ -141,7 +165,9 @@ def main():
         "stage_gemms": {"algorithmic_tflop_per_step": round(gemm_flops / 1e12, 5),
                         "achieved_tflops": round(gemm_flops / gemm_s / 1e12, 2) if gemm_s > 0 else None,
                         "frac_of_bf16_mfma_peak": round(gemm_flops / gemm_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5) if gemm_s > 0 else None,
-                        "note": "includes loss, bias-gradient and launch gaps of the eager profiling pass"},
+                        "note": "flops of the Linear products (and the attention core) over the whole forward + backward "
+                                "phase time of the eager profiling pass: loss, LayerNorm, bias-gradient, embedding kernels "
+                                "and launch gaps are inside that time"},
     }
     if args.cpu_steps > 0:
         out["cpu_baseline"] = cpu_baseline(w, params, tau_fwd, tau_bkwd, args.cpu_steps)
@@ -172,9 +198,9 @@ def cpu_baseline(w, params, tau_fwd, tau_bkwd, n_steps):
     except Exception:
         threads = os.cpu_count()
     o = w.opt
-    orc = make_oracle(w, params, tau_fwd, tau_bkwd, opt=o["kind"], lr=o["lr"], beta=o["beta"], D=o["D"], K=o["K"],
-                      weight_decay=o["weight_decay"])
-    stream = wl.BatchStream(w)
+    orc = make_oracle(w, params, tau_fwd, tau_bkwd, opt=o["kind"], lr=o["lr"], beta=o["beta"], beta2=o.get("beta2", 0.98),
+                      D=o["D"], K=o["K"], weight_decay=o["weight_decay"], sched=o.get("sched"))
+    stream = wl.batch_stream(w)
     batches = [stream.batch(k) for k in range(n_steps + 2)]
     for k in range(2):
         orc.step(batches[k])

@@ -227,7 +227,7 @@ pm_status pm_linear_bwd_weight(void* stream, int32_t dtype, int32_t M, int32_t n
 
 /* Weight-free and vector-weight operators of the Transformer stages as stand-alone primitives for
  * kernel-level tests and measurement.  rows = tokens, row r = sequence r / S, position r % S.
- * Element type of the "T" matrices per `dtype` (bf16 raw 16-bit, or fp32); d a multiple of 8.
+ * Element type of the "T" matrices per `dtype` (bf16 raw 16-bit, or fp32); d a multiple of 4 up to 1024.
  *   layernorm_fwd: y = (x - mean) * rstd * gain + bias        x fp32 [rows,d], gain/bias T [d] -> y T [rows,d],
  *                  mean, rstd fp32 [rows]
  *   layernorm_bwd: dx = (dx_res or 0) + rstd (dxh - mean(dxh) - xhat mean(dxh xhat)), dxh = dy * gain_bkwd

@@ -71,11 +71,13 @@ struct Layout {
   // Transformer activations (byte offsets; see launch_tfm).  Per layer: index [layer]
   struct TfmLayer {
     size_t x, mu1, rs1, n1, q, k, v, lse, o, h, mu2, rs2, n2, z1, f;
+    size_t dzq, dzk, dzv, dzo, dz1, dz2;   // d loss / d (output of Wq, Wk, Wv, Wo, W1, W2), kept until the weight gradients
   };
   std::vector<TfmLayer> tl;
   size_t t_xf, t_muf, t_rsf, t_nf, t_logits, t_dlogits;      // final LayerNorm and head
-  size_t t_dx, t_dxt, t_dn, t_dff, t_do, t_dq, t_dk, t_dv;   // backward scratch, reused by every layer
+  size_t t_dx, t_dn, t_do;                                   // backward scratch, reused by every layer
   size_t t_pos, t_zero;                                      // positions fp32 [S, d]; zero-region table
+  size_t t_wprobs, t_wtiles;                                 // grouped weight-gradient launch: problems (2 sets), tile starts
   int n_zero = 0;
   int64_t zero_max = 0;
 };
@@ -200,13 +202,15 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
       b.lse = take(Tk * o->n_heads * 4); b.o = take(Tk * d * e);
       b.h = take(Tk * d * 4); b.mu2 = take(Tk * 4); b.rs2 = take(Tk * 4); b.n2 = take(Tk * d * e);
       b.z1 = take(Tk * dff * e); b.f = take(Tk * dff * e);
+      b.dzq = take(Tk * d * e); b.dzk = take(Tk * d * e); b.dzv = take(Tk * d * e); b.dzo = take(Tk * d * e);
+      b.dz1 = take(Tk * dff * e); b.dz2 = take(Tk * d * e);
     }
     lay.t_xf = take(Tk * d * 4); lay.t_muf = take(Tk * 4); lay.t_rsf = take(Tk * 4); lay.t_nf = take(Tk * d * e);
     lay.t_logits = take(Tk * ldV * 4); lay.t_dlogits = take(Tk * ldV * e);
-    lay.t_dx = take(Tk * d * 4); lay.t_dxt = take(Tk * d * e); lay.t_dn = take(Tk * d * 4);
-    lay.t_dff = take(Tk * dff * e); lay.t_do = take(Tk * d * e);
-    lay.t_dq = take(Tk * d * e); lay.t_dk = take(Tk * d * e); lay.t_dv = take(Tk * d * e);
+    lay.t_dx = take(Tk * d * 4); lay.t_dn = take(Tk * d * 4); lay.t_do = take(Tk * d * e);
     lay.t_pos = take((size_t)o->seq_len * d * 4);
+    lay.t_wprobs = take(sizeof(PmGemmProb<PmEpiBwdWeight>) * 2 * L);
+    lay.t_wtiles = take(sizeof(int32_t) * (L + 1));
     // gradient regions that are accumulated with atomics and therefore cleared at the start of a
     // minibatch: the embedding table and every LayerNorm
     lay.n_zero = 0;
@@ -252,6 +256,7 @@ struct pm_ctx {
   // all weight-gradient products as one grouped MFMA launch (problem tables live in the arena)
   bool dw_grouped = false;
   int dw_maxI = 0, dw_maxJ = 0;
+  int dw_nprob = 0, dw_ntiles = 0;   // Transformer: problems and 128 x 128 tiles of the grouped launch
   // overlap of the update of step t with the forward of step t+1 (second stream owned by the library)
   bool overlap = false;
   int32_t min_tau_f = 0;
@@ -592,32 +597,45 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
   }
   float* dx = F(lay.t_dx);
   float* dn = F(lay.t_dn);
-  T* dxt = TT(lay.t_dxt);
-  wgrad(L - 1, TT(lay.t_dlogits), ldV, TT(lay.t_nf), V, d);
+  // Weight gradients depend only on stored tensors (dz of the unit, its forward input).  On the MFMA
+  // path they are deferred: every unit's dz stays in a buffer of its own and ONE grouped launch at the
+  // end computes all dW and db.  Otherwise each unit's products go out as they become available.
+  const bool grouped = c->dw_grouped;
+  auto wg = [&](int u, const T* dz, int ld_dz, const T* a_in, int n_out, int n_in) {
+    if (!grouped) wgrad(u, dz, ld_dz, a_in, n_out, n_in);
+  };
+  wg(L - 1, TT(lay.t_dlogits), ldV, TT(lay.t_nf), V, d);
   dgrad_f32(L - 1, TT(lay.t_dlogits), ldV, V, d, dn, 0);
-  ln_bwd(L - 2, dn, F(lay.t_xf), F(lay.t_muf), F(lay.t_rsf), nullptr, dx, dxt);
+  ln_bwd(L - 2, dn, F(lay.t_xf), F(lay.t_muf), F(lay.t_rsf), nullptr, dx, nl ? TT(lay.tl[nl - 1].dz2) : nullptr);
   for (int l = nl - 1; l >= 0; --l) {
     const Layout::TfmLayer& b = lay.tl[l];
     const int u = 1 + 8 * l;
     // y = h + f W2^T + b2
-    wgrad(u + 7, dxt, d, TT(b.f), d, dff);
-    dgrad_t(u + 7, dxt, d, dff, TT(b.z1), U(u + 6).d.act, TT(lay.t_dff));
-    wgrad(u + 6, TT(lay.t_dff), dff, TT(b.n2), dff, d);
-    dgrad_f32(u + 6, TT(lay.t_dff), dff, dff, d, dn, 0);
-    ln_bwd(u + 5, dn, F(b.h), F(b.mu2), F(b.rs2), dx, dx, dxt);          // dx is now d loss / d h
+    wg(u + 7, TT(b.dz2), d, TT(b.f), d, dff);
+    dgrad_t(u + 7, TT(b.dz2), d, dff, TT(b.z1), U(u + 6).d.act, TT(b.dz1));
+    wg(u + 6, TT(b.dz1), dff, TT(b.n2), dff, d);
+    dgrad_f32(u + 6, TT(b.dz1), dff, dff, d, dn, 0);
+    ln_bwd(u + 5, dn, F(b.h), F(b.mu2), F(b.rs2), dx, dx, TT(b.dzo));          // dx is now d loss / d h
     // h = x + o Wo^T + bo
-    wgrad(u + 4, dxt, d, TT(b.o), d, d);
-    dgrad_t(u + 4, dxt, d, d, nullptr, PM_ACT_NONE, TT(lay.t_do));
-    if (!pm_attn_bwd_launch<T>(st, B, S, H, dh, TT(b.q), TT(b.k), TT(b.v), TT(b.o), TT(lay.t_do), F(b.lse), TT(lay.t_dq),
-                               TT(lay.t_dk), TT(lay.t_dv)))
+    wg(u + 4, TT(b.dzo), d, TT(b.o), d, d);
+    dgrad_t(u + 4, TT(b.dzo), d, d, nullptr, PM_ACT_NONE, TT(lay.t_do));
+    if (!pm_attn_bwd_launch<T>(st, B, S, H, dh, TT(b.q), TT(b.k), TT(b.v), TT(b.o), TT(lay.t_do), F(b.lse), TT(b.dzq),
+                               TT(b.dzk), TT(b.dzv)))
       return fail(PM_EINVAL, "attention shape not supported");
-    wgrad(u + 1, TT(lay.t_dq), d, TT(b.n1), d, d);
-    wgrad(u + 2, TT(lay.t_dk), d, TT(b.n1), d, d);
-    wgrad(u + 3, TT(lay.t_dv), d, TT(b.n1), d, d);
-    dgrad_f32(u + 1, TT(lay.t_dq), d, d, d, dn, 0);
-    dgrad_f32(u + 2, TT(lay.t_dk), d, d, d, dn, 1);
-    dgrad_f32(u + 3, TT(lay.t_dv), d, d, d, dn, 1);
-    ln_bwd(u, dn, F(b.x), F(b.mu1), F(b.rs1), dx, dx, dxt);              // dx is now d loss / d x
+    wg(u + 1, TT(b.dzq), d, TT(b.n1), d, d);
+    wg(u + 2, TT(b.dzk), d, TT(b.n1), d, d);
+    wg(u + 3, TT(b.dzv), d, TT(b.n1), d, d);
+    dgrad_f32(u + 1, TT(b.dzq), d, d, d, dn, 0);
+    dgrad_f32(u + 2, TT(b.dzk), d, d, d, dn, 1);
+    dgrad_f32(u + 3, TT(b.dzv), d, d, d, dn, 1);
+    ln_bwd(u, dn, F(b.x), F(b.mu1), F(b.rs1), dx, dx, l ? TT(lay.tl[l - 1].dz2) : nullptr);   // dx is now d loss / d x
+  }
+  if constexpr (sizeof(T) == 2) {
+    if (grouped) {
+      const auto* tab = c->at<PmGemmProb<PmEpiBwdWeight>>(lay.t_wprobs) + (accumulate ? c->dw_nprob : 0);
+      hipLaunchKernelGGL((pm_gemm_big_grouped_kernel<PmBig128, false, false, PmEpiBwdWeight>), dim3(c->dw_ntiles),
+                         dim3(PmBig128::NT), 0, st, tab, c->at<int32_t>(lay.t_wtiles), c->dw_nprob);
+    }
   }
   {
     const int64_t tot = (int64_t)Tk * d;
@@ -883,6 +901,53 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
       if (lay.units[l].d.kind != PM_LINEAR) { zero_tab.push_back(lay.units[l].off); zero_tab.push_back(lay.units[l].n_pad); }
     if ((e = hipMemcpyAsync(c->arena + lay.t_pos, pos.data(), pos.size() * 4, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy positions");
     if ((e = hipMemcpyAsync(c->arena + lay.t_zero, zero_tab.data(), zero_tab.size() * 8, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy region table");
+    if (c->o.dtype == PM_BF16) {
+      // grouped weight-gradient launch: one problem per Linear unit, largest first
+      const int nl = (L - 3) / 8, Tk = c->o.microbatch * S, V = lay.units[0].d.n_in;
+      const int ldV = (int)round_up(V, 8);
+      float* g = c->at<float>(lay.g_off);
+      struct WP { int u; const bf16_t* dz; int ld_dz; const bf16_t* a_in; };
+      std::vector<WP> wp;
+      wp.push_back({L - 1, c->at<bf16_t>(lay.t_dlogits), ldV, c->at<bf16_t>(lay.t_nf)});
+      for (int l = 0; l < nl; ++l) {
+        const Layout::TfmLayer& b = lay.tl[l];
+        const int u = 1 + 8 * l;
+        wp.push_back({u + 1, c->at<bf16_t>(b.dzq), d, c->at<bf16_t>(b.n1)});
+        wp.push_back({u + 2, c->at<bf16_t>(b.dzk), d, c->at<bf16_t>(b.n1)});
+        wp.push_back({u + 3, c->at<bf16_t>(b.dzv), d, c->at<bf16_t>(b.n1)});
+        wp.push_back({u + 4, c->at<bf16_t>(b.dzo), d, c->at<bf16_t>(b.o)});
+        wp.push_back({u + 6, c->at<bf16_t>(b.dz1), lay.units[u + 6].d.n_out, c->at<bf16_t>(b.n2)});
+        wp.push_back({u + 7, c->at<bf16_t>(b.dz2), d, c->at<bf16_t>(b.f)});
+      }
+      auto tiles_of = [&](const WP& w) {
+        const pm_layer_desc& dd = lay.units[w.u].d;
+        return (int64_t)((dd.n_out + 127) / 128) * ((dd.n_in + 127) / 128);
+      };
+      std::stable_sort(wp.begin(), wp.end(), [&](const WP& a, const WP& b) { return tiles_of(a) > tiles_of(b); });
+      const int np = (int)wp.size();
+      probs.resize((size_t)2 * np);
+      std::vector<int32_t> starts(np + 1, 0);
+      bool fits = true;
+      for (int i = 0; i < np; ++i) {
+        const Unit& u = lay.units[wp[i].u];
+        fits = fits && pm_mfma_fits(u.d.n_out, u.d.n_in, Tk, wp[i].dz, 1, wp[i].ld_dz, wp[i].a_in, 0, 1, u.d.n_in);
+        for (int acc = 0; acc < 2; ++acc) {
+          PmGemmProb<PmEpiBwdWeight>& pr = probs[(size_t)acc * np + i];
+          pr.I = u.d.n_out; pr.J = u.d.n_in; pr.K = Tk;
+          pr.A = wp[i].dz; pr.lda = wp[i].ld_dz;
+          pr.B = PmWLoc<bf16_t>{wp[i].a_in, nullptr, 0}; pr.ldb = u.d.n_in;
+          pr.epi = PmEpiBwdWeight{g + u.off, u.d.n_in, acc, g + u.off + u.boff};
+        }
+        starts[i + 1] = starts[i] + (int32_t)tiles_of(wp[i]);
+      }
+      c->dw_grouped = fits;
+      c->dw_nprob = np;
+      c->dw_ntiles = starts[np];
+      if ((e = hipMemcpyAsync(c->arena + lay.t_wprobs, probs.data(), probs.size() * sizeof(probs[0]), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy problem table");
+      if ((e = hipMemcpyAsync(c->arena + lay.t_wtiles, starts.data(), starts.size() * 4, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy tile table");
+      if ((e = hipStreamSynchronize(st)) != hipSuccess) return bail(e, "synchronise after tables");   // `starts` goes out of scope
+      probs.clear();
+    }
   }
   if (c->o.dtype == PM_BF16 && c->o.arch == PM_ARCH_CHAIN) {
     // weight-gradient problem tables (first microbatch: overwrite, later ones: accumulate)
@@ -1092,15 +1157,17 @@ pm_status pm_linear_bwd_weight(void* stream, int32_t dtype, int32_t M, int32_t n
 pm_status pm_layernorm_fwd(void* stream, int32_t dtype, int32_t rows, int32_t d, const float* x_dev, const void* gain_dev,
                            const void* bias_dev, void* y_dev, float* mean_dev, float* rstd_dev) {
   if (dtype != PM_F32 && dtype != PM_BF16) return fail(PM_EINVAL, "dtype must be PM_F32 or PM_BF16");
-  if (rows < 1 || d < 1 || d > 1024) return fail(PM_EINVAL, "need rows >= 1 and 1 <= d <= 1024");
+  if (rows < 1 || d < 4 || d > 1024 || (d & 3)) return fail(PM_EINVAL, "need rows >= 1 and d a multiple of 4 in 4..1024");
   if (!x_dev || !gain_dev || !bias_dev || !y_dev || !mean_dev || !rstd_dev) return fail(PM_EINVAL, "NULL argument");
   hipStream_t st = (hipStream_t)stream;
   if (dtype == PM_BF16) {
     const bf16_t* gp = (const bf16_t*)gain_dev;
+    if (((const bf16_t*)bias_dev - gp) & 3) return fail(PM_EINVAL, "bias must lie a multiple of 4 elements after the gain");
     pm_ln_fwd_launch<bf16_t>(st, x_dev, PmWLoc<bf16_t>{gp, nullptr, 0}, (int)((const bf16_t*)bias_dev - gp), (bf16_t*)y_dev,
                              mean_dev, rstd_dev, rows, d);
   } else {
     const float* gp = (const float*)gain_dev;
+    if (((const float*)bias_dev - gp) & 3) return fail(PM_EINVAL, "bias must lie a multiple of 4 elements after the gain");
     pm_ln_fwd_launch<float>(st, x_dev, PmWLoc<float>{gp, nullptr, 0}, (int)((const float*)bias_dev - gp), (float*)y_dev,
                             mean_dev, rstd_dev, rows, d);
   }
@@ -1112,7 +1179,7 @@ pm_status pm_layernorm_bwd(void* stream, int32_t dtype, int32_t rows, int32_t d,
                            const float* mean_dev, const float* rstd_dev, const void* gain_bkwd_dev,
                            const float* dx_res_dev, float* dx_dev, void* dx_t_dev, float* dgain_dev, float* dbias_dev) {
   if (dtype != PM_F32 && dtype != PM_BF16) return fail(PM_EINVAL, "dtype must be PM_F32 or PM_BF16");
-  if (rows < 1 || d < 1 || d > 1024) return fail(PM_EINVAL, "need rows >= 1 and 1 <= d <= 1024");
+  if (rows < 1 || d < 4 || d > 1024 || (d & 3)) return fail(PM_EINVAL, "need rows >= 1 and d a multiple of 4 in 4..1024");
   if (!dy_dev || !x_dev || !mean_dev || !rstd_dev || !gain_bkwd_dev || !dx_dev || !dgain_dev || !dbias_dev)
     return fail(PM_EINVAL, "NULL argument");
   hipStream_t st = (hipStream_t)stream;

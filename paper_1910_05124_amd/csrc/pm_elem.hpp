@@ -15,9 +15,10 @@ __global__ __launch_bounds__(256) void pm_stage_input_kernel(const float* __rest
   }
 }
 
-// Softmax cross-entropy, mean over rows.  One wavefront per row; logits fp32 [M, ld].
-// Writes dz = (softmax - onehot)/M in the compute dtype (pad columns zero) and adds the row's
-// loss / M to hdr->loss.
+// Softmax cross-entropy, mean over rows.  One wavefront per row; logits fp32 [M, ld], ld a multiple
+// of 8.  Writes dz = (softmax - onehot)/M in the compute dtype (pad columns zero) and adds the row's
+// loss / M to hdr->loss.  Two passes over the row: running (max, sum of exponentials) per lane,
+// merged across the wave; then the gradient, eight columns per lane and access.
 template <typename T>
 __global__ __launch_bounds__(256) void pm_xent_kernel(const float* __restrict__ logits, const int32_t* __restrict__ y,
                                                       T* __restrict__ dz, int M, int C, int ld, PmStepHdr* hdr) {
@@ -25,21 +26,39 @@ __global__ __launch_bounds__(256) void pm_xent_kernel(const float* __restrict__ 
   const int lane = threadIdx.x & 63;
   if (row >= M) return;
   const float* z = logits + (int64_t)row * ld;
-  float mx = -3.0e38f;
-  for (int c = lane; c < C; c += 64) mx = fmaxf(mx, z[c]);
-  mx = pm_wave_max(mx);
-  float se = 0.f;
-  for (int c = lane; c < C; c += 64) se += __expf(z[c] - mx);
-  se = pm_wave_sum(se);
+  float mx = -3.0e38f, se = 0.f;
+  const int C4 = C >> 2;
+  for (int c = lane; c < C4; c += 64) {
+    const float4 v = reinterpret_cast<const float4*>(z)[c];
+    const float m4 = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
+    if (m4 > mx) {
+      se *= __expf(mx - m4);
+      mx = m4;
+    }
+    se += __expf(v.x - mx) + __expf(v.y - mx) + __expf(v.z - mx) + __expf(v.w - mx);
+  }
+  for (int c = 4 * C4 + lane; c < C; c += 64) {
+    const float v = z[c];
+    if (v > mx) {
+      se *= __expf(mx - v);
+      mx = v;
+    }
+    se += __expf(v - mx);
+  }
+  const float mall = pm_wave_max(mx);
+  se = pm_wave_sum(se * __expf(mx - mall));        // a lane that saw nothing has se = 0
   const int label = y[row];
   const bool label_ok = label >= 0 && label < C;      // an out-of-range label contributes nothing
   const float inv = 1.f / se, invM = 1.f / (float)M;
-  for (int c = lane; c < ld; c += 64) {
-    float v = 0.f;
-    if (c < C) v = (__expf(z[c] - mx) * inv - (c == label ? 1.f : 0.f)) * invM;
-    stf(dz + (int64_t)row * ld + c, v);
+  for (int c = lane * 8; c < ld; c += 512) {
+    float v[8], o[8];
+    pm_ld8(z + c, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      o[e] = (c + e < C) ? (__expf(v[e] - mall) * inv - (c + e == label ? 1.f : 0.f)) * invM : 0.f;
+    pm_st8(dz + (int64_t)row * ld + c, o);
   }
-  if (lane == 0 && label_ok) atomicAdd(&hdr->loss, (logf(se) + mx - z[label]) * invM);
+  if (lane == 0 && label_ok) atomicAdd(&hdr->loss, (logf(se) + mall - z[label]) * invM);
 }
 
 // Mean squared error over all M*C outputs: dz = 2 (out - y) / (M C).

@@ -388,18 +388,22 @@ struct PmBigCfg {
   static constexpr int WPE = (BI_ / WI_) * (BJ_ / WJ_) >= 128 * 128 ? 1 : 2;
 };
 
+template <class Cfg, bool AKC, bool BKC>
+struct PmBigLds {
+  static constexpr int elems = 2 * (PmBigTile<Cfg::BI, AKC>::elems + PmBigTile<Cfg::BJ, BKC>::elems);
+};
+
+// id: index of this block among the tiles_i * tiles_j blocks of the problem
 template <class Cfg, bool AKC, bool BKC, class Epi>
-__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(1, Cfg::WPE))) void pm_gemm_big_kernel(PmGemmProb<Epi> pr, int tiles_i, int tiles_j) {
+__device__ __forceinline__ void pm_gemm_big_body(const PmGemmProb<Epi>& pr, int id, int tiles_i, int tiles_j, bf16_t* smem) {
   constexpr int BI = Cfg::BI, BJ = Cfg::BJ, WI = Cfg::WI, WJ = Cfg::WJ, NT = Cfg::NT, BK = 64;
   constexpr int TI = BI / WI / 32, TJ = BJ / WJ / 32;
   using SA = PmBigTile<BI, AKC>;
   using SB = PmBigTile<BJ, BKC>;
-  __shared__ __attribute__((aligned(16))) bf16_t smem[2 * (SA::elems + SB::elems)];
   constexpr int STAGE = SA::elems + SB::elems;      // stage s: A at s*STAGE, B at s*STAGE + SA::elems
 
   // XCD-aware mapping: consecutive block ids land on consecutive XCDs (8 of them), so give each
   // XCD a contiguous range of tiles, and inside it walk the tiles in column panels of 8 row tiles.
-  int id = blockIdx.x;
   const int nblk = tiles_i * tiles_j;
   if ((nblk & 7) == 0) id = (id & 7) * (nblk >> 3) + (id >> 3);
   constexpr int GROUP = 8;
@@ -500,7 +504,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(1, Cfg:
   // fp32 tile row-major in a private region, then every lane takes 8 consecutive columns of a row,
   // so global accesses are 16-byte pieces of full 128-byte row segments instead of 2-byte scatters.
   constexpr int WT_I = TI * 32, WT_J = TJ * 32, ES = WT_J + 4;          // wave tile and its padded row stride
-  static_assert(sizeof(smem) >= (size_t)WI * WJ * WT_I * ES * 4, "epilogue staging does not fit the operand stages");
+  static_assert((size_t)PmBigLds<Cfg, AKC, BKC>::elems * 2 >= (size_t)WI * WJ * WT_I * ES * 4, "epilogue staging does not fit the operand stages");
   float* es = reinterpret_cast<float*>(smem) + (size_t)wave * WT_I * ES;
 #pragma unroll
   for (int a = 0; a < TI; ++a)
@@ -526,6 +530,30 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(1, Cfg:
       for (int e = 0; e < 8 && j + e < J; ++e) epi(i, j + e, vals[e]);
     }
   }
+}
+
+template <class Cfg, bool AKC, bool BKC, class Epi>
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(1, Cfg::WPE))) void pm_gemm_big_kernel(PmGemmProb<Epi> pr, int tiles_i, int tiles_j) {
+  __shared__ __attribute__((aligned(16))) bf16_t smem[PmBigLds<Cfg, AKC, BKC>::elems];
+  pm_gemm_big_body<Cfg, AKC, BKC, Epi>(pr, blockIdx.x, tiles_i, tiles_j, smem);
+}
+
+// Many problems in one launch: tile_start[p] .. tile_start[p + 1] - 1 are the blocks of problem p
+// (tile_start has nprob + 1 entries, the last is the grid size).  All weight-gradient products of a
+// token-rich step go out together: single problems of 64 tiles cannot fill 256 compute units, a
+// few thousand tiles in one grid can, with no split of the contraction and no atomics.
+template <class Cfg, bool AKC, bool BKC, class Epi>
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(1, Cfg::WPE))) void pm_gemm_big_grouped_kernel(const PmGemmProb<Epi>* __restrict__ probs, const int* __restrict__ tile_start, int nprob) {
+  __shared__ __attribute__((aligned(16))) bf16_t smem[PmBigLds<Cfg, AKC, BKC>::elems];
+  const int bid = blockIdx.x;
+  int lo = 0, hi = nprob - 1;                 // largest p with tile_start[p] <= bid
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (tile_start[mid] <= bid) lo = mid; else hi = mid - 1;
+  }
+  const PmGemmProb<Epi> pr = probs[lo];
+  const int ti = (pr.I + Cfg::BI - 1) / Cfg::BI, tj = (pr.J + Cfg::BJ - 1) / Cfg::BJ;
+  pm_gemm_big_body<Cfg, AKC, BKC, Epi>(pr, bid - tile_start[lo], ti, tj, smem);
 }
 
 // 128 x 128 block, 4 waves x (64 x 64): 80 KB of LDS, so two blocks share a CU and cover each

@@ -115,28 +115,61 @@ __global__ __launch_bounds__(256) void pm_embed_bwd_kernel(const int32_t* __rest
   }
 }
 
+__device__ __forceinline__ float4 pm_ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 pm_ld4(const bf16_t* p) {
+  const uint2 a = *reinterpret_cast<const uint2*>(p);
+  return make_float4(__uint_as_float(a.x << 16), __uint_as_float(a.x & 0xffff0000u), __uint_as_float(a.y << 16),
+                     __uint_as_float(a.y & 0xffff0000u));
+}
+__device__ __forceinline__ void pm_st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void pm_st4(bf16_t* p, float4 v) {
+  uint2 o;
+  o.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+  o.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+  *reinterpret_cast<uint2*>(p) = o;
+}
+
 // ---------------------------------------------------------------------------------------------
-// LayerNorm forward: one wavefront per row.  Stores mean and 1/sqrt(var + eps) for the backward.
-// gb: gain at offset 0, bias at offset boff of the unit's ring slot.
+// LayerNorm forward: one wavefront per row, the row held in registers (lane l owns columns
+// 256 c + 4 l .. + 3, d <= 256 NC, d a multiple of 4).  Stores mean and 1/sqrt(var + eps) for the
+// backward.  gb: gain at offset 0, bias at offset boff of the unit's ring slot.
 // ---------------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, int NC>
 __global__ __launch_bounds__(256) void pm_ln_fwd_kernel(const float* __restrict__ x, PmWLoc<T> gb, int boff,
                                                         T* __restrict__ out, float* __restrict__ mean,
                                                         float* __restrict__ rstd, int rows, int d) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (row >= rows) return;
-  const float* xr = x + (int64_t)row * d;
+  const int64_t ro = (int64_t)row * d;
+  float4 xv[NC];
   float s = 0.f;
-  for (int j = lane; j < d; j += 64) s += xr[j];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int j = 256 * c + 4 * lane;
+    xv[c] = j < d ? pm_ld4(x + ro + j) : make_float4(0.f, 0.f, 0.f, 0.f);
+    s += xv[c].x + xv[c].y + xv[c].z + xv[c].w;
+  }
   const float mu = pm_wave_sum(s) / (float)d;
   float v = 0.f;
-  for (int j = lane; j < d; j += 64) {
-    const float c = xr[j] - mu;
-    v += c * c;
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int j = 256 * c + 4 * lane;
+    if (j < d) {
+      xv[c] = make_float4(xv[c].x - mu, xv[c].y - mu, xv[c].z - mu, xv[c].w - mu);
+      v += xv[c].x * xv[c].x + xv[c].y * xv[c].y + xv[c].z * xv[c].z + xv[c].w * xv[c].w;
+    }
   }
   const float rs = rsqrtf(pm_wave_sum(v) / (float)d + PM_LN_EPS);
   const T* g = gb.get();
-  for (int j = lane; j < d; j += 64) stf(out + (int64_t)row * d + j, (xr[j] - mu) * rs * ldf(g + j) + ldf(g + boff + j));
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int j = 256 * c + 4 * lane;
+    if (j < d) {
+      const float4 gg = pm_ld4(g + j), bb = pm_ld4(g + boff + j);
+      pm_st4(out + ro + j, make_float4(xv[c].x * rs * gg.x + bb.x, xv[c].y * rs * gg.y + bb.y, xv[c].z * rs * gg.z + bb.z,
+                                       xv[c].w * rs * gg.w + bb.w));
+    }
+  }
   if (lane == 0) {
     mean[row] = mu;
     rstd[row] = rs;
@@ -149,67 +182,85 @@ __global__ __launch_bounds__(256) void pm_ln_fwd_kernel(const float* __restrict_
 //   dgain += sum_rows dy * xhat,  dbias += sum_rows dy      (fp32 atomics, one set per block)
 // dx_res is the gradient already on the residual stream (same shape); dx_out may alias it.
 // dx_out_t (optional) receives a copy in the compute dtype for the GEMMs that consume it.
-// Each block takes 32 rows (4 waves x 8); lane l owns columns l, l+64, ... (d <= 64 * CPL).
+// Block = 8 waves x 4 rows; lane l owns columns 256 c + 4 l .. + 3 (16-byte accesses), d <= 256 NC,
+// d a multiple of 4.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int CPL>
-__global__ __launch_bounds__(256) void pm_ln_bwd_kernel(const float* __restrict__ dy, const float* __restrict__ x,
+template <typename T, int NC>
+__global__ __launch_bounds__(512) void pm_ln_bwd_kernel(const float* __restrict__ dy, const float* __restrict__ x,
                                                         const float* __restrict__ mean, const float* __restrict__ rstd,
                                                         PmWLoc<T> gain_bkwd, const float* dx_res, float* dx_out,
                                                         T* dx_out_t, float* __restrict__ dgain, float* __restrict__ dbias,
                                                         int rows, int d) {
+  __shared__ float red[2][256 * NC];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const T* g = gain_bkwd.get();
-  float gj[CPL], ag[CPL], ab[CPL];
-#pragma unroll
-  for (int c = 0; c < CPL; ++c) {
-    const int j = lane + 64 * c;
-    gj[c] = j < d ? ldf(g + j) : 0.f;
-    ag[c] = 0.f;
-    ab[c] = 0.f;
+  for (int j = threadIdx.x; j < 256 * NC; j += 512) {
+    red[0][j] = 0.f;
+    red[1][j] = 0.f;
   }
-  for (int r = 0; r < 8; ++r) {
-    const int row = blockIdx.x * 32 + wave * 8 + r;
+  const T* g = gain_bkwd.get();
+  const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 gj[NC], ag[NC], ab[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int j = 256 * c + 4 * lane;
+    gj[c] = j < d ? pm_ld4(g + j) : zero4;
+    ag[c] = zero4;
+    ab[c] = zero4;
+  }
+  for (int r = 0; r < 4; ++r) {
+    const int row = blockIdx.x * 32 + wave * 4 + r;
     if (row >= rows) break;                                   // wave-uniform
     const float mu = mean[row], rs = rstd[row];
-    float xh[CPL], dxh[CPL], s1 = 0.f, s2 = 0.f;
+    const int64_t ro = (int64_t)row * d;
+    float4 xh[NC], dxh[NC], rr[NC];
+    float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) {
-      const int j = lane + 64 * c;
-      float dyv = 0.f, xv = 0.f;
+    for (int c = 0; c < NC; ++c) {
+      const int j = 256 * c + 4 * lane;
+      float4 dyv = zero4, xv = zero4;
+      rr[c] = zero4;
       if (j < d) {
-        dyv = dy[(int64_t)row * d + j];
-        xv = (x[(int64_t)row * d + j] - mu) * rs;
+        dyv = pm_ld4(dy + ro + j);
+        xv = pm_ld4(x + ro + j);
+        if (dx_res) rr[c] = pm_ld4(dx_res + ro + j);
+        xv = make_float4((xv.x - mu) * rs, (xv.y - mu) * rs, (xv.z - mu) * rs, (xv.w - mu) * rs);
       }
       xh[c] = xv;
-      dxh[c] = dyv * gj[c];
-      ag[c] += dyv * xv;
-      ab[c] += dyv;
-      s1 += dxh[c];
-      s2 += dxh[c] * xv;
+      dxh[c] = make_float4(dyv.x * gj[c].x, dyv.y * gj[c].y, dyv.z * gj[c].z, dyv.w * gj[c].w);
+      ag[c].x += dyv.x * xv.x; ag[c].y += dyv.y * xv.y; ag[c].z += dyv.z * xv.z; ag[c].w += dyv.w * xv.w;
+      ab[c].x += dyv.x; ab[c].y += dyv.y; ab[c].z += dyv.z; ab[c].w += dyv.w;
+      s1 += dxh[c].x + dxh[c].y + dxh[c].z + dxh[c].w;
+      s2 += dxh[c].x * xv.x + dxh[c].y * xv.y + dxh[c].z * xv.z + dxh[c].w * xv.w;
     }
     s1 = pm_wave_sum(s1) / (float)d;
     s2 = pm_wave_sum(s2) / (float)d;
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) {
-      const int j = lane + 64 * c;
+    for (int c = 0; c < NC; ++c) {
+      const int j = 256 * c + 4 * lane;
       if (j < d) {
-        const int64_t o = (int64_t)row * d + j;
-        const float v = (dx_res ? dx_res[o] : 0.f) + rs * (dxh[c] - s1 - xh[c] * s2);
-        dx_out[o] = v;
-        if (dx_out_t) stf(dx_out_t + o, v);
+        float4 v;
+        v.x = rr[c].x + rs * (dxh[c].x - s1 - xh[c].x * s2);
+        v.y = rr[c].y + rs * (dxh[c].y - s1 - xh[c].y * s2);
+        v.z = rr[c].z + rs * (dxh[c].z - s1 - xh[c].z * s2);
+        v.w = rr[c].w + rs * (dxh[c].w - s1 - xh[c].w * s2);
+        pm_st4(dx_out + ro + j, v);
+        if (dx_out_t) pm_st4(dx_out_t + ro + j, v);
       }
     }
   }
-  __shared__ float red[2][4][64 * CPL];
+  __syncthreads();                                            // red is zeroed
 #pragma unroll
-  for (int c = 0; c < CPL; ++c) {
-    red[0][wave][lane + 64 * c] = ag[c];
-    red[1][wave][lane + 64 * c] = ab[c];
+  for (int c = 0; c < NC; ++c) {
+    const int j = 256 * c + 4 * lane;
+    atomicAdd(&red[0][j], ag[c].x); atomicAdd(&red[0][j + 1], ag[c].y);
+    atomicAdd(&red[0][j + 2], ag[c].z); atomicAdd(&red[0][j + 3], ag[c].w);
+    atomicAdd(&red[1][j], ab[c].x); atomicAdd(&red[1][j + 1], ab[c].y);
+    atomicAdd(&red[1][j + 2], ab[c].z); atomicAdd(&red[1][j + 3], ab[c].w);
   }
   __syncthreads();
-  for (int j = threadIdx.x; j < d; j += 256) {
-    atomicAdd(dgain + j, red[0][0][j] + red[0][1][j] + red[0][2][j] + red[0][3][j]);
-    atomicAdd(dbias + j, red[1][0][j] + red[1][1][j] + red[1][2][j] + red[1][3][j]);
+  for (int j = threadIdx.x; j < d; j += 512) {
+    atomicAdd(dgain + j, red[0][j]);
+    atomicAdd(dbias + j, red[1][j]);
   }
 }
 
@@ -374,7 +425,15 @@ __global__ void pm_attn_bwd_kernel(const T* __restrict__ q, const T* __restrict_
 template <typename T>
 inline bool pm_ln_fwd_launch(hipStream_t st, const float* x, PmWLoc<T> gb, int boff, T* out, float* mean, float* rstd,
                              int rows, int d) {
-  hipLaunchKernelGGL((pm_ln_fwd_kernel<T>), dim3((rows + 3) / 4), dim3(256), 0, st, x, gb, boff, out, mean, rstd, rows, d);
+  if ((d & 3) || (boff & 3)) return false;
+  const dim3 grid((rows + 3) / 4), blk(256);
+#define PM_LNF(NC) hipLaunchKernelGGL((pm_ln_fwd_kernel<T, NC>), grid, blk, 0, st, x, gb, boff, out, mean, rstd, rows, d)
+  if (d <= 256) PM_LNF(1);
+  else if (d <= 512) PM_LNF(2);
+  else if (d <= 768) PM_LNF(3);
+  else if (d <= 1024) PM_LNF(4);
+  else return false;
+#undef PM_LNF
   return true;
 }
 
@@ -382,13 +441,13 @@ template <typename T>
 inline bool pm_ln_bwd_launch(hipStream_t st, const float* dy, const float* x, const float* mean, const float* rstd,
                              PmWLoc<T> gain_bkwd, const float* dx_res, float* dx_out, T* dx_out_t, float* dgain,
                              float* dbias, int rows, int d) {
-  const dim3 grid((rows + 31) / 32), blk(256);
-#define PM_LNB(CPL) hipLaunchKernelGGL((pm_ln_bwd_kernel<T, CPL>), grid, blk, 0, st, dy, x, mean, rstd, gain_bkwd, dx_res, dx_out, dx_out_t, dgain, dbias, rows, d)
-  if (d <= 64) PM_LNB(1);
-  else if (d <= 128) PM_LNB(2);
-  else if (d <= 256) PM_LNB(4);
-  else if (d <= 512) PM_LNB(8);
-  else if (d <= 1024) PM_LNB(16);
+  if (d & 3) return false;
+  const dim3 grid((rows + 31) / 32), blk(512);
+#define PM_LNB(NC) hipLaunchKernelGGL((pm_ln_bwd_kernel<T, NC>), grid, blk, 0, st, dy, x, mean, rstd, gain_bkwd, dx_res, dx_out, dx_out_t, dgain, dbias, rows, d)
+  if (d <= 256) PM_LNB(1);
+  else if (d <= 512) PM_LNB(2);
+  else if (d <= 768) PM_LNB(3);
+  else if (d <= 1024) PM_LNB(4);
   else return false;
 #undef PM_LNB
   return true;

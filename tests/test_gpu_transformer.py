@@ -171,7 +171,7 @@ def test_tiny_transformer_modes(torch_cuda, case):
     dtype = "bf16" if case.endswith("bf16") else "f32"
     V = 61 if case != "gelu_ragged_vocab" else 45
     w = wl.transformer(2, 32, 4, 64, V, 10, 3, dtype=dtype, K=6,
-                       sched=dict(kind="warmup_invsqrt", base=2e-3, init=1e-5, warmup=5))
+                       sched=dict(kind="warmup_invsqrt", base=1e-3, init=1e-5, warmup=5))
     kw = _kw(w)
     tau, N = None, 1
     if case == "sgdm_bf16":

@@ -16,7 +16,8 @@ from typing import List, Tuple
 
 import numpy as np
 
-__all__ = ["Layer", "Workload", "config", "init_params", "BatchStream", "n_params", "transformer", "TokenStream"]
+__all__ = ["Layer", "Workload", "config", "init_params", "BatchStream", "n_params", "transformer", "TokenStream",
+           "batch_stream"]
 
 
 @dataclass(frozen=True)
@@ -68,6 +69,10 @@ def config(idx: int) -> Workload:
     0: tiny fp32 4-stage MLP (64-wide, ReLU, scalar regression head, MSE).
     1: 16-stage MLP, 1024-wide, GELU, 10-class head sharing the last stage,
        bf16 compute with fp32 master weights.
+    2: 6-layer fine-grained Transformer (width 512, 8 heads, feed-forward 2048, vocabulary 8192,
+       32 sequences of 128 tokens), bf16 compute, AdamW.
+    4: 12-layer fine-grained Transformer (width 1024, 16 heads, feed-forward 4096, vocabulary 32000,
+       16 sequences of 512 tokens), bf16 compute, AdamW.
     """
     if idx == 0:
         return _mlp("mlp4_f32", [64, 64, 64, 64, 1], ["relu", "relu", "relu", "none"], [1, 2, 3, 4],
@@ -82,6 +87,20 @@ def config(idx: int) -> Workload:
                     N=1, loss="xent", dtype="bf16", microbatch=128, n_classes=10,
                     opt=dict(kind="sgdm", lr=0.001, beta=0.9, D=0.9, K=125, weight_decay=0.0),
                     steps=500, init="he")
+    if idx == 2:
+        # fine-grained 6-layer Transformer, one stage per weight matrix (P = 38, 51 weight units); AdamW with
+        # the linear warm-up of the paper's Transformer recipe (App. C: 8000 steps from 1e-7 to 5e-4,
+        # betas 0.9 / 0.98, weight decay 1e-4), T1 annealing over 5x the warm-up (Sec. 3.1), D = 0.1 (App. C)
+        return transformer(6, 512, 8, 2048, 8192, 128, 32, dtype="bf16", name="tfm6x512_bf16", steps=40,
+                           lr=5e-4, D=0.1, K=40000, weight_decay=1e-4,
+                           sched=dict(kind="warmup_invsqrt", base=5e-4, init=1e-7, warmup=8000))
+    if idx == 4:
+        # 12 layers, width 1024, 16 heads, feed-forward 4096, vocabulary 32000, sequences of 512 tokens:
+        # every weight unit a stage of its own: P = 99 (tau_fwd up to 197), ~217 M parameters
+        return transformer(12, 1024, 16, 4096, 32000, 512, 16, dtype="bf16", name="tfm12x1024_bf16", steps=6,
+                           ln_own_stage=True,
+                           lr=7e-4, D=0.1, K=40000, weight_decay=0.0,
+                           sched=dict(kind="warmup_invsqrt", base=7e-4, init=1e-7, warmup=8000))
     raise ValueError(f"unknown workload index {idx}")
 
 
@@ -155,28 +174,31 @@ class BatchStream:
 
 
 def transformer(n_layers: int, d_model: int, n_heads: int, d_ff: int, vocab: int, seq: int, microbatch: int,
-                dtype: str = "bf16", name: str | None = None, steps: int = 0, **opt) -> Workload:
-    """Fine-grained pre-LN causal Transformer: one pipeline stage per weight matrix (a LayerNorm rides
-    in the stage of the matrix that consumes it).  Units in topological order:
-    embed | per layer: ln1, Wq, Wk, Wv, Wo, ln2, W1, W2 | final ln, head.
-    Stages: embed = 1, then Wq, Wk, Wv, Wo, W1, W2 of every layer, head last: P = 6 * n_layers + 2."""
+                dtype: str = "bf16", name: str | None = None, steps: int = 0, ln_own_stage: bool = False, **opt) -> Workload:
+    """Fine-grained pre-LN causal Transformer: one pipeline stage per weight unit.  Units in topological
+    order: embed | per layer: ln1, Wq, Wk, Wv, Wo, ln2, W1, W2 | final ln, head.
+    ln_own_stage False: a LayerNorm rides in the stage of the matrix that consumes it, P = 6 n_layers + 2.
+    ln_own_stage True: every unit is a stage of its own, P = 8 n_layers + 3."""
     layers = [Layer("embed", vocab, d_model, "none", 1)]
     st = 1
-    for _ in range(n_layers):
-        layers.append(Layer("layernorm", d_model, d_model, "none", st + 1))
-        for _w in range(3):
+
+    def add(kind, n_in, n_out, act, new_stage):
+        nonlocal st
+        if new_stage:
             st += 1
-            layers.append(Layer("linear", d_model, d_model, "none", st))
-        st += 1
-        layers.append(Layer("linear", d_model, d_model, "none", st))
-        layers.append(Layer("layernorm", d_model, d_model, "none", st + 1))
-        st += 1
-        layers.append(Layer("linear", d_model, d_ff, "relu", st))
-        st += 1
-        layers.append(Layer("linear", d_ff, d_model, "none", st))
-    st += 1
-    layers.append(Layer("layernorm", d_model, d_model, "none", st))
-    layers.append(Layer("linear", d_model, vocab, "none", st))
+        layers.append(Layer(kind, n_in, n_out, act, st))
+
+    for _ in range(n_layers):
+        add("layernorm", d_model, d_model, "none", True)
+        add("linear", d_model, d_model, "none", ln_own_stage)
+        add("linear", d_model, d_model, "none", True)
+        add("linear", d_model, d_model, "none", True)
+        add("linear", d_model, d_model, "none", True)
+        add("layernorm", d_model, d_model, "none", True)
+        add("linear", d_model, d_ff, "relu", ln_own_stage)
+        add("linear", d_ff, d_model, "none", True)
+    add("layernorm", d_model, d_model, "none", True)
+    add("linear", d_model, vocab, "none", ln_own_stage)
     o = dict(kind="adamw", lr=5e-4, beta=0.9, beta2=0.98, eps=1e-8, D=0.1, K=0, weight_decay=0.0,
              sched=dict(kind="warmup_invsqrt", base=5e-4, init=1e-7, warmup=40))
     o.update(opt)
@@ -204,3 +226,8 @@ class TokenStream:
         u = rng.random((wl.microbatch, S + 1))
         ids = np.minimum(np.searchsorted(self.cdf, u), V - 1).astype(np.int32)
         return np.ascontiguousarray(ids[:, :S]), np.ascontiguousarray(ids[:, 1:])
+
+
+def batch_stream(wl: Workload):
+    """The microbatch generator that fits the workload."""
+    return TokenStream(wl) if wl.arch.get("kind") == "transformer" else BatchStream(wl)
