@@ -257,6 +257,7 @@ struct pm_ctx {
   bool dw_grouped = false;
   int dw_maxI = 0, dw_maxJ = 0;
   int dw_nprob = 0, dw_ntiles = 0;   // Transformer: problems and 128 x 128 tiles of the grouped launch
+  bool dw_aligned = false;           // no tile of the grouped launch needs a bounds test
   // overlap of the update of step t with the forward of step t+1 (second stream owned by the library)
   bool overlap = false;
   int32_t min_tau_f = 0;
@@ -633,8 +634,12 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
   if constexpr (sizeof(T) == 2) {
     if (grouped) {
       const auto* tab = c->at<PmGemmProb<PmEpiBwdWeight>>(lay.t_wprobs) + (accumulate ? c->dw_nprob : 0);
-      hipLaunchKernelGGL((pm_gemm_big_grouped_kernel<PmBig128, false, false, PmEpiBwdWeight>), dim3(c->dw_ntiles),
-                         dim3(PmBig128::NT), 0, st, tab, c->at<int32_t>(lay.t_wtiles), c->dw_nprob);
+      if (c->dw_aligned)
+        hipLaunchKernelGGL((pm_gemm_big_grouped_kernel<PmBig128, false, false, false, PmEpiBwdWeight>), dim3(c->dw_ntiles),
+                           dim3(PmBig128::NT), 0, st, tab, c->at<int32_t>(lay.t_wtiles), c->dw_nprob);
+      else
+        hipLaunchKernelGGL((pm_gemm_big_grouped_kernel<PmBig128, false, false, true, PmEpiBwdWeight>), dim3(c->dw_ntiles),
+                           dim3(PmBig128::NT), 0, st, tab, c->at<int32_t>(lay.t_wtiles), c->dw_nprob);
     }
   }
   {
@@ -927,10 +932,11 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
       const int np = (int)wp.size();
       probs.resize((size_t)2 * np);
       std::vector<int32_t> starts(np + 1, 0);
-      bool fits = true;
+      bool fits = true, aligned = true;
       for (int i = 0; i < np; ++i) {
         const Unit& u = lay.units[wp[i].u];
         fits = fits && pm_mfma_fits(u.d.n_out, u.d.n_in, Tk, wp[i].dz, 1, wp[i].ld_dz, wp[i].a_in, 0, 1, u.d.n_in);
+        aligned = aligned && pm_big_aligned<PmBig128>(u.d.n_out, u.d.n_in, Tk);
         for (int acc = 0; acc < 2; ++acc) {
           PmGemmProb<PmEpiBwdWeight>& pr = probs[(size_t)acc * np + i];
           pr.I = u.d.n_out; pr.J = u.d.n_in; pr.K = Tk;
@@ -941,6 +947,7 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
         starts[i + 1] = starts[i] + (int32_t)tiles_of(wp[i]);
       }
       c->dw_grouped = fits;
+      c->dw_aligned = aligned;
       c->dw_nprob = np;
       c->dw_ntiles = starts[np];
       if ((e = hipMemcpyAsync(c->arena + lay.t_wprobs, probs.data(), probs.size() * sizeof(probs[0]), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy problem table");

@@ -29,6 +29,8 @@
 // base pointers multiples of 8 elements; memory readable up to the next multiple of 8 along the
 // contiguous index, holding zeros beyond the logical extent.
 #pragma once
+#include <type_traits>
+
 #include "pm_common.hpp"
 #include "pm_elem.hpp"
 
@@ -329,6 +331,9 @@ struct PmBigLoader {
   static_assert(S::chunks % NT == 0, "tile must split evenly over the block");
   static constexpr int PER = S::chunks / NT;
   uint4 r[PER];
+  // CHECK false: the tile lies fully inside the operand (no predicates: the loads of a slab issue
+  // back to back and the compiler can count them exactly when it waits for an older slab)
+  template <bool CHECK>
   __device__ __forceinline__ void load(const bf16_t* __restrict__ X, int64_t ld, int r0, int k0, int R, int K) {
     const int R8 = (R + 7) & ~7, K8 = (K + 7) & ~7;
 #pragma unroll
@@ -338,10 +343,10 @@ struct PmBigLoader {
       uint4 v = make_uint4(0, 0, 0, 0);
       if (KC) {
         const int row = r0 + lr, k = k0 + lc;
-        if (row < R && k < K8) v = *reinterpret_cast<const uint4*>(X + (int64_t)row * ld + k);
+        if (!CHECK || (row < R && k < K8)) v = *reinterpret_cast<const uint4*>(X + (int64_t)row * ld + k);
       } else {
         const int k = k0 + lr, row = r0 + lc;
-        if (k < K && row < R8) v = *reinterpret_cast<const uint4*>(X + (int64_t)k * ld + row);
+        if (!CHECK || (k < K && row < R8)) v = *reinterpret_cast<const uint4*>(X + (int64_t)k * ld + row);
       }
       r[p] = v;
     }
@@ -386,6 +391,8 @@ struct PmBigCfg {
   // waves per SIMD the register budget is sized for: the 128 x 128 wave tile holds 256 accumulator
   // registers and needs the whole 512-entry file (its LDS footprint allows one block per CU anyway)
   static constexpr int WPE = (BI_ / WI_) * (BJ_ / WJ_) >= 128 * 128 ? 1 : 2;
+  // first k-step (of 4) behind which the staged next slab is written to LDS
+  static constexpr int STORE_FROM = (BI_ / WI_) * (BJ_ / WJ_) >= 128 * 128 ? 2 : 0;
 };
 
 template <class Cfg, bool AKC, bool BKC>
@@ -393,8 +400,15 @@ struct PmBigLds {
   static constexpr int elems = 2 * (PmBigTile<Cfg::BI, AKC>::elems + PmBigTile<Cfg::BJ, BKC>::elems);
 };
 
-// id: index of this block among the tiles_i * tiles_j blocks of the problem
-template <class Cfg, bool AKC, bool BKC, class Epi>
+// id: index of this block among the tiles_i * tiles_j blocks of the problem.
+// CHECK false: I, J multiples of the block tile and K a multiple of 64 (no bounds tests anywhere).
+//
+// Software pipeline over the 64-deep slabs of the contraction: two LDS stages and two register sets.
+// While the MFMAs of slab kt run on LDS stage kt & 1, the global loads of slab kt + 2 are issued into
+// the register set that slab kt came from, and slab kt + 1 (loaded one iteration earlier) moves from
+// the other register set into the other LDS stage, a part behind each k-step.  A load therefore has
+// more than a slab of MFMA time to arrive before it is waited for; one barrier per slab.
+template <class Cfg, bool AKC, bool BKC, bool CHECK, class Epi>
 __device__ __forceinline__ void pm_gemm_big_body(const PmGemmProb<Epi>& pr, int id, int tiles_i, int tiles_j, bf16_t* smem) {
   constexpr int BI = Cfg::BI, BJ = Cfg::BJ, WI = Cfg::WI, WJ = Cfg::WJ, NT = Cfg::NT, BK = 64;
   constexpr int TI = BI / WI / 32, TJ = BJ / WJ / 32;
@@ -436,21 +450,34 @@ __device__ __forceinline__ void pm_gemm_big_body(const PmGemmProb<Epi>& pr, int 
   using LA = PmBigLoader<BI, AKC, NT>;
   using LB = PmBigLoader<BJ, BKC, NT>;
   constexpr int QA = (LA::PER + 3) / 4, QB = (LB::PER + 3) / 4;
-  LA la;
-  LB lb;
+  LA la0, la1;
+  LB lb0, lb1;
   const int nk = (K + BK - 1) / BK;
-  la.load(A, lda, i0, 0, I, K);
-  lb.load(B, ldb, j0, 0, J, K);
-  la.store(smem);
-  lb.store(smem + SA::elems);
+  la0.template load<CHECK>(A, lda, i0, 0, I, K);
+  lb0.template load<CHECK>(B, ldb, j0, 0, J, K);
+  la0.store(smem);
+  lb0.store(smem + SA::elems);
+  if (nk > 1) {
+    la1.template load<CHECK>(A, lda, i0, BK, I, K);
+    lb1.template load<CHECK>(B, ldb, j0, BK, J, K);
+  }
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
+
+  // one slab: fa / fb = register set that is free (refilled with slab kt + 2), na / nb = register set
+  // holding slab kt + 1 (moved to the other LDS stage).  steady (compile-time): slabs kt + 1 and
+  // kt + 2 exist, so the loads and stores are unconditional and the compiler's wait counts before
+  // the LDS stores cover exactly the older register set.
+  auto slab = [&](auto steady, int kt, LA& fa_set, LB& fb_set, const LA& na_set, const LB& nb_set) {
+    constexpr bool STEADY = decltype(steady)::value;
     const int cur = kt & 1;
     const bf16_t* cA = smem + cur * STAGE;
     const bf16_t* cB = cA + SA::elems;
-    if (kt + 1 < nk) {
-      la.load(A, lda, i0, (kt + 1) * BK, I, K);
-      lb.load(B, ldb, j0, (kt + 1) * BK, J, K);
+    if (STEADY || kt + 2 < nk) {
+      fa_set.template load<CHECK>(A, lda, i0, (kt + 2) * BK, I, K);
+      fb_set.template load<CHECK>(B, ldb, j0, (kt + 2) * BK, J, K);
+      // keep the loads here, ahead of the slab's MFMAs (the instruction scheduler otherwise sinks
+      // them to the end of the slab to shorten register live ranges, which costs the latency cover)
+      __builtin_amdgcn_sched_barrier(0);
     }
     if (Epi::kColSumA && !AKC) {
       if (do_colsum && threadIdx.x < BI) {
@@ -479,71 +506,82 @@ __device__ __forceinline__ void pm_gemm_big_body(const PmGemmProb<Epi>& pr, int 
 #pragma unroll
         for (int b = 0; b < TJ; ++b)
           acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][a], fb[c][b], acc[a][b], 0, 0, 0);
-      // a quarter of the staged next slab goes to the other LDS stage behind each k-step's MFMAs
-      if (kt + 1 < nk) {
+      if (STEADY || kt + 1 < nk) {
         if (ks * QA < LA::PER) {
 #pragma unroll
           for (int q = 0; q < QA; ++q)
-            if (ks * QA + q < LA::PER) la.store_part(smem + (cur ^ 1) * STAGE, ks * QA + q);
+            if (ks * QA + q < LA::PER) na_set.store_part(smem + (cur ^ 1) * STAGE, ks * QA + q);
         }
         if (ks * QB < LB::PER) {
 #pragma unroll
           for (int q = 0; q < QB; ++q)
-            if (ks * QB + q < LB::PER) lb.store_part(smem + (cur ^ 1) * STAGE + SA::elems, ks * QB + q);
+            if (ks * QB + q < LB::PER) nb_set.store_part(smem + (cur ^ 1) * STAGE + SA::elems, ks * QB + q);
         }
       }
     }
     __syncthreads();
+  };
+  int kt = 0;
+  for (; kt + 3 < nk; kt += 2) {          // both slabs of the pair have successors kt + 2 and kt + 3
+    slab(std::true_type{}, kt, la0, lb0, la1, lb1);
+    slab(std::true_type{}, kt + 1, la1, lb1, la0, lb0);
+  }
+  for (; kt < nk; kt += 2) {              // the last one to three slabs
+    slab(std::false_type{}, kt, la0, lb0, la1, lb1);
+    if (kt + 1 < nk) slab(std::false_type{}, kt + 1, la1, lb1, la0, lb0);
   }
 
   epi.begin();
   if (Epi::kColSumA && !AKC) {
-    if (do_colsum && threadIdx.x < BI && i0 + (int)threadIdx.x < I) epi.colsum(i0 + threadIdx.x, colsum);
+    if (do_colsum && threadIdx.x < BI && (!CHECK || i0 + (int)threadIdx.x < I)) epi.colsum(i0 + threadIdx.x, colsum);
   }
-  // Epilogue through LDS (the operand stages are dead after the last barrier): each wave parks its
-  // fp32 tile row-major in a private region, then every lane takes 8 consecutive columns of a row,
-  // so global accesses are 16-byte pieces of full 128-byte row segments instead of 2-byte scatters.
+  // Epilogue through LDS (the operand stages are dead after the last barrier): each wave parks one
+  // 32-row stripe of its fp32 tile at a time, row-major in a private region, then every lane takes 8
+  // consecutive columns of a row, so global accesses are 16-byte pieces of full row segments instead
+  // of 2-byte scatters.  (A wave's LDS accesses complete in program order: no barrier is needed
+  // between parking and reading back inside one wave.)
   constexpr int WT_I = TI * 32, WT_J = TJ * 32, ES = WT_J + 4;          // wave tile and its padded row stride
-  static_assert((size_t)PmBigLds<Cfg, AKC, BKC>::elems * 2 >= (size_t)WI * WJ * WT_I * ES * 4, "epilogue staging does not fit the operand stages");
-  float* es = reinterpret_cast<float*>(smem) + (size_t)wave * WT_I * ES;
+  static_assert((size_t)PmBigLds<Cfg, AKC, BKC>::elems * 2 >= (size_t)WI * WJ * 32 * ES * 4, "epilogue staging does not fit the operand stages");
+  float* es = reinterpret_cast<float*>(smem) + (size_t)wave * 32 * ES;
+  const int wi0 = i0 + wi * WT_I, wj0 = j0 + wj * WT_J;
 #pragma unroll
-  for (int a = 0; a < TI; ++a)
+  for (int a = 0; a < TI; ++a) {
 #pragma unroll
     for (int b = 0; b < TJ; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v)
-        es[(a * 32 + 8 * (v >> 2) + 4 * kg + (v & 3)) * ES + b * 32 + lr] = acc[a][b][v];
-  const int wi0 = i0 + wi * WT_I, wj0 = j0 + wj * WT_J;
+        es[(8 * (v >> 2) + 4 * kg + (v & 3)) * ES + b * 32 + lr] = acc[a][b][v];
 #pragma unroll 4
-  for (int c = lane; c < WT_I * (WT_J / 8); c += 64) {
-    const int r = c / (WT_J / 8), c8 = (c % (WT_J / 8)) * 8;
-    const int i = wi0 + r, j = wj0 + c8;
-    if (i >= I || j >= J) continue;
-    float vals[8];
-    const float4 v0 = *reinterpret_cast<const float4*>(es + r * ES + c8);
-    const float4 v1 = *reinterpret_cast<const float4*>(es + r * ES + c8 + 4);
-    vals[0] = v0.x; vals[1] = v0.y; vals[2] = v0.z; vals[3] = v0.w;
-    vals[4] = v1.x; vals[5] = v1.y; vals[6] = v1.z; vals[7] = v1.w;
-    if (j + 8 <= J) {
-      epi.op8(i, j, vals);
-    } else {
-      for (int e = 0; e < 8 && j + e < J; ++e) epi(i, j + e, vals[e]);
+    for (int c = lane; c < 32 * (WT_J / 8); c += 64) {
+      const int r = c / (WT_J / 8), c8 = (c % (WT_J / 8)) * 8;
+      const int i = wi0 + a * 32 + r, j = wj0 + c8;
+      if (CHECK && (i >= I || j >= J)) continue;
+      float vals[8];
+      const float4 v0 = *reinterpret_cast<const float4*>(es + r * ES + c8);
+      const float4 v1 = *reinterpret_cast<const float4*>(es + r * ES + c8 + 4);
+      vals[0] = v0.x; vals[1] = v0.y; vals[2] = v0.z; vals[3] = v0.w;
+      vals[4] = v1.x; vals[5] = v1.y; vals[6] = v1.z; vals[7] = v1.w;
+      if (!CHECK || j + 8 <= J) {
+        epi.op8(i, j, vals);
+      } else {
+        for (int e = 0; e < 8 && j + e < J; ++e) epi(i, j + e, vals[e]);
+      }
     }
   }
 }
 
-template <class Cfg, bool AKC, bool BKC, class Epi>
-__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(1, Cfg::WPE))) void pm_gemm_big_kernel(PmGemmProb<Epi> pr, int tiles_i, int tiles_j) {
+template <class Cfg, bool AKC, bool BKC, bool CHECK, class Epi>
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WPE, Cfg::WPE))) void pm_gemm_big_kernel(PmGemmProb<Epi> pr, int tiles_i, int tiles_j) {
   __shared__ __attribute__((aligned(16))) bf16_t smem[PmBigLds<Cfg, AKC, BKC>::elems];
-  pm_gemm_big_body<Cfg, AKC, BKC, Epi>(pr, blockIdx.x, tiles_i, tiles_j, smem);
+  pm_gemm_big_body<Cfg, AKC, BKC, CHECK, Epi>(pr, blockIdx.x, tiles_i, tiles_j, smem);
 }
 
 // Many problems in one launch: tile_start[p] .. tile_start[p + 1] - 1 are the blocks of problem p
 // (tile_start has nprob + 1 entries, the last is the grid size).  All weight-gradient products of a
 // token-rich step go out together: single problems of 64 tiles cannot fill 256 compute units, a
 // few thousand tiles in one grid can, with no split of the contraction and no atomics.
-template <class Cfg, bool AKC, bool BKC, class Epi>
-__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(1, Cfg::WPE))) void pm_gemm_big_grouped_kernel(const PmGemmProb<Epi>* __restrict__ probs, const int* __restrict__ tile_start, int nprob) {
+template <class Cfg, bool AKC, bool BKC, bool CHECK, class Epi>
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WPE, Cfg::WPE))) void pm_gemm_big_grouped_kernel(const PmGemmProb<Epi>* __restrict__ probs, const int* __restrict__ tile_start, int nprob) {
   __shared__ __attribute__((aligned(16))) bf16_t smem[PmBigLds<Cfg, AKC, BKC>::elems];
   const int bid = blockIdx.x;
   int lo = 0, hi = nprob - 1;                 // largest p with tile_start[p] <= bid
@@ -553,18 +591,28 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(1, Cfg:
   }
   const PmGemmProb<Epi> pr = probs[lo];
   const int ti = (pr.I + Cfg::BI - 1) / Cfg::BI, tj = (pr.J + Cfg::BJ - 1) / Cfg::BJ;
-  pm_gemm_big_body<Cfg, AKC, BKC, Epi>(pr, bid - tile_start[lo], ti, tj, smem);
+  pm_gemm_big_body<Cfg, AKC, BKC, CHECK, Epi>(pr, bid - tile_start[lo], ti, tj, smem);
 }
 
 // 128 x 128 block, 4 waves x (64 x 64): 80 KB of LDS, so two blocks share a CU and cover each
 // other's barriers.  Measured on 8192-row problems (K, N in {1024, 4096}) this beat 256 x 256
 // (8 waves x 128 x 64) and 256 x 128 (4 waves x 128 x 64) blocks in 7 of 9 shape / layout cases.
 using PmBig128 = PmBigCfg<128, 128, 2, 2>;
+// 256 x 256 block, 4 waves x (128 x 128): one block per CU, one wave per SIMD holding 256 accumulator
+// registers; every LDS byte read feeds twice the MFMA work of the 64 x 64 wave tile
+using PmBig256 = PmBigCfg<256, 256, 2, 2>;
+
+// true if no tile of the problem needs a bounds test
+template <class Cfg>
+inline bool pm_big_aligned(int I, int J, int K) { return I % Cfg::BI == 0 && J % Cfg::BJ == 0 && K % 64 == 0; }
 
 template <class Cfg, bool AKC, bool BKC, class Epi>
 inline void pm_big_launch(hipStream_t st, const PmGemmProb<Epi>& pr) {
   const int ti = (pr.I + Cfg::BI - 1) / Cfg::BI, tj = (pr.J + Cfg::BJ - 1) / Cfg::BJ;
-  hipLaunchKernelGGL((pm_gemm_big_kernel<Cfg, AKC, BKC, Epi>), dim3(ti * tj), dim3(Cfg::NT), 0, st, pr, ti, tj);
+  if (pm_big_aligned<Cfg>(pr.I, pr.J, pr.K))
+    hipLaunchKernelGGL((pm_gemm_big_kernel<Cfg, AKC, BKC, false, Epi>), dim3(ti * tj), dim3(Cfg::NT), 0, st, pr, ti, tj);
+  else
+    hipLaunchKernelGGL((pm_gemm_big_kernel<Cfg, AKC, BKC, true, Epi>), dim3(ti * tj), dim3(Cfg::NT), 0, st, pr, ti, tj);
 }
 
 // true if the problem was large enough for (and was launched on) the big-tile kernel
