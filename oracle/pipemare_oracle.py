@@ -263,6 +263,7 @@ class PipeMareOracle:
         self.s = [np.zeros_like(h[0]) for h in self.hist]      # Adam second moment
         self.last_lr = [0.0] * self.U
         self.last_versions = [(0, 0)] * self.U
+        self.last_grads = None          # the gradients the most recent update consumed (after averaging and clipping)
 
     # -- helpers
     def _tf(self, u): return self.tau_fwd[self.stage[u] - 1]
@@ -317,6 +318,7 @@ class PipeMareOracle:
             scale = min(1.0, o["clip_norm"] / gn) if gn > 0.0 else 1.0
             grads = [g * scale for g in grads]
 
+        self.last_grads = grads
         a_base = base_lr(o["sched"], t)
         for u in range(self.U):
             w = self.hist[u][t]
