@@ -17,13 +17,14 @@ from typing import List, Tuple
 import numpy as np
 
 __all__ = ["Layer", "Workload", "config", "init_params", "BatchStream", "n_params", "transformer", "TokenStream",
-           "batch_stream"]
+           "batch_stream", "resnet", "ImageStream"]
 
 
 @dataclass(frozen=True)
 class Layer:
     """One weight unit (weight matrix + bias), assigned to pipeline stage `stage` (1-based)."""
     kind: str      # "linear" | "embed" (n_in = vocab, n_out = width, no bias) | "layernorm" (gain + bias of width n_out)
+                   # | "conv3x3" (n_in, n_out channels; weight n_out x 3 x 3 x n_in, then per-channel scale and shift)
     n_in: int
     n_out: int
     act: str       # "none" | "relu" | "gelu"
@@ -54,6 +55,8 @@ def n_params(layer: Layer) -> int:
         return layer.n_in * layer.n_out
     if layer.kind == "layernorm":
         return 2 * layer.n_out
+    if layer.kind == "conv3x3":
+        return layer.n_out * 9 * layer.n_in + 2 * layer.n_out
     return layer.n_out * layer.n_in + layer.n_out
 
 
@@ -69,6 +72,8 @@ def config(idx: int) -> Workload:
     0: tiny fp32 4-stage MLP (64-wide, ReLU, scalar regression head, MSE).
     1: 16-stage MLP, 1024-wide, GELU, 10-class head sharing the last stage,
        bf16 compute with fp32 master weights.
+    3: ResNet-20-shaped CNN (19 3x3 convolutions with folded per-channel affine + classifier, one stage
+       each), 128 images of 3x32x32, bf16 compute, momentum SGD.
     2: 6-layer fine-grained Transformer (width 512, 8 heads, feed-forward 2048, vocabulary 8192,
        32 sequences of 128 tokens), bf16 compute, AdamW.
     4: 12-layer fine-grained Transformer (width 1024, 16 heads, feed-forward 4096, vocabulary 32000,
@@ -135,6 +140,13 @@ def init_params(wl: Workload, seed: int | None = None) -> List[np.ndarray]:
             g = 1.0 + rng.uniform(-0.1, 0.1, size=L.n_out)
             b = rng.uniform(-0.1, 0.1, size=L.n_out)
             out.append(np.concatenate([g, b]).astype(np.float32))
+            continue
+        if L.kind == "conv3x3":        # W ~ U(+-sqrt(6 / fan_in)), fan_in = 9 C_in; scale 1 + U(+-0.1), shift U(+-0.1)
+            bound = np.sqrt(6.0 / (9 * L.n_in))
+            W = rng.uniform(-bound, bound, size=(L.n_out, 9 * L.n_in))
+            sc = 1.0 + rng.uniform(-0.1, 0.1, size=L.n_out)
+            sh = rng.uniform(-0.1, 0.1, size=L.n_out)
+            out.append(np.concatenate([W.ravel(), sc, sh]).astype(np.float32))
             continue
         if wl.init == "he":
             bound = np.sqrt((6.0 if L.act in ("relu", "gelu") else 3.0) / L.n_in)
@@ -228,6 +240,48 @@ class TokenStream:
         return np.ascontiguousarray(ids[:, :S]), np.ascontiguousarray(ids[:, 1:])
 
 
+def resnet(n_blocks: int, microbatch: int, dtype: str = "bf16", image: int = 32, n_classes: int = 10,
+           name: str | None = None, steps: int = 0, **opt) -> Workload:
+    """ResNet-20-shaped CNN (n_blocks = 3): conv 3 -> 16, three groups of n_blocks two-convolution blocks with
+    16 / 32 / 64 channels (the first convolution of groups 2 and 3 has stride 2, recognisable by
+    n_out = 2 n_in), global average pool, classifier.  One pipeline stage per weight unit."""
+    layers = [Layer("conv3x3", 3, 16, "relu", 1)]
+    c, st = 16, 1
+    for g in range(3):
+        for b in range(n_blocks):
+            cin = c
+            if g > 0 and b == 0:
+                c *= 2
+            st += 1
+            layers.append(Layer("conv3x3", cin, c, "relu", st))
+            st += 1
+            layers.append(Layer("conv3x3", c, c, "relu", st))
+    st += 1
+    layers.append(Layer("linear", 64, n_classes, "none", st))
+    o = dict(kind="sgdm", lr=0.01, beta=0.9, D=0.5, K=0, weight_decay=0.0)
+    o.update(opt)
+    return Workload(name=name or f"resnet{6 * n_blocks + 2}_{dtype}", layers=tuple(layers), P=st, N=1, loss="xent",
+                    dtype=dtype, microbatch=microbatch, n_classes=n_classes, opt=o, steps=steps,
+                    arch=dict(kind="resnet", n_blocks=n_blocks, image=image))
+
+
+class ImageStream:
+    """Deterministic image microbatches: x ~ N(0,1) fp32 [M, 3, H, W] (NCHW), labels uniform over the classes
+    (int32 [M]).  Stands in for CIFAR10 / ImageNet batches (same tensor shapes)."""
+
+    def __init__(self, wl: Workload):
+        self.wl = wl
+
+    def batch(self, k: int):
+        wl = self.wl
+        H = wl.arch["image"]
+        rng = np.random.default_rng([wl.seed_data, k])
+        x = rng.standard_normal((wl.microbatch, 3, H, H)).astype(np.float32)
+        y = rng.integers(0, wl.n_classes, size=wl.microbatch).astype(np.int32)
+        return x, y
+
+
 def batch_stream(wl: Workload):
     """The microbatch generator that fits the workload."""
-    return TokenStream(wl) if wl.arch.get("kind") == "transformer" else BatchStream(wl)
+    kind = wl.arch.get("kind")
+    return TokenStream(wl) if kind == "transformer" else ImageStream(wl) if kind == "resnet" else BatchStream(wl)
