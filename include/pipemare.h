@@ -46,11 +46,14 @@ typedef enum {
 typedef enum {
   PM_LINEAR = 0,     /* W [n_out, n_in] row-major + bias [n_out] */
   PM_EMBED = 1,      /* table E [n_in = vocabulary, n_out = width], no bias */
-  PM_LAYERNORM = 2   /* gain [n_out] + bias [n_out] over rows of width n_in = n_out, eps 1e-5 */
+  PM_LAYERNORM = 2,  /* gain [n_out] + bias [n_out] over rows of width n_in = n_out, eps 1e-5 */
+  PM_CONV3X3 = 3     /* 3x3 convolution, zero padding 1: W [n_out][3][3][n_in] + per-channel scale [n_out] and
+                        shift [n_out] (a folded normalisation); stride 2 where n_out = 2 n_in, else 1 */
 } pm_layer_kind;
 typedef enum {
   PM_ARCH_CHAIN = 0,       /* Linear units in sequence, unit l feeds unit l+1 */
-  PM_ARCH_TRANSFORMER = 1  /* embed | per layer: ln1, Wq, Wk, Wv, Wo, ln2, W1, W2 | final ln, head (see pm_opts) */
+  PM_ARCH_TRANSFORMER = 1, /* embed | per layer: ln1, Wq, Wk, Wv, Wo, ln2, W1, W2 | final ln, head (see pm_opts) */
+  PM_ARCH_RESNET = 2       /* conv | blocks of two convs with parameter-free shortcuts | pool, classifier (see pm_opts) */
 } pm_arch;
 typedef enum { PM_ACT_NONE = 0, PM_ACT_RELU = 1, PM_ACT_GELU = 2 /* exact erf form */ } pm_act;
 typedef enum { PM_METHOD_PIPEMARE = 0, PM_METHOD_PIPEDREAM = 1, PM_METHOD_GPIPE = 2 } pm_method;
@@ -64,7 +67,7 @@ typedef enum { PM_LOSS_MSE = 0, PM_LOSS_XENT = 1 } pm_loss_kind;
  * topological order; several consecutive units may share a stage (a LayerNorm normally rides in the
  * stage of the matrix that consumes it).  Packed host layout of a unit's values, used by
  * init_weights_host, pm_weights, pm_state and pm_set_grads: [W | b] (Linear), [E] (embedding),
- * [gain | bias] (LayerNorm). */
+ * [gain | bias] (LayerNorm), [W | scale | shift] (convolution). */
 typedef struct {
   int32_t kind;   /* pm_layer_kind */
   int32_t n_in;
@@ -121,6 +124,14 @@ typedef struct {
                                 int32 next-token targets of the same shape as y. */
   int32_t n_heads;           /* Transformer: attention heads (d % n_heads == 0) */
   int32_t seq_len;           /* Transformer: tokens per sequence */
+  int32_t image_size;        /* PM_ARCH_RESNET: input images are 3 x image_size x image_size (a multiple of 4).  The
+                                L = 2 * blocks + 2 units must be CONV3X3(c0_in -> c) | blocks x { CONV3X3(a -> b),
+                                CONV3X3(b -> b) } with b = a or b = 2a (then stride 2 and the shortcut takes every
+                                second pixel, new channels zero) | LINEAR(last b -> classes).  y = relu(scale * conv(x)
+                                + shift [+ shortcut(block input)]); global average pool before the classifier;
+                                cross-entropy (loss must be PM_LOSS_XENT).  Channel counts multiples of 8.  pm_step
+                                takes fp32 images [microbatch, c0_in, image_size, image_size] (NCHW) as x and int32
+                                labels [microbatch] as y. */
 } pm_opts;
 
 const char* pm_status_str(pm_status s);
@@ -248,6 +259,20 @@ pm_status pm_attention_fwd(void* stream, int32_t dtype, int32_t B, int32_t S, in
 pm_status pm_attention_bwd(void* stream, int32_t dtype, int32_t B, int32_t S, int32_t H, int32_t dh,
                            const void* q_dev, const void* k_dev, const void* v_dev, const void* o_dev,
                            const void* do_dev, const float* lse_dev, void* dq_dev, void* dk_dev, void* dv_dev);
+
+/* The three products of one 3x3 convolution unit (zero padding 1, stride 1 or 2) as stand-alone
+ * primitives for kernel-level tests and measurement.  Tensors NHWC in the element type of `dtype`;
+ * params = [W (C_out x 3 x 3 x C_in) | scale (C_out) | shift (C_out)].  bf16 with C_in and C_out multiples
+ * of 16 (at most 64) runs as implicit GEMM on MFMA, anything else on plain kernels.  C_out a multiple of 8.
+ *   fwd:        z = conv(x, W); y = relu(scale * z + shift)     x [B,H,W,C_in] -> z, y [B,Ho,Wo,C_out], Ho = (H-1)/stride+1
+ *   bwd_data:   dx = transposed convolution of dz with W        dz [B,Ho,Wo,C_out] -> dx [B,H,W,C_in]
+ *   bwd_weight: dW (fp32 [C_out][3][3][C_in]) = correlation of dz with x; overwritten (dW is cleared first) */
+pm_status pm_conv3x3_fwd(void* stream, int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t C_in, int32_t C_out,
+                         int32_t stride, const void* x_dev, const void* params_dev, void* z_dev, void* y_dev);
+pm_status pm_conv3x3_bwd_data(void* stream, int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t C_in, int32_t C_out,
+                              int32_t stride, const void* dz_dev, const void* params_dev, void* dx_dev);
+pm_status pm_conv3x3_bwd_weight(void* stream, int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t C_in, int32_t C_out,
+                                int32_t stride, const void* dz_dev, const void* x_dev, float* dW_dev);
 
 /* Waits for everything the context has enqueued, on the caller's stream and on the library's
  * second stream (overlap_update). */

@@ -19,6 +19,7 @@ __all__ = [
     "pm_state", "pm_device_step_table", "pm_stats", "pm_set_grads", "pm_apply_update", "pm_destroy",
     "pm_linear_fwd", "pm_linear_bwd_data", "pm_linear_bwd_weight", "pm_profile_begin", "pm_profile_end",
     "pm_synchronize", "PipeMare", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
+    "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight",
     "PM_LINEAR", "PM_KIND", "PM_ARCH", "PM_ACT", "PM_METHOD", "PM_LR", "PM_OPT", "PM_DTYPE", "PM_LOSS", "EXPORTS",
 ]
 
@@ -30,8 +31,8 @@ if not os.path.exists(_LIB_PATH):
 lib = C.CDLL(_LIB_PATH)
 
 PM_LINEAR = 0
-PM_KIND = {"linear": 0, "embed": 1, "layernorm": 2}
-PM_ARCH = {"chain": 0, "transformer": 1}
+PM_KIND = {"linear": 0, "embed": 1, "layernorm": 2, "conv3x3": 3}
+PM_ARCH = {"chain": 0, "transformer": 1, "resnet": 2}
 PM_ACT = {"none": 0, "relu": 1, "gelu": 2}
 PM_METHOD = {"pipemare": 0, "pipedream": 1, "gpipe": 2}
 PM_LR = {"const": 0, "step": 1, "warmup_invsqrt": 2}
@@ -44,7 +45,7 @@ EXPORTS = ["pm_status_str", "pm_last_error", "pm_delays", "pm_slots", "pm_t1_lr"
            "pm_create", "pm_step", "pm_weights", "pm_state", "pm_device_step_table", "pm_stats",
            "pm_set_grads", "pm_apply_update", "pm_profile_begin", "pm_profile_end", "pm_linear_fwd", "pm_linear_bwd_data",
            "pm_linear_bwd_weight", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
-           "pm_synchronize", "pm_destroy"]
+           "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight", "pm_synchronize", "pm_destroy"]
 
 
 class pm_layer_desc(C.Structure):
@@ -64,7 +65,7 @@ class pm_opts(C.Structure):
                 ("t2_enabled", C.c_int32), ("n_microbatches", C.c_int32), ("dtype", C.c_int32),
                 ("loss", C.c_int32), ("microbatch", C.c_int32), ("use_graph", C.c_int32),
                 ("sync_warmup_steps", C.c_int64), ("overlap_update", C.c_int32), ("arch", C.c_int32),
-                ("n_heads", C.c_int32), ("seq_len", C.c_int32)]
+                ("n_heads", C.c_int32), ("seq_len", C.c_int32), ("image_size", C.c_int32)]
 
 
 class PmError(RuntimeError):
@@ -101,6 +102,9 @@ lib.pm_layernorm_fwd.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp,
 lib.pm_layernorm_bwd.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.pm_attention_fwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
 lib.pm_attention_bwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.pm_conv3x3_fwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]
+lib.pm_conv3x3_bwd_data.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
+lib.pm_conv3x3_bwd_weight.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
 lib.pm_synchronize.argtypes = [_vp]
 lib.pm_destroy.argtypes = [_vp]
 lib.pm_destroy.restype = None
@@ -255,16 +259,29 @@ def pm_attention_bwd(stream, dtype, B, S, H, dh, q, k, v, o, do, lse, dq, dk, dv
     _check(lib.pm_attention_bwd(_vp(stream), PM_DTYPE[dtype], B, S, H, dh, q, k, v, o, do, lse, dq, dk, dv))
 
 
+def pm_conv3x3_fwd(stream, dtype, B, H, W, C_in, C_out, stride, x, params, z, y):
+    _check(lib.pm_conv3x3_fwd(_vp(stream), PM_DTYPE[dtype], B, H, W, C_in, C_out, stride, x, params, z, y))
+
+
+def pm_conv3x3_bwd_data(stream, dtype, B, H, W, C_in, C_out, stride, dz, params, dx):
+    _check(lib.pm_conv3x3_bwd_data(_vp(stream), PM_DTYPE[dtype], B, H, W, C_in, C_out, stride, dz, params, dx))
+
+
+def pm_conv3x3_bwd_weight(stream, dtype, B, H, W, C_in, C_out, stride, dz, x, dW):
+    _check(lib.pm_conv3x3_bwd_weight(_vp(stream), PM_DTYPE[dtype], B, H, W, C_in, C_out, stride, dz, x, dW))
+
+
 def make_sched(kind="const", base=0.01, init=0.0, factor=1.0, interval=1, K=0) -> pm_lr_sched:
     return pm_lr_sched(PM_LR[kind], base, init, factor, interval, K)
 
 
 def make_opts(opt="sgdm", beta1=0.9, beta2=0.98, eps=1e-8, weight_decay=0.0, clip_norm=0.0, D=1.0,
               gamma_override=None, t1=True, t2=True, N=1, dtype="f32", loss="mse", microbatch=1,
-              use_graph=False, sync_warmup=0, overlap_update=False, arch="chain", n_heads=0, seq_len=0) -> pm_opts:
+              use_graph=False, sync_warmup=0, overlap_update=False, arch="chain", n_heads=0, seq_len=0,
+              image_size=0) -> pm_opts:
     o = pm_opts(PM_OPT[opt], beta1, beta2, eps, weight_decay, clip_norm, D, None, int(t1), int(t2), N,
                 PM_DTYPE[dtype], PM_LOSS[loss], microbatch, int(use_graph), int(sync_warmup), int(overlap_update),
-                PM_ARCH[arch], int(n_heads), int(seq_len))
+                PM_ARCH[arch], int(n_heads), int(seq_len), int(image_size))
     if gamma_override is not None:
         arr = (C.c_double * len(gamma_override))(*gamma_override)
         o._keep = arr
@@ -278,6 +295,8 @@ def _unit_size(L) -> int:
         return L.n_in * L.n_out
     if kind == "layernorm":
         return 2 * L.n_out
+    if kind == "conv3x3":
+        return L.n_out * 9 * L.n_in + 2 * L.n_out
     return L.n_out * L.n_in + L.n_out
 
 
@@ -303,7 +322,8 @@ class PipeMare:
         self.arena_bytes = nbytes
 
     def step(self, x, y, want_loss=False):
-        """Chain: x cuda fp32 [M, n_in]; y cuda fp32 [M, n_out] or int32 [M].  Transformer: x, y cuda int32 [M, S]."""
+        """Chain: x cuda fp32 [M, n_in]; y cuda fp32 [M, n_out] or int32 [M].  Transformer: x, y cuda int32 [M, S].
+        ResNet: x cuda fp32 [M, 3, H, H], y cuda int32 [M]."""
         return pm_step(self.ctx, x.data_ptr(), y.data_ptr(), want_loss)
 
     def weights(self, layer=None):

@@ -18,6 +18,7 @@
 #include "pm_gemm_mfma.hpp"
 #include "pm_update.hpp"
 #include "pm_transformer.hpp"
+#include "pm_conv.hpp"
 
 namespace {
 
@@ -74,6 +75,13 @@ struct Layout {
     size_t dzq, dzk, dzv, dzo, dz1, dz2;   // d loss / d (output of Wq, Wk, Wv, Wo, W1, W2), kept until the weight gradients
   };
   std::vector<TfmLayer> tl;
+  // CNN activations per convolution unit (byte offsets), all [B, Ho, Wo, Cout] in the compute dtype
+  struct ConvBuf {
+    PmConvGeom g;
+    size_t z, y, da, dz, dy;
+  };
+  std::vector<ConvBuf> cv;
+  size_t r_x, r_pool, r_logits, r_dlogits, r_dpool;
   size_t t_xf, t_muf, t_rsf, t_nf, t_logits, t_dlogits;      // final LayerNorm and head
   size_t t_dx, t_dn, t_do;                                   // backward scratch, reused by every layer
   size_t t_pos, t_zero;                                      // positions fp32 [S, d]; zero-region table
@@ -92,18 +100,38 @@ pm_status validate(int32_t P, int32_t L, const pm_layer_desc* layers, const int3
   if (!(o->D > 0.0 && o->D <= 1.0)) return fail(PM_EINVAL, "D must be in (0, 1]");
   if (o->sync_warmup_steps < 0) return fail(PM_EINVAL, "sync_warmup_steps must be >= 0");
   if (o->clip_norm < 0.0 || o->weight_decay < 0.0) return fail(PM_EINVAL, "clip_norm and weight_decay must be >= 0");
-  if (o->arch != PM_ARCH_CHAIN && o->arch != PM_ARCH_TRANSFORMER) return fail(PM_EINVAL, "unknown architecture");
+  if (o->arch < PM_ARCH_CHAIN || o->arch > PM_ARCH_RESNET) return fail(PM_EINVAL, "unknown architecture");
   int prev_stage = 1;
   for (int l = 0; l < L; ++l) {
     const pm_layer_desc& d = layers[l];
-    if (d.kind < PM_LINEAR || d.kind > PM_LAYERNORM) return fail(PM_EINVAL, "unit %d: unknown kind", l);
+    if (d.kind < PM_LINEAR || d.kind > PM_CONV3X3) return fail(PM_EINVAL, "unit %d: unknown kind", l);
     if (o->arch == PM_ARCH_CHAIN && d.kind != PM_LINEAR) return fail(PM_EINVAL, "unit %d: a chain holds Linear units only", l);
+    if (o->arch == PM_ARCH_TRANSFORMER && d.kind == PM_CONV3X3) return fail(PM_EINVAL, "unit %d: convolutions need PM_ARCH_RESNET", l);
     if (d.n_in < 1 || d.n_out < 1) return fail(PM_EINVAL, "unit %d: sizes must be positive", l);
     if (d.act < PM_ACT_NONE || d.act > PM_ACT_GELU) return fail(PM_EINVAL, "unit %d: unknown activation", l);
     if (d.stage < 1 || d.stage > P) return fail(PM_EINVAL, "unit %d: stage %d outside 1..%d", l, d.stage, P);
     if (d.stage < prev_stage) return fail(PM_EINVAL, "unit %d: stages must be non-decreasing along the chain", l);
     prev_stage = d.stage;
     if (o->arch == PM_ARCH_CHAIN && l > 0 && layers[l - 1].n_out != d.n_in) return fail(PM_EINVAL, "unit %d: n_in %d does not chain with previous n_out %d", l, d.n_in, layers[l - 1].n_out);
+  }
+  if (o->arch == PM_ARCH_RESNET) {
+    if (o->loss != PM_LOSS_XENT) return fail(PM_EINVAL, "the CNN is trained with cross-entropy (PM_LOSS_XENT)");
+    if (L < 4 || (L % 2)) return fail(PM_EINVAL, "a CNN has 2 * blocks + 2 units, got %d", L);
+    if (o->image_size < 4 || (o->image_size % 4)) return fail(PM_EINVAL, "image_size must be a positive multiple of 4");
+    for (int l = 0; l < L - 1; ++l) {
+      if (layers[l].kind != PM_CONV3X3) return fail(PM_EINVAL, "unit %d must be a 3x3 convolution", l);
+      if (layers[l].n_out & 7) return fail(PM_EINVAL, "unit %d: channel count %d must be a multiple of 8", l, layers[l].n_out);
+      if (2048 % layers[l].n_out) return fail(PM_EINVAL, "unit %d: channel count %d must divide 2048", l, layers[l].n_out);
+      if (layers[l].act != PM_ACT_RELU) return fail(PM_EINVAL, "unit %d: convolutions are followed by ReLU", l);
+      if (l > 0 && layers[l].n_in != layers[l - 1].n_out) return fail(PM_EINVAL, "unit %d: n_in %d does not chain with previous n_out %d", l, layers[l].n_in, layers[l - 1].n_out);
+      if (l > 0 && (l % 2) == 0 && layers[l].n_in != layers[l].n_out) return fail(PM_EINVAL, "unit %d: the second convolution of a block keeps the channel count", l);
+      if (l > 0 && (l % 2) == 1 && layers[l].n_out != layers[l].n_in && layers[l].n_out != 2 * layers[l].n_in)
+        return fail(PM_EINVAL, "unit %d: the first convolution of a block keeps or doubles the channel count", l);
+    }
+    int strides = 0;
+    for (int l = 1; l < L - 1; l += 2) strides += layers[l].n_out == 2 * layers[l].n_in;
+    if ((o->image_size >> strides) < 1 || (o->image_size % (1 << strides))) return fail(PM_EINVAL, "image_size %d does not survive %d halvings", o->image_size, strides);
+    if (layers[L - 1].kind != PM_LINEAR || layers[L - 1].n_in != layers[L - 2].n_out) return fail(PM_EINVAL, "the last unit must be the classifier on the pooled channels");
   }
   if (o->arch == PM_ARCH_TRANSFORMER) {
     if (o->loss != PM_LOSS_XENT) return fail(PM_EINVAL, "the Transformer is trained with token cross-entropy (PM_LOSS_XENT)");
@@ -150,6 +178,7 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
     u.d = layers[l];
     if (u.d.kind == PM_LAYERNORM) { u.nw = u.d.n_out; u.nb = u.d.n_out; }
     else if (u.d.kind == PM_EMBED) { u.nw = (int64_t)u.d.n_in * u.d.n_out; u.nb = 0; }
+    else if (u.d.kind == PM_CONV3X3) { u.nw = (int64_t)u.d.n_out * 9 * u.d.n_in; u.nb = 2 * (int64_t)u.d.n_out; }
     else { u.nw = (int64_t)u.d.n_out * u.d.n_in; u.nb = u.d.n_out; }
     u.boff = round_up(u.nw, 8);
     u.n = u.boff + u.nb;
@@ -217,6 +246,31 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
     lay.zero_max = 0;
     for (int l = 0; l < L; ++l)
       if (lay.units[l].d.kind != PM_LINEAR) { lay.n_zero += 1; lay.zero_max = std::max(lay.zero_max, lay.units[l].n_pad); }
+    lay.t_zero = take(sizeof(int64_t) * 2 * lay.n_zero);
+  } else if (o->arch == PM_ARCH_RESNET) {
+    const size_t e = lay.esz;
+    const int nconv = L - 1;
+    lay.x_off = 0;
+    lay.cv.resize(nconv);
+    int H = o->image_size;
+    lay.r_x = take((size_t)M * H * H * lay.units[0].d.n_in * e);
+    for (int u = 0; u < nconv; ++u) {
+      Layout::ConvBuf& b = lay.cv[u];
+      const pm_layer_desc& dd = lay.units[u].d;
+      const int stride = (u > 0 && (u % 2) == 1 && dd.n_out == 2 * dd.n_in) ? 2 : 1;
+      b.g = PmConvGeom{M, H, H, dd.n_in, dd.n_out, stride, (H - 1) / stride + 1, (H - 1) / stride + 1};
+      H = b.g.Ho;
+      const size_t n = (size_t)M * H * H * dd.n_out * e;
+      b.z = take(n); b.y = take(n); b.da = take(n); b.dz = take(n); b.dy = take(n);
+    }
+    const int C = lay.units[L - 2].d.n_out, ncls = lay.units[L - 1].d.n_out;
+    lay.r_pool = take((size_t)M * C * e);
+    lay.r_logits = take((size_t)M * round_up(ncls, 8) * 4);
+    lay.r_dlogits = take((size_t)M * round_up(ncls, 8) * e);
+    lay.r_dpool = take((size_t)M * C * e);
+    lay.n_zero = nconv;
+    lay.zero_max = 0;
+    for (int u = 0; u < nconv; ++u) lay.zero_max = std::max(lay.zero_max, lay.units[u].n_pad);
     lay.t_zero = take(sizeof(int64_t) * 2 * lay.n_zero);
   } else {
     lay.x_off = take((size_t)M * lay.units[0].ld_in * lay.esz);
@@ -651,6 +705,100 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
   return PM_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// ResNet-shaped CNN: one microbatch forward on the tau_fwd-stale ring slots, cross-entropy, backward
+// on the corrected weights.  Unit u < L - 1 is a 3x3 convolution with folded affine and ReLU;
+// units (1, 2), (3, 4), ... form residual blocks; the last unit is the classifier on the pooled map.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+pm_status launch_resnet(pm_ctx* c, const void* x_dev, const void* y_dev, int accumulate, int par) {
+  const Layout& lay = c->lay;
+  hipStream_t st = c->stream;
+  const int L = c->L, nconv = L - 1, B = c->o.microbatch;
+  T* ring = c->at<T>(lay.ring_off);
+  T* ub = c->at<T>(lay.ub_off);
+  float* g = c->at<float>(lay.g_off);
+  PmLayerStep* tab = c->ld(par);
+  auto U = [&](int u) -> const Unit& { return lay.units[u]; };
+  auto Wf = [&](int u, int64_t extra) { return PmWLoc<T>{ring + U(u).ring_off + extra, &tab[u].fwd_slot, U(u).n_pad}; };
+  auto Wb = [&](int u, int64_t extra) {
+    return U(u).corr ? PmWLoc<T>{ub + U(u).off + extra, nullptr, 0}
+                     : PmWLoc<T>{ring + U(u).ring_off + extra, &tab[u].bkwd_slot, U(u).n_pad};
+  };
+  auto TT = [&](size_t off) { return c->at<T>(off); };
+  const int fc = L - 1, C = U(fc).d.n_in, ncls = U(fc).d.n_out, ldc = (int)round_up(ncls, 8);
+  const PmConvGeom& gl = lay.cv[nconv - 1].g;
+  const int HW = gl.Ho * gl.Wo;
+
+  prof_mark(c, 0);
+  hipLaunchKernelGGL(pm_begin_tokens_kernel, dim3(1), dim3(256), 0, st, c->hdr(), c->ls(), tab, accumulate ? 0 : L,
+                     sched_dev(c), par);
+  {
+    const PmConvGeom& g0 = lay.cv[0].g;
+    const int64_t tot = (int64_t)B * g0.H * g0.W * g0.Cin;
+    hipLaunchKernelGGL((pm_image_stage_kernel<T>), dim3((unsigned)std::min<int64_t>(2048, (tot + 255) / 256)), dim3(256), 0, st,
+                       (const float*)x_dev, TT(lay.r_x), B, g0.Cin, g0.H, g0.W);
+  }
+  // ---- forward
+  auto input_of = [&](int u) { return u == 0 ? TT(lay.r_x) : TT(lay.cv[u - 1].y); };
+  for (int u = 0; u < nconv; ++u) {
+    const Layout::ConvBuf& b = lay.cv[u];
+    PmShortcut<T> sc{nullptr, 0, 0, 0, 1};
+    if (u >= 2 && (u % 2) == 0) {                     // second convolution of a block: add the block input
+      const PmConvGeom& g1 = lay.cv[u - 1].g;         // geometry of the block's first convolution
+      sc = PmShortcut<T>{input_of(u - 1), g1.H, g1.W, g1.Cin, g1.stride};
+    }
+    pm_conv_fwd_launch<T>(st, b.g, input_of(u), Wf(u, 0), sc, TT(b.z), TT(b.y));
+  }
+  hipLaunchKernelGGL((pm_pool_fwd_kernel<T>), dim3((B * C + 255) / 256), dim3(256), 0, st, TT(lay.cv[nconv - 1].y),
+                     TT(lay.r_pool), B, HW, C);
+  {
+    PmEpiFwd<T> epi;
+    epi.bias = Wf(fc, U(fc).boff);
+    epi.z = nullptr; epi.a = nullptr; epi.z32 = c->at<float>(lay.r_logits); epi.ld = ldc; epi.act = PM_ACT_NONE; epi.b_ = nullptr;
+    launch_gemm<T>(c, B, ncls, C, TT(lay.r_pool), C, 1, Wf(fc, 0), C, 1, epi);
+  }
+  hipLaunchKernelGGL((pm_xent_kernel<T>), dim3((B + 3) / 4), dim3(256), 0, st, c->at<float>(lay.r_logits),
+                     (const int32_t*)y_dev, TT(lay.r_dlogits), B, ncls, ldc, c->hdr());
+  prof_mark(c, 1);
+  {
+    pm_status qs = quiesce(c);
+    if (qs != PM_OK) return qs;
+  }
+  // ---- backward
+  if (!accumulate) {
+    const unsigned bx = (unsigned)std::max<int64_t>(1, std::min<int64_t>(64, lay.zero_max / 4 / 256));
+    hipLaunchKernelGGL(pm_zero_regions_kernel, dim3(bx, lay.n_zero), dim3(256), 0, st, g, c->at<int64_t>(lay.t_zero));
+  }
+  {
+    PmEpiBwdWeight ew{g + U(fc).off, C, accumulate, nullptr};
+    launch_gemm<T>(c, ncls, C, B, TT(lay.r_dlogits), 1, ldc, PmWLoc<T>{TT(lay.r_pool), nullptr, 0}, 1, C, ew);
+    launch_bias_grad<T>(st, TT(lay.r_dlogits), g + U(fc).off + U(fc).boff, B, ncls, ldc, accumulate);
+    PmEpiBwdData<T> ed{nullptr, TT(lay.r_dpool), C, PM_ACT_NONE};
+    launch_gemm<T>(c, B, C, ncls, TT(lay.r_dlogits), ldc, 1, Wb(fc, 0), 1, C, ed);
+    const int64_t tot = (int64_t)B * HW * C;
+    hipLaunchKernelGGL((pm_pool_bwd_kernel<T>), dim3((unsigned)std::min<int64_t>(2048, (tot + 255) / 256)), dim3(256), 0, st,
+                       TT(lay.r_dpool), TT(lay.cv[nconv - 1].dy), B, HW, C);
+  }
+  for (int u = nconv - 1; u >= 0; --u) {
+    const Layout::ConvBuf& b = lay.cv[u];
+    const int64_t nw = U(u).nw, tot = (int64_t)B * b.g.Ho * b.g.Wo * b.g.Cout;
+    if (!pm_conv_affine_bwd_launch<T>(st, TT(b.dy), TT(b.y), TT(b.z), Wb(u, nw), TT(b.da), TT(b.dz), g + U(u).off + nw,
+                                      g + U(u).off + nw + b.g.Cout, tot, b.g.Cout))
+      return fail(PM_EINVAL, "unit %d: channel count not supported", u);
+    pm_conv_wgrad_launch<T>(st, b.g, TT(b.dz), input_of(u), g + U(u).off, accumulate);
+    if (u == 0) break;
+    PmShortcutBwd<T> sb{nullptr, 0, 0, 0, 1};
+    if ((u % 2) == 1) {                               // first convolution of a block: its input also feeds the shortcut
+      const PmConvGeom& g2 = lay.cv[u + 1].g;
+      sb = PmShortcutBwd<T>{TT(lay.cv[u + 1].da), g2.Ho, g2.Wo, g2.Cout, b.g.stride};
+    }
+    pm_conv_dgrad_launch<T>(st, b.g, TT(b.dz), Wb(u, 0), sb, TT(lay.cv[u - 1].dy));
+  }
+  PM_HIP(hipGetLastError());
+  return PM_OK;
+}
+
 template <typename T>
 pm_status enqueue_step(pm_ctx* c, const void* x, const void* y, bool first_micro, bool last_micro) {
   const int par = c->par();
@@ -665,6 +813,7 @@ pm_status enqueue_step(pm_ctx* c, const void* x, const void* y, bool first_micro
     if (qs != PM_OK) return qs;
   }
   pm_status s = c->o.arch == PM_ARCH_TRANSFORMER ? launch_tfm<T>(c, x, y, first_micro ? 0 : 1, par)
+                : c->o.arch == PM_ARCH_RESNET    ? launch_resnet<T>(c, x, y, first_micro ? 0 : 1, par)
                                                  : launch_fwd_bwd<T>(c, x, y, first_micro ? 0 : 1, par);
   if (s != PM_OK) return s;
   if (last_micro) {
@@ -956,6 +1105,10 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
       probs.clear();
     }
   }
+  if (c->o.arch == PM_ARCH_RESNET) {
+    for (int l = 0; l < L - 1; ++l) { zero_tab.push_back(lay.units[l].off); zero_tab.push_back(lay.units[l].n_pad); }
+    if ((e = hipMemcpyAsync(c->arena + lay.t_zero, zero_tab.data(), zero_tab.size() * 8, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy region table");
+  }
   if (c->o.dtype == PM_BF16 && c->o.arch == PM_ARCH_CHAIN) {
     // weight-gradient problem tables (first microbatch: overwrite, later ones: accumulate)
     const int M = c->o.microbatch;
@@ -1227,6 +1380,68 @@ pm_status pm_attention_bwd(void* stream, int32_t dtype, int32_t B, int32_t S, in
       : pm_attn_bwd_launch<float>(st, B, S, H, dh, (const float*)q_dev, (const float*)k_dev, (const float*)v_dev, (const float*)o_dev,
                                   (const float*)do_dev, lse_dev, (float*)dq_dev, (float*)dk_dev, (float*)dv_dev);
   if (!ok) return fail(PM_EINVAL, "attention shape (S %d, head size %d) not supported for this dtype", S, dh);
+  PM_HIP(hipGetLastError());
+  return PM_OK;
+}
+
+namespace {
+pm_status check_conv(int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t Cin, int32_t Cout, int32_t stride) {
+  if (dtype != PM_F32 && dtype != PM_BF16) return fail(PM_EINVAL, "dtype must be PM_F32 or PM_BF16");
+  if (B < 1 || H < 1 || W < 1 || Cin < 1 || Cout < 1) return fail(PM_EINVAL, "sizes must be positive");
+  if (stride != 1 && stride != 2) return fail(PM_EINVAL, "stride must be 1 or 2");
+  if (Cout & 7) return fail(PM_EINVAL, "C_out must be a multiple of 8");
+  return PM_OK;
+}
+PmConvGeom conv_geom(int B, int H, int W, int Cin, int Cout, int stride) {
+  return PmConvGeom{B, H, W, Cin, Cout, stride, (H - 1) / stride + 1, (W - 1) / stride + 1};
+}
+}  // namespace
+
+pm_status pm_conv3x3_fwd(void* stream, int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t C_in, int32_t C_out,
+                         int32_t stride, const void* x_dev, const void* params_dev, void* z_dev, void* y_dev) {
+  pm_status s = check_conv(dtype, B, H, W, C_in, C_out, stride);
+  if (s != PM_OK) return s;
+  if (!x_dev || !params_dev || !z_dev || !y_dev) return fail(PM_EINVAL, "NULL argument");
+  const PmConvGeom g = conv_geom(B, H, W, C_in, C_out, stride);
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == PM_BF16)
+    pm_conv_fwd_launch<bf16_t>(st, g, (const bf16_t*)x_dev, PmWLoc<bf16_t>{(const bf16_t*)params_dev, nullptr, 0},
+                               PmShortcut<bf16_t>{nullptr, 0, 0, 0, 1}, (bf16_t*)z_dev, (bf16_t*)y_dev);
+  else
+    pm_conv_fwd_launch<float>(st, g, (const float*)x_dev, PmWLoc<float>{(const float*)params_dev, nullptr, 0},
+                              PmShortcut<float>{nullptr, 0, 0, 0, 1}, (float*)z_dev, (float*)y_dev);
+  PM_HIP(hipGetLastError());
+  return PM_OK;
+}
+
+pm_status pm_conv3x3_bwd_data(void* stream, int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t C_in, int32_t C_out,
+                              int32_t stride, const void* dz_dev, const void* params_dev, void* dx_dev) {
+  pm_status s = check_conv(dtype, B, H, W, C_in, C_out, stride);
+  if (s != PM_OK) return s;
+  if (!dz_dev || !params_dev || !dx_dev) return fail(PM_EINVAL, "NULL argument");
+  const PmConvGeom g = conv_geom(B, H, W, C_in, C_out, stride);
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == PM_BF16)
+    pm_conv_dgrad_launch<bf16_t>(st, g, (const bf16_t*)dz_dev, PmWLoc<bf16_t>{(const bf16_t*)params_dev, nullptr, 0},
+                                 PmShortcutBwd<bf16_t>{nullptr, 0, 0, 0, 1}, (bf16_t*)dx_dev);
+  else
+    pm_conv_dgrad_launch<float>(st, g, (const float*)dz_dev, PmWLoc<float>{(const float*)params_dev, nullptr, 0},
+                                PmShortcutBwd<float>{nullptr, 0, 0, 0, 1}, (float*)dx_dev);
+  PM_HIP(hipGetLastError());
+  return PM_OK;
+}
+
+pm_status pm_conv3x3_bwd_weight(void* stream, int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t C_in, int32_t C_out,
+                                int32_t stride, const void* dz_dev, const void* x_dev, float* dW_dev) {
+  pm_status s = check_conv(dtype, B, H, W, C_in, C_out, stride);
+  if (s != PM_OK) return s;
+  if (!dz_dev || !x_dev || !dW_dev) return fail(PM_EINVAL, "NULL argument");
+  const PmConvGeom g = conv_geom(B, H, W, C_in, C_out, stride);
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t n = (int64_t)C_out * 9 * C_in;
+  hipLaunchKernelGGL(pm_zero_f32_kernel, dim3((unsigned)std::min<int64_t>(1024, (n + 255) / 256)), dim3(256), 0, st, dW_dev, n);
+  if (dtype == PM_BF16) pm_conv_wgrad_launch<bf16_t>(st, g, (const bf16_t*)dz_dev, (const bf16_t*)x_dev, dW_dev, 0);
+  else pm_conv_wgrad_launch<float>(st, g, (const float*)dz_dev, (const float*)x_dev, dW_dev, 0);
   PM_HIP(hipGetLastError());
   return PM_OK;
 }

@@ -115,20 +115,6 @@ __global__ __launch_bounds__(256) void pm_embed_bwd_kernel(const int32_t* __rest
   }
 }
 
-__device__ __forceinline__ float4 pm_ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
-__device__ __forceinline__ float4 pm_ld4(const bf16_t* p) {
-  const uint2 a = *reinterpret_cast<const uint2*>(p);
-  return make_float4(__uint_as_float(a.x << 16), __uint_as_float(a.x & 0xffff0000u), __uint_as_float(a.y << 16),
-                     __uint_as_float(a.y & 0xffff0000u));
-}
-__device__ __forceinline__ void pm_st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
-__device__ __forceinline__ void pm_st4(bf16_t* p, float4 v) {
-  uint2 o;
-  o.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
-  o.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
-  *reinterpret_cast<uint2*>(p) = o;
-}
-
 // ---------------------------------------------------------------------------------------------
 // LayerNorm forward: one wavefront per row, the row held in registers (lane l owns columns
 // 256 c + 4 l .. + 3, d <= 256 NC, d a multiple of 4).  Stores mean and 1/sqrt(var + eps) for the

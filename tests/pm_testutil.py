@@ -21,6 +21,9 @@ def make_oracle(w, params, tau_fwd, tau_bkwd, *, opt="sgdm", lr=0.01, beta=0.9, 
             from oracle.transformer_oracle import TransformerModel
             a = w.arch
             model = TransformerModel(a["n_layers"], a["d_model"], a["n_heads"], a["d_ff"], a["vocab"], a["seq"])
+        elif w.arch.get("kind") == "resnet":
+            from oracle.resnet_oracle import ResNetModel
+            model = ResNetModel(w.arch["n_blocks"], w.n_classes, w.arch["image"])
         else:
             model = po.MLPModel(w.layers, w.loss)
     o = dict(kind=opt, beta=beta, beta1=beta, beta2=beta2, eps=eps, weight_decay=weight_decay,
@@ -41,7 +44,8 @@ def make_gpu(w, params, tau_fwd, tau_bkwd, *, opt="sgdm", lr=0.01, beta=0.9, bet
                      D=D, gamma_override=gamma_override, t1=t1, t2=t2, N=N, dtype=dtype or w.dtype, loss=w.loss,
                      microbatch=w.microbatch, use_graph=use_graph, sync_warmup=sync_warmup,
                      overlap_update=overlap_update, arch=w.arch.get("kind", "chain"),
-                     n_heads=w.arch.get("n_heads", 0), seq_len=w.arch.get("seq", 0))
+                     n_heads=w.arch.get("n_heads", 0), seq_len=w.arch.get("seq", 0),
+                     image_size=w.arch.get("image", 0))
     return pm.PipeMare(w.layers, w.P, tau_fwd, tau_bkwd, sc, o, params, stream=stream)
 
 

@@ -99,6 +99,10 @@ def config(idx: int) -> Workload:
         return transformer(6, 512, 8, 2048, 8192, 128, 32, dtype="bf16", name="tfm6x512_bf16", steps=40,
                            lr=5e-4, D=0.1, K=40000, weight_decay=1e-4,
                            sched=dict(kind="warmup_invsqrt", base=5e-4, init=1e-7, warmup=8000))
+    if idx == 3:
+        # ResNet-20 shape: 19 convolutions + the classifier, one stage each (P = 20); momentum SGD with a
+        # constant base step, T1 annealing over a quarter of the run, D = 0.5 (the paper's CIFAR10 value, App. C)
+        return resnet(3, 128, dtype="bf16", name="resnet20_bf16", steps=200, lr=0.01, D=0.5, K=50)
     if idx == 4:
         # 12 layers, width 1024, 16 heads, feed-forward 4096, vocabulary 32000, sequences of 512 tokens:
         # every weight unit a stage of its own: P = 99 (tau_fwd up to 197), ~217 M parameters
@@ -141,10 +145,14 @@ def init_params(wl: Workload, seed: int | None = None) -> List[np.ndarray]:
             b = rng.uniform(-0.1, 0.1, size=L.n_out)
             out.append(np.concatenate([g, b]).astype(np.float32))
             continue
-        if L.kind == "conv3x3":        # W ~ U(+-sqrt(6 / fan_in)), fan_in = 9 C_in; scale 1 + U(+-0.1), shift U(+-0.1)
+        if L.kind == "conv3x3":
+            # W ~ U(+-sqrt(6 / fan_in)), fan_in = 9 C_in; scale 0.5 + U(+-0.05), shift U(+-0.1).  The scale stands
+            # for a folded normalisation (gamma / sigma): at 0.5 a residual branch adds about a sixteenth of its
+            # input's second moment per block, so activations stay O(1) through the 9 blocks and the initial
+            # loss is near log(classes)
             bound = np.sqrt(6.0 / (9 * L.n_in))
             W = rng.uniform(-bound, bound, size=(L.n_out, 9 * L.n_in))
-            sc = 1.0 + rng.uniform(-0.1, 0.1, size=L.n_out)
+            sc = 0.5 + rng.uniform(-0.05, 0.05, size=L.n_out)
             sh = rng.uniform(-0.1, 0.1, size=L.n_out)
             out.append(np.concatenate([W.ravel(), sc, sh]).astype(np.float32))
             continue
