@@ -1,4 +1,4 @@
-"""Full-size parity of the fine-grained Transformer workloads, in the launch configuration bench.py
+"""Full-size parity of the Transformer and CNN workloads, in the launch configuration bench.py
 times (captured HIP graph replayed on a side stream, fixed batch buffers), against the fp64 oracle
 run on the host in the same process.
 
@@ -36,12 +36,14 @@ def _run(cfg, steps, checkpoints, grad_tol, move_tol, sgdm_lr=None):
     o_ = w.opt
     params = wl.init_params(w)
     tf, tb = po.pipeline_delays(w.P, 1)
-    if sgdm_lr is None:
+    if sgdm_lr is None and o_["kind"] == "sgdm":
+        kw = dict(opt="sgdm", lr=o_["lr"], beta=o_["beta"], D=o_["D"], K=o_["K"], weight_decay=o_["weight_decay"])
+    elif sgdm_lr is None:
         kw = dict(opt=o_["kind"], beta=o_["beta"], beta2=o_["beta2"], eps=o_["eps"], D=o_["D"], K=o_["K"],
                   weight_decay=o_["weight_decay"], sched=o_["sched"])
     else:
         kw = dict(opt="sgdm", lr=sgdm_lr, beta=0.9, D=o_["D"], K=8, weight_decay=o_["weight_decay"])
-    stream = wl.TokenStream(w)
+    stream = wl.batch_stream(w)
     o = make_oracle(w, params, tf, tb, **kw)
     skip = key_bias_entries(w)
     side = torch.cuda.Stream()
@@ -57,7 +59,8 @@ def _run(cfg, steps, checkpoints, grad_tol, move_tol, sgdm_lr=None):
             lo = o.step((x, y))
             chk = k + 1 in checkpoints
             lg = g.step(xd, yd, want_loss=True)
-            print(f"step {k}: loss oracle {lo:.5f} gpu {lg:.5f}  ({time.time() - t0:.0f}s)", flush=True)
+            if k < 3 or chk or k % 10 == 0:
+                print(f"step {k}: loss oracle {lo:.5f} gpu {lg:.5f}  ({time.time() - t0:.0f}s)", flush=True)
             assert lg == pytest.approx(lo, rel=5e-3)
             if not chk:
                 continue
@@ -85,7 +88,8 @@ def _run(cfg, steps, checkpoints, grad_tol, move_tol, sgdm_lr=None):
                   f"movement rel-L2 max {max(merr):.3e}", flush=True)
             print("   per unit: weight max-rel", np.array2string(np.array(werrs), precision=1, max_line_width=250),
                   "movement rel-L2", np.array2string(np.array(merr), precision=3, max_line_width=250), flush=True)
-            assert max(gerr) <= grad_tol, np.round(gerr, 4)
+            # after the first step each side evaluates its gradient at its own, slightly different weights
+            assert max(gerr) <= (grad_tol if k == 0 else 4 * grad_tol), np.round(gerr, 4)
             assert werr <= 2e-3, werrs
             if move_tol is not None and k + 1 == steps:       # the first steps are below fp32 resolution (T1 divides by tau)
                 assert max(merr) <= move_tol, np.round(merr, 4)
@@ -108,3 +112,10 @@ def test_config4_transformer12_bf16_full_size():
     """12 layers, width 1024, 16 heads, feed-forward 4096, vocabulary 32000, 16 x 512 tokens, P = 99
     (tau_fwd 197 .. 1), ~217 M parameters, 43 GB ring: 2 steps (the oracle needs minutes per step)."""
     _run(4, 2, (1, 2), grad_tol=3e-2, move_tol=None)
+
+
+@pytest.mark.timeout(1500)
+def test_config3_resnet20_bf16_full_size():
+    """ResNet-20 shape, 128 images of 3x32x32, P = 20 (tau_fwd 39 .. 1), momentum SGD: 100 steps, so every
+    stage reads genuinely delayed versions for most of the run."""
+    _run(3, 100, (1, 10, 50, 100), grad_tol=3e-2, move_tol=0.05)
