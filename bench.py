@@ -35,7 +35,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1,
                     help="workload index (0: tiny fp32 MLP, 1: 16-stage bf16 MLP (default, the headline workload), "
-                         "2: 6-layer Transformer, 4: 12-layer Transformer)")
+                         "2: 6-layer Transformer, 3: ResNet-20, 4: 12-layer Transformer)")
     ap.add_argument("--launch", choices=["graph", "eager", "overlap"], default="graph",
                     help="overlap: eager launches, the update of step t on the library's second stream concurrent "
                          "with the forward of step t+1; graph: replay a captured HIP graph; eager: one stream")
@@ -64,6 +64,7 @@ def main():
     n_params = int(sum(p.size for p in params))
     stream_data = wl.batch_stream(w)
     is_tfm = w.arch.get("kind") == "transformer"
+    is_cnn = w.arch.get("kind") == "resnet"
     launch = "eager" if args.no_graph else args.launch
     use_graph = launch == "graph"
     side = torch.cuda.Stream()
@@ -75,7 +76,8 @@ def main():
                             weight_decay=o["weight_decay"], t1=True, t2=True,
                             N=w.N, dtype=w.dtype, loss=w.loss, microbatch=w.microbatch, use_graph=use_graph,
                             overlap_update=(launch == "overlap"), arch=w.arch.get("kind", "chain"),
-                            n_heads=w.arch.get("n_heads", 0), seq_len=w.arch.get("seq", 0))
+                            n_heads=w.arch.get("n_heads", 0), seq_len=w.arch.get("seq", 0),
+                            image_size=w.arch.get("image", 0))
         eng = pm.PipeMare(w.layers, w.P, tau_fwd, tau_bkwd, sched, opts, params, stream=side)
         pool = [stream_data.batch(k) for k in range(args.pool)]
         xs = [torch.from_numpy(x).cuda() for x, _ in pool]
@@ -131,6 +133,16 @@ def main():
         attn_flops = 6.0 * a["seq"] ** 2 * (a["d_model"] // a["n_heads"]) * w.microbatch * a["n_heads"] * a["n_layers"]
         gemm_flops += attn_flops
         samples = tokens
+    elif is_cnn:
+        # every convolution: forward, data gradient (not for the first), weight gradient, 2 * pixels_out * C_out * 9 C_in each
+        H = w.arch["image"]
+        gemm_flops = 0.0
+        for u, L in enumerate(w.layers[:-1]):
+            if u > 0 and u % 2 == 1 and L.n_out == 2 * L.n_in:
+                H //= 2
+            gemm_flops += (3.0 if u > 0 else 2.0) * 2.0 * w.microbatch * H * H * L.n_out * 9 * L.n_in
+        gemm_flops += 6.0 * w.microbatch * w.layers[-1].n_in * w.layers[-1].n_out
+        samples = w.microbatch
     else:
         gemm_flops = 6.0 * w.microbatch * sum(L.n_in * L.n_out for L in lin) - 2.0 * w.microbatch * lin[0].n_in * lin[0].n_out
         samples = w.microbatch
@@ -150,7 +162,7 @@ def main():
         "vs_baseline": None,
         "dtype": w.dtype if w.dtype != "f32" else "f32",
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.P}-stage {'Transformer' if is_tfm else 'MLP'}, {len(w.layers)} weight units, {n_params} params, "
+        "config": {"workload": f"{w.name}: {w.P}-stage {'Transformer' if is_tfm else 'CNN' if is_cnn else 'MLP'}, {len(w.layers)} weight units, {n_params} params, "
                                f"microbatch {w.microbatch}{' x ' + str(w.arch['seq']) + ' tokens' if is_tfm else ''}, "
                                f"PipeMare delays tau_fwd={tau_fwd[0]}..{tau_fwd[-1]}, tau_bkwd=0, "
                                f"{o['kind']} beta {o['beta']}, T1 K={o['K']}, T2 D={o['D']}",
@@ -198,7 +210,7 @@ def cpu_baseline(w, params, tau_fwd, tau_bkwd, n_steps):
     except Exception:
         threads = os.cpu_count()
     o = w.opt
-    orc = make_oracle(w, params, tau_fwd, tau_bkwd, opt=o["kind"], lr=o["lr"], beta=o["beta"], beta2=o.get("beta2", 0.98),
+    orc = make_oracle(w, params, tau_fwd, tau_bkwd, opt=o["kind"], lr=o.get("lr", 0.0), beta=o["beta"], beta2=o.get("beta2", 0.98),
                       D=o["D"], K=o["K"], weight_decay=o["weight_decay"], sched=o.get("sched"))
     stream = wl.batch_stream(w)
     batches = [stream.batch(k) for k in range(n_steps + 2)]

@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
+#include <climits>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -85,7 +86,7 @@ struct Layout {
   size_t t_xf, t_muf, t_rsf, t_nf, t_logits, t_dlogits;      // final LayerNorm and head
   size_t t_dx, t_dn, t_do;                                   // backward scratch, reused by every layer
   size_t t_pos, t_zero;                                      // positions fp32 [S, d]; zero-region table
-  size_t t_wprobs, t_wtiles;                                 // grouped weight-gradient launch: problems (2 sets), tile starts
+  size_t t_wprobs, t_wtiles, t_wsegs;                        // grouped weight-gradient launch: problems (2 sets), tiles per XCD, segments
   int n_zero = 0;
   int64_t zero_max = 0;
 };
@@ -239,7 +240,8 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
     lay.t_dx = take(Tk * d * 4); lay.t_dn = take(Tk * d * 4); lay.t_do = take(Tk * d * e);
     lay.t_pos = take((size_t)o->seq_len * d * 4);
     lay.t_wprobs = take(sizeof(PmGemmProb<PmEpiBwdWeight>) * 2 * L);
-    lay.t_wtiles = take(sizeof(int32_t) * (L + 1));
+    lay.t_wtiles = take(sizeof(int32_t) * 8);
+    lay.t_wsegs = take(sizeof(PmXcdSeg) * 8 * (size_t)(L + 8));
     // gradient regions that are accumulated with atomics and therefore cleared at the start of a
     // minibatch: the embedding table and every LayerNorm
     lay.n_zero = 0;
@@ -310,7 +312,8 @@ struct pm_ctx {
   // all weight-gradient products as one grouped MFMA launch (problem tables live in the arena)
   bool dw_grouped = false;
   int dw_maxI = 0, dw_maxJ = 0;
-  int dw_nprob = 0, dw_ntiles = 0;   // Transformer: problems and 128 x 128 tiles of the grouped launch
+  int dw_nprob = 0, dw_ntiles = 0;   // Transformer: problems and grid size (8 x the longest XCD list) of the grouped launch
+  int dw_max_segs = 0;
   bool dw_aligned = false;           // no tile of the grouped launch needs a bounds test
   // overlap of the update of step t with the forward of step t+1 (second stream owned by the library)
   bool overlap = false;
@@ -690,10 +693,12 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
       const auto* tab = c->at<PmGemmProb<PmEpiBwdWeight>>(lay.t_wprobs) + (accumulate ? c->dw_nprob : 0);
       if (c->dw_aligned)
         hipLaunchKernelGGL((pm_gemm_big_grouped_kernel<PmBig128, false, false, false, PmEpiBwdWeight>), dim3(c->dw_ntiles),
-                           dim3(PmBig128::NT), 0, st, tab, c->at<int32_t>(lay.t_wtiles), c->dw_nprob);
+                           dim3(PmBig128::NT), 0, st, tab, c->at<PmXcdSeg>(lay.t_wsegs), c->at<int32_t>(lay.t_wtiles),
+                           c->dw_max_segs);
       else
         hipLaunchKernelGGL((pm_gemm_big_grouped_kernel<PmBig128, false, false, true, PmEpiBwdWeight>), dim3(c->dw_ntiles),
-                           dim3(PmBig128::NT), 0, st, tab, c->at<int32_t>(lay.t_wtiles), c->dw_nprob);
+                           dim3(PmBig128::NT), 0, st, tab, c->at<PmXcdSeg>(lay.t_wsegs), c->at<int32_t>(lay.t_wtiles),
+                           c->dw_max_segs);
     }
   }
   {
@@ -1080,7 +1085,6 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
       std::stable_sort(wp.begin(), wp.end(), [&](const WP& a, const WP& b) { return tiles_of(a) > tiles_of(b); });
       const int np = (int)wp.size();
       probs.resize((size_t)2 * np);
-      std::vector<int32_t> starts(np + 1, 0);
       bool fits = true, aligned = true;
       for (int i = 0; i < np; ++i) {
         const Unit& u = lay.units[wp[i].u];
@@ -1093,15 +1097,50 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
           pr.B = PmWLoc<bf16_t>{wp[i].a_in, nullptr, 0}; pr.ldb = u.d.n_in;
           pr.epi = PmEpiBwdWeight{g + u.off, u.d.n_in, acc, g + u.off + u.boff};
         }
-        starts[i + 1] = starts[i] + (int32_t)tiles_of(wp[i]);
       }
+      // Work lists per XCD (largest problems first, each to the least loaded XCD).  A problem with more
+      // than 1/8 of all tiles is cut into ranges of whole 8-row tile panels spread over all XCDs.
+      int64_t total_tiles = 0;
+      for (int i = 0; i < np; ++i) total_tiles += tiles_of(wp[i]);
+      const int max_segs = np + 8;
+      std::vector<PmXcdSeg> segs((size_t)8 * max_segs, PmXcdSeg{0, 0, INT32_MAX, 0});
+      int32_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0}, nseg[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      auto push = [&](int x, int prob, int tile0, int count) {
+        segs[(size_t)x * max_segs + nseg[x]] = PmXcdSeg{prob, tile0, load[x], 0};
+        nseg[x] += 1;
+        load[x] += count;
+      };
+      for (int i = 0; i < np; ++i) {
+        const pm_layer_desc& dd = lay.units[wp[i].u].d;
+        const int ti = (dd.n_out + 127) / 128, tj = (dd.n_in + 127) / 128;
+        if ((int64_t)ti * tj * 8 > total_tiles && ti >= 16) {
+          const int panels = (ti + 7) / 8;                       // panels of 8 tile rows (the body's walking order)
+          int p0 = 0;
+          for (int x = 0; x < 8; ++x) {
+            const int p1 = (int)((int64_t)panels * (x + 1) / 8);
+            if (p1 > p0) {
+              const int r0 = p0 * 8, r1 = std::min(p1 * 8, ti);
+              push(x, i, r0 * tj, (r1 - r0) * tj);
+            }
+            p0 = p1;
+          }
+        } else {
+          int best = 0;
+          for (int x = 1; x < 8; ++x)
+            if (load[x] < load[best]) best = x;
+          push(best, i, 0, ti * tj);
+        }
+      }
+      const int32_t longest = *std::max_element(load, load + 8);
       c->dw_grouped = fits;
       c->dw_aligned = aligned;
       c->dw_nprob = np;
-      c->dw_ntiles = starts[np];
+      c->dw_ntiles = longest * 8;
+      c->dw_max_segs = max_segs;
       if ((e = hipMemcpyAsync(c->arena + lay.t_wprobs, probs.data(), probs.size() * sizeof(probs[0]), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy problem table");
-      if ((e = hipMemcpyAsync(c->arena + lay.t_wtiles, starts.data(), starts.size() * 4, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy tile table");
-      if ((e = hipStreamSynchronize(st)) != hipSuccess) return bail(e, "synchronise after tables");   // `starts` goes out of scope
+      if ((e = hipMemcpyAsync(c->arena + lay.t_wtiles, load, sizeof load, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy tile table");
+      if ((e = hipMemcpyAsync(c->arena + lay.t_wsegs, segs.data(), segs.size() * sizeof(PmXcdSeg), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy segment table");
+      if ((e = hipStreamSynchronize(st)) != hipSuccess) return bail(e, "synchronise after tables");   // host tables go out of scope
       probs.clear();
     }
   }

@@ -409,7 +409,8 @@ struct PmBigLds {
 // the other register set into the other LDS stage, a part behind each k-step.  A load therefore has
 // more than a slab of MFMA time to arrive before it is waited for; one barrier per slab.
 template <class Cfg, bool AKC, bool BKC, bool CHECK, class Epi>
-__device__ __forceinline__ void pm_gemm_big_body(const PmGemmProb<Epi>& pr, int id, int tiles_i, int tiles_j, bf16_t* smem) {
+__device__ __forceinline__ void pm_gemm_big_body(const PmGemmProb<Epi>& pr, int id, int tiles_i, int tiles_j, bf16_t* smem,
+                                                 bool xcd_remap = true) {
   constexpr int BI = Cfg::BI, BJ = Cfg::BJ, WI = Cfg::WI, WJ = Cfg::WJ, NT = Cfg::NT, BK = 64;
   constexpr int TI = BI / WI / 32, TJ = BJ / WJ / 32;
   using SA = PmBigTile<BI, AKC>;
@@ -419,7 +420,7 @@ __device__ __forceinline__ void pm_gemm_big_body(const PmGemmProb<Epi>& pr, int 
   // XCD-aware mapping: consecutive block ids land on consecutive XCDs (8 of them), so give each
   // XCD a contiguous range of tiles, and inside it walk the tiles in column panels of 8 row tiles.
   const int nblk = tiles_i * tiles_j;
-  if ((nblk & 7) == 0) id = (id & 7) * (nblk >> 3) + (id >> 3);
+  if (xcd_remap && (nblk & 7) == 0) id = (id & 7) * (nblk >> 3) + (id >> 3);
   constexpr int GROUP = 8;
   const int panel = id / (GROUP * tiles_j);
   const int first_i = panel * GROUP;
@@ -576,22 +577,36 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WP
   pm_gemm_big_body<Cfg, AKC, BKC, CHECK, Epi>(pr, blockIdx.x, tiles_i, tiles_j, smem);
 }
 
-// Many problems in one launch: tile_start[p] .. tile_start[p + 1] - 1 are the blocks of problem p
-// (tile_start has nprob + 1 entries, the last is the grid size).  All weight-gradient products of a
-// token-rich step go out together: single problems of 64 tiles cannot fill 256 compute units, a
-// few thousand tiles in one grid can, with no split of the contraction and no atomics.
+// Many problems in one launch, scheduled per XCD.  Consecutive block ids land on consecutive XCDs
+// (8 of them, each with its own L2), so block b works for XCD b % 8 at position b / 8 of that XCD's
+// own work list: a list of segments (problem, first tile, tile count) built by the host so that the
+// tiles that run concurrently on one XCD come from one problem (or one row range of a huge one) and
+// share their operand panels through that XCD's L2.  All weight-gradient products of a token-rich
+// step go out together this way: single problems of 64 tiles cannot fill 256 compute units, and with
+// the contraction over thousands of tokens every re-read of an operand panel from memory is what
+// bounds the kernel.  No split of the contraction, no atomics.
+struct PmXcdSeg {
+  int32_t prob;        // problem index
+  int32_t tile0;       // first tile of the problem handled by this segment (panel order, see the body)
+  int32_t start;       // position of the segment's first tile in the XCD's list
+  int32_t pad_;
+};
+// segs: 8 lists of `max_segs` entries each (unused entries have start = INT_MAX); nseg[x] entries are valid
 template <class Cfg, bool AKC, bool BKC, bool CHECK, class Epi>
-__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WPE, Cfg::WPE))) void pm_gemm_big_grouped_kernel(const PmGemmProb<Epi>* __restrict__ probs, const int* __restrict__ tile_start, int nprob) {
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WPE, Cfg::WPE))) void pm_gemm_big_grouped_kernel(const PmGemmProb<Epi>* __restrict__ probs, const PmXcdSeg* __restrict__ segs, const int32_t* __restrict__ xcd_tiles, int max_segs) {
   __shared__ __attribute__((aligned(16))) bf16_t smem[PmBigLds<Cfg, AKC, BKC>::elems];
-  const int bid = blockIdx.x;
-  int lo = 0, hi = nprob - 1;                 // largest p with tile_start[p] <= bid
+  const int x = blockIdx.x & 7, pos = blockIdx.x >> 3;
+  if (pos >= xcd_tiles[x]) return;
+  const PmXcdSeg* list = segs + (size_t)x * max_segs;
+  int lo = 0, hi = max_segs - 1;                 // last segment with start <= pos
   while (lo < hi) {
     const int mid = (lo + hi + 1) >> 1;
-    if (tile_start[mid] <= bid) lo = mid; else hi = mid - 1;
+    if (list[mid].start <= pos) lo = mid; else hi = mid - 1;
   }
-  const PmGemmProb<Epi> pr = probs[lo];
+  const PmXcdSeg sg = list[lo];
+  const PmGemmProb<Epi> pr = probs[sg.prob];
   const int ti = (pr.I + Cfg::BI - 1) / Cfg::BI, tj = (pr.J + Cfg::BJ - 1) / Cfg::BJ;
-  pm_gemm_big_body<Cfg, AKC, BKC, CHECK, Epi>(pr, bid - tile_start[lo], ti, tj, smem);
+  pm_gemm_big_body<Cfg, AKC, BKC, CHECK, Epi>(pr, sg.tile0 + (pos - sg.start), ti, tj, smem, false);
 }
 
 // 128 x 128 block, 4 waves x (64 x 64): 80 KB of LDS, so two blocks share a CU and cover each
