@@ -266,13 +266,18 @@ pm_status pm_attention_bwd(void* stream, int32_t dtype, int32_t B, int32_t S, in
  * of 16 (at most 64) runs as implicit GEMM on MFMA, anything else on plain kernels.  C_out a multiple of 8.
  *   fwd:        z = conv(x, W); y = relu(scale * z + shift)     x [B,H,W,C_in] -> z, y [B,Ho,Wo,C_out], Ho = (H-1)/stride+1
  *   bwd_data:   dx = transposed convolution of dz with W        dz [B,Ho,Wo,C_out] -> dx [B,H,W,C_in]
- *   bwd_weight: dW (fp32 [C_out][3][3][C_in]) = correlation of dz with x; overwritten (dW is cleared first) */
+ *   bwd_weight: dW (fp32 [C_out][3][3][C_in]) = correlation of dz with x; overwritten.  The MFMA path reduces per-block
+ *               partial results through a caller-provided device workspace of pm_conv3x3_bwd_weight_scratch bytes
+ *               (0 for shapes on the plain path; PM_ENOMEM if the workspace is too small). */
 pm_status pm_conv3x3_fwd(void* stream, int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t C_in, int32_t C_out,
                          int32_t stride, const void* x_dev, const void* params_dev, void* z_dev, void* y_dev);
 pm_status pm_conv3x3_bwd_data(void* stream, int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t C_in, int32_t C_out,
                               int32_t stride, const void* dz_dev, const void* params_dev, void* dx_dev);
+pm_status pm_conv3x3_bwd_weight_scratch(int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t C_in, int32_t C_out,
+                                        int32_t stride, size_t* out_bytes);
 pm_status pm_conv3x3_bwd_weight(void* stream, int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t C_in, int32_t C_out,
-                                int32_t stride, const void* dz_dev, const void* x_dev, float* dW_dev);
+                                int32_t stride, const void* dz_dev, const void* x_dev, float* dW_dev, void* scratch_dev,
+                                size_t scratch_bytes);
 
 /* Waits for everything the context has enqueued, on the caller's stream and on the library's
  * second stream (overlap_update). */

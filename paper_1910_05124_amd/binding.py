@@ -19,7 +19,7 @@ __all__ = [
     "pm_state", "pm_device_step_table", "pm_stats", "pm_set_grads", "pm_apply_update", "pm_destroy",
     "pm_linear_fwd", "pm_linear_bwd_data", "pm_linear_bwd_weight", "pm_profile_begin", "pm_profile_end",
     "pm_synchronize", "PipeMare", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
-    "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight",
+    "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight", "pm_conv3x3_bwd_weight_scratch",
     "PM_LINEAR", "PM_KIND", "PM_ARCH", "PM_ACT", "PM_METHOD", "PM_LR", "PM_OPT", "PM_DTYPE", "PM_LOSS", "EXPORTS",
 ]
 
@@ -45,7 +45,8 @@ EXPORTS = ["pm_status_str", "pm_last_error", "pm_delays", "pm_slots", "pm_t1_lr"
            "pm_create", "pm_step", "pm_weights", "pm_state", "pm_device_step_table", "pm_stats",
            "pm_set_grads", "pm_apply_update", "pm_profile_begin", "pm_profile_end", "pm_linear_fwd", "pm_linear_bwd_data",
            "pm_linear_bwd_weight", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
-           "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight", "pm_synchronize", "pm_destroy"]
+           "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight", "pm_conv3x3_bwd_weight_scratch",
+           "pm_synchronize", "pm_destroy"]
 
 
 class pm_layer_desc(C.Structure):
@@ -104,7 +105,8 @@ lib.pm_attention_fwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _v
 lib.pm_attention_bwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.pm_conv3x3_fwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]
 lib.pm_conv3x3_bwd_data.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
-lib.pm_conv3x3_bwd_weight.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
+lib.pm_conv3x3_bwd_weight.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, C.c_size_t]
+lib.pm_conv3x3_bwd_weight_scratch.argtypes = [_i32, _i32, _i32, _i32, _i32, _i32, _i32, C.POINTER(C.c_size_t)]
 lib.pm_synchronize.argtypes = [_vp]
 lib.pm_destroy.argtypes = [_vp]
 lib.pm_destroy.restype = None
@@ -267,8 +269,15 @@ def pm_conv3x3_bwd_data(stream, dtype, B, H, W, C_in, C_out, stride, dz, params,
     _check(lib.pm_conv3x3_bwd_data(_vp(stream), PM_DTYPE[dtype], B, H, W, C_in, C_out, stride, dz, params, dx))
 
 
-def pm_conv3x3_bwd_weight(stream, dtype, B, H, W, C_in, C_out, stride, dz, x, dW):
-    _check(lib.pm_conv3x3_bwd_weight(_vp(stream), PM_DTYPE[dtype], B, H, W, C_in, C_out, stride, dz, x, dW))
+def pm_conv3x3_bwd_weight_scratch(dtype, B, H, W, C_in, C_out, stride) -> int:
+    out = C.c_size_t()
+    _check(lib.pm_conv3x3_bwd_weight_scratch(PM_DTYPE[dtype], B, H, W, C_in, C_out, stride, C.byref(out)))
+    return out.value
+
+
+def pm_conv3x3_bwd_weight(stream, dtype, B, H, W, C_in, C_out, stride, dz, x, dW, scratch=None, scratch_bytes=0):
+    _check(lib.pm_conv3x3_bwd_weight(_vp(stream), PM_DTYPE[dtype], B, H, W, C_in, C_out, stride, dz, x, dW, scratch,
+                                     scratch_bytes))
 
 
 def make_sched(kind="const", base=0.01, init=0.0, factor=1.0, interval=1, K=0) -> pm_lr_sched:

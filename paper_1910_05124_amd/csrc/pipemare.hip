@@ -82,7 +82,7 @@ struct Layout {
     size_t z, y, da, dz, dy;
   };
   std::vector<ConvBuf> cv;
-  size_t r_x, r_pool, r_logits, r_dlogits, r_dpool;
+  size_t r_x, r_pool, r_logits, r_dlogits, r_dpool, r_wscratch;
   size_t t_xf, t_muf, t_rsf, t_nf, t_logits, t_dlogits;      // final LayerNorm and head
   size_t t_dx, t_dn, t_do;                                   // backward scratch, reused by every layer
   size_t t_pos, t_zero;                                      // positions fp32 [S, d]; zero-region table
@@ -270,6 +270,10 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
     lay.r_logits = take((size_t)M * round_up(ncls, 8) * 4);
     lay.r_dlogits = take((size_t)M * round_up(ncls, 8) * e);
     lay.r_dpool = take((size_t)M * C * e);
+    size_t ws = 0;
+    for (int u = 0; u < nconv; ++u)
+      ws = std::max(ws, o->dtype == PM_BF16 ? pm_conv_wgrad_scratch_elems<bf16_t>(lay.cv[u].g) : (size_t)0);
+    lay.r_wscratch = take(ws * 4);
     lay.n_zero = nconv;
     lay.zero_max = 0;
     for (int u = 0; u < nconv; ++u) lay.zero_max = std::max(lay.zero_max, lay.units[u].n_pad);
@@ -791,7 +795,7 @@ pm_status launch_resnet(pm_ctx* c, const void* x_dev, const void* y_dev, int acc
     if (!pm_conv_affine_bwd_launch<T>(st, TT(b.dy), TT(b.y), TT(b.z), Wb(u, nw), TT(b.da), TT(b.dz), g + U(u).off + nw,
                                       g + U(u).off + nw + b.g.Cout, tot, b.g.Cout))
       return fail(PM_EINVAL, "unit %d: channel count not supported", u);
-    pm_conv_wgrad_launch<T>(st, b.g, TT(b.dz), input_of(u), g + U(u).off, accumulate);
+    pm_conv_wgrad_launch<T>(st, b.g, TT(b.dz), input_of(u), g + U(u).off, accumulate, c->at<float>(lay.r_wscratch));
     if (u == 0) break;
     PmShortcutBwd<T> sb{nullptr, 0, 0, 0, 1};
     if ((u % 2) == 1) {                               // first convolution of a block: its input also feeds the shortcut
@@ -1470,17 +1474,28 @@ pm_status pm_conv3x3_bwd_data(void* stream, int32_t dtype, int32_t B, int32_t H,
   return PM_OK;
 }
 
+pm_status pm_conv3x3_bwd_weight_scratch(int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t C_in, int32_t C_out,
+                                        int32_t stride, size_t* out_bytes) {
+  pm_status s = check_conv(dtype, B, H, W, C_in, C_out, stride);
+  if (s != PM_OK) return s;
+  if (!out_bytes) return fail(PM_EINVAL, "out_bytes is NULL");
+  const PmConvGeom g = conv_geom(B, H, W, C_in, C_out, stride);
+  *out_bytes = 4 * (dtype == PM_BF16 ? pm_conv_wgrad_scratch_elems<bf16_t>(g) : (size_t)0);
+  return PM_OK;
+}
+
 pm_status pm_conv3x3_bwd_weight(void* stream, int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t C_in, int32_t C_out,
-                                int32_t stride, const void* dz_dev, const void* x_dev, float* dW_dev) {
+                                int32_t stride, const void* dz_dev, const void* x_dev, float* dW_dev, void* scratch_dev,
+                                size_t scratch_bytes) {
   pm_status s = check_conv(dtype, B, H, W, C_in, C_out, stride);
   if (s != PM_OK) return s;
   if (!dz_dev || !x_dev || !dW_dev) return fail(PM_EINVAL, "NULL argument");
   const PmConvGeom g = conv_geom(B, H, W, C_in, C_out, stride);
+  const size_t need = 4 * (dtype == PM_BF16 ? pm_conv_wgrad_scratch_elems<bf16_t>(g) : (size_t)0);
+  if (need && (!scratch_dev || scratch_bytes < need)) return fail(PM_ENOMEM, "scratch has %zu bytes, %zu needed", scratch_bytes, need);
   hipStream_t st = (hipStream_t)stream;
-  const int64_t n = (int64_t)C_out * 9 * C_in;
-  hipLaunchKernelGGL(pm_zero_f32_kernel, dim3((unsigned)std::min<int64_t>(1024, (n + 255) / 256)), dim3(256), 0, st, dW_dev, n);
-  if (dtype == PM_BF16) pm_conv_wgrad_launch<bf16_t>(st, g, (const bf16_t*)dz_dev, (const bf16_t*)x_dev, dW_dev, 0);
-  else pm_conv_wgrad_launch<float>(st, g, (const float*)dz_dev, (const float*)x_dev, dW_dev, 0);
+  if (dtype == PM_BF16) pm_conv_wgrad_launch<bf16_t>(st, g, (const bf16_t*)dz_dev, (const bf16_t*)x_dev, dW_dev, 0, (float*)scratch_dev);
+  else pm_conv_wgrad_launch<float>(st, g, (const float*)dz_dev, (const float*)x_dev, dW_dev, 0, (float*)scratch_dev);
   PM_HIP(hipGetLastError());
   return PM_OK;
 }

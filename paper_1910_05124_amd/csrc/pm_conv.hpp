@@ -345,95 +345,191 @@ __global__ __launch_bounds__(256) void pm_conv_dgrad_mfma_kernel(PmConvGeom g, c
     }
 }
 
-// weight gradient.  Each wave owns a run of output pixels, 32 at a time: it parks the dz rows and
-// the (tap-shifted) input rows of the 32 pixels in a private LDS region and reads both transposed
-// (contraction = pixels).  One tap at a time; partial sums leave through fp32 atomics (the caller
-// zeroes the gradient at the start of a minibatch).  No block-level barrier after the set-up.
-template <int NTO, int NTI>   // channel tiles of 32 of Cout and Cin
+// weight gradient.  Each wave owns a run of output pixels, 32 at a time ("chunk"): it parks the dz
+// rows and the (tap-shifted) input rows of the 32 pixels in a private LDS region and reads both
+// transposed (contraction = pixels).  Work items are (tap, chunk) pairs, tap outermost so that one
+// accumulator set serves a tap; the global loads of the next item are in flight in a second register
+// set while the current item is stored to LDS and multiplied (a wave has no other wave to hide its
+// load latency behind here).  At the end of a tap the four waves of the block park their accumulators
+// in LDS, the block sums them and writes ITS partial dW of that tap to a scratch area;
+// pm_conv_wgrad_reduce_kernel sums the blocks' partials.  (Measured alternatives: fp32 atomics of
+// every wave straight into dW, or LDS float atomics for the block sum, each cost several times the
+// rest of the kernel.)
+template <int NTO, int NTI, int NCH>   // channel tiles of 32 of Cout and Cin; chunks of 32 pixels per wave
 __global__ __launch_bounds__(256) void pm_conv_wgrad_mfma_kernel(PmConvGeom g, const bf16_t* __restrict__ dz,
-                                                                 const bf16_t* __restrict__ x, float* __restrict__ dW,
-                                                                 int chunks_per_wave) {
+                                                                 const bf16_t* __restrict__ x, float* __restrict__ part) {
   constexpr int SA = NTO * 32 + 8, SB = NTI * 32 + 8;     // LDS row strides (elements)
+  constexpr int PA = NTO * 2, PB = NTI * 2;               // 16-byte pieces per lane of a 32-pixel tile
+  constexpr int RW = NTI * 32;                            // row width of the block's reduction tile
   __shared__ __attribute__((aligned(16))) bf16_t sA[4][32 * SA];
   __shared__ __attribute__((aligned(16))) bf16_t sB[4][32 * SB];
+  __shared__ float red[4][NTO * 32 * RW];                 // one accumulator image per wave
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   bf16_t* wa = sA[wave];
   bf16_t* wb = sB[wave];
   for (int c = lane; c < 32 * SA / 8; c += 64) *reinterpret_cast<uint4*>(wa + c * 8) = make_uint4(0, 0, 0, 0);
   for (int c = lane; c < 32 * SB / 8; c += 64) *reinterpret_cast<uint4*>(wb + c * 8) = make_uint4(0, 0, 0, 0);
-  __builtin_amdgcn_wave_barrier();
-  const int64_t npix = (int64_t)g.B * g.Ho * g.Wo;
-  const int64_t p_begin = ((int64_t)blockIdx.x * 4 + wave) * chunks_per_wave * 32;
+  __syncthreads();
+  const int npix = g.B * g.Ho * g.Wo;                      // fits 32 bits (checked by the dispatcher)
+  const int p_begin = (blockIdx.x * 4 + wave) * NCH * 32;
   const int pa = g.Cout / 8, pb = g.Cin / 8;               // 16-byte pieces per row
-  for (int tap = 0; tap < 9; ++tap) {
-    pm_f32x16 acc[NTO][NTI];
+  const int64_t nW = (int64_t)g.Cout * 9 * g.Cin;
+  float* my_part = part + (int64_t)blockIdx.x * nW;
+
+  // Per chunk and piece, once: where this lane's piece comes from.  Loads are unconditional (clamped
+  // to a valid address) and zeroed by a select afterwards, so they issue back to back and the waits
+  // before the LDS stores count only the older register set.
+  int a_off[NCH][PA];        // element offset into dz, or -1 (piece not used / pixel past the end)
+  int b_ctr[NCH][PB];        // input pixel index of the centre tap, or -1
+  int b_yx[NCH][PB];         // (iy << 16 | ix) of the centre tap
+#pragma unroll
+  for (int ch = 0; ch < NCH; ++ch) {
+#pragma unroll
+    for (int j = 0; j < PA; ++j) {
+      const int c = lane + 64 * j, p = p_begin + ch * 32 + c / pa;
+      a_off[ch][j] = (c < 32 * pa && p < npix) ? p * g.Cout + (c % pa) * 8 : -1;
+    }
+#pragma unroll
+    for (int j = 0; j < PB; ++j) {
+      const int c = lane + 64 * j, p = p_begin + ch * 32 + c / pb;
+      if (c < 32 * pb && p < npix) {
+        const unsigned up = (unsigned)p, wo = (unsigned)g.Wo, ho = (unsigned)g.Ho;
+        const int ox = (int)(up % wo), oy = (int)((up / wo) % ho), bb = (int)(up / (wo * ho));
+        const int iy = oy * g.stride, ix = ox * g.stride;
+        b_ctr[ch][j] = (bb * g.H + iy) * g.W + ix;
+        b_yx[ch][j] = (iy << 16) | ix;
+      } else {
+        b_ctr[ch][j] = -1;
+        b_yx[ch][j] = 0;
+      }
+    }
+  }
+  int cbv[PB];                                             // column of this lane's j-th input piece
+#pragma unroll
+  for (int j = 0; j < PB; ++j) cbv[j] = ((lane + 64 * j) % pb) * 8;
+
+  auto load_regs = [&](int tap, int ch, uint4* ra, uint4* rb) __attribute__((always_inline)) {
+    const int dy = tap / 3 - 1, dx = tap % 3 - 1;
+#pragma unroll
+    for (int j = 0; j < PA; ++j) {
+      const int o = a_off[ch][j];
+      ra[j] = *reinterpret_cast<const uint4*>(dz + (o < 0 ? 0 : o));
+    }
+#pragma unroll
+    for (int j = 0; j < PB; ++j) {
+      const int ctr = b_ctr[ch][j];
+      const int iy = (b_yx[ch][j] >> 16) + dy, ix = (b_yx[ch][j] & 0xffff) + dx;
+      const bool ok = ctr >= 0 && iy >= 0 && iy < g.H && ix >= 0 && ix < g.W;
+      rb[j] = *reinterpret_cast<const uint4*>(x + (ok ? (int64_t)(ctr + dy * g.W + dx) * g.Cin + cbv[j] : 0));
+    }
+  };
+  // zero what must not contribute (after the data has arrived, right before it is parked)
+  auto store_regs = [&](int tap, int ch, const uint4* ra, const uint4* rb) __attribute__((always_inline)) {
+    const int dy = tap / 3 - 1, dx = tap % 3 - 1;
+    // (component-wise selects: a select between whole uint4 objects would go through memory)
+#pragma unroll
+    for (int j = 0; j < PA; ++j) {
+      const int c = lane + 64 * j;
+      const unsigned m = a_off[ch][j] < 0 ? 0u : 0xffffffffu;
+      if (c < 32 * pa)
+        *reinterpret_cast<uint4*>(wa + (c / pa) * SA + (c % pa) * 8) = make_uint4(ra[j].x & m, ra[j].y & m, ra[j].z & m, ra[j].w & m);
+    }
+#pragma unroll
+    for (int j = 0; j < PB; ++j) {
+      const int c = lane + 64 * j;
+      const int iy = (b_yx[ch][j] >> 16) + dy, ix = (b_yx[ch][j] & 0xffff) + dx;
+      const bool ok = b_ctr[ch][j] >= 0 && iy >= 0 && iy < g.H && ix >= 0 && ix < g.W;
+      const unsigned m = ok ? 0xffffffffu : 0u;
+      if (c < 32 * pb) *reinterpret_cast<uint4*>(wb + (c / pb) * SB + cbv[j]) = make_uint4(rb[j].x & m, rb[j].y & m, rb[j].z & m, rb[j].w & m);
+    }
+  };
+  pm_f32x16 acc[NTO][NTI];
+  auto mma = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      pm_bf16x8 fa[NTO], fb[NTI];
+      const int ql = lane >> 4, q = lane & 15;
+      typedef pm_v4s __attribute__((address_space(3))) * lds_v4s;
+#pragma unroll
+      for (int a = 0; a < NTO; ++a) {
+        const bf16_t* pp = wa + (ks * 16 + 8 * (ql >> 1) + (q >> 2)) * SA + a * 32 + 16 * (ql & 1) + 4 * (q & 3);
+        union { pm_bf16x8 v; pm_v4s h[2]; } u;
+        u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(pp));
+        u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(pp + 4 * SA));
+        fa[a] = u.v;
+      }
+#pragma unroll
+      for (int bb = 0; bb < NTI; ++bb) {
+        const bf16_t* pp = wb + (ks * 16 + 8 * (ql >> 1) + (q >> 2)) * SB + bb * 32 + 16 * (ql & 1) + 4 * (q & 3);
+        union { pm_bf16x8 v; pm_v4s h[2]; } u;
+        u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(pp));
+        u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(pp + 4 * SB));
+        fb[bb] = u.v;
+      }
+#pragma unroll
+      for (int a = 0; a < NTO; ++a)
+#pragma unroll
+        for (int bb = 0; bb < NTI; ++bb)
+          acc[a][bb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[bb], acc[a][bb], 0, 0, 0);
+    }
+  };
+  uint4 ra[2][PA], rb[2][PB];
+  load_regs(0, 0, ra[0], rb[0]);
+#pragma unroll
+  for (int tap = 0; tap < 9; ++tap) {       // fully unrolled: every register-set and table index is static
 #pragma unroll
     for (int a = 0; a < NTO; ++a)
 #pragma unroll
       for (int bb = 0; bb < NTI; ++bb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[a][bb][e] = 0.f;
-    for (int ch = 0; ch < chunks_per_wave; ++ch) {
-      const int64_t p0 = p_begin + (int64_t)ch * 32;
-      if (p0 >= npix) break;                                // wave-uniform
-      for (int c = lane; c < 32 * pa; c += 64) {
-        const int r = c / pa, col = (c % pa) * 8;
-        const int64_t p = p0 + r;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (p < npix) v = *reinterpret_cast<const uint4*>(dz + p * g.Cout + col);
-        *reinterpret_cast<uint4*>(wa + r * SA + col) = v;
-      }
-      for (int c = lane; c < 32 * pb; c += 64) {
-        const int r = c / pb, col = (c % pb) * 8;
-        const int64_t p = p0 + r;
-        const int ox = (int)(p % g.Wo), oy = (int)((p / g.Wo) % g.Ho), b = (int)(p / ((int64_t)g.Wo * g.Ho));
-        const int iy = oy * g.stride + tap / 3 - 1, ix = ox * g.stride + tap % 3 - 1;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (p < npix && iy >= 0 && iy < g.H && ix >= 0 && ix < g.W)
-          v = *reinterpret_cast<const uint4*>(x + (((int64_t)b * g.H + iy) * g.W + ix) * g.Cin + col);
-        *reinterpret_cast<uint4*>(wb + r * SB + col) = v;
-      }
+    // items (tap, 0 .. NCH - 1); item (tap, ch) sits in register set ch & 1 (NCH is even or 1, and the
+    // first item of the next tap is requested during the last item of this one into set 0)
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      const int cur = NCH == 1 ? (tap & 1) : (ch & 1);
+      store_regs(tap, ch, ra[cur], rb[cur]);
+      if (ch + 1 < NCH) load_regs(tap, ch + 1, ra[cur ^ 1], rb[cur ^ 1]);
+      else if (tap + 1 < 9) load_regs(tap + 1, 0, ra[cur ^ 1], rb[cur ^ 1]);
       __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        pm_bf16x8 fa[NTO], fb[NTI];
-        const int ql = lane >> 4, q = lane & 15;
-        typedef pm_v4s __attribute__((address_space(3))) * lds_v4s;
-#pragma unroll
-        for (int a = 0; a < NTO; ++a) {
-          const bf16_t* pp = wa + (ks * 16 + 8 * (ql >> 1) + (q >> 2)) * SA + a * 32 + 16 * (ql & 1) + 4 * (q & 3);
-          union { pm_bf16x8 v; pm_v4s h[2]; } u;
-          u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(pp));
-          u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(pp + 4 * SA));
-          fa[a] = u.v;
-        }
-#pragma unroll
-        for (int bb = 0; bb < NTI; ++bb) {
-          const bf16_t* pp = wb + (ks * 16 + 8 * (ql >> 1) + (q >> 2)) * SB + bb * 32 + 16 * (ql & 1) + 4 * (q & 3);
-          union { pm_bf16x8 v; pm_v4s h[2]; } u;
-          u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(pp));
-          u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(pp + 4 * SB));
-          fb[bb] = u.v;
-        }
-#pragma unroll
-        for (int a = 0; a < NTO; ++a)
-#pragma unroll
-          for (int bb = 0; bb < NTI; ++bb)
-            acc[a][bb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[bb], acc[a][bb], 0, 0, 0);
-      }
+      mma();
       __builtin_amdgcn_wave_barrier();
     }
-    // accumulator value v of lane l: row co = 32 a + 8 (v / 4) + 4 (l / 32) + v % 4, column ci = 32 bb + l % 32
-    const int kg = lane >> 5, cl = lane & 31;
+    // block reduction of the tap: accumulator value v of lane l is row co = 32 a + 8 (v / 4) + 4 (l / 32) + v % 4,
+    // column ci = 32 bb + l % 32
+    {
+      const int kg = lane >> 5, cl = lane & 31;
 #pragma unroll
-    for (int a = 0; a < NTO; ++a)
+      for (int a = 0; a < NTO; ++a)
 #pragma unroll
-      for (int bb = 0; bb < NTI; ++bb)
+        for (int bb = 0; bb < NTI; ++bb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int co = a * 32 + 8 * (v >> 2) + 4 * kg + (v & 3), ci = bb * 32 + cl;
-          if (co < g.Cout && ci < g.Cin) atomicAdd(dW + ((int64_t)co * 9 + tap) * g.Cin + ci, acc[a][bb][v]);
-        }
+          for (int v = 0; v < 16; ++v)
+            red[wave][(a * 32 + 8 * (v >> 2) + 4 * kg + (v & 3)) * RW + bb * 32 + cl] = acc[a][bb][v];
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < g.Cout * g.Cin; e += 256) {
+      const int co = e / g.Cin, ci = e - co * g.Cin, o = co * RW + ci;
+      my_part[((int64_t)co * 9 + tap) * g.Cin + ci] = red[0][o] + red[1][o] + red[2][o] + red[3][o];
+    }
+    __syncthreads();
+  }
+}
+
+// dW[e] (+)= sum over the blocks' partials.  Block = 64 elements x 4 slices of the partial range.
+__global__ __launch_bounds__(256) void pm_conv_wgrad_reduce_kernel(const float* __restrict__ part, int nparts, int64_t nW,
+                                                                   float* __restrict__ dW, int accumulate) {
+  const int el = threadIdx.x & 63, sl = threadIdx.x >> 6;
+  const int64_t e = (int64_t)blockIdx.x * 64 + el;
+  float acc = 0.f;
+  if (e < nW)
+    for (int p = sl; p < nparts; p += 4) acc += part[(int64_t)p * nW + e];
+  __shared__ float s[4][64];
+  s[sl][el] = acc;
+  __syncthreads();
+  if (sl == 0 && e < nW) {
+    const float v = s[0][el] + s[1][el] + s[2][el] + s[3][el];
+    dW[e] = accumulate ? dW[e] + v : v;
   }
 }
 
@@ -478,25 +574,44 @@ inline void pm_conv_dgrad_launch(hipStream_t st, const PmConvGeom& g, const T* d
                      0, st, g, dz, w, sb, dx);
 }
 
-// dW (fp32 [Cout][9][Cin]).  The MFMA path ADDS to dW (atomics): the caller clears it first unless
-// accumulating.  The plain path overwrites or accumulates per `accumulate`.
+// blocks and chunks per wave (4 on large maps, 1 on small ones) of the MFMA weight-gradient kernel
+inline void pm_conv_wgrad_plan(const PmConvGeom& g, int* blocks, int* cpw) {
+  const int64_t npix = (int64_t)g.B * g.Ho * g.Wo;
+  const int64_t chunks = (npix + 31) / 32;
+  const int c = chunks >= 2048 ? 4 : 1;
+  *cpw = c;
+  *blocks = (int)((chunks + (int64_t)c * 4 - 1) / ((int64_t)c * 4));
+}
+// fp32 scratch elements the MFMA path needs (0: the plain path is used)
 template <typename T>
-inline void pm_conv_wgrad_launch(hipStream_t st, const PmConvGeom& g, const T* dz, const T* x, float* dW, int accumulate) {
+inline size_t pm_conv_wgrad_scratch_elems(const PmConvGeom& g) {
+  if (sizeof(T) != 2 || !pm_conv_mfma_fits(g.Cin, g.Cout)) return 0;
+  if ((int64_t)g.B * g.H * g.W * std::max(g.Cin, g.Cout) >= (int64_t)1 << 31) return 0;   // 32-bit indexing inside
+  int blocks, cpw;
+  pm_conv_wgrad_plan(g, &blocks, &cpw);
+  return (size_t)blocks * g.Cout * 9 * g.Cin;
+}
+
+// dW (fp32 [Cout][9][Cin]) = (accumulate ? dW : 0) + correlation of dz with x.  `scratch` must hold
+// pm_conv_wgrad_scratch_elems floats (unused by the plain path).
+template <typename T>
+inline void pm_conv_wgrad_launch(hipStream_t st, const PmConvGeom& g, const T* dz, const T* x, float* dW, int accumulate,
+                                 float* scratch) {
   if constexpr (sizeof(T) == 2) {
-    if (pm_conv_mfma_fits(g.Cin, g.Cout)) {
-      const int64_t npix = (int64_t)g.B * g.Ho * g.Wo;
-      const int64_t chunks = (npix + 31) / 32;
-      // about 256 blocks of 4 waves; fewer, longer runs for the small late maps (fewer atomics)
-      int cpw = (int)((chunks + 1023) / 1024);
-      if (cpw < 4) cpw = 4;
-      const unsigned blocks = (unsigned)((chunks + (int64_t)cpw * 4 - 1) / ((int64_t)cpw * 4));
+    if (pm_conv_wgrad_scratch_elems<T>(g) > 0) {
+      int blocks, cpw;
+      pm_conv_wgrad_plan(g, &blocks, &cpw);
       const dim3 grid(blocks), blk(256);
-#define PM_CW(A, B) hipLaunchKernelGGL((pm_conv_wgrad_mfma_kernel<A, B>), grid, blk, 0, st, g, dz, x, dW, cpw)
+#define PM_CW(A, B) do { if (cpw == 4) hipLaunchKernelGGL((pm_conv_wgrad_mfma_kernel<A, B, 4>), grid, blk, 0, st, g, dz, x, scratch); \
+                         else hipLaunchKernelGGL((pm_conv_wgrad_mfma_kernel<A, B, 1>), grid, blk, 0, st, g, dz, x, scratch); } while (0)
       if (g.Cout <= 32 && g.Cin <= 32) PM_CW(1, 1);
       else if (g.Cout <= 32) PM_CW(1, 2);
       else if (g.Cin <= 32) PM_CW(2, 1);
       else PM_CW(2, 2);
 #undef PM_CW
+      const int64_t nW = (int64_t)g.Cout * 9 * g.Cin;
+      hipLaunchKernelGGL(pm_conv_wgrad_reduce_kernel, dim3((unsigned)((nW + 63) / 64)), dim3(256), 0, st, scratch, blocks, nW,
+                         dW, accumulate);
       return;
     }
   }

@@ -177,12 +177,8 @@ __global__ __launch_bounds__(512) void pm_ln_bwd_kernel(const float* __restrict_
                                                         PmWLoc<T> gain_bkwd, const float* dx_res, float* dx_out,
                                                         T* dx_out_t, float* __restrict__ dgain, float* __restrict__ dbias,
                                                         int rows, int d) {
-  __shared__ float red[2][256 * NC];
+  __shared__ float4 red[8][2][64 * NC];                       // per wave: gain and bias partial sums
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  for (int j = threadIdx.x; j < 256 * NC; j += 512) {
-    red[0][j] = 0.f;
-    red[1][j] = 0.f;
-  }
   const T* g = gain_bkwd.get();
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
   float4 gj[NC], ag[NC], ab[NC];
@@ -234,19 +230,26 @@ __global__ __launch_bounds__(512) void pm_ln_bwd_kernel(const float* __restrict_
       }
     }
   }
-  __syncthreads();                                            // red is zeroed
+  // block sum of the per-wave partials (plain LDS stores and loads: LDS float atomics were measured
+  // several times slower), then one fp32 atomic per column and block
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
-    const int j = 256 * c + 4 * lane;
-    atomicAdd(&red[0][j], ag[c].x); atomicAdd(&red[0][j + 1], ag[c].y);
-    atomicAdd(&red[0][j + 2], ag[c].z); atomicAdd(&red[0][j + 3], ag[c].w);
-    atomicAdd(&red[1][j], ab[c].x); atomicAdd(&red[1][j + 1], ab[c].y);
-    atomicAdd(&red[1][j + 2], ab[c].z); atomicAdd(&red[1][j + 3], ab[c].w);
+    red[wave][0][64 * c + lane] = ag[c];
+    red[wave][1][64 * c + lane] = ab[c];
   }
   __syncthreads();
   for (int j = threadIdx.x; j < d; j += 512) {
-    atomicAdd(dgain + j, red[0][j]);
-    atomicAdd(dbias + j, red[1][j]);
+    float sg = 0.f, sb = 0.f;
+    const int c = j >> 8, l4 = (j & 255) >> 2, e = j & 3;      // column j = 256 c + 4 lane + e
+#pragma unroll
+    for (int w = 0; w < 8; ++w) {
+      const float* pg = reinterpret_cast<const float*>(&red[w][0][64 * c + l4]);
+      const float* pb = reinterpret_cast<const float*>(&red[w][1][64 * c + l4]);
+      sg += pg[e];
+      sb += pb[e];
+    }
+    atomicAdd(dgain + j, sg);
+    atomicAdd(dbias + j, sb);
   }
 }
 

@@ -49,7 +49,10 @@ def test_conv_primitives_against_numpy(torch_cuda, dtype, shape):
     st = torch.cuda.current_stream().cuda_stream
     pm.pm_conv3x3_fwd(st, dtype, B, H, W, Cin, Cout, stride, x.data_ptr(), params.data_ptr(), z.data_ptr(), y.data_ptr())
     pm.pm_conv3x3_bwd_data(st, dtype, B, H, W, Cin, Cout, stride, dz.data_ptr(), params.data_ptr(), dx.data_ptr())
-    pm.pm_conv3x3_bwd_weight(st, dtype, B, H, W, Cin, Cout, stride, dz.data_ptr(), x.data_ptr(), dW.data_ptr())
+    nscr = pm.pm_conv3x3_bwd_weight_scratch(dtype, B, H, W, Cin, Cout, stride)
+    scr = torch.empty(max(nscr, 4), dtype=torch.uint8, device="cuda")
+    pm.pm_conv3x3_bwd_weight(st, dtype, B, H, W, Cin, Cout, stride, dz.data_ptr(), x.data_ptr(), dW.data_ptr(),
+                             scr.data_ptr(), nscr)
     torch.cuda.synchronize()
     X, P, DZ = host(x), host(params), host(dz)
     Wm, sc, sh = P[:Cout * 9 * Cin].reshape(Cout, 9 * Cin), P[Cout * 9 * Cin:Cout * 9 * Cin + Cout], P[Cout * 9 * Cin + Cout:]
@@ -96,7 +99,7 @@ def test_small_resnet_modes(torch_cuda, case):
     dtype = "bf16" if case.endswith("bf16") else "f32"
     nb = 2 if case == "two_blocks_bf16" else 1
     w = wl.resnet(nb, 6, dtype=dtype, image=8)
-    kw = dict(opt="sgdm", lr=0.02 if dtype == "f32" else 0.005, beta=0.9, D=0.5, K=6)
+    kw = dict(opt="sgdm", lr=0.01 if dtype == "f32" else 0.005, beta=0.9, D=0.5, K=6)
     tau, N = None, 1
     if case == "t2_off":
         kw["t2"] = False
