@@ -122,7 +122,7 @@ pm_status validate(int32_t P, int32_t L, const pm_layer_desc* layers, const int3
     for (int l = 0; l < L - 1; ++l) {
       if (layers[l].kind != PM_CONV3X3) return fail(PM_EINVAL, "unit %d must be a 3x3 convolution", l);
       if (layers[l].n_out & 7) return fail(PM_EINVAL, "unit %d: channel count %d must be a multiple of 8", l, layers[l].n_out);
-      if (2048 % layers[l].n_out) return fail(PM_EINVAL, "unit %d: channel count %d must divide 2048", l, layers[l].n_out);
+      if (layers[l].n_out > 256 || (layers[l].n_out & (layers[l].n_out - 1))) return fail(PM_EINVAL, "unit %d: channel count %d must be a power of two up to 256", l, layers[l].n_out);
       if (layers[l].act != PM_ACT_RELU) return fail(PM_EINVAL, "unit %d: convolutions are followed by ReLU", l);
       if (l > 0 && layers[l].n_in != layers[l - 1].n_out) return fail(PM_EINVAL, "unit %d: n_in %d does not chain with previous n_out %d", l, layers[l].n_in, layers[l - 1].n_out);
       if (l > 0 && (l % 2) == 0 && layers[l].n_in != layers[l].n_out) return fail(PM_EINVAL, "unit %d: the second convolution of a block keeps the channel count", l);
@@ -272,7 +272,8 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
     lay.r_dpool = take((size_t)M * C * e);
     size_t ws = 0;
     for (int u = 0; u < nconv; ++u)
-      ws = std::max(ws, o->dtype == PM_BF16 ? pm_conv_wgrad_scratch_elems<bf16_t>(lay.cv[u].g) : (size_t)0);
+      ws = std::max(ws, o->dtype == PM_BF16 ? pm_conv_wgrad_scratch_elems<bf16_t>(lay.cv[u].g)
+                                            : pm_conv_wgrad_scratch_elems<float>(lay.cv[u].g));
     lay.r_wscratch = take(ws * 4);
     lay.n_zero = nconv;
     lay.zero_max = 0;
@@ -1480,7 +1481,7 @@ pm_status pm_conv3x3_bwd_weight_scratch(int32_t dtype, int32_t B, int32_t H, int
   if (s != PM_OK) return s;
   if (!out_bytes) return fail(PM_EINVAL, "out_bytes is NULL");
   const PmConvGeom g = conv_geom(B, H, W, C_in, C_out, stride);
-  *out_bytes = 4 * (dtype == PM_BF16 ? pm_conv_wgrad_scratch_elems<bf16_t>(g) : (size_t)0);
+  *out_bytes = 4 * (dtype == PM_BF16 ? pm_conv_wgrad_scratch_elems<bf16_t>(g) : pm_conv_wgrad_scratch_elems<float>(g));
   return PM_OK;
 }
 
@@ -1491,7 +1492,7 @@ pm_status pm_conv3x3_bwd_weight(void* stream, int32_t dtype, int32_t B, int32_t 
   if (s != PM_OK) return s;
   if (!dz_dev || !x_dev || !dW_dev) return fail(PM_EINVAL, "NULL argument");
   const PmConvGeom g = conv_geom(B, H, W, C_in, C_out, stride);
-  const size_t need = 4 * (dtype == PM_BF16 ? pm_conv_wgrad_scratch_elems<bf16_t>(g) : (size_t)0);
+  const size_t need = 4 * (dtype == PM_BF16 ? pm_conv_wgrad_scratch_elems<bf16_t>(g) : pm_conv_wgrad_scratch_elems<float>(g));
   if (need && (!scratch_dev || scratch_bytes < need)) return fail(PM_ENOMEM, "scratch has %zu bytes, %zu needed", scratch_bytes, need);
   hipStream_t st = (hipStream_t)stream;
   if (dtype == PM_BF16) pm_conv_wgrad_launch<bf16_t>(st, g, (const bf16_t*)dz_dev, (const bf16_t*)x_dev, dW_dev, 0, (float*)scratch_dev);

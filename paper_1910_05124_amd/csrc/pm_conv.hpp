@@ -153,6 +153,54 @@ __global__ __launch_bounds__(256) void pm_conv_wgrad_plain_kernel(PmConvGeom g, 
   }
 }
 
+// weight gradient of a convolution with very few input channels (the 3-channel input layer), any T.
+// grid (pixel groups, 9 taps); a thread walks pixels of its group and keeps the CO x CI outer-product
+// sums of its pixels in registers; wave shuffles, then LDS across the four waves; the block writes
+// its partial of the tap to scratch [group][co][tap][ci] for pm_conv_wgrad_reduce_kernel.
+template <typename T, int CO, int CI>
+__global__ __launch_bounds__(256) void pm_conv_wgrad_thin_kernel(PmConvGeom g, const T* __restrict__ dz,
+                                                                 const T* __restrict__ x, float* __restrict__ part) {
+  const int tap = blockIdx.y, dy = tap / 3 - 1, dx = tap % 3 - 1;
+  const int npix = g.B * g.Ho * g.Wo;
+  float acc[CO][CI];
+#pragma unroll
+  for (int a = 0; a < CO; ++a)
+#pragma unroll
+    for (int b = 0; b < CI; ++b) acc[a][b] = 0.f;
+  for (int p = blockIdx.x * 256 + threadIdx.x; p < npix; p += gridDim.x * 256) {
+    const unsigned up = (unsigned)p, wo = (unsigned)g.Wo, ho = (unsigned)g.Ho;
+    const int ox = (int)(up % wo), oy = (int)((up / wo) % ho), bb = (int)(up / (wo * ho));
+    const int iy = oy * g.stride + dy, ix = ox * g.stride + dx;
+    if (iy < 0 || iy >= g.H || ix < 0 || ix >= g.W) continue;
+    float xv[CI], dv[CO];
+    const T* xr = x + ((int64_t)(bb * g.H + iy) * g.W + ix) * CI;
+#pragma unroll
+    for (int b = 0; b < CI; ++b) xv[b] = ldf(xr + b);
+#pragma unroll
+    for (int a = 0; a < CO; a += 8) pm_ld8(dz + (int64_t)p * CO + a, dv + a);
+#pragma unroll
+    for (int a = 0; a < CO; ++a)
+#pragma unroll
+      for (int b = 0; b < CI; ++b) acc[a][b] += dv[a] * xv[b];
+  }
+  __shared__ float red[4][CO * CI];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+  for (int a = 0; a < CO; ++a)
+#pragma unroll
+    for (int b = 0; b < CI; ++b) {
+      const float s = pm_wave_sum(acc[a][b]);
+      if (lane == 0) red[wave][a * CI + b] = s;
+    }
+  __syncthreads();
+  if (threadIdx.x < CO * CI) {
+    const int a = threadIdx.x / CI, b = threadIdx.x % CI;
+    part[(int64_t)blockIdx.x * (CO * 9 * CI) + ((int64_t)a * 9 + tap) * CI + b] =
+        red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
+  }
+}
+constexpr int PM_CONV_THIN_GROUPS = 64;
+
 // da = dy * [y > 0];  dz = da * scale_bkwd;  dscale += sum da * z;  dshift += sum da   (fp32 atomics;
 // the caller zeroes dscale / dshift at the start of a minibatch).  Thread t of a block always sees
 // channel (t * 8 .. t * 8 + 7) mod C because a block's span is a multiple of C elements.
@@ -162,11 +210,9 @@ __global__ __launch_bounds__(256) void pm_conv_affine_bwd_kernel(const T* __rest
                                                                  T* __restrict__ da, T* __restrict__ dz,
                                                                  float* __restrict__ dscale, float* __restrict__ dshift,
                                                                  int64_t total, int C) {
-  __shared__ float red[2][256];
-  for (int j = threadIdx.x; j < 2 * 256; j += 256) (&red[0][0])[j] = 0.f;
-  __syncthreads();
+  __shared__ float red[4][2][256];
   const T* sbk = scale_bkwd.get();
-  const int c0 = (threadIdx.x * 8) % C;            // C is a multiple of 8 and divides 2048
+  const int c0 = (threadIdx.x * 8) % C;            // C is a power of two, 8 <= C <= 256
   float s8[8], as[8], at[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -190,15 +236,27 @@ __global__ __launch_bounds__(256) void pm_conv_affine_bwd_kernel(const T* __rest
     pm_st8(da + i, o1);
     pm_st8(dz + i, o2);
   }
+  // lanes l and l + C / 8 (mod 64) own the same channels: butterfly over the lane bits above C / 8, then
+  // the four waves meet in LDS (plain stores: LDS float atomics are slow), one fp32 atomic per channel and block
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, per = C >> 3;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    atomicAdd(&red[0][c0 + e], as[e]);
-    atomicAdd(&red[1][c0 + e], at[e]);
+    for (int o = 32; o >= per && o > 0; o >>= 1) {
+      as[e] += __shfl_xor(as[e], o, 64);
+      at[e] += __shfl_xor(at[e], o, 64);
+    }
+  }
+  if (lane < per || per > 64) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      red[wave][0][c0 + e] = as[e];
+      red[wave][1][c0 + e] = at[e];
+    }
   }
   __syncthreads();
   for (int j = threadIdx.x; j < C; j += 256) {
-    atomicAdd(dscale + j, red[0][j]);
-    atomicAdd(dshift + j, red[1][j]);
+    atomicAdd(dscale + j, red[0][0][j] + red[1][0][j] + red[2][0][j] + red[3][0][j]);
+    atomicAdd(dshift + j, red[0][1][j] + red[1][1][j] + red[2][1][j] + red[3][1][j]);
   }
 }
 
@@ -583,8 +641,12 @@ inline void pm_conv_wgrad_plan(const PmConvGeom& g, int* blocks, int* cpw) {
   *blocks = (int)((chunks + (int64_t)c * 4 - 1) / ((int64_t)c * 4));
 }
 // fp32 scratch elements the MFMA path needs (0: the plain path is used)
+inline bool pm_conv_thin_fits(const PmConvGeom& g) {
+  return g.Cin == 3 && g.Cout == 16 && (int64_t)g.B * g.H * g.W * 16 < ((int64_t)1 << 31);
+}
 template <typename T>
 inline size_t pm_conv_wgrad_scratch_elems(const PmConvGeom& g) {
+  if (pm_conv_thin_fits(g)) return (size_t)PM_CONV_THIN_GROUPS * g.Cout * 9 * g.Cin;
   if (sizeof(T) != 2 || !pm_conv_mfma_fits(g.Cin, g.Cout)) return 0;
   if ((int64_t)g.B * g.H * g.W * std::max(g.Cin, g.Cout) >= (int64_t)1 << 31) return 0;   // 32-bit indexing inside
   int blocks, cpw;
@@ -598,7 +660,7 @@ template <typename T>
 inline void pm_conv_wgrad_launch(hipStream_t st, const PmConvGeom& g, const T* dz, const T* x, float* dW, int accumulate,
                                  float* scratch) {
   if constexpr (sizeof(T) == 2) {
-    if (pm_conv_wgrad_scratch_elems<T>(g) > 0) {
+    if (!pm_conv_thin_fits(g) && pm_conv_wgrad_scratch_elems<T>(g) > 0) {
       int blocks, cpw;
       pm_conv_wgrad_plan(g, &blocks, &cpw);
       const dim3 grid(blocks), blk(256);
@@ -615,6 +677,13 @@ inline void pm_conv_wgrad_launch(hipStream_t st, const PmConvGeom& g, const T* d
       return;
     }
   }
+  if (pm_conv_thin_fits(g)) {
+    const int64_t nW = (int64_t)g.Cout * 9 * g.Cin;
+    hipLaunchKernelGGL((pm_conv_wgrad_thin_kernel<T, 16, 3>), dim3(PM_CONV_THIN_GROUPS, 9), dim3(256), 0, st, g, dz, x, scratch);
+    hipLaunchKernelGGL(pm_conv_wgrad_reduce_kernel, dim3((unsigned)((nW + 63) / 64)), dim3(256), 0, st, scratch,
+                       PM_CONV_THIN_GROUPS, nW, dW, accumulate);
+    return;
+  }
   hipLaunchKernelGGL((pm_conv_wgrad_plain_kernel<T>), dim3((unsigned)(g.Cout * 9 * g.Cin)), dim3(256), 0, st, g, dz, x, dW,
                      accumulate);
 }
@@ -622,7 +691,7 @@ inline void pm_conv_wgrad_launch(hipStream_t st, const PmConvGeom& g, const T* d
 template <typename T>
 inline bool pm_conv_affine_bwd_launch(hipStream_t st, const T* dy, const T* y, const T* z, PmWLoc<T> scale_bkwd, T* da, T* dz,
                                       float* dscale, float* dshift, int64_t total, int C) {
-  if ((C & 7) || (2048 % C) || C > 256) return false;
+  if (C < 8 || C > 256 || (C & (C - 1))) return false;        // a power of two in 8 .. 256
   const unsigned blocks = (unsigned)std::max<int64_t>(1, std::min<int64_t>(512, (total + 2047) / 2048));
   hipLaunchKernelGGL((pm_conv_affine_bwd_kernel<T>), dim3(blocks), dim3(256), 0, st, dy, y, z, scale_bkwd, da, dz, dscale,
                      dshift, total, C);
