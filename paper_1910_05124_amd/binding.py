@@ -28,6 +28,12 @@ _LIB_PATH = os.path.join(_HERE, "libpipemare.so")
 if not os.path.exists(_LIB_PATH):
     raise ImportError(f"{_LIB_PATH} is missing: build it with `python paper_1910_05124_amd/build.py` "
                       "(there is no fallback implementation)")
+# The arena and the streams handed to the library belong to PyTorch, so both must talk to ONE HIP
+# runtime.  PyTorch ships its own copy of libamdhip64 and loads it by path; loading it first makes
+# the library's dependency of the same soname resolve to that copy instead of a second runtime
+# (whose calls on PyTorch's pointers fail with "no ROCm-capable device").
+import torch  # noqa: E402,F401
+
 lib = C.CDLL(_LIB_PATH)
 
 PM_LINEAR = 0

@@ -123,3 +123,18 @@ def test_create_rejects_bad_arguments_before_touching_the_gpu():
     with pytest.raises(pm.PmError):
         pm.pm_apply_update(None)
     pm.pm_destroy(None)                                                # no-op
+
+
+def test_library_shares_the_hip_runtime_pytorch_loaded():
+    """The binding imports PyTorch before the library so that both use one copy of the HIP runtime
+    (a second copy cannot use PyTorch's device pointers and streams)."""
+    import subprocess
+    import sys
+    code = ("import paper_1910_05124_amd, re\n"
+            "libs = {l.split()[-1] for l in open('/proc/self/maps') if re.search(r'libamdhip64', l)}\n"
+            "assert len(libs) == 1, libs\n"
+            "import torch, os\n"
+            "assert os.path.dirname(next(iter(libs))) == os.path.join(os.path.dirname(torch.__file__), 'lib'), libs\n")
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True,
+                       cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    assert r.returncode == 0, r.stderr
