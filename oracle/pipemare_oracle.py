@@ -16,6 +16,11 @@ What it computes, with the paper passages it follows:
   * SGD with momentum in the paper's form v <- beta v - alpha g, w <- w + v               [App. B.3]
   * AdamW (decoupled weight decay) as the Transformer experiments' base optimizer         [App. C, Transformer table]
   * backpropagation with two weight sets: forward with u_fwd, data-gradient path with u_bkwd [Sec. 2.1]
+  * recomputation: activations inside a segment of stages are rebuilt in the backward pass from the
+    segment's stored input with a third weight set (u_recomp,t)_i = (w_{t - tau_recomp,i})_i, corrected
+    like u_bkwd: minus (tau_fwd,i - tau_recomp,i) * delta_t       [App. "Statistical efficiency and recompute"]
+    with tau_recomp,i = tau_bkwd,i + ceil(2 (S - j) / N) for the j-th of the S stages of a segment
+                                                                  [App. "PipeMare Recompute"]
 
 Readings where the paper is silent (documented in the design notes of the repository):
 versions before step 0 clamp to w_0; stages are 1-based; tau_i in T1 is tau_fwd,i and
@@ -28,8 +33,9 @@ equal-delay special case, the stability threshold of Lemma 1 from both sides, th
 momentum and T2 characteristic polynomials as annihilators of the oracle's trajectory,
 T1 closed form, delay tables, hand-worked scalar recurrences, finite differences and an
 autograd construction of the two-weight gradient.
-Parity unpinned: the T2 correction with tau_bkwd > 0 (the paper's text and its appendix
-polynomial disagree there; the text is followed); the inverse-square-root tail of the warmup
+Parity unpinned: the T2 correction with tau_bkwd > 0, and the recompute correction with
+tau_recomp > 0 (in both the paper's text uses the current delta_t while its appendix polynomials
+correspond to a delayed delta; the text is followed and pinned against the polynomial derived from it); the inverse-square-root tail of the warmup
 schedule (the paper only gives the warmup part).
 """
 from __future__ import annotations
@@ -58,6 +64,28 @@ def pipeline_delays(P: int, N: int = 1, method: str = "pipemare"):
     if method == "pipedream":
         return tau_fwd, list(tau_fwd)
     raise ValueError(method)
+
+
+def recompute_delays(P: int, S: int, N: int = 1, tau_bkwd=None):
+    """tau_recomp per stage (index i-1) when the P stages are cut into segments of S consecutive stages
+    (the last one may be shorter): the j-th stage of a segment with S' stages recomputes 2 (S' - j)
+    microbatch slots before its backward pass (App. "PipeMare Recompute"), i.e.
+    tau_recomp,i = tau_bkwd,i + ceil(2 (S' - j) / N)."""
+    if P < 1 or S < 1 or N < 1:
+        raise ValueError("P, S, N >= 1 required")
+    tb = [0] * P if tau_bkwd is None else list(tau_bkwd)
+    out = []
+    for i in range(1, P + 1):
+        first = ((i - 1) // S) * S + 1
+        size = min(S, P - first + 1)
+        j = i - first + 1
+        out.append(tb[i - 1] + -((-2 * (size - j)) // N))
+    return out
+
+
+def segment_starts(P: int, S: int):
+    """First stage (1-based) of every segment."""
+    return list(range(1, P + 1, S))
 
 
 def gpipe_utilization(N: int, P: int) -> float:
@@ -122,16 +150,19 @@ class QuadraticModel:
     """The paper's one-dimensional analysis model, one scalar weight per stage.
 
     grad_i = (lam + Delta) * u_fwd,i - Delta * u_bkwd,i - eta_t   (Sec. 3.2; Delta = 0 gives Sec. 3's model)
+    With recomputation (App. "Statistical efficiency and recompute") a third term with sensitivity Phi:
+    grad_i = (lam + Delta) * u_fwd,i - (Delta - Phi) * u_bkwd,i - Phi * u_recomp,i - eta_t.
     The 'batch' passed to the step is the noise sample eta_t (scalar or per-stage array).
     """
 
-    def __init__(self, n_stages: int, lam: float = 1.0, Delta: float = 0.0):
+    def __init__(self, n_stages: int, lam: float = 1.0, Delta: float = 0.0, Phi: float = 0.0):
         self.n = n_stages
-        self.lam, self.Delta = float(lam), float(Delta)
+        self.lam, self.Delta, self.Phi = float(lam), float(Delta), float(Phi)
 
-    def loss_and_grads(self, u_fwd, u_bkwd, eta):
+    def loss_and_grads(self, u_fwd, u_bkwd, eta, u_recomp=None, checkpoints=None):
         eta = np.broadcast_to(np.asarray(0.0 if eta is None else eta, dtype=np.float64), (self.n,))
-        grads = [(self.lam + self.Delta) * u_fwd[i] - self.Delta * u_bkwd[i] - eta[i]
+        u_r = u_bkwd if u_recomp is None else u_recomp
+        grads = [(self.lam + self.Delta) * u_fwd[i] - (self.Delta - self.Phi) * u_bkwd[i] - self.Phi * u_r[i] - eta[i]
                  for i in range(self.n)]
         loss = 0.5 * self.lam * float(sum(np.sum(u ** 2) for u in u_fwd))
         return loss, grads
@@ -207,10 +238,27 @@ class MLPModel:
             return val, d / M
         raise ValueError(loss)
 
-    def loss_and_grads(self, u_fwd, u_bkwd, batch):
+    def loss_and_grads(self, u_fwd, u_bkwd, batch, u_recomp=None, checkpoints=None):
+        """checkpoints (with u_recomp): indices of the layers whose INPUT the forward pass keeps (the
+        first layer of every segment; 0 is always one).  Everything else the backward pass needs -
+        the inputs and pre-activations of the layers inside a segment - is rebuilt from the segment's
+        kept input with the weights u_recomp.  The loss and its gradient come from the forward pass."""
         x, y = batch
         acts, zs = self.forward(u_fwd, x)
         loss, da = self.loss_and_dout(acts[-1], y, self.loss_kind)
+        if u_recomp is not None:
+            cps = sorted(set([0] + [int(c) for c in (checkpoints or [])]))
+            nL = len(self.layers)
+            acts_r, zs_r = list(acts), list(zs)
+            for si, s0 in enumerate(cps):
+                s1 = cps[si + 1] if si + 1 < len(cps) else nL
+                a = acts[s0]                                   # kept by the forward pass
+                for l in range(s0, s1):
+                    W, b = self.unpack(u_recomp[l], l)
+                    acts_r[l] = a
+                    zs_r[l] = a @ W.T + b
+                    a = _act(zs_r[l], self.layers[l].act)
+            acts, zs = acts_r, zs_r
         grads = [None] * len(self.layers)
         for l in range(len(self.layers) - 1, -1, -1):
             L = self.layers[l]
@@ -236,7 +284,9 @@ class PipeMareOracle:
                    K; t1 (bool); t2 (bool); sched (dict for base_lr); N (microbatches);
                    sync_warmup (int E_w >= 0): the first E_w steps run synchronously (all delays 0,
                    base step size: "PipeMareW", Sec. 4), after which the delays apply and the T1
-                   counter starts at 0; delta keeps accumulating during the warm-up
+                   counter starts at 0; delta keeps accumulating during the warm-up;
+                   tau_recomp (list per stage, or None = no recomputation) and segment (stages per
+                   segment): the backward pass rebuilds activations with u_recomp (see the header)
     keep_history   True keeps every version; False drops versions no delay can reach any more
                    (still indexed by absolute version number).
     """
@@ -252,9 +302,22 @@ class PipeMareOracle:
                 raise ValueError("need 0 <= tau_bkwd <= tau_fwd")
         o = dict(kind="sgdm", beta=0.0, beta1=0.9, beta2=0.98, eps=1e-8, weight_decay=0.0,
                  clip_norm=0.0, D=1.0, gamma_override=None, K=0, t1=True, t2=True,
-                 sched=dict(kind="const", base=0.1), N=1, sync_warmup=0)
+                 sched=dict(kind="const", base=0.1), N=1, sync_warmup=0, tau_recomp=None, segment=0)
         o.update(opt)
         self.opt = o
+        self.tau_recomp = None
+        self.checkpoints = None
+        if o["tau_recomp"] is not None:
+            self.tau_recomp = [int(t) for t in o["tau_recomp"]]
+            for tf, tb, tr in zip(self.tau_fwd, self.tau_bkwd, self.tau_recomp):
+                if tr < tb or tr > tf:
+                    raise ValueError("need tau_bkwd <= tau_recomp <= tau_fwd")
+            if int(o["segment"]) < 1:
+                raise ValueError("recomputation needs segment >= 1 (stages per segment)")
+            starts = set(segment_starts(len(self.tau_fwd), int(o["segment"])))
+            # a unit opens a segment if it is the first unit of a stage that opens one
+            self.checkpoints = [u for u in range(self.U)
+                                if self.stage[u] in starts and (u == 0 or self.stage[u - 1] != self.stage[u])]
         self.keep_history = keep_history
         self.t = 0
         self.hist = [{0: np.array(w, dtype=np.float64).copy()} for w in w0]
@@ -304,11 +367,22 @@ class PipeMareOracle:
             if o["t2"] and d > 0 and not warm:
                 base = base - d * self.delta[u]
             u_bkwd.append(base)
+        extra = {}
+        if self.tau_recomp is not None:
+            u_rec = []
+            for u in range(self.U):
+                tr = 0 if warm else self.tau_recomp[self.stage[u] - 1]
+                base = self.hist[u][max(t - tr, 0)]
+                d = self._tf(u) - tr
+                if o["t2"] and d > 0 and not warm:
+                    base = base - d * self.delta[u]
+                u_rec.append(base)
+            extra = dict(u_recomp=u_rec, checkpoints=self.checkpoints)
 
         mbs = batch if isinstance(batch, list) else [batch]
         loss, grads = 0.0, None
         for mb in mbs:
-            l_, g_ = self.model.loss_and_grads(u_fwd, u_bkwd, mb)
+            l_, g_ = self.model.loss_and_grads(u_fwd, u_bkwd, mb, **extra)
             loss += l_ / len(mbs)
             g_ = [np.asarray(g, dtype=np.float64) / len(mbs) for g in g_]
             grads = g_ if grads is None else [a + b for a, b in zip(grads, g_)]
