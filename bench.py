@@ -42,6 +42,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="same as --launch eager")
     ap.add_argument("--cpu-steps", type=int, default=24, help="oracle steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--pool", type=int, default=64, help="distinct device-resident microbatches cycled through")
+    ap.add_argument("--recompute", type=int, default=0,
+                    help="MLP workloads: S > 0 turns on recomputation with segments of S stages (the backward pass "
+                         "rebuilds the activations inside each segment with the delayed, corrected recompute weights)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run three plain device-to-device copies of this many MiB after the timed region "
                          "(a kernel of known traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings by)")
@@ -60,6 +63,7 @@ def main():
     w = wl.config(args.config)
     o = w.opt
     tau_fwd, tau_bkwd = pm.pm_delays(w.P, w.N, "pipemare")
+    tau_recomp = pm.pm_recompute_delays(w.P, args.recompute, w.N, tau_bkwd) if args.recompute > 0 else None
     params = wl.init_params(w)
     n_params = int(sum(p.size for p in params))
     stream_data = wl.batch_stream(w)
@@ -77,7 +81,7 @@ def main():
                             N=w.N, dtype=w.dtype, loss=w.loss, microbatch=w.microbatch, use_graph=use_graph,
                             overlap_update=(launch == "overlap"), arch=w.arch.get("kind", "chain"),
                             n_heads=w.arch.get("n_heads", 0), seq_len=w.arch.get("seq", 0),
-                            image_size=w.arch.get("image", 0))
+                            image_size=w.arch.get("image", 0), tau_recomp=tau_recomp, segment_size=args.recompute)
         eng = pm.PipeMare(w.layers, w.P, tau_fwd, tau_bkwd, sched, opts, params, stream=side)
         pool = [stream_data.batch(k) for k in range(args.pool)]
         xs = [torch.from_numpy(x).cuda() for x, _ in pool]
@@ -122,6 +126,13 @@ def main():
     # an embedding has no corrected backward weights (nothing flows through it): one 2- or 4-byte stream less
     esz = 2 if w.dtype == "bf16" else 4
     alg_bytes = sum(wl.n_params(L) * (bpp - (esz if L.kind == "embed" else 0)) for L in w.layers)
+    if tau_recomp is not None:
+        # units that keep corrected recompute weights of their own (delay or coefficient differs from the
+        # backward weights'): one more stored stream, plus a read of the older ring version when tau_recomp > 0
+        for L in w.layers:
+            tr, tf_, tb_ = tau_recomp[L.stage - 1], tau_fwd[L.stage - 1], tau_bkwd[L.stage - 1]
+            if tf_ - tr > 0 and not (tr == tb_):
+                alg_bytes += wl.n_params(L) * esz * (2 if tr > 0 else 1)
     achieved = alg_bytes / upd_s / 1e9 if upd_s > 0 else 0.0
     lin = [L for L in w.layers if L.kind == "linear"]
     if is_tfm:
@@ -146,6 +157,8 @@ def main():
     else:
         gemm_flops = 6.0 * w.microbatch * sum(L.n_in * L.n_out for L in lin) - 2.0 * w.microbatch * lin[0].n_in * lin[0].n_out
         samples = w.microbatch
+        if tau_recomp is not None:      # the rebuilt forward of every unit but the head
+            gemm_flops += 2.0 * w.microbatch * sum(L.n_in * L.n_out for L in lin[:-1])
     gemm_s = (prof["fwd_ms"] + prof["bwd_ms"]) * 1e-3
     out = {
         "metric": "async pipeline train steps/s",
@@ -165,11 +178,13 @@ def main():
         "config": {"workload": f"{w.name}: {w.P}-stage {'Transformer' if is_tfm else 'CNN' if is_cnn else 'MLP'}, {len(w.layers)} weight units, {n_params} params, "
                                f"microbatch {w.microbatch}{' x ' + str(w.arch['seq']) + ' tokens' if is_tfm else ''}, "
                                f"PipeMare delays tau_fwd={tau_fwd[0]}..{tau_fwd[-1]}, tau_bkwd=0, "
-                               f"{o['kind']} beta {o['beta']}, T1 K={o['K']}, T2 D={o['D']}",
+                               f"{o['kind']} beta {o['beta']}, T1 K={o['K']}, T2 D={o['D']}"
+                               + (f", recomputation in segments of {args.recompute} stages (tau_recomp={tau_recomp[0]}..{tau_recomp[-1]})"
+                                  if tau_recomp is not None else ""),
                    "launch": launch, "final_loss": round(stats["loss"], 5)},
         "roofline": {"kernel": "pm_fused_update_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic(w.name), "algorithmic_bytes": alg_bytes,
+                     "traffic": measured_traffic(w.name) if tau_recomp is None else None, "algorithmic_bytes": alg_bytes,
                      "bytes_per_param": bpp, "params": n_params,
                      "avg_kernel_ms": round(prof["update_ms"], 5), "launches_timed": prof["n"]},
         "phases_ms": {"forward_loss": round(prof["fwd_ms"], 4), "backward": round(prof["bwd_ms"], 4),
@@ -182,7 +197,7 @@ def main():
                                 "and launch gaps are inside that time"},
     }
     if args.cpu_steps > 0:
-        out["cpu_baseline"] = cpu_baseline(w, params, tau_fwd, tau_bkwd, args.cpu_steps)
+        out["cpu_baseline"] = cpu_baseline(w, params, tau_fwd, tau_bkwd, args.cpu_steps, tau_recomp, args.recompute)
     print(json.dumps(out), flush=True)
 
 
@@ -200,7 +215,7 @@ def measured_traffic(workload_name):
     return None
 
 
-def cpu_baseline(w, params, tau_fwd, tau_bkwd, n_steps):
+def cpu_baseline(w, params, tau_fwd, tau_bkwd, n_steps, tau_recomp=None, segment=0):
     """The fp64 NumPy oracle as it stands, timed on the host cores on the first n_steps of the workload."""
     import workloads as wl
     from pm_testutil import make_oracle
@@ -211,7 +226,8 @@ def cpu_baseline(w, params, tau_fwd, tau_bkwd, n_steps):
         threads = os.cpu_count()
     o = w.opt
     orc = make_oracle(w, params, tau_fwd, tau_bkwd, opt=o["kind"], lr=o.get("lr", 0.0), beta=o["beta"], beta2=o.get("beta2", 0.98),
-                      D=o["D"], K=o["K"], weight_decay=o["weight_decay"], sched=o.get("sched"))
+                      D=o["D"], K=o["K"], weight_decay=o["weight_decay"], sched=o.get("sched"),
+                      tau_recomp=tau_recomp, segment=segment)
     stream = wl.batch_stream(w)
     batches = [stream.batch(k) for k in range(n_steps + 2)]
     for k in range(2):

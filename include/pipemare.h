@@ -132,6 +132,14 @@ typedef struct {
                                 cross-entropy (loss must be PM_LOSS_XENT).  Channel counts multiples of 8.  pm_step
                                 takes fp32 images [microbatch, c0_in, image_size, image_size] (NCHW) as x and int32
                                 labels [microbatch] as y. */
+  const int32_t* tau_recomp; /* host, P entries or NULL.  Non-NULL turns on recomputation (PM_ARCH_CHAIN only; App.
+                                "Statistical efficiency and recompute"): the forward pass is taken to keep only the
+                                input of every segment of `segment_size` consecutive stages; the backward pass rebuilds
+                                the activations inside a segment from that input with the weights of version
+                                max(t - tau_recomp,i, 0), corrected - when t2_enabled - by (tau_fwd,i - tau_recomp,i)
+                                delta_t ("T2 for Recompute").  Needs tau_bkwd,i <= tau_recomp,i <= tau_fwd,i.
+                                pm_recompute_delays gives the delays of PipeMare Recompute. */
+  int32_t segment_size;      /* stages per segment (>= 1) when tau_recomp is given; the last segment may be shorter */
 } pm_opts;
 
 const char* pm_status_str(pm_status s);
@@ -142,6 +150,13 @@ const char* pm_last_error(void);
  * tau_fwd,i = ceil((2(P-i)+1)/N); tau_bkwd,i = 0 (PipeMare) | tau_fwd,i (PipeDream); both 0 for
  * GPipe.  Host arrays of P entries each (index i-1).  PM_EINVAL if P < 1 or N < 1. */
 pm_status pm_delays(int32_t P, int32_t N, int32_t method, int32_t* tau_fwd, int32_t* tau_bkwd);
+
+/* Recompute delays of PipeMare Recompute (App. "Trade compute for memory via PipeMare Recompute"): with the P
+ * stages cut into segments of S consecutive stages (the last may be shorter), the j-th stage of a segment of S'
+ * stages recomputes 2 (S' - j) microbatch slots before its backward pass:
+ * tau_recomp,i = tau_bkwd,i + ceil(2 (S' - j) / N).  tau_bkwd: host, P entries, or NULL for all zero;
+ * tau_recomp: host, P entries (out).  PM_EINVAL if P, S or N < 1. */
+pm_status pm_recompute_delays(int32_t P, int32_t S, int32_t N, const int32_t* tau_bkwd, int32_t* tau_recomp);
 
 /* Ring-slot arithmetic for one stage at optimizer step t (Sec. 2.1 delayed reads; the ring of
  * R = tau_fwd + 1 slots is this library's stand-in for the paper's queue of stale weights):
@@ -188,8 +203,10 @@ pm_status pm_step(pm_ctx* ctx, const void* x_dev, const void* y_dev, float* loss
 pm_status pm_weights(pm_ctx* ctx, int32_t layer, float* dst_host, size_t n);
 
 /* Same layout for the delta accumulator (which = 1), the optimizer's first state v or m
- * (which = 2), the corrected backward weights currently stored (which = 3, widened to fp32) and
- * the gradient buffer (which = 4). */
+ * (which = 2), the corrected backward weights currently stored (which = 3, widened to fp32), the
+ * gradient buffer (which = 4) and the corrected recompute weights (which = 5; PM_ESTATE if the
+ * context keeps none: they exist only for units whose recompute delay or coefficient differs
+ * from the backward one). */
 pm_status pm_state(pm_ctx* ctx, int32_t which, int32_t layer, float* dst_host, size_t n);
 
 /* What the kernels of the most recent step actually used, read back from the device-resident
@@ -197,6 +214,11 @@ pm_status pm_state(pm_ctx* ctx, int32_t which, int32_t layer, float* dst_host, s
  * entries (any may be NULL); *t_used receives that step's index.  Synchronises. */
 pm_status pm_device_step_table(pm_ctx* ctx, int64_t* t_used, int32_t* fwd_slot, int32_t* bkwd_slot,
                                int32_t* write_slot, float* lr);
+
+/* With recomputation: per unit the ring slot (max(t - tau_recomp, 0)) mod R of the most recent
+ * step, from the device-resident step table (host array of L entries, may be NULL).
+ * PM_ESTATE without recomputation.  Synchronises. */
+pm_status pm_device_recompute_slots(pm_ctx* ctx, int64_t* t_used, int32_t* rec_slot);
 
 /* Running numbers: last loss, global gradient L2 norm of the last update (only when clipping is
  * on, else 0), L2 norm of the master weights, number of completed optimizer steps.  Any output

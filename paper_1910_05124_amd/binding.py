@@ -16,7 +16,7 @@ import numpy as np
 __all__ = [
     "lib", "PmError", "pm_layer_desc", "pm_lr_sched", "pm_opts",
     "pm_delays", "pm_slots", "pm_t1_lr", "pm_query_bytes", "pm_create", "pm_step", "pm_weights",
-    "pm_state", "pm_device_step_table", "pm_stats", "pm_set_grads", "pm_apply_update", "pm_destroy",
+    "pm_state", "pm_device_step_table", "pm_stats", "pm_recompute_delays", "pm_device_recompute_slots", "pm_set_grads", "pm_apply_update", "pm_destroy",
     "pm_linear_fwd", "pm_linear_bwd_data", "pm_linear_bwd_weight", "pm_profile_begin", "pm_profile_end",
     "pm_synchronize", "PipeMare", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
     "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight", "pm_conv3x3_bwd_weight_scratch",
@@ -49,6 +49,7 @@ _STATUS = {0: "PM_OK", 1: "PM_EINVAL", 2: "PM_ENOMEM", 3: "PM_EHIP", 4: "PM_ESTA
 
 EXPORTS = ["pm_status_str", "pm_last_error", "pm_delays", "pm_slots", "pm_t1_lr", "pm_query_bytes",
            "pm_create", "pm_step", "pm_weights", "pm_state", "pm_device_step_table", "pm_stats",
+           "pm_recompute_delays", "pm_device_recompute_slots",
            "pm_set_grads", "pm_apply_update", "pm_profile_begin", "pm_profile_end", "pm_linear_fwd", "pm_linear_bwd_data",
            "pm_linear_bwd_weight", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
            "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight", "pm_conv3x3_bwd_weight_scratch",
@@ -72,7 +73,8 @@ class pm_opts(C.Structure):
                 ("t2_enabled", C.c_int32), ("n_microbatches", C.c_int32), ("dtype", C.c_int32),
                 ("loss", C.c_int32), ("microbatch", C.c_int32), ("use_graph", C.c_int32),
                 ("sync_warmup_steps", C.c_int64), ("overlap_update", C.c_int32), ("arch", C.c_int32),
-                ("n_heads", C.c_int32), ("seq_len", C.c_int32), ("image_size", C.c_int32)]
+                ("n_heads", C.c_int32), ("seq_len", C.c_int32), ("image_size", C.c_int32),
+                ("tau_recomp", C.POINTER(C.c_int32)), ("segment_size", C.c_int32)]
 
 
 class PmError(RuntimeError):
@@ -97,6 +99,8 @@ lib.pm_step.argtypes = [_vp, _vp, _vp, _f32p]
 lib.pm_weights.argtypes = [_vp, _i32, _f32p, C.c_size_t]
 lib.pm_state.argtypes = [_vp, _i32, _i32, _f32p, C.c_size_t]
 lib.pm_device_step_table.argtypes = [_vp, C.POINTER(_i64), _i32p, _i32p, _i32p, _f32p]
+lib.pm_recompute_delays.argtypes = [_i32, _i32, _i32, _i32p, _i32p]
+lib.pm_device_recompute_slots.argtypes = [_vp, C.POINTER(_i64), _i32p]
 lib.pm_stats.argtypes = [_vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(_i64)]
 lib.pm_set_grads.argtypes = [_vp, _i32, _f32p, C.c_size_t]
 lib.pm_apply_update.argtypes = [_vp]
@@ -139,6 +143,13 @@ def pm_delays(P: int, N: int = 1, method: str = "pipemare"):
     tf, tb = (C.c_int32 * max(P, 1))(), (C.c_int32 * max(P, 1))()
     _check(lib.pm_delays(P, N, PM_METHOD[method], tf, tb))
     return list(tf), list(tb)
+
+
+def pm_recompute_delays(P: int, S: int, N: int = 1, tau_bkwd=None):
+    tr = (C.c_int32 * max(P, 1))()
+    tb = None if tau_bkwd is None else (C.c_int32 * len(tau_bkwd))(*[int(t) for t in tau_bkwd])
+    _check(lib.pm_recompute_delays(P, S, N, tb, tr))
+    return list(tr)
 
 
 def pm_slots(tau_fwd: int, tau_bkwd: int, t: int):
@@ -203,6 +214,13 @@ def pm_device_step_table(ctx: int, L: int):
     lr = (C.c_float * L)()
     _check(lib.pm_device_step_table(ctx, C.byref(t), f, b, w, lr))
     return t.value, list(f), list(b), list(w), np.array(lr[:], dtype=np.float32)
+
+
+def pm_device_recompute_slots(ctx: int, L: int):
+    t = _i64()
+    r = (C.c_int32 * L)()
+    _check(lib.pm_device_recompute_slots(ctx, C.byref(t), r))
+    return t.value, list(r)
 
 
 def pm_stats(ctx: int, param_norm: bool = False):
@@ -293,10 +311,14 @@ def make_sched(kind="const", base=0.01, init=0.0, factor=1.0, interval=1, K=0) -
 def make_opts(opt="sgdm", beta1=0.9, beta2=0.98, eps=1e-8, weight_decay=0.0, clip_norm=0.0, D=1.0,
               gamma_override=None, t1=True, t2=True, N=1, dtype="f32", loss="mse", microbatch=1,
               use_graph=False, sync_warmup=0, overlap_update=False, arch="chain", n_heads=0, seq_len=0,
-              image_size=0) -> pm_opts:
+              image_size=0, tau_recomp=None, segment_size=0) -> pm_opts:
     o = pm_opts(PM_OPT[opt], beta1, beta2, eps, weight_decay, clip_norm, D, None, int(t1), int(t2), N,
                 PM_DTYPE[dtype], PM_LOSS[loss], microbatch, int(use_graph), int(sync_warmup), int(overlap_update),
-                PM_ARCH[arch], int(n_heads), int(seq_len), int(image_size))
+                PM_ARCH[arch], int(n_heads), int(seq_len), int(image_size), None, int(segment_size))
+    if tau_recomp is not None:
+        arr_r = (C.c_int32 * len(tau_recomp))(*[int(t) for t in tau_recomp])
+        o._keep_r = arr_r
+        o.tau_recomp = C.cast(arr_r, C.POINTER(C.c_int32))
     if gamma_override is not None:
         arr = (C.c_double * len(gamma_override))(*gamma_override)
         o._keep = arr

@@ -55,6 +55,12 @@ struct Unit {
   int32_t tau_f, tau_b, R;
   double gamma;
   int32_t corr;      // tau_f - tau_b when T2 applies, else 0
+  // recomputation (chain only): delay of the weights that rebuild this unit's activations in the
+  // backward pass, the coefficient of their correction when the unit keeps a corrected copy of its own
+  // (0: the copy would equal the corrected backward weights, or no correction applies), and the
+  // unit's place in its segment
+  int32_t tau_r = 0, corr_r = 0;
+  bool seg_first = false, seg_last = false;
   int ld_in, ld_out; // leading dimensions of the activation matrices (multiples of 8)
   // activation buffers (byte offsets into the arena)
   size_t z_off, a_off, dz_off, z32_off;
@@ -68,7 +74,7 @@ struct Layout {
   int64_t n_chunks = 0;
   size_t esz = 4;         // bytes per element of the compute dtype
   // byte offsets
-  size_t w_off, g_off, v_off, s_off, d_off, ub_off, ring_off, chunk_off, ls_off, ld_off, hdr_off, probs_off, x_off;
+  size_t w_off, g_off, v_off, s_off, d_off, ub_off, ur_off, ring_off, chunk_off, ls_off, ld_off, hdr_off, probs_off, x_off;
   size_t act_begin, act_end, total;
   // Transformer activations (byte offsets; see launch_tfm).  Per layer: index [layer]
   struct TfmLayer {
@@ -89,6 +95,8 @@ struct Layout {
   size_t t_wprobs, t_wtiles, t_wsegs;                        // grouped weight-gradient launch: problems (2 sets), tiles per XCD, segments
   int n_zero = 0;
   int64_t zero_max = 0;
+  bool recompute = false;   // the backward pass rebuilds the activations inside each segment
+  bool has_ur = false;      // some unit keeps corrected recompute weights of its own
 };
 
 pm_status validate(int32_t P, int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
@@ -166,6 +174,15 @@ pm_status validate(int32_t P, int32_t L, const pm_layer_desc* layers, const int3
     if (tau_fwd[i] < 0) return fail(PM_EINVAL, "tau_fwd[%d] < 0", i);
     if (tau_bkwd && (tau_bkwd[i] < 0 || tau_bkwd[i] > tau_fwd[i])) return fail(PM_EINVAL, "need 0 <= tau_bkwd[%d] <= tau_fwd[%d]", i, i);
   }
+  if (o->tau_recomp) {
+    if (o->arch != PM_ARCH_CHAIN) return fail(PM_EINVAL, "recomputation is implemented for PM_ARCH_CHAIN only");
+    if (o->segment_size < 1) return fail(PM_EINVAL, "recomputation needs segment_size >= 1 (stages per segment)");
+    for (int i = 0; i < P; ++i) {
+      const int tb = tau_bkwd ? tau_bkwd[i] : 0;
+      if (o->tau_recomp[i] < tb || o->tau_recomp[i] > tau_fwd[i])
+        return fail(PM_EINVAL, "need tau_bkwd[%d] <= tau_recomp[%d] <= tau_fwd[%d]", i, i, i);
+    }
+  }
   return PM_OK;
 }
 
@@ -194,6 +211,19 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
     u.corr = (o->t2_enabled && dd > 0 && u.d.kind != PM_EMBED) ? dd : 0;
     if (o->gamma_override) u.gamma = o->gamma_override[u.d.stage - 1];
     else u.gamma = dd > 0 ? std::pow(o->D, 1.0 / dd) : 0.0;
+    u.tau_r = u.tau_b;
+    u.corr_r = 0;
+    if (o->tau_recomp) {
+      lay.recompute = true;
+      u.tau_r = o->tau_recomp[u.d.stage - 1];
+      const int dr = u.tau_f - u.tau_r;
+      const int cr = (o->t2_enabled && dr > 0) ? dr : 0;
+      // same delay and same coefficient as the backward weights: those are read instead
+      if (cr > 0 && !(u.tau_r == u.tau_b && cr == u.corr)) { u.corr_r = cr; lay.has_ur = true; }
+      const int seg = (u.d.stage - 1) / o->segment_size;
+      u.seg_first = l == 0 || (layers[l - 1].stage - 1) / o->segment_size != seg;
+      u.seg_last = l == L - 1 || (layers[l + 1].stage - 1) / o->segment_size != seg;
+    }
     u.ld_in = (int)round_up(u.d.n_in, 8);
     u.ld_out = (int)round_up(u.d.n_out, 8);
     off += u.n_pad;
@@ -212,6 +242,7 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
   lay.s_off = take(o->opt == PM_OPT_ADAMW ? lay.n_flat * 4 : 0);
   lay.d_off = take(lay.n_flat * 4);
   lay.ub_off = take(lay.n_flat * lay.esz);
+  lay.ur_off = take(lay.has_ur ? lay.n_flat * lay.esz : 0);
   lay.ring_off = take(lay.ring_elems * lay.esz);
   lay.chunk_off = take(lay.n_chunks * 4);
   lay.ls_off = take(sizeof(PmLayerStatic) * L);
@@ -301,7 +332,7 @@ struct pm_ctx {
   pm_opts o;
   pm_lr_sched sched;
   std::vector<double> gamma_override;
-  std::vector<int32_t> tau_f, tau_b;
+  std::vector<int32_t> tau_f, tau_b, tau_r;
   Layout lay;
   char* arena;
   hipStream_t stream;
@@ -380,6 +411,7 @@ pm_status launch_update(pm_ctx* c, hipStream_t st, int par) {
   a.d = c->at<float>(lay.d_off);
   a.ring = c->at<T>(lay.ring_off);
   a.ub = c->at<T>(lay.ub_off);
+  a.ur = lay.has_ur ? c->at<T>(lay.ur_off) : nullptr;
   a.chunk_layer = c->at<int32_t>(lay.chunk_off);
   a.ls = c->ls();
   a.ld = c->ld(par);
@@ -506,7 +538,7 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
   // ---- backward, data-gradient chain: da_in[M, n_in] = dz . W_bkwd, fused with act'(z_prev).
   // W_bkwd = corrected buffer when the T2 coefficient is non-zero, else version max(t - tau_bkwd, 0).
   // The first unit needs none (its backward weights never enter any gradient).
-  for (int l = L - 1; l >= 1; --l) {
+  auto bwd_data = [&](int l) {
     const Unit& u = lay.units[l];
     const Unit& up = lay.units[l - 1];
     const T* dz = c->at<T>(u.dz_off);
@@ -514,6 +546,48 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
                           : PmWLoc<T>{ring + u.ring_off, &c->ld(par)[l].bkwd_slot, u.n_pad};
     PmEpiBwdData<T> ed{c->at<T>(up.z_off), c->at<T>(up.dz_off), up.ld_out, up.d.act};
     launch_gemm<T>(c, M, u.d.n_in, u.d.n_out, dz, u.ld_out, 1, Wb, 1, u.d.n_in, ed);
+  };
+  if (!lay.recompute) {
+    for (int l = L - 1; l >= 1; --l) bwd_data(l);
+  } else {
+    // Recomputation (App. on recompute): the forward pass is taken to have kept only the input of
+    // every segment; before a segment's backward its pre-activations and inner inputs are rebuilt
+    // from that input with the weights u_recomp = version max(t - tau_recomp, 0), corrected by
+    // (tau_fwd - tau_recomp) delta_t ("T2 for Recompute").  The rebuilt values overwrite the forward's
+    // in place - except a segment's output, which is the next segment's kept input.  The head needs
+    // no pre-activation (no activation function) and is not recomputed.
+    // (The product that crosses a segment boundary multiplies by act'(z) of the earlier segment's
+    // last unit, a rebuilt value: it waits until that segment has been recomputed.)
+    T* ur = lay.has_ur ? c->at<T>(lay.ur_off) : nullptr;
+    int hi = L - 1, pending = -1;
+    while (hi >= 0) {
+      int lo = hi;
+      while (!lay.units[lo].seg_first) --lo;
+      for (int l = lo; l <= hi; ++l) {
+        if (l == L - 1) continue;
+        const Unit& u = lay.units[l];
+        const T* a_in = l == 0 ? c->at<T>(lay.x_off) : c->at<T>(lay.units[l - 1].a_off);
+        const T* base;
+        const int32_t* slot;
+        if (u.corr_r) { base = ur + u.off; slot = nullptr; }                       // own corrected copy
+        else if (u.tau_r == u.tau_b && u.corr) { base = ub + u.off; slot = nullptr; }   // same as the backward weights
+        else { base = ring + u.ring_off; slot = &c->ld(par)[l].rec_slot; }          // plain version, read in place
+        PmWLoc<T> W{base, slot, slot ? u.n_pad : 0};
+        PmEpiFwd<T> epi;
+        epi.bias = PmWLoc<T>{base + u.boff, slot, slot ? u.n_pad : 0};
+        epi.z = c->at<T>(u.z_off);
+        epi.a = l == hi ? nullptr : c->at<T>(u.a_off);
+        epi.z32 = nullptr;
+        epi.ld = u.ld_out;
+        epi.act = u.d.act;
+        epi.b_ = nullptr;
+        launch_gemm<T>(c, M, u.d.n_out, u.d.n_in, a_in, u.ld_in, 1, W, u.d.n_in, 1, epi);
+      }
+      if (pending >= 1) bwd_data(pending);
+      for (int l = hi; l > lo; --l) bwd_data(l);
+      pending = lo;
+      hi = lo - 1;
+    }
   }
   // ---- weight gradients from the stored forward activations: dW[n_out, n_in] = dz^T . a_in,
   // db = column sums of dz.  They depend only on stored tensors, so all units go out as ONE
@@ -926,6 +1000,17 @@ pm_status pm_delays(int32_t P, int32_t N, int32_t method, int32_t* tau_fwd, int3
   return PM_OK;
 }
 
+pm_status pm_recompute_delays(int32_t P, int32_t S, int32_t N, const int32_t* tau_bkwd, int32_t* tau_recomp) {
+  if (P < 1 || S < 1 || N < 1 || !tau_recomp) return fail(PM_EINVAL, "P, S, N >= 1 and an output array required");
+  for (int32_t i = 1; i <= P; ++i) {
+    const int32_t first = ((i - 1) / S) * S + 1;                 // first stage of i's segment
+    const int32_t size = std::min(S, P - first + 1);             // stages in that segment
+    const int32_t j = i - first + 1;                             // i's position in it
+    tau_recomp[i - 1] = (tau_bkwd ? tau_bkwd[i - 1] : 0) + (2 * (size - j) + N - 1) / N;
+  }
+  return PM_OK;
+}
+
 pm_status pm_slots(int32_t tau_fwd, int32_t tau_bkwd, int64_t t, int32_t* fwd_slot, int32_t* bkwd_slot,
                    int32_t* write_slot) {
   if (tau_fwd < 0 || tau_bkwd < 0 || tau_bkwd > tau_fwd || t < 0) return fail(PM_EINVAL, "need 0 <= tau_bkwd <= tau_fwd and t >= 0");
@@ -989,6 +1074,7 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
   for (int l = 0; l < L; ++l)
     if (!init_weights_host[l]) return fail(PM_EINVAL, "init_weights_host[%d] is NULL", l);
   if (L > 65535) return fail(PM_EINVAL, "too many units");
+  if (opts->use_graph && !hip_stream) return fail(PM_EINVAL, "use_graph needs a stream of its own: the default stream cannot be captured");
 
   pm_ctx* c = new pm_ctx();
   c->P = P;
@@ -1001,6 +1087,10 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
   }
   c->tau_f.assign(tau_fwd, tau_fwd + P);
   c->tau_b.assign(tau_bkwd, tau_bkwd + P);
+  if (opts->tau_recomp) {
+    c->tau_r.assign(opts->tau_recomp, opts->tau_recomp + P);
+    c->o.tau_recomp = c->tau_r.data();
+  }
   make_layout(L, layers, tau_fwd, tau_bkwd, &c->o, c->lay);
   const Layout& lay = c->lay;
   if (arena_bytes < lay.total) {
@@ -1035,6 +1125,7 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
     PmLayerStatic& S = ls[l];
     S.off = u.off; S.n_pad = u.n_pad; S.ring_off = u.ring_off; S.R = u.R; S.tau_f = u.tau_f; S.tau_b = u.tau_b;
     S.stage = u.d.stage; S.gamma = (float)u.gamma; S.corr = (float)u.corr;
+    S.tau_r = u.tau_r; S.corr_r = (float)u.corr_r;
   }
   hipStream_t st = c->stream;
   auto bail = [&](hipError_t e, const char* what) {
@@ -1179,10 +1270,12 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
   if (c->o.dtype == PM_BF16)
     hipLaunchKernelGGL((pm_init_ring_kernel<bf16_t>), dim3((unsigned)lay.n_chunks), dim3(256), 0, st,
                        c->at<float>(lay.w_off), c->at<bf16_t>(lay.ring_off), c->at<bf16_t>(lay.ub_off),
+                       lay.has_ur ? c->at<bf16_t>(lay.ur_off) : nullptr,
                        c->at<int32_t>(lay.chunk_off), c->ls());
   else
     hipLaunchKernelGGL((pm_init_ring_kernel<float>), dim3((unsigned)lay.n_chunks), dim3(256), 0, st,
                        c->at<float>(lay.w_off), c->at<float>(lay.ring_off), c->at<float>(lay.ub_off),
+                       lay.has_ur ? c->at<float>(lay.ur_off) : nullptr,
                        c->at<int32_t>(lay.chunk_off), c->ls());
   if ((e = hipGetLastError()) != hipSuccess) return bail(e, "init kernel");
   if ((e = hipStreamSynchronize(st)) != hipSuccess) return bail(e, "synchronise after init");   // host images go out of scope
@@ -1243,9 +1336,13 @@ pm_status pm_state(pm_ctx* c, int32_t which, int32_t layer, float* dst, size_t n
     case 2: base = lay.v_off; break;
     case 3: base = lay.ub_off; break;
     case 4: base = lay.g_off; break;
+    case 5:
+      if (!lay.has_ur) return fail(PM_ESTATE, "this context keeps no corrected recompute weights");
+      base = lay.ur_off;
+      break;
     default: return fail(PM_EINVAL, "unknown state selector %d", which);
   }
-  if (which == 3 && c->o.dtype == PM_BF16) {
+  if ((which == 3 || which == 5) && c->o.dtype == PM_BF16) {
     std::vector<bf16_t> tmp((size_t)u.n);
     PM_HIP(hipMemcpyAsync(tmp.data(), c->at<bf16_t>(base) + u.off, tmp.size() * 2, hipMemcpyDeviceToHost, c->stream));
     PM_HIP(hipStreamSynchronize(c->stream));
@@ -1278,6 +1375,22 @@ pm_status pm_device_step_table(pm_ctx* c, int64_t* t_used, int32_t* fwd_slot, in
     if (write_slot) write_slot[l] = ld[l].write_slot;
     if (lr) lr[l] = ld[l].lr;
   }
+  return PM_OK;
+}
+
+pm_status pm_device_recompute_slots(pm_ctx* c, int64_t* t_used, int32_t* rec_slot) {
+  if (!c) return fail(PM_EINVAL, "NULL context");
+  if (!c->lay.recompute) return fail(PM_ESTATE, "this context does not recompute");
+  pm_status qs = quiesce(c);
+  if (qs != PM_OK) return qs;
+  std::vector<PmLayerStep> ld(c->L);
+  PmStepHdr h;
+  PM_HIP(hipMemcpyAsync(ld.data(), c->ld(c->last_par), sizeof(PmLayerStep) * c->L, hipMemcpyDeviceToHost, c->stream));
+  PM_HIP(hipMemcpyAsync(&h, c->hdr(), sizeof h, hipMemcpyDeviceToHost, c->stream));
+  PM_HIP(hipStreamSynchronize(c->stream));
+  if (t_used) *t_used = h.t_used;
+  if (rec_slot)
+    for (int l = 0; l < c->L; ++l) rec_slot[l] = ld[l].rec_slot;
   return PM_OK;
 }
 

@@ -19,6 +19,8 @@ struct PmLayerStatic {
   int32_t stage;
   float gamma;       // decay of the delta accumulator (T2)
   float corr;        // tau_fwd - tau_bkwd if the correction is active, else 0
+  int32_t tau_r;     // recomputation delay (App. on recompute); equals tau_b when nothing is recomputed
+  float corr_r;      // tau_fwd - tau_recomp if the unit keeps corrected recompute weights of its own, else 0
 };
 
 // Per-step values for a unit, rewritten by the prologue kernel from the device step counter.
@@ -29,7 +31,10 @@ struct PmLayerStep {
   int32_t ub_slot;     // (max(t + 1 - tau_bkwd, 0)) mod R : base of the next corrected weights
   float lr;            // alpha_{t,i}
   float corr_next;     // T2 coefficient of the NEXT step's corrected weights (0 during synchronous warm-up)
-  int32_t pad_[2];
+  int32_t rec_slot;    // (max(t - tau_recomp, 0)) mod R : version the recomputation reads when it needs no correction
+  int32_t ur_slot;     // (max(t + 1 - tau_recomp, 0)) mod R : base of the next corrected recompute weights
+  float corr_r_next;   // coefficient of the NEXT step's corrected recompute weights (0 during synchronous warm-up)
+  int32_t pad_[3];
 };
 
 // The step table and the per-step scalars exist twice (index = step parity): the update of step t,

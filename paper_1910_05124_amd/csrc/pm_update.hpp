@@ -32,9 +32,12 @@ __device__ __forceinline__ void pm_prologue_block(PmStepHdr* hdr, const PmLayerS
     const PmLayerStatic S = ls[l];
     PmLayerStep D;
     const long long tf = warm ? 0 : S.tau_f, tb = warm ? 0 : S.tau_b, tbn = warm_next ? 0 : S.tau_b;
+    const long long tr = warm ? 0 : S.tau_r, trn = warm_next ? 0 : S.tau_r;
     const long long vf = t - tf > 0 ? t - tf : 0;
     const long long vb = t - tb > 0 ? t - tb : 0;
     const long long vu = t + 1 - tbn > 0 ? t + 1 - tbn : 0;
+    const long long vr = t - tr > 0 ? t - tr : 0;
+    const long long vur = t + 1 - trn > 0 ? t + 1 - trn : 0;
     D.fwd_slot = (int32_t)(vf % S.R);
     D.bkwd_slot = (int32_t)(vb % S.R);
     D.write_slot = (int32_t)((t + 1) % S.R);
@@ -46,7 +49,10 @@ __device__ __forceinline__ void pm_prologue_block(PmStepHdr* hdr, const PmLayerS
     }
     D.lr = (float)lr;
     D.corr_next = warm_next ? 0.f : S.corr;
-    D.pad_[0] = D.pad_[1] = 0;
+    D.rec_slot = (int32_t)(vr % S.R);
+    D.ur_slot = (int32_t)(vur % S.R);
+    D.corr_r_next = warm_next ? 0.f : S.corr_r;
+    D.pad_[0] = D.pad_[1] = D.pad_[2] = 0;
     ld[l] = D;
   }
   __syncthreads();
@@ -117,6 +123,9 @@ __global__ void pm_clip_scale_kernel(PmStepHdr* hdr, float clip, int par) {
 //   ring[(t+1) mod R_i] <- round(w_new)                               (the version the forward reads later)
 //   ub <- round(base - (tau_fwd,i - tau_bkwd,i) delta_new)            (Sec. 3.2, corrected backward weights
 //        of the NEXT step; base = w_new when tau_bkwd = 0, else the stored version t+1-tau_bkwd)
+//   ur <- round(base_r - (tau_fwd,i - tau_recomp,i) delta_new)        (App. on recompute, "T2 for Recompute":
+//        corrected recompute weights of the NEXT step, only for units that keep such a buffer;
+//        base_r = w_new when tau_recomp = 0, else the stored version t+1-tau_recomp)
 // Each block owns PM_CHUNK consecutive elements, all of one unit (units are padded to the chunk),
 // so the per-unit scalars are wave-uniform; each thread owns 2 x 4 elements (see PmAcc below).
 // ---------------------------------------------------------------------------------------------
@@ -129,6 +138,7 @@ struct PmUpdArgs {
   float* d;   // delta
   RT* ring;
   RT* ub;
+  RT* ur;     // corrected recompute weights (NULL when no unit keeps any)
   const int32_t* chunk_layer;
   const PmLayerStatic* ls;
   const PmLayerStep* ld;
@@ -249,12 +259,20 @@ __global__ __launch_bounds__(256) void pm_fused_update_kernel(PmUpdArgs<RT> a) {
     for (int j = 0; j < 8; ++j) ubv[j] = (ub_from_ring ? ubv[j] : wn[j]) - corr * d[j];
     X::st(a.ub + e, ubv);
   }
+  if (S.corr_r != 0.f) {        // block-uniform; the ring slot read here is never the one written above (tau_recomp >= 1)
+    const float cr = D.corr_r_next;
+    const bool ur_from_ring = (cr != 0.f) && (S.tau_r > 0);
+    if (ur_from_ring) X::ld(a.ring + S.ring_off + (int64_t)D.ur_slot * S.n_pad + rel, ubv);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ubv[j] = (ur_from_ring ? ubv[j] : wn[j]) - cr * d[j];
+    X::st(a.ur + e, ubv);
+  }
   if (bad) a.hdr->diverged = 1;
 }
 
 // Fill every ring slot and the corrected-weight buffer of all units with the initial weights.
 template <typename RT>
-__global__ __launch_bounds__(256) void pm_init_ring_kernel(const float* __restrict__ w, RT* ring, RT* ub,
+__global__ __launch_bounds__(256) void pm_init_ring_kernel(const float* __restrict__ w, RT* ring, RT* ub, RT* ur,
                                                            const int32_t* chunk_layer,
                                                            const PmLayerStatic* ls) {
   const int c = blockIdx.x;
@@ -263,5 +281,6 @@ __global__ __launch_bounds__(256) void pm_init_ring_kernel(const float* __restri
   float x[8];
   pm_ld8(w + e, x);
   pm_st8(ub + e, x);
+  if (ur) pm_st8(ur + e, x);
   for (int r = 0; r < S.R; ++r) pm_st8(ring + S.ring_off + (int64_t)r * S.n_pad + (e - S.off), x);
 }

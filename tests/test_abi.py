@@ -34,6 +34,15 @@ def test_delays_match_oracle():
         pm.pm_delays(4, 0)
 
 
+def test_recompute_delays_match_oracle():
+    for P, S, N in ((16, 4, 1), (5, 2, 1), (4, 4, 2), (4, 4, 3), (99, 8, 1), (7, 3, 2), (1, 1, 1), (20, 20, 1)):
+        assert pm.pm_recompute_delays(P, S, N) == po.recompute_delays(P, S, N)
+    tb = [1, 0, 2, 1, 0]
+    assert pm.pm_recompute_delays(5, 3, 1, tb) == po.recompute_delays(5, 3, 1, tb)
+    with pytest.raises(pm.PmError):
+        pm.pm_recompute_delays(4, 0, 1)
+
+
 def test_slots_brute_force_against_oracle_versions():
     for tf in (0, 1, 2, 7, 31):
         for tb in sorted({0, tf // 2, tf}):

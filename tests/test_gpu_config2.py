@@ -19,7 +19,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.timeout(1500)
-@pytest.mark.parametrize("launch", ["graph", "overlap"])
+@pytest.mark.parametrize("launch", ["graph", "overlap", "graph_recompute4"])
 def test_config1_bf16_mlp16_500_steps(launch):
     import torch
     w = wl.config(1)
@@ -28,10 +28,16 @@ def test_config1_bf16_mlp16_500_steps(launch):
     tf, tb = po.pipeline_delays(w.P, 1)
     assert tf == [2 * (16 - i) + 1 for i in range(1, 17)] and tb == [0] * 16
     kw = dict(lr=o_["lr"], beta=o_["beta"], D=o_["D"], K=o_["K"])
+    n_steps = w.steps
+    if launch == "graph_recompute4":
+        # the same workload with recomputation in segments of 4 stages (App. on recompute), 200 steps
+        kw.update(tau_recomp=po.recompute_delays(w.P, 4, 1), segment=4)
+        assert kw["tau_recomp"] == [6, 4, 2, 0] * 4
+        launch, n_steps = "graph", 200
     stream = wl.BatchStream(w)
     o = make_oracle(w, params, tf, tb, **kw)
     side = torch.cuda.Stream()
-    checkpoints = (1, 10, 100, w.steps)
+    checkpoints = (1, 10, 100, n_steps)
     report = {}
     t0 = time.time()
     with torch.cuda.stream(side):
@@ -39,7 +45,7 @@ def test_config1_bf16_mlp16_500_steps(launch):
                      stream=side, **kw)
         x0, y0 = stream.batch(0)
         xd, yd = torch.from_numpy(x0).cuda(), torch.from_numpy(y0).cuda()
-        for k in range(w.steps):
+        for k in range(n_steps):
             x, y = stream.batch(k)
             xd.copy_(torch.from_numpy(x))
             yd.copy_(torch.from_numpy(y))
@@ -62,4 +68,4 @@ def test_config1_bf16_mlp16_500_steps(launch):
         g.close()
     for n, (err, move) in report.items():
         assert err <= 2e-3, (n, err)
-    assert report[w.steps][1] > 0.02          # the weights really moved: the bound is not met vacuously
+    assert report[n_steps][1] > 0.02          # the weights really moved: the bound is not met vacuously

@@ -1,0 +1,173 @@
+"""GPU parity of the recomputation path (backward pass rebuilds the activations inside each segment
+with a third, delayed and corrected weight set) against the fp64 CPU oracle.
+
+Bars as everywhere: slot indices and step counters bit-exact, master weights within 1e-5 (fp32) /
+2e-3 (bf16) max-relative error per unit.
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import pipemare_oracle as po
+from pm_testutil import GivenGrads, make_gpu, make_oracle, max_rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-3}
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch
+
+
+def test_recompute_delays_match_oracle():
+    import paper_1910_05124_amd as pm
+    for P, S, N in ((16, 4, 1), (5, 2, 1), (4, 4, 2), (4, 4, 3), (99, 8, 1), (7, 3, 2), (1, 1, 1)):
+        assert pm.pm_recompute_delays(P, S, N) == po.recompute_delays(P, S, N)
+    tb = [1, 0, 2, 1, 0]
+    assert pm.pm_recompute_delays(5, 3, 1, tb) == po.recompute_delays(5, 3, 1, tb)
+    with pytest.raises(pm.PmError):
+        pm.pm_recompute_delays(4, 0, 1)
+
+
+def _run(torch, w, steps, S, *, N=1, tau=None, tau_recomp=None, check_tables=True, gpu_kw=None, **kw):
+    import paper_1910_05124_amd as pm
+    params = wl.init_params(w)
+    tf, tb = tau if tau is not None else po.pipeline_delays(w.P, N)
+    tr = tau_recomp if tau_recomp is not None else po.recompute_delays(w.P, S, N, tb)
+    stream = wl.BatchStream(w)
+    o = make_oracle(w, params, tf, tb, N=N, tau_recomp=tr, segment=S, **kw)
+    warm = kw.get("sync_warmup", 0)
+    side = torch.cuda.Stream()                       # a captured graph needs a non-default stream
+    with torch.cuda.stream(side):
+        g = make_gpu(w, params, tf, tb, N=N, tau_recomp=tr, segment=S, stream=side, **dict(kw, **(gpu_kw or {})))
+        # fixed device buffers: a captured graph is bound to the batch pointers
+        x0, y0 = stream.batch(0)
+        xd, yd = torch.from_numpy(x0).cuda(), torch.from_numpy(y0).cuda()
+        for k in range(steps):
+            mbs = [stream.batch(k * N + j) for j in range(N)]
+            lo = o.step(mbs if N > 1 else mbs[0])
+            lg = 0.0
+            for x, y in mbs:
+                xd.copy_(torch.from_numpy(x))
+                yd.copy_(torch.from_numpy(y))
+                lg += g.step(xd, yd, want_loss=True) / N
+            assert lg == pytest.approx(lo, rel=2e-2 if w.dtype == "bf16" else 1e-4, abs=1e-6)
+            if check_tables:
+                t_used, rs = pm.pm_device_recompute_slots(g.ctx, len(w.layers))
+                assert t_used == k
+                for u, L in enumerate(w.layers):
+                    R = tf[L.stage - 1] + 1
+                    want = k if k < warm else max(k - tr[L.stage - 1], 0)
+                    assert rs[u] == want % R                                   # bit-exact integers
+    return g, o, tf, tb, tr
+
+
+CASES = {
+    # name: (dtype, width, depth, layers_per_stage, S, extra)
+    "f32_S2": ("f32", 48, 6, 1, 2, {}),
+    "f32_S3_ragged_last": ("f32", 40, 7, 1, 3, {}),
+    "f32_one_segment": ("f32", 48, 4, 1, 8, {}),
+    "f32_every_stage_a_segment": ("f32", 48, 4, 1, 1, {}),
+    "f32_two_layers_per_stage": ("f32", 40, 6, 2, 2, {}),
+    "f32_t2_off": ("f32", 48, 6, 1, 2, dict(t2=False)),
+    "f32_adamw_clip": ("f32", 48, 5, 1, 2, dict(opt="adamw", lr=2e-3, clip_norm=0.5, weight_decay=0.01)),
+    "f32_sync_warmup": ("f32", 48, 5, 1, 2, dict(sync_warmup=4)),
+    "bf16_S2": ("bf16", 64, 6, 1, 2, {}),
+    "bf16_S4_wide": ("bf16", 256, 8, 1, 4, {}),
+    "bf16_graph": ("bf16", 64, 6, 1, 3, dict(_graph=True)),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_recompute_training_matches_oracle(torch_cuda, name):
+    dtype, width, depth, lps, S, extra = CASES[name]
+    extra = dict(extra)
+    gpu_kw = dict(use_graph=True) if extra.pop("_graph", False) else None
+    M = 24 if dtype == "f32" else 32
+    w = wl.small_mlp(width, depth, 10, "gelu", "xent", dtype, M, layers_per_stage=lps)
+    # (bf16: a step size at which 20 steps stay inside the 2e-3 band with or without recomputation; the
+    # fast-moving 10-class head dominates the error)
+    kw = dict(lr=0.05 if dtype == "f32" else 0.01, beta=0.9, D=0.5, K=10)
+    kw.update(extra)
+    g, o, tf, tb, tr = _run(torch_cuda, w, 30 if dtype == "f32" else 20, S, gpu_kw=gpu_kw, **kw)
+    err, errs = max_rel_err(g.weights(), o.weights())
+    assert err < TOL[dtype], errs
+    # the recomputation is not a no-op in these settings: the oracle without it ends elsewhere
+    # (resolved in fp32 only: the effect is below the bf16 band)
+    if S > 1 and dtype == "f32":
+        params = wl.init_params(w)
+        o2 = make_oracle(w, params, tf, tb, **kw)
+        stream = wl.BatchStream(w)
+        for k in range(30):
+            o2.step(stream.batch(k))
+        diff, _ = max_rel_err([x.astype(np.float32) for x in o2.weights()], o.weights())
+        assert diff > 10 * err
+    g.close()
+
+
+def test_recompute_microbatches(torch_cuda):
+    w = wl.small_mlp(48, 6, 10, "gelu", "xent", "f32", 16)
+    g, o, *_ = _run(torch_cuda, w, 16, 3, N=2, lr=0.05, beta=0.9, D=0.5, K=6)
+    err, errs = max_rel_err(g.weights(), o.weights())
+    assert err < TOL["f32"], errs
+    g.close()
+
+
+def test_recompute_with_backward_delay_and_given_recompute_delays(torch_cuda):
+    """tau_bkwd > 0 (backward weights read from the ring) and caller-chosen recompute delays, including a
+    stage whose recompute weights equal its backward weights and one with tau_recomp = tau_fwd."""
+    w = wl.small_mlp(48, 5, 10, "relu", "xent", "f32", 16)
+    P = w.P
+    tf = [9, 7, 5, 3, 1][-P:] if P <= 5 else None
+    assert P == 5
+    tb = [1, 0, 2, 0, 0]
+    tr = [4, 0, 2, 3, 1]
+    g, o, *_ = _run(torch_cuda, w, 30, 2, tau=(tf, tb), tau_recomp=tr, lr=0.05, beta=0.9, D=0.5, K=6)
+    err, errs = max_rel_err(g.weights(), o.weights())
+    assert err < TOL["f32"], errs
+    g.close()
+
+
+def test_corrected_recompute_weights_after_given_updates(torch_cuda):
+    """The update pass alone: after given gradients the stored recompute weights are
+    w_{t+1-tau_recomp} - (tau_fwd - tau_recomp) delta_{t+1}."""
+    layers = (wl.Layer("linear", 40, 70, "relu", 1), wl.Layer("linear", 70, 33, "relu", 2),
+              wl.Layer("linear", 33, 129, "relu", 3), wl.Layer("linear", 129, 5, "none", 4))
+    for dtype in ("f32", "bf16"):
+        w = wl.Workload("upd", layers, 4, 1, "mse", dtype, 4, 5)
+        params = wl.init_params(w, 11)
+        tf, tb, tr = [7, 5, 3, 1], [0, 0, 0, 0], [2, 0, 3, 0]      # own copy from the ring | = backward | coefficient 0 | = backward
+        kw = dict(lr=0.02, beta=0.9, D=0.3, K=6)
+        o = make_oracle(w, params, tf, tb, model=GivenGrads(), keep_history=True, **kw)
+        g = make_gpu(w, params, tf, tb, tau_recomp=tr, segment=2, **kw)
+        rng = np.random.default_rng(0)
+        for k in range(9):
+            grads = [rng.standard_normal(p.size).astype(np.float32) * 0.1 for p in params]
+            o.step(tuple(grads))
+            g.set_grads(grads)
+            g.apply_update()
+        got = g.state(5, 0)
+        want = o.hist[0][max(o.t - tr[0], 0)] - (tf[0] - tr[0]) * o.delta[0]
+        tol = 1e-5 if dtype == "f32" else 2.0 ** -7
+        assert np.max(np.abs(got - want)) <= tol * np.max(np.abs(want))
+        g.close()
+
+
+def test_recompute_rejected_outside_the_chain_and_bad_delays(torch_cuda):
+    import paper_1910_05124_amd as pm
+    w = wl.small_mlp(32, 3, 4, "relu", "xent", "f32", 8)
+    params = wl.init_params(w)
+    tf, tb = po.pipeline_delays(w.P, 1)
+    with pytest.raises(pm.PmError):
+        make_gpu(w, params, tf, tb, tau_recomp=[t + 1 for t in tf], segment=2)
+    with pytest.raises(pm.PmError):
+        make_gpu(w, params, tf, tb, tau_recomp=[0] * w.P, segment=0)
+    wt = wl.transformer(1, 16, 2, 32, 40, 8, 2, dtype="f32")
+    pt = wl.init_params(wt)
+    tft, tbt = po.pipeline_delays(wt.P, 1)
+    with pytest.raises(pm.PmError):
+        make_gpu(wt, pt, tft, tbt, tau_recomp=[0] * wt.P, segment=2)
