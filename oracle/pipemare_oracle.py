@@ -22,6 +22,9 @@ What it computes, with the paper passages it follows:
     with tau_recomp,i = tau_bkwd,i + ceil(2 (S - j) / N) for the j-th of the S stages of a segment
                                                                   [App. "PipeMare Recompute"]
 
+  * Hogwild-style stochastic delays: every step draws a delay per stage from an exponential
+    distribution truncated at tau_max, stages differing in its mean; T1 uses the mean  [App. "Hogwild! asynchrony"]
+
 Readings where the paper is silent (documented in the design notes of the repository):
 versions before step 0 clamp to w_0; stages are 1-based; tau_i in T1 is tau_fwd,i and
 max(tau_i,1) is used so that tau=0 gives scale 1; step counter k is 0-based; delta_0 = v_0 = 0;
@@ -86,6 +89,43 @@ def recompute_delays(P: int, S: int, N: int = 1, tau_bkwd=None):
 def segment_starts(P: int, S: int):
     """First stage (1-based) of every segment."""
     return list(range(1, P + 1, S))
+
+
+# --------------------------------------------------------------------------- stochastic delays (App. "Hogwild! asynchrony")
+_M64 = (1 << 64) - 1
+
+
+def counter_u32(seed: int, t: int, i: int, P: int) -> int:
+    """32 random bits for (step t, stage i of P), a pure function of its arguments: output number
+    t*P + i of the SplitMix64 generator (Steele, Lea, Flood 2014) started at `seed`, upper half."""
+    z = (seed + (t * P + i) * 0x9E3779B97F4A7C15) & _M64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _M64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _M64
+    z ^= z >> 31
+    return z >> 32
+
+
+def delay_thresholds(mean: float, tau_max: int):
+    """Integer inverse-CDF table of the delay of one stage: X ~ Exp(mean) truncated to [0, tau_max + 1),
+    delay = floor(X) in {0..tau_max}.  P(delay <= k) = (1 - e^{-(k+1)/mean}) / (1 - e^{-(tau_max+1)/mean});
+    T[k] = min(floor(2^32 P(delay <= k)), 2^32 - 1) for k = 0..tau_max-1.  mean <= 0: always delay 0."""
+    if tau_max < 0:
+        raise ValueError("tau_max >= 0 required")
+    if mean <= 0:
+        return [0xFFFFFFFF] * tau_max
+    norm = 1.0 - math.exp(-(tau_max + 1) / mean)
+    return [min(int(math.floor((1.0 - math.exp(-(k + 1) / mean)) / norm * 4294967296.0)), 0xFFFFFFFF)
+            for k in range(tau_max)]
+
+
+def delay_from_u32(r: int, thresholds) -> int:
+    """delay = number of table entries the draw exceeds (the table is non-decreasing)."""
+    return sum(1 for T in thresholds if r > T)
+
+
+def stochastic_delay(seed: int, t: int, i: int, P: int, thresholds) -> int:
+    """Delay of stage i (1-based) at step t."""
+    return delay_from_u32(counter_u32(seed, t, i, P), thresholds)
 
 
 def gpipe_utilization(N: int, P: int) -> float:
@@ -286,7 +326,11 @@ class PipeMareOracle:
                    base step size: "PipeMareW", Sec. 4), after which the delays apply and the T1
                    counter starts at 0; delta keeps accumulating during the warm-up;
                    tau_recomp (list per stage, or None = no recomputation) and segment (stages per
-                   segment): the backward pass rebuilds activations with u_recomp (see the header)
+                   segment): the backward pass rebuilds activations with u_recomp (see the header);
+                   stochastic (None, or dict(tau_max, seed)): Hogwild-style delays - at every step each
+                   stage i draws a delay from the exponential with mean tau_fwd,i truncated at tau_max,
+                   and both passes read that version of its weights (no forward/backward discrepancy,
+                   hence no T2); T1 keeps dividing by the mean tau_fwd,i; tau_bkwd is ignored
     keep_history   True keeps every version; False drops versions no delay can reach any more
                    (still indexed by absolute version number).
     """
@@ -302,9 +346,18 @@ class PipeMareOracle:
                 raise ValueError("need 0 <= tau_bkwd <= tau_fwd")
         o = dict(kind="sgdm", beta=0.0, beta1=0.9, beta2=0.98, eps=1e-8, weight_decay=0.0,
                  clip_norm=0.0, D=1.0, gamma_override=None, K=0, t1=True, t2=True,
-                 sched=dict(kind="const", base=0.1), N=1, sync_warmup=0, tau_recomp=None, segment=0)
+                 sched=dict(kind="const", base=0.1), N=1, sync_warmup=0, tau_recomp=None, segment=0,
+                 stochastic=None)
         o.update(opt)
         self.opt = o
+        self.stoch = None
+        if o["stochastic"] is not None:
+            if o["tau_recomp"] is not None:
+                raise ValueError("stochastic delays and recomputation are not combined")
+            tm, P_ = int(o["stochastic"]["tau_max"]), len(self.tau_fwd)
+            self.stoch = dict(tau_max=tm, seed=int(o["stochastic"]["seed"]),
+                              tables=[delay_thresholds(float(m), tm) for m in self.tau_fwd])
+            self.last_delays = [0] * P_
         self.tau_recomp = None
         self.checkpoints = None
         if o["tau_recomp"] is not None:
@@ -349,6 +402,11 @@ class PipeMareOracle:
         t = self.t if t is None else t
         if t < self.opt["sync_warmup"]:
             return [(t, t)] * self.U
+        if self.stoch is not None:
+            P_ = len(self.tau_fwd)
+            d = [stochastic_delay(self.stoch["seed"], t, i, P_, self.stoch["tables"][i - 1]) for i in range(1, P_ + 1)]
+            self.last_delays = d
+            return [(max(t - d[self.stage[u] - 1], 0),) * 2 for u in range(self.U)]
         return [(max(t - self._tf(u), 0), max(t - self._tb(u), 0)) for u in range(self.U)]
 
     # -- one optimizer step
@@ -364,7 +422,7 @@ class PipeMareOracle:
         for u in range(self.U):
             base = self.hist[u][vers[u][1]]
             d = self._tf(u) - self._tb(u)
-            if o["t2"] and d > 0 and not warm:
+            if o["t2"] and d > 0 and not warm and self.stoch is None:
                 base = base - d * self.delta[u]
             u_bkwd.append(base)
         extra = {}
@@ -416,7 +474,7 @@ class PipeMareOracle:
             self.delta[u] = gam * self.delta[u] + (1.0 - gam) * (w_new - w)
             self.hist[u][t + 1] = w_new
             if not self.keep_history:
-                oldest = t + 1 - self._tf(u)
+                oldest = t + 1 - (self._tf(u) if self.stoch is None else self.stoch["tau_max"])
                 for ver in [k for k in self.hist[u] if k < oldest]:
                     del self.hist[u][ver]
         self.t = t + 1
