@@ -45,6 +45,9 @@ def main():
     ap.add_argument("--recompute", type=int, default=0,
                     help="MLP workloads: S > 0 turns on recomputation with segments of S stages (the backward pass "
                          "rebuilds the activations inside each segment with the delayed, corrected recompute weights)")
+    ap.add_argument("--stochastic", type=int, default=-1,
+                    help="TAU_MAX >= 0 turns on Hogwild-style stochastic delays: every step each stage draws its delay from "
+                         "the exponential with the pipeline's delay as mean, truncated at TAU_MAX")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run three plain device-to-device copies of this many MiB after the timed region "
                          "(a kernel of known traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings by)")
@@ -63,6 +66,7 @@ def main():
     w = wl.config(args.config)
     o = w.opt
     tau_fwd, tau_bkwd = pm.pm_delays(w.P, w.N, "pipemare")
+    stoch = dict(tau_max=args.stochastic, seed=20191005) if args.stochastic >= 0 else None
     tau_recomp = pm.pm_recompute_delays(w.P, args.recompute, w.N, tau_bkwd) if args.recompute > 0 else None
     params = wl.init_params(w)
     n_params = int(sum(p.size for p in params))
@@ -81,7 +85,8 @@ def main():
                             N=w.N, dtype=w.dtype, loss=w.loss, microbatch=w.microbatch, use_graph=use_graph,
                             overlap_update=(launch == "overlap"), arch=w.arch.get("kind", "chain"),
                             n_heads=w.arch.get("n_heads", 0), seq_len=w.arch.get("seq", 0),
-                            image_size=w.arch.get("image", 0), tau_recomp=tau_recomp, segment_size=args.recompute)
+                            image_size=w.arch.get("image", 0), tau_recomp=tau_recomp, segment_size=args.recompute,
+                            stochastic=stoch)
         eng = pm.PipeMare(w.layers, w.P, tau_fwd, tau_bkwd, sched, opts, params, stream=side)
         pool = [stream_data.batch(k) for k in range(args.pool)]
         xs = [torch.from_numpy(x).cuda() for x, _ in pool]
@@ -122,6 +127,8 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     steps_per_s = args.steps / dt
     bpp = BYTES_PER_PARAM[(o["kind"], w.dtype)]
+    if stoch is not None:
+        bpp -= 2 if w.dtype == "bf16" else 4        # no corrected backward weights are written
     upd_s = prof["update_ms"] * 1e-3
     # an embedding has no corrected backward weights (nothing flows through it): one 2- or 4-byte stream less
     esz = 2 if w.dtype == "bf16" else 4
@@ -179,12 +186,14 @@ def main():
                                f"microbatch {w.microbatch}{' x ' + str(w.arch['seq']) + ' tokens' if is_tfm else ''}, "
                                f"PipeMare delays tau_fwd={tau_fwd[0]}..{tau_fwd[-1]}, tau_bkwd=0, "
                                f"{o['kind']} beta {o['beta']}, T1 K={o['K']}, T2 D={o['D']}"
+                               + (f", stochastic delays (truncated exponential, tau_max {args.stochastic}; both passes read the drawn version, no T2)"
+                                  if stoch is not None else "")
                                + (f", recomputation in segments of {args.recompute} stages (tau_recomp={tau_recomp[0]}..{tau_recomp[-1]})"
                                   if tau_recomp is not None else ""),
                    "launch": launch, "final_loss": round(stats["loss"], 5)},
         "roofline": {"kernel": "pm_fused_update_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic(w.name) if tau_recomp is None else None, "algorithmic_bytes": alg_bytes,
+                     "traffic": measured_traffic(w.name) if tau_recomp is None and stoch is None else None, "algorithmic_bytes": alg_bytes,
                      "bytes_per_param": bpp, "params": n_params,
                      "avg_kernel_ms": round(prof["update_ms"], 5), "launches_timed": prof["n"]},
         "phases_ms": {"forward_loss": round(prof["fwd_ms"], 4), "backward": round(prof["bwd_ms"], 4),
@@ -197,7 +206,7 @@ def main():
                                 "and launch gaps are inside that time"},
     }
     if args.cpu_steps > 0:
-        out["cpu_baseline"] = cpu_baseline(w, params, tau_fwd, tau_bkwd, args.cpu_steps, tau_recomp, args.recompute)
+        out["cpu_baseline"] = cpu_baseline(w, params, tau_fwd, tau_bkwd, args.cpu_steps, tau_recomp, args.recompute, stoch)
     print(json.dumps(out), flush=True)
 
 
@@ -215,7 +224,7 @@ def measured_traffic(workload_name):
     return None
 
 
-def cpu_baseline(w, params, tau_fwd, tau_bkwd, n_steps, tau_recomp=None, segment=0):
+def cpu_baseline(w, params, tau_fwd, tau_bkwd, n_steps, tau_recomp=None, segment=0, stochastic=None):
     """The fp64 NumPy oracle as it stands, timed on the host cores on the first n_steps of the workload."""
     import workloads as wl
     from pm_testutil import make_oracle
@@ -227,7 +236,7 @@ def cpu_baseline(w, params, tau_fwd, tau_bkwd, n_steps, tau_recomp=None, segment
     o = w.opt
     orc = make_oracle(w, params, tau_fwd, tau_bkwd, opt=o["kind"], lr=o.get("lr", 0.0), beta=o["beta"], beta2=o.get("beta2", 0.98),
                       D=o["D"], K=o["K"], weight_decay=o["weight_decay"], sched=o.get("sched"),
-                      tau_recomp=tau_recomp, segment=segment)
+                      tau_recomp=tau_recomp, segment=segment, stochastic=stochastic)
     stream = wl.batch_stream(w)
     batches = [stream.batch(k) for k in range(n_steps + 2)]
     for k in range(2):

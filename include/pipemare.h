@@ -140,6 +140,15 @@ typedef struct {
                                 delta_t ("T2 for Recompute").  Needs tau_bkwd,i <= tau_recomp,i <= tau_fwd,i.
                                 pm_recompute_delays gives the delays of PipeMare Recompute. */
   int32_t segment_size;      /* stages per segment (>= 1) when tau_recomp is given; the last segment may be shorter */
+  int32_t stochastic_delays; /* 1: Hogwild-style stochastic delays (App. "Hogwild! asynchrony"): at every optimizer step
+                                each stage i draws a delay from the exponential distribution with mean tau_fwd[i-1]
+                                truncated at tau_max, and BOTH passes read that version of the stage's weights (no
+                                forward/backward discrepancy, so T2 does not apply and tau_bkwd is ignored); T1 keeps
+                                dividing by the mean tau_fwd[i-1].  Every ring then has tau_max + 1 slots.  The draw is
+                                a pure function of (delay_seed, step, stage): see pm_stochastic_delays.  Not combined
+                                with recomputation. */
+  int32_t tau_max;           /* stochastic delays: largest delay, 0 .. 65535 */
+  uint64_t delay_seed;       /* stochastic delays: seed of the counter-based generator */
 } pm_opts;
 
 const char* pm_status_str(pm_status s);
@@ -150,6 +159,19 @@ const char* pm_last_error(void);
  * tau_fwd,i = ceil((2(P-i)+1)/N); tau_bkwd,i = 0 (PipeMare) | tau_fwd,i (PipeDream); both 0 for
  * GPipe.  Host arrays of P entries each (index i-1).  PM_EINVAL if P < 1 or N < 1. */
 pm_status pm_delays(int32_t P, int32_t N, int32_t method, int32_t* tau_fwd, int32_t* tau_bkwd);
+
+/* Stochastic delays (App. "Hogwild! asynchrony"): integer inverse-CDF table of one stage's delay.
+ * X ~ Exp(mean) truncated to [0, tau_max + 1), delay = floor(X) in 0..tau_max;
+ * thresholds[k] = min(floor(2^32 P(delay <= k)), 2^32 - 1) for k = 0..tau_max-1 (host array, out);
+ * a 32-bit draw r gives delay = #{k : r > thresholds[k]}.  mean <= 0: always 0. */
+pm_status pm_delay_thresholds(double mean, int32_t tau_max, uint32_t* thresholds);
+
+/* The delays all P stages draw at optimizer step t: stage i (1-based) takes output number t * P + i
+ * of the SplitMix64 generator started at `seed` (upper 32 bits) through the table of mean
+ * mean_tau[i-1].  Pure host integer function, identical to what the device computes.
+ * mean_tau: host, P entries; tau_out: host, P entries (out). */
+pm_status pm_stochastic_delays(int32_t P, const int32_t* mean_tau, int32_t tau_max, uint64_t seed, int64_t t,
+                               int32_t* tau_out);
 
 /* Recompute delays of PipeMare Recompute (App. "Trade compute for memory via PipeMare Recompute"): with the P
  * stages cut into segments of S consecutive stages (the last may be shorter), the j-th stage of a segment of S'

@@ -43,6 +43,22 @@ pm_status fail(pm_status s, const char* fmt, ...) {
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
+// Integer inverse-CDF table of one stage's delay (App. "Hogwild! asynchrony": exponential, truncated):
+// X ~ Exp(mean) truncated to [0, tau_max + 1), delay = floor(X);
+// T[k] = min(floor(2^32 P(delay <= k)), 2^32 - 1), P(delay <= k) = (1 - e^{-(k+1)/mean}) / (1 - e^{-(tau_max+1)/mean}).
+// mean <= 0: the delay is always 0.
+inline void delay_thresholds(double mean, int tau_max, uint32_t* T) {
+  if (mean <= 0.0) {
+    for (int k = 0; k < tau_max; ++k) T[k] = 0xFFFFFFFFu;
+    return;
+  }
+  const double norm = 1.0 - std::exp(-(double)(tau_max + 1) / mean);
+  for (int k = 0; k < tau_max; ++k) {
+    const double v = std::floor((1.0 - std::exp(-(double)(k + 1) / mean)) / norm * 4294967296.0);
+    T[k] = v >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)v;
+  }
+}
+
 struct Unit {
   pm_layer_desc d;
   int64_t nw;        // values of the first part: W (n_out * n_in), embedding table, or LayerNorm gain
@@ -74,7 +90,7 @@ struct Layout {
   int64_t n_chunks = 0;
   size_t esz = 4;         // bytes per element of the compute dtype
   // byte offsets
-  size_t w_off, g_off, v_off, s_off, d_off, ub_off, ur_off, ring_off, chunk_off, ls_off, ld_off, hdr_off, probs_off, x_off;
+  size_t w_off, g_off, v_off, s_off, d_off, ub_off, ur_off, cdf_off, ring_off, chunk_off, ls_off, ld_off, hdr_off, probs_off, x_off;
   size_t act_begin, act_end, total;
   // Transformer activations (byte offsets; see launch_tfm).  Per layer: index [layer]
   struct TfmLayer {
@@ -174,6 +190,10 @@ pm_status validate(int32_t P, int32_t L, const pm_layer_desc* layers, const int3
     if (tau_fwd[i] < 0) return fail(PM_EINVAL, "tau_fwd[%d] < 0", i);
     if (tau_bkwd && (tau_bkwd[i] < 0 || tau_bkwd[i] > tau_fwd[i])) return fail(PM_EINVAL, "need 0 <= tau_bkwd[%d] <= tau_fwd[%d]", i, i);
   }
+  if (o->stochastic_delays) {
+    if (o->tau_max < 0 || o->tau_max > 65535) return fail(PM_EINVAL, "tau_max must be in 0..65535");
+    if (o->tau_recomp) return fail(PM_EINVAL, "stochastic delays and recomputation are not combined");
+  }
   if (o->tau_recomp) {
     if (o->arch != PM_ARCH_CHAIN) return fail(PM_EINVAL, "recomputation is implemented for PM_ARCH_CHAIN only");
     if (o->segment_size < 1) return fail(PM_EINVAL, "recomputation needs segment_size >= 1 (stages per segment)");
@@ -205,8 +225,9 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
     u.ring_off = roff;
     u.tau_f = tau_fwd[u.d.stage - 1];
     u.tau_b = tau_bkwd ? tau_bkwd[u.d.stage - 1] : 0;
-    u.R = u.tau_f + 1;
-    const int dd = u.tau_f - u.tau_b;
+    u.R = (o->stochastic_delays ? o->tau_max : u.tau_f) + 1;
+    // stochastic delays: both passes read the drawn version, so there is nothing to correct
+    const int dd = o->stochastic_delays ? 0 : u.tau_f - u.tau_b;
     // nothing flows through an embedding to earlier units: its backward weights are never read
     u.corr = (o->t2_enabled && dd > 0 && u.d.kind != PM_EMBED) ? dd : 0;
     if (o->gamma_override) u.gamma = o->gamma_override[u.d.stage - 1];
@@ -243,6 +264,11 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
   lay.d_off = take(lay.n_flat * 4);
   lay.ub_off = take(lay.n_flat * lay.esz);
   lay.ur_off = take(lay.has_ur ? lay.n_flat * lay.esz : 0);
+  {
+    int P = 0;
+    for (int l = 0; l < L; ++l) P = std::max(P, (int)layers[l].stage);
+    lay.cdf_off = take(o->stochastic_delays ? sizeof(uint32_t) * (size_t)P * (size_t)o->tau_max : 0);
+  }
   lay.ring_off = take(lay.ring_elems * lay.esz);
   lay.chunk_off = take(lay.n_chunks * 4);
   lay.ls_off = take(sizeof(PmLayerStatic) * L);
@@ -385,6 +411,11 @@ PmSchedDev sched_dev(const pm_ctx* c) {
   s.beta2 = c->o.beta2;
   s.gscale0 = 1.0 / c->o.n_microbatches;
   s.sync_warmup = c->o.sync_warmup_steps;
+  s.stoch = c->o.stochastic_delays ? 1 : 0;
+  s.tau_max = c->o.tau_max;
+  s.P = c->P;
+  s.seed = c->o.delay_seed;
+  s.cdf = c->o.stochastic_delays ? c->at<uint32_t>(c->lay.cdf_off) : nullptr;
   return s;
 }
 
@@ -1000,6 +1031,23 @@ pm_status pm_delays(int32_t P, int32_t N, int32_t method, int32_t* tau_fwd, int3
   return PM_OK;
 }
 
+pm_status pm_delay_thresholds(double mean, int32_t tau_max, uint32_t* thresholds) {
+  if (tau_max < 0 || (tau_max > 0 && !thresholds)) return fail(PM_EINVAL, "tau_max >= 0 and an output array required");
+  delay_thresholds(mean, tau_max, thresholds);
+  return PM_OK;
+}
+
+pm_status pm_stochastic_delays(int32_t P, const int32_t* mean_tau, int32_t tau_max, uint64_t seed, int64_t t,
+                               int32_t* tau_out) {
+  if (P < 1 || !mean_tau || tau_max < 0 || t < 0 || !tau_out) return fail(PM_EINVAL, "P >= 1, tau_max >= 0, t >= 0 and arrays required");
+  std::vector<uint32_t> T((size_t)std::max(tau_max, 1));
+  for (int32_t i = 1; i <= P; ++i) {
+    delay_thresholds((double)mean_tau[i - 1], tau_max, T.data());
+    tau_out[i - 1] = pm_delay_from_u32(pm_counter_u32(seed, t, i, P), T.data(), tau_max);
+  }
+  return PM_OK;
+}
+
 pm_status pm_recompute_delays(int32_t P, int32_t S, int32_t N, const int32_t* tau_bkwd, int32_t* tau_recomp) {
   if (P < 1 || S < 1 || N < 1 || !tau_recomp) return fail(PM_EINVAL, "P, S, N >= 1 and an output array required");
   for (int32_t i = 1; i <= P; ++i) {
@@ -1099,7 +1147,7 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
   }
   c->arena = (char*)device_arena;
   c->stream = (hipStream_t)hip_stream;
-  c->min_tau_f = *std::min_element(c->tau_f.begin(), c->tau_f.end());
+  c->min_tau_f = opts->stochastic_delays ? 0 : *std::min_element(c->tau_f.begin(), c->tau_f.end());   // a drawn delay can be 0
   c->overlap = opts->overlap_update != 0 && opts->use_graph == 0;
   if (c->overlap) {
     // host-side objects only; default priority
@@ -1140,6 +1188,12 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
   if ((e = hipMemcpyAsync(c->arena + lay.w_off, w0.data(), w0.size() * 4, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy weights");
   if ((e = hipMemcpyAsync(c->arena + lay.chunk_off, chunk_layer.data(), chunk_layer.size() * 4, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy chunk table");
   if ((e = hipMemcpyAsync(c->arena + lay.ls_off, ls.data(), ls.size() * sizeof(PmLayerStatic), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy unit table");
+  std::vector<uint32_t> cdf;
+  if (c->o.stochastic_delays && c->o.tau_max > 0) {
+    cdf.resize((size_t)P * c->o.tau_max);
+    for (int i = 0; i < P; ++i) delay_thresholds((double)tau_fwd[i], c->o.tau_max, &cdf[(size_t)i * c->o.tau_max]);
+    if ((e = hipMemcpyAsync(c->arena + lay.cdf_off, cdf.data(), cdf.size() * 4, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy delay table");
+  }
   std::vector<PmGemmProb<PmEpiBwdWeight>> probs;
   std::vector<float> pos;
   std::vector<int64_t> zero_tab;

@@ -60,7 +60,30 @@ struct PmSchedDev {
   double beta1, beta2;
   double gscale0;      // 1 / N (mean over microbatches)
   long long sync_warmup;  // E_w: steps t < E_w run with all delays 0 and the base step size
+  // Hogwild-style stochastic delays (App. "Hogwild! asynchrony"): every step draws a delay per stage
+  int32_t stoch;            // 1: on
+  int32_t tau_max;          // delays lie in 0 .. tau_max; every ring has tau_max + 1 slots
+  int32_t P;                // stages
+  unsigned long long seed;
+  const uint32_t* cdf;      // device: per stage tau_max thresholds T[k] = floor(2^32 P(delay <= k))
 };
+
+// 32 random bits for (step t, stage i of P), i 1-based: output number t * P + i of the SplitMix64
+// generator (Steele, Lea, Flood 2014) started at `seed`, upper half.  A pure function, the same on
+// host and device.
+__host__ __device__ inline uint32_t pm_counter_u32(unsigned long long seed, long long t, int i, int P) {
+  unsigned long long z = seed + (unsigned long long)(t * P + i) * 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z ^= z >> 31;
+  return (uint32_t)(z >> 32);
+}
+// delay = number of thresholds the draw exceeds (the table is non-decreasing)
+__host__ __device__ inline int pm_delay_from_u32(uint32_t r, const uint32_t* T, int tau_max) {
+  int d = 0;
+  for (int k = 0; k < tau_max; ++k) d += r > T[k];
+  return d;
+}
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 

@@ -31,8 +31,14 @@ __device__ __forceinline__ void pm_prologue_block(PmStepHdr* hdr, const PmLayerS
   for (int l = threadIdx.x; l < L; l += blockDim.x) {
     const PmLayerStatic S = ls[l];
     PmLayerStep D;
-    const long long tf = warm ? 0 : S.tau_f, tb = warm ? 0 : S.tau_b, tbn = warm_next ? 0 : S.tau_b;
+    long long tf = warm ? 0 : S.tau_f, tb = warm ? 0 : S.tau_b;
+    const long long tbn = warm_next ? 0 : S.tau_b;
     const long long tr = warm ? 0 : S.tau_r, trn = warm_next ? 0 : S.tau_r;
+    if (sc.stoch && !warm) {
+      // this step's delay of the unit's stage; both passes read that version (no discrepancy, no T2)
+      tf = tb = pm_delay_from_u32(pm_counter_u32(sc.seed, t, S.stage, sc.P), sc.cdf + (size_t)(S.stage - 1) * sc.tau_max,
+                                  sc.tau_max);
+    }
     const long long vf = t - tf > 0 ? t - tf : 0;
     const long long vb = t - tb > 0 ? t - tb : 0;
     const long long vu = t + 1 - tbn > 0 ? t + 1 - tbn : 0;

@@ -15,7 +15,8 @@ def sched_dict(kind="const", base=0.01, init=0.0, factor=1.0, interval=1):
 
 def make_oracle(w, params, tau_fwd, tau_bkwd, *, opt="sgdm", lr=0.01, beta=0.9, beta2=0.98, eps=1e-8,
                 weight_decay=0.0, clip_norm=0.0, D=0.9, K=0, t1=True, t2=True, N=1, sched=None,
-                gamma_override=None, model=None, keep_history=False, sync_warmup=0, tau_recomp=None, segment=0):
+                gamma_override=None, model=None, keep_history=False, sync_warmup=0, tau_recomp=None, segment=0,
+                stochastic=None):
     if model is None:
         if w.arch.get("kind") == "transformer":
             from oracle.transformer_oracle import TransformerModel
@@ -29,7 +30,7 @@ def make_oracle(w, params, tau_fwd, tau_bkwd, *, opt="sgdm", lr=0.01, beta=0.9, 
     o = dict(kind=opt, beta=beta, beta1=beta, beta2=beta2, eps=eps, weight_decay=weight_decay,
              clip_norm=clip_norm, D=D, K=K, t1=t1, t2=t2, N=N, gamma_override=gamma_override,
              sched=sched or dict(kind="const", base=lr), sync_warmup=sync_warmup, tau_recomp=tau_recomp,
-             segment=segment)
+             segment=segment, stochastic=stochastic)
     return po.PipeMareOracle(model, [p.astype(np.float64) for p in params], [L.stage for L in w.layers],
                              tau_fwd, tau_bkwd, o, keep_history=keep_history)
 
@@ -37,7 +38,7 @@ def make_oracle(w, params, tau_fwd, tau_bkwd, *, opt="sgdm", lr=0.01, beta=0.9, 
 def make_gpu(w, params, tau_fwd, tau_bkwd, *, opt="sgdm", lr=0.01, beta=0.9, beta2=0.98, eps=1e-8,
              weight_decay=0.0, clip_norm=0.0, D=0.9, K=0, t1=True, t2=True, N=1, sched=None,
              gamma_override=None, use_graph=False, dtype=None, stream=None, sync_warmup=0, overlap_update=False,
-             tau_recomp=None, segment=0):
+             tau_recomp=None, segment=0, stochastic=None):
     import paper_1910_05124_amd as pm
     s = sched or dict(kind="const", base=lr)
     sc = pm.make_sched(kind=s["kind"], base=s["base"], init=s.get("init", 0.0), factor=s.get("factor", 1.0),
@@ -47,7 +48,8 @@ def make_gpu(w, params, tau_fwd, tau_bkwd, *, opt="sgdm", lr=0.01, beta=0.9, bet
                      microbatch=w.microbatch, use_graph=use_graph, sync_warmup=sync_warmup,
                      overlap_update=overlap_update, arch=w.arch.get("kind", "chain"),
                      n_heads=w.arch.get("n_heads", 0), seq_len=w.arch.get("seq", 0),
-                     image_size=w.arch.get("image", 0), tau_recomp=tau_recomp, segment_size=segment)
+                     image_size=w.arch.get("image", 0), tau_recomp=tau_recomp, segment_size=segment,
+                     stochastic=stochastic)
     return pm.PipeMare(w.layers, w.P, tau_fwd, tau_bkwd, sc, o, params, stream=stream)
 
 

@@ -43,6 +43,19 @@ def test_recompute_delays_match_oracle():
         pm.pm_recompute_delays(4, 0, 1)
 
 
+def test_stochastic_delay_tables_and_draws_match_oracle_bit_for_bit():
+    for mean, tau_max in ((3.0, 5), (1.0, 12), (31.0, 40), (7.0, 200), (0.5, 3), (0.0, 6), (197.0, 300), (4.0, 0)):
+        assert pm.pm_delay_thresholds(mean, tau_max) == po.delay_thresholds(mean, tau_max)
+    for P, tau_max, seed in ((4, 9, 7), (16, 40, 2**63 + 11), (99, 250, 0), (1, 0, 5)):
+        mean = po.pipeline_delays(P, 1)[0]
+        tabs = [po.delay_thresholds(float(m), tau_max) for m in mean]
+        for t in list(range(40)) + [10**6, 2**40 + 3]:
+            want = [po.stochastic_delay(seed, t, i, P, tabs[i - 1]) for i in range(1, P + 1)]
+            assert pm.pm_stochastic_delays(P, mean, tau_max, seed, t) == want
+    with pytest.raises(pm.PmError):
+        pm.pm_stochastic_delays(3, [1, 1, 1], -1, 0, 0)
+
+
 def test_slots_brute_force_against_oracle_versions():
     for tf in (0, 1, 2, 7, 31):
         for tb in sorted({0, tf // 2, tf}):

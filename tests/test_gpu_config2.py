@@ -19,7 +19,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.timeout(1500)
-@pytest.mark.parametrize("launch", ["graph", "overlap", "graph_recompute4"])
+@pytest.mark.parametrize("launch", ["graph", "overlap", "graph_recompute4", "graph_stochastic"])
 def test_config1_bf16_mlp16_500_steps(launch):
     import torch
     w = wl.config(1)
@@ -34,6 +34,12 @@ def test_config1_bf16_mlp16_500_steps(launch):
         kw.update(tau_recomp=po.recompute_delays(w.P, 4, 1), segment=4)
         assert kw["tau_recomp"] == [6, 4, 2, 0] * 4
         launch, n_steps = "graph", 200
+    stoch = None
+    if launch == "graph_stochastic":
+        # the same workload under Hogwild-style stochastic delays (means = the pipeline's delays), 150 steps
+        stoch = dict(tau_max=40, seed=20191005)
+        kw.update(stochastic=stoch)
+        launch, n_steps = "graph", 150
     stream = wl.BatchStream(w)
     o = make_oracle(w, params, tf, tb, **kw)
     side = torch.cuda.Stream()
@@ -61,7 +67,7 @@ def test_config1_bf16_mlp16_500_steps(launch):
                 t_used, fs, bs, ws, lrs = g.step_table()
                 assert t_used == k
                 for u, L in enumerate(w.layers):
-                    R = tf[L.stage - 1] + 1
+                    R = (tf[L.stage - 1] if stoch is None else stoch["tau_max"]) + 1
                     vf, vb = o.last_versions[u]
                     assert (fs[u], bs[u], ws[u]) == (vf % R, vb % R, (k + 1) % R)
                     assert lrs[u] == pytest.approx(o.last_lr[u], rel=2e-7)
