@@ -83,16 +83,28 @@ struct PmTileLoader {
   }
 };
 
-// MFMA operand fragment for tile row `row` (0..ROWS-1): 8 consecutive k from kbase
+typedef short pm_v4s __attribute__((ext_vector_type(4)));
+
+// MFMA operand fragment of the 32-row tile starting at tile row r32 for contraction indices
+// kb .. kb+15 (kb a multiple of 16): lane l holds row r32 + l%32, k = kb + 8*(l/32) .. +7.
+// KC tile: one 16-byte read.  RC tile ([k][row] in LDS): the gfx950 LDS transpose load - in each
+// group of 16 lanes, lane q supplies the address of 4 consecutive elements (one k-row, 4 operand
+// rows) and receives, for the operand row given by its index in the group, the elements of 4
+// consecutive k-rows; lane q of group g addresses k-row kb + 8*(g/2) + q/4, operand rows
+// r32 + 16*(g%2) + 4*(q%4) .. +3 (two such loads, k-rows +0 and +4, make the fragment).
 template <int ROWS, bool KC, int BK>
-__device__ __forceinline__ pm_bf16x8 pm_read_frag(const bf16_t* s, int row, int kbase) {
+__device__ __forceinline__ pm_bf16x8 pm_read_frag(const bf16_t* s, int r32, int kb, int lane) {
   using S = PmTileShape<ROWS, KC, BK>;
   if (KC) {
-    return *reinterpret_cast<const pm_bf16x8*>(s + row * S::stride + kbase);
+    return *reinterpret_cast<const pm_bf16x8*>(s + (r32 + (lane & 31)) * S::stride + kb + (lane >> 5) * 8);
   } else {
-    union { pm_bf16x8 v; bf16_t h[8]; } u;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) u.h[e] = s[(kbase + e) * S::stride + row];
+    static_assert((S::stride & 3) == 0, "transpose loads need 8-byte aligned k-rows");
+    const int g = lane >> 4, q = lane & 15;
+    const bf16_t* p = s + (kb + 8 * (g >> 1) + (q >> 2)) * S::stride + r32 + 16 * (g & 1) + 4 * (q & 3);
+    typedef pm_v4s __attribute__((address_space(3))) * lds_v4s;
+    union { pm_bf16x8 v; pm_v4s h[2]; } u;
+    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p));
+    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p + 4 * S::stride));
     return u.v;
   }
 }
@@ -172,12 +184,12 @@ __device__ __forceinline__ void pm_gemm_body(const PmGemmProb<Epi>& pr, Epi epi,
     }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const int kbase = (wk * KS + ks) * 16 + kg * 8;
+      const int kb = (wk * KS + ks) * 16;
       pm_bf16x8 fa[TI], fb[TJ];
 #pragma unroll
-      for (int a = 0; a < TI; ++a) fa[a] = pm_read_frag<BI, AKC, BK>(sA, (wi * TI + a) * 32 + lr, kbase);
+      for (int a = 0; a < TI; ++a) fa[a] = pm_read_frag<BI, AKC, BK>(sA, (wi * TI + a) * 32, kb, lane);
 #pragma unroll
-      for (int b = 0; b < TJ; ++b) fb[b] = pm_read_frag<BJ, BKC, BK>(sB, (wj * TJ + b) * 32 + lr, kbase);
+      for (int b = 0; b < TJ; ++b) fb[b] = pm_read_frag<BJ, BKC, BK>(sB, (wj * TJ + b) * 32, kb, lane);
 #pragma unroll
       for (int a = 0; a < TI; ++a)
 #pragma unroll
@@ -311,8 +323,6 @@ inline bool pm_mfma_gemm_try(hipStream_t st, int I, int J, int K, const bf16_t* 
 // transpose load (ds_read_b64_tr_b16: two instructions per fragment instead of eight 2-byte
 // reads), XCD-aware block -> tile mapping so that tiles sharing operand panels share an L2.
 // ---------------------------------------------------------------------------------------------
-typedef short pm_v4s __attribute__((ext_vector_type(4)));
-
 template <int ROWS, bool KC>
 struct PmBigTile {                         // (ROWS x 64) operand slab in LDS
   static constexpr int BK = 64;
