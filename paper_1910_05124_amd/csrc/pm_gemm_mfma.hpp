@@ -272,12 +272,15 @@ using PmCfgSkinny1K = PmGemmCfg<32, 32, 1, 1, 4, 1024>;
 
 template <bool AKC, bool BKC, class Epi>
 inline bool pm_big_try(hipStream_t st, const PmGemmProb<Epi>& pr);
+template <bool AKC, bool BKC, class Epi>
+inline bool pm_mid_try(hipStream_t st, const PmGemmProb<Epi>& pr);
 
 template <bool AKC, bool BKC, class Epi>
 inline void pm_mfma_pick(hipStream_t st, const PmGemmProb<Epi>& pr) {
   if (pm_big_try<AKC, BKC>(st, pr)) return;
   const long tiles128 = (long)((pr.I + 127) / 128) * ((pr.J + 127) / 128);
   const long tiles64 = (long)((pr.I + 63) / 64) * ((pr.J + 63) / 64);
+  if (pm_mid_try<AKC, BKC>(st, pr)) return;
   if (tiles128 >= 512) pm_mfma_launch<PmCfgBig, AKC, BKC>(st, pr);
   else if (pr.K <= 128) pm_mfma_launch<PmCfgShortK, AKC, BKC>(st, pr);
   else if (tiles64 >= 192 || pr.K <= 256) pm_mfma_launch<PmCfgMid, AKC, BKC>(st, pr);
@@ -400,7 +403,7 @@ struct PmBigCfg {
   static constexpr int BI = BI_, BJ = BJ_, WI = WI_, WJ = WJ_, NT = WI_ * WJ_ * 64;
   // waves per SIMD the register budget is sized for: the 128 x 128 wave tile holds 256 accumulator
   // registers and needs the whole 512-entry file (its LDS footprint allows one block per CU anyway)
-  static constexpr int WPE = (BI_ / WI_) * (BJ_ / WJ_) >= 128 * 128 ? 1 : 2;
+  static constexpr int WPE = (BI_ / WI_) * (BJ_ / WJ_) >= 128 * 128 ? 1 : (BI_ / WI_) * (BJ_ / WJ_) <= 32 * 32 ? 4 : 2;
   // first k-step (of 4) behind which the staged next slab is written to LDS
   static constexpr int STORE_FROM = (BI_ / WI_) * (BJ_ / WJ_) >= 128 * 128 ? 2 : 0;
 };
@@ -626,6 +629,10 @@ using PmBig128 = PmBigCfg<128, 128, 2, 2>;
 // 256 x 256 block, 4 waves x (128 x 128): one block per CU, one wave per SIMD holding 256 accumulator
 // registers; every LDS byte read feeds twice the MFMA work of the 64 x 64 wave tile
 using PmBig256 = PmBigCfg<256, 256, 2, 2>;
+// 64 x 64 block, 4 waves x (32 x 32): 37 KB of LDS, four blocks per CU.  For token counts in the low
+// thousands with narrow layers (4096 x 512 x 512 ...): enough tiles to fill the chip, and the same
+// software pipeline hides the memory latency that a load - store - compute loop pays once per slab.
+using PmBig64 = PmBigCfg<64, 64, 2, 2>;
 
 // true if no tile of the problem needs a bounds test
 template <class Cfg>
@@ -638,6 +645,15 @@ inline void pm_big_launch(hipStream_t st, const PmGemmProb<Epi>& pr) {
     hipLaunchKernelGGL((pm_gemm_big_kernel<Cfg, AKC, BKC, false, Epi>), dim3(ti * tj), dim3(Cfg::NT), 0, st, pr, ti, tj);
   else
     hipLaunchKernelGGL((pm_gemm_big_kernel<Cfg, AKC, BKC, true, Epi>), dim3(ti * tj), dim3(Cfg::NT), 0, st, pr, ti, tj);
+}
+
+// mid-size problems on the pipelined kernel with 64 x 64 blocks
+template <bool AKC, bool BKC, class Epi>
+inline bool pm_mid_try(hipStream_t st, const PmGemmProb<Epi>& pr) {
+  const long tiles64 = (long)((pr.I + 63) / 64) * ((pr.J + 63) / 64);
+  if (tiles64 < 256 || pr.K < 256) return false;
+  pm_big_launch<PmBig64, AKC, BKC>(st, pr);
+  return true;
 }
 
 // true if the problem was large enough for (and was launched on) the big-tile kernel
