@@ -189,21 +189,39 @@ __global__ __launch_bounds__(512) void pm_ln_bwd_kernel(const float* __restrict_
     ag[c] = zero4;
     ab[c] = zero4;
   }
+  // all loads of the wave's four rows go out first (rows past the end re-read the last row and are
+  // masked out below), so the wave pays the memory latency once instead of once per row
+  float4 dyr[4][NC], xr[4][NC];
+  float mur[4], rsr[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = blockIdx.x * 32 + wave * 4 + r;
+    const int rowc = row < rows ? row : rows - 1;
+    const int64_t ro = (int64_t)rowc * d;
+    mur[r] = mean[rowc];
+    rsr[r] = rstd[rowc];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int j = 256 * c + 4 * lane;
+      dyr[r][c] = j < d ? pm_ld4(dy + ro + j) : zero4;
+      xr[r][c] = j < d ? pm_ld4(x + ro + j) : zero4;
+    }
+  }
+#pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int row = blockIdx.x * 32 + wave * 4 + r;
     if (row >= rows) break;                                   // wave-uniform
-    const float mu = mean[row], rs = rstd[row];
+    const float mu = mur[r], rs = rsr[r];
     const int64_t ro = (int64_t)row * d;
     float4 xh[NC], dxh[NC], rr[NC];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       const int j = 256 * c + 4 * lane;
-      float4 dyv = zero4, xv = zero4;
+      float4 dyv = dyr[r][c], xv = zero4;
       rr[c] = zero4;
       if (j < d) {
-        dyv = pm_ld4(dy + ro + j);
-        xv = pm_ld4(x + ro + j);
+        xv = xr[r][c];
         if (dx_res) rr[c] = pm_ld4(dx_res + ro + j);
         xv = make_float4((xv.x - mu) * rs, (xv.y - mu) * rs, (xv.z - mu) * rs, (xv.w - mu) * rs);
       }
