@@ -556,19 +556,25 @@ __device__ __forceinline__ void pm_gemm_big_body(const PmGemmProb<Epi>& pr, int 
   // between parking and reading back inside one wave.)
   constexpr int WT_I = TI * 32, WT_J = TJ * 32, ES = WT_J + 4;          // wave tile and its padded row stride
   static_assert((size_t)PmBigLds<Cfg, AKC, BKC>::elems * 2 >= (size_t)WI * WJ * 32 * ES * 4, "epilogue staging does not fit the operand stages");
-  float* es = reinterpret_cast<float*>(smem) + (size_t)wave * 32 * ES;
+  // all stripes of the wave tile at once when the stages are large enough (one write -> read round trip
+  // through LDS per tile instead of one per stripe), else stripe by stripe
+  constexpr bool ALL = (size_t)PmBigLds<Cfg, AKC, BKC>::elems * 2 >= (size_t)WI * WJ * WT_I * ES * 4;
+  constexpr int SR = ALL ? WT_I : 32;                                   // rows staged per pass
+  float* es = reinterpret_cast<float*>(smem) + (size_t)wave * SR * ES;
   const int wi0 = i0 + wi * WT_I, wj0 = j0 + wj * WT_J;
 #pragma unroll
-  for (int a = 0; a < TI; ++a) {
+  for (int a0 = 0; a0 < TI; a0 += SR / 32) {
 #pragma unroll
-    for (int b = 0; b < TJ; ++b)
+    for (int a = a0; a < a0 + SR / 32; ++a)
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        es[(8 * (v >> 2) + 4 * kg + (v & 3)) * ES + b * 32 + lr] = acc[a][b][v];
+      for (int b = 0; b < TJ; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          es[((a - a0) * 32 + 8 * (v >> 2) + 4 * kg + (v & 3)) * ES + b * 32 + lr] = acc[a][b][v];
 #pragma unroll 4
-    for (int c = lane; c < 32 * (WT_J / 8); c += 64) {
+    for (int c = lane; c < SR * (WT_J / 8); c += 64) {
       const int r = c / (WT_J / 8), c8 = (c % (WT_J / 8)) * 8;
-      const int i = wi0 + a * 32 + r, j = wj0 + c8;
+      const int i = wi0 + a0 * 32 + r, j = wj0 + c8;
       if (CHECK && (i >= I || j >= J)) continue;
       float vals[8];
       const float4 v0 = *reinterpret_cast<const float4*>(es + r * ES + c8);
