@@ -75,3 +75,34 @@ def test_threshold_separates_the_oracles_trajectories(t2):
         w = np.abs(trajectory(o, 4000)[0])
         return w[3600:4000].max() / w[2600:3000].max()
     assert growth(0.93 * a_star) < 1.0 < growth(1.07 * a_star)
+
+
+@pytest.mark.parametrize("tf,tb", [(10, 6), (10, 0), (5, 4), (40, 10), (3, 1)])
+def test_lemma2_bound_on_the_stable_range_with_discrepancy(tf, tb):
+    """Sec. 3.2, lemma on the discrepancy-dependent update: for Delta > 0 instability sets in at some
+    alpha <= min(2 / (Delta (tau_fwd - tau_bkwd)), (2 / lam) sin(pi / (4 tau_fwd + 2)))."""
+    lam = 1.0
+    for Delta in (0.5, 5.0, 50.0):
+        a = stab.largest_stable_alpha(lambda x: stab.uncorrected_polynomial(tf, tb, x, lam, Delta))
+        bound = min(2.0 / (Delta * (tf - tb)), stab.lemma1_threshold(tf, lam))
+        assert a <= bound * (1 + 1e-6), (Delta, a, bound)
+
+
+def test_discrepancy_figure_setting():
+    """Sec. 3.2 figure, tau_fwd 10, tau_bkwd 6, lam 1: (a) a non-zero Delta makes a step size diverge that
+    converges with Delta = 0; (b) with Delta = 5 the discrepancy raises the largest eigenvalue magnitude,
+    the correction with D = 0.1 lowers it again, close to the value without discrepancy."""
+    tf, tb, lam, Delta, D = 10, 6, 1.0, 5.0, 0.1
+    g = stab.gamma_from_D(D, tf, tb)
+    for alpha in (0.04, 0.06, 0.08):
+        r_none = stab.spectral_radius(stab.uncorrected_polynomial(tf, tb, alpha, lam, 0.0))
+        r_disc = stab.spectral_radius(stab.uncorrected_polynomial(tf, tb, alpha, lam, Delta))
+        r_corr = stab.spectral_radius(stab.t2_polynomial(tf, tb, alpha, lam, Delta, g))
+        assert r_none < 1.0 < r_disc
+        assert r_corr < 1.0 and abs(r_corr - r_none) < 0.25 * abs(r_disc - r_none)
+    # the same on the recurrence itself (noise-free trajectories of the oracle)
+    def growth(Delta_, alpha):
+        o = scalar_oracle(1, [tf], [tb], lam=lam, Delta=Delta_, sched=dict(kind="const", base=alpha), t1=False, t2=False)
+        w = np.abs(trajectory(o, 1500)[0])
+        return w[1300:1500].max() / w[800:1000].max()
+    assert growth(0.0, 0.06) < 1.0 < growth(Delta, 0.06)
