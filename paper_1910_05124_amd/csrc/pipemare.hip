@@ -104,7 +104,7 @@ struct Layout {
     size_t z, y, da, dz, dy;
   };
   std::vector<ConvBuf> cv;
-  size_t r_x, r_pool, r_logits, r_dlogits, r_dpool, r_wscratch;
+  size_t r_x, r_pool, r_logits, r_dlogits, r_dpool, r_wscratch, r_ascratch;
   size_t t_xf, t_muf, t_rsf, t_nf, t_logits, t_dlogits;      // final LayerNorm and head
   size_t t_dx, t_dn, t_do;                                   // backward scratch, reused by every layer
   size_t t_pos, t_zero;                                      // positions fp32 [S, d]; zero-region table
@@ -332,6 +332,7 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
       ws = std::max(ws, o->dtype == PM_BF16 ? pm_conv_wgrad_scratch_elems<bf16_t>(lay.cv[u].g)
                                             : pm_conv_wgrad_scratch_elems<float>(lay.cv[u].g));
     lay.r_wscratch = take(ws * 4);
+    lay.r_ascratch = take((size_t)PM_CONV_AFFINE_MAX_BLOCKS * 2 * 256 * 4);     // per-block channel sums of the affine backward
     lay.n_zero = nconv;
     lay.zero_max = 0;
     for (int u = 0; u < nconv; ++u) lay.zero_max = std::max(lay.zero_max, lay.units[u].n_pad);
@@ -898,10 +899,13 @@ pm_status launch_resnet(pm_ctx* c, const void* x_dev, const void* y_dev, int acc
   for (int u = nconv - 1; u >= 0; --u) {
     const Layout::ConvBuf& b = lay.cv[u];
     const int64_t nw = U(u).nw, tot = (int64_t)B * b.g.Ho * b.g.Wo * b.g.Cout;
+    // the per-channel sums of the affine backward ride on the weight gradient's reduce launch when it has one
+    PmReduceJob sums{nullptr, 0, 0, nullptr, 1};
+    float* apart = pm_conv_wgrad_has_reduce<T>(b.g) ? c->at<float>(lay.r_ascratch) : nullptr;
     if (!pm_conv_affine_bwd_launch<T>(st, TT(b.dy), TT(b.y), TT(b.z), Wb(u, nw), TT(b.da), TT(b.dz), g + U(u).off + nw,
-                                      g + U(u).off + nw + b.g.Cout, tot, b.g.Cout))
+                                      g + U(u).off + nw + b.g.Cout, tot, b.g.Cout, apart, &sums))
       return fail(PM_EINVAL, "unit %d: channel count not supported", u);
-    pm_conv_wgrad_launch<T>(st, b.g, TT(b.dz), input_of(u), g + U(u).off, accumulate, c->at<float>(lay.r_wscratch));
+    pm_conv_wgrad_launch<T>(st, b.g, TT(b.dz), input_of(u), g + U(u).off, accumulate, c->at<float>(lay.r_wscratch), sums);
     if (u == 0) break;
     PmShortcutBwd<T> sb{nullptr, 0, 0, 0, 1};
     if ((u % 2) == 1) {                               // first convolution of a block: its input also feeds the shortcut

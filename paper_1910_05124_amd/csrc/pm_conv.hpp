@@ -201,15 +201,18 @@ __global__ __launch_bounds__(256) void pm_conv_wgrad_thin_kernel(PmConvGeom g, c
 }
 constexpr int PM_CONV_THIN_GROUPS = 64;
 
-// da = dy * [y > 0];  dz = da * scale_bkwd;  dscale += sum da * z;  dshift += sum da   (fp32 atomics;
-// the caller zeroes dscale / dshift at the start of a minibatch).  Thread t of a block always sees
-// channel (t * 8 .. t * 8 + 7) mod C because a block's span is a multiple of C elements.
+// da = dy * [y > 0];  dz = da * scale_bkwd;  dscale += sum da * z;  dshift += sum da.  The caller zeroes
+// dscale / dshift at the start of a minibatch.  With `part` the block writes its sums to
+// part[block][0 = scale | 1 = shift][C] and the weight-gradient reduce kernel that follows adds them up
+// (hundreds of blocks adding into the same few dozen addresses with fp32 atomics serialise: that tail
+// cost more than the streaming part of the kernel); without it, fp32 atomics.  Thread t of a block always
+// sees channel (t * 8 .. t * 8 + 7) mod C because a block's span is a multiple of C elements.
 template <typename T>
 __global__ __launch_bounds__(256) void pm_conv_affine_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ y,
                                                                  const T* __restrict__ z, PmWLoc<T> scale_bkwd,
                                                                  T* __restrict__ da, T* __restrict__ dz,
                                                                  float* __restrict__ dscale, float* __restrict__ dshift,
-                                                                 int64_t total, int C) {
+                                                                 float* __restrict__ part, int64_t total, int C) {
   __shared__ float red[4][2][256];
   const T* sbk = scale_bkwd.get();
   const int c0 = (threadIdx.x * 8) % C;            // C is a power of two, 8 <= C <= 256
@@ -255,8 +258,15 @@ __global__ __launch_bounds__(256) void pm_conv_affine_bwd_kernel(const T* __rest
   }
   __syncthreads();
   for (int j = threadIdx.x; j < C; j += 256) {
-    atomicAdd(dscale + j, red[0][0][j] + red[1][0][j] + red[2][0][j] + red[3][0][j]);
-    atomicAdd(dshift + j, red[0][1][j] + red[1][1][j] + red[2][1][j] + red[3][1][j]);
+    const float vs = red[0][0][j] + red[1][0][j] + red[2][0][j] + red[3][0][j];
+    const float vt = red[0][1][j] + red[1][1][j] + red[2][1][j] + red[3][1][j];
+    if (part) {
+      part[((int64_t)blockIdx.x * 2 + 0) * C + j] = vs;
+      part[((int64_t)blockIdx.x * 2 + 1) * C + j] = vt;
+    } else {
+      atomicAdd(dscale + j, vs);
+      atomicAdd(dshift + j, vt);
+    }
   }
 }
 
@@ -574,21 +584,47 @@ __global__ __launch_bounds__(256) void pm_conv_wgrad_mfma_kernel(PmConvGeom g, c
   }
 }
 
-// dW[e] (+)= sum over the blocks' partials.  Block = 64 elements x 4 slices of the partial range.
-__global__ __launch_bounds__(256) void pm_conv_wgrad_reduce_kernel(const float* __restrict__ part, int nparts, int64_t nW,
-                                                                   float* __restrict__ dW, int accumulate) {
-  const int el = threadIdx.x & 63, sl = threadIdx.x >> 6;
-  const int64_t e = (int64_t)blockIdx.x * 64 + el;
+// out[e] (+)= sum over nparts partial vectors of n elements each (part[p][e]).  Block = 16 elements x 16
+// slices of the partial range: many short chains of independent loads instead of a few long ones (the
+// arrays are small; what matters is the latency of the longest chain).  A launch carries up to two
+// jobs: the blocks after the first job's work on the second one (used for the per-channel sums of the
+// affine backward, whose out is always added to).
+struct PmReduceJob {
+  const float* part;
+  int nparts;
+  int64_t n;
+  float* out;
+  int accumulate;
+};
+__global__ __launch_bounds__(256) void pm_conv_wgrad_reduce_kernel(PmReduceJob j0, PmReduceJob j1, int blocks0) {
+  const bool second = (int)blockIdx.x >= blocks0;
+  const PmReduceJob jb = second ? j1 : j0;
+  const int el = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int64_t e = (int64_t)(second ? blockIdx.x - blocks0 : blockIdx.x) * 16 + el;
   float acc = 0.f;
-  if (e < nW)
-    for (int p = sl; p < nparts; p += 4) acc += part[(int64_t)p * nW + e];
-  __shared__ float s[4][64];
+  if (e < jb.n) {
+    int p = sl;
+#pragma unroll 1
+    for (; p + 48 < jb.nparts; p += 64) {
+      const float a0 = jb.part[(int64_t)p * jb.n + e], a1 = jb.part[(int64_t)(p + 16) * jb.n + e];
+      const float a2 = jb.part[(int64_t)(p + 32) * jb.n + e], a3 = jb.part[(int64_t)(p + 48) * jb.n + e];
+      acc += (a0 + a1) + (a2 + a3);
+    }
+    for (; p < jb.nparts; p += 16) acc += jb.part[(int64_t)p * jb.n + e];
+  }
+  __shared__ float s[16][16];
   s[sl][el] = acc;
   __syncthreads();
-  if (sl == 0 && e < nW) {
-    const float v = s[0][el] + s[1][el] + s[2][el] + s[3][el];
-    dW[e] = accumulate ? dW[e] + v : v;
+  if (sl == 0 && e < jb.n) {
+    float v = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) v += s[q][el];
+    jb.out[e] = jb.accumulate ? jb.out[e] + v : v;
   }
+}
+inline void pm_conv_reduce_launch(hipStream_t st, const PmReduceJob& j0, const PmReduceJob& j1) {
+  const int b0 = (int)((j0.n + 15) / 16), b1 = j1.part ? (int)((j1.n + 15) / 16) : 0;
+  hipLaunchKernelGGL(pm_conv_wgrad_reduce_kernel, dim3((unsigned)(b0 + b1)), dim3(256), 0, st, j0, j1, b0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -656,9 +692,15 @@ inline size_t pm_conv_wgrad_scratch_elems(const PmConvGeom& g) {
 
 // dW (fp32 [Cout][9][Cin]) = (accumulate ? dW : 0) + correlation of dz with x.  `scratch` must hold
 // pm_conv_wgrad_scratch_elems floats (unused by the plain path).
+// true if the weight gradient of this geometry ends in a reduce launch (which can carry a second job)
+template <typename T>
+inline bool pm_conv_wgrad_has_reduce(const PmConvGeom& g) {
+  return pm_conv_thin_fits(g) || pm_conv_wgrad_scratch_elems<T>(g) > 0;
+}
+
 template <typename T>
 inline void pm_conv_wgrad_launch(hipStream_t st, const PmConvGeom& g, const T* dz, const T* x, float* dW, int accumulate,
-                                 float* scratch) {
+                                 float* scratch, PmReduceJob extra = PmReduceJob{nullptr, 0, 0, nullptr, 1}) {
   if constexpr (sizeof(T) == 2) {
     if (!pm_conv_thin_fits(g) && pm_conv_wgrad_scratch_elems<T>(g) > 0) {
       int blocks, cpw;
@@ -672,28 +714,33 @@ inline void pm_conv_wgrad_launch(hipStream_t st, const PmConvGeom& g, const T* d
       else PM_CW(2, 2);
 #undef PM_CW
       const int64_t nW = (int64_t)g.Cout * 9 * g.Cin;
-      hipLaunchKernelGGL(pm_conv_wgrad_reduce_kernel, dim3((unsigned)((nW + 63) / 64)), dim3(256), 0, st, scratch, blocks, nW,
-                         dW, accumulate);
+      pm_conv_reduce_launch(st, PmReduceJob{scratch, blocks, nW, dW, accumulate}, extra);
       return;
     }
   }
   if (pm_conv_thin_fits(g)) {
     const int64_t nW = (int64_t)g.Cout * 9 * g.Cin;
     hipLaunchKernelGGL((pm_conv_wgrad_thin_kernel<T, 16, 3>), dim3(PM_CONV_THIN_GROUPS, 9), dim3(256), 0, st, g, dz, x, scratch);
-    hipLaunchKernelGGL(pm_conv_wgrad_reduce_kernel, dim3((unsigned)((nW + 63) / 64)), dim3(256), 0, st, scratch,
-                       PM_CONV_THIN_GROUPS, nW, dW, accumulate);
+    pm_conv_reduce_launch(st, PmReduceJob{scratch, PM_CONV_THIN_GROUPS, nW, dW, accumulate}, extra);
     return;
   }
   hipLaunchKernelGGL((pm_conv_wgrad_plain_kernel<T>), dim3((unsigned)(g.Cout * 9 * g.Cin)), dim3(256), 0, st, g, dz, x, dW,
                      accumulate);
 }
 
+constexpr int PM_CONV_AFFINE_MAX_BLOCKS = 1024;
+// part: NULL (fp32 atomics into dscale / dshift), or room for PM_CONV_AFFINE_MAX_BLOCKS * 2 * C floats; then
+// *job receives the reduction the caller must hand to the next reduce launch (out = dscale, n = 2 C:
+// dshift follows dscale in memory).
 template <typename T>
 inline bool pm_conv_affine_bwd_launch(hipStream_t st, const T* dy, const T* y, const T* z, PmWLoc<T> scale_bkwd, T* da, T* dz,
-                                      float* dscale, float* dshift, int64_t total, int C) {
+                                      float* dscale, float* dshift, int64_t total, int C, float* part = nullptr,
+                                      PmReduceJob* job = nullptr) {
   if (C < 8 || C > 256 || (C & (C - 1))) return false;        // a power of two in 8 .. 256
-  const unsigned blocks = (unsigned)std::max<int64_t>(1, std::min<int64_t>(512, (total + 2047) / 2048));
+  if (part && dshift != dscale + C) return false;
+  const unsigned blocks = (unsigned)std::max<int64_t>(1, std::min<int64_t>(part ? PM_CONV_AFFINE_MAX_BLOCKS : 512, (total + 2047) / 2048));
   hipLaunchKernelGGL((pm_conv_affine_bwd_kernel<T>), dim3(blocks), dim3(256), 0, st, dy, y, z, scale_bkwd, da, dz, dscale,
-                     dshift, total, C);
+                     dshift, part, total, C);
+  if (part && job) *job = PmReduceJob{part, (int)blocks, (int64_t)2 * C, dscale, 1};
   return true;
 }
