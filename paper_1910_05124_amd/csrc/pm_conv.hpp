@@ -423,9 +423,13 @@ __global__ __launch_bounds__(256) void pm_conv_dgrad_mfma_kernel(PmConvGeom g, c
 // pm_conv_wgrad_reduce_kernel sums the blocks' partials.  (Measured alternatives: fp32 atomics of
 // every wave straight into dW, or LDS float atomics for the block sum, each cost several times the
 // rest of the kernel.)
-template <int NTO, int NTI, int NCH>   // channel tiles of 32 of Cout and Cin; chunks of 32 pixels per wave
+// TPB taps per block (9: all of them; 3: blockIdx.y picks the tap row dy = blockIdx.y - 1, for small
+// maps whose pixel chunks alone would leave most of the chip idle; the rows write disjoint entries of
+// the block's partial, so nothing else changes).
+template <int NTO, int NTI, int NCH, int TPB = 9>   // channel tiles of 32 of Cout and Cin; chunks of 32 pixels per wave
 __global__ __launch_bounds__(256) void pm_conv_wgrad_mfma_kernel(PmConvGeom g, const bf16_t* __restrict__ dz,
                                                                  const bf16_t* __restrict__ x, float* __restrict__ part) {
+  const int tap0 = TPB == 9 ? 0 : (int)blockIdx.y * 3;
   constexpr int SA = NTO * 32 + 8, SB = NTI * 32 + 8;     // LDS row strides (elements)
   constexpr int PA = NTO * 2, PB = NTI * 2;               // 16-byte pieces per lane of a 32-pixel tile
   constexpr int RW = NTI * 32;                            // row width of the block's reduction tile
@@ -476,8 +480,8 @@ __global__ __launch_bounds__(256) void pm_conv_wgrad_mfma_kernel(PmConvGeom g, c
 #pragma unroll
   for (int j = 0; j < PB; ++j) cbv[j] = ((lane + 64 * j) % pb) * 8;
 
-  auto load_regs = [&](int tap, int ch, uint4* ra, uint4* rb) __attribute__((always_inline)) {
-    const int dy = tap / 3 - 1, dx = tap % 3 - 1;
+  auto load_regs = [&](int tl, int ch, uint4* ra, uint4* rb) __attribute__((always_inline)) {
+    const int dy = (tap0 + tl) / 3 - 1, dx = tl % 3 - 1;       // tap0 is a multiple of 3
 #pragma unroll
     for (int j = 0; j < PA; ++j) {
       const int o = a_off[ch][j];
@@ -492,8 +496,8 @@ __global__ __launch_bounds__(256) void pm_conv_wgrad_mfma_kernel(PmConvGeom g, c
     }
   };
   // zero what must not contribute (after the data has arrived, right before it is parked)
-  auto store_regs = [&](int tap, int ch, const uint4* ra, const uint4* rb) __attribute__((always_inline)) {
-    const int dy = tap / 3 - 1, dx = tap % 3 - 1;
+  auto store_regs = [&](int tl, int ch, const uint4* ra, const uint4* rb) __attribute__((always_inline)) {
+    const int dy = (tap0 + tl) / 3 - 1, dx = tl % 3 - 1;
     // (component-wise selects: a select between whole uint4 objects would go through memory)
 #pragma unroll
     for (int j = 0; j < PA; ++j) {
@@ -544,7 +548,7 @@ __global__ __launch_bounds__(256) void pm_conv_wgrad_mfma_kernel(PmConvGeom g, c
   uint4 ra[2][PA], rb[2][PB];
   load_regs(0, 0, ra[0], rb[0]);
 #pragma unroll
-  for (int tap = 0; tap < 9; ++tap) {       // fully unrolled: every register-set and table index is static
+  for (int tap = 0; tap < TPB; ++tap) {     // fully unrolled: every register-set and table index is static
 #pragma unroll
     for (int a = 0; a < NTO; ++a)
 #pragma unroll
@@ -558,7 +562,7 @@ __global__ __launch_bounds__(256) void pm_conv_wgrad_mfma_kernel(PmConvGeom g, c
       const int cur = NCH == 1 ? (tap & 1) : (ch & 1);
       store_regs(tap, ch, ra[cur], rb[cur]);
       if (ch + 1 < NCH) load_regs(tap, ch + 1, ra[cur ^ 1], rb[cur ^ 1]);
-      else if (tap + 1 < 9) load_regs(tap + 1, 0, ra[cur ^ 1], rb[cur ^ 1]);
+      else if (tap + 1 < TPB) load_regs(tap + 1, 0, ra[cur ^ 1], rb[cur ^ 1]);
       __builtin_amdgcn_wave_barrier();
       mma();
       __builtin_amdgcn_wave_barrier();
@@ -578,7 +582,7 @@ __global__ __launch_bounds__(256) void pm_conv_wgrad_mfma_kernel(PmConvGeom g, c
     __syncthreads();
     for (int e = threadIdx.x; e < g.Cout * g.Cin; e += 256) {
       const int co = e / g.Cin, ci = e - co * g.Cin, o = co * RW + ci;
-      my_part[((int64_t)co * 9 + tap) * g.Cin + ci] = red[0][o] + red[1][o] + red[2][o] + red[3][o];
+      my_part[((int64_t)co * 9 + tap0 + tap) * g.Cin + ci] = red[0][o] + red[1][o] + red[2][o] + red[3][o];
     }
     __syncthreads();
   }
@@ -705,8 +709,10 @@ inline void pm_conv_wgrad_launch(hipStream_t st, const PmConvGeom& g, const T* d
     if (!pm_conv_thin_fits(g) && pm_conv_wgrad_scratch_elems<T>(g) > 0) {
       int blocks, cpw;
       pm_conv_wgrad_plan(g, &blocks, &cpw);
-      const dim3 grid(blocks), blk(256);
+      const bool split = blocks < 128;                 // too few pixel chunks to fill the chip: one tap row per block
+      const dim3 grid(blocks, split ? 3 : 1), blk(256);
 #define PM_CW(A, B) do { if (cpw == 4) hipLaunchKernelGGL((pm_conv_wgrad_mfma_kernel<A, B, 4>), grid, blk, 0, st, g, dz, x, scratch); \
+                         else if (split) hipLaunchKernelGGL((pm_conv_wgrad_mfma_kernel<A, B, 1, 3>), grid, blk, 0, st, g, dz, x, scratch); \
                          else hipLaunchKernelGGL((pm_conv_wgrad_mfma_kernel<A, B, 1>), grid, blk, 0, st, g, dz, x, scratch); } while (0)
       if (g.Cout <= 32 && g.Cin <= 32) PM_CW(1, 1);
       else if (g.Cout <= 32) PM_CW(1, 2);
