@@ -295,7 +295,8 @@ __global__ __launch_bounds__(256) void pm_pool_bwd_kernel(const T* __restrict__ 
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ pm_bf16x8 pm_cv_ld8(const bf16_t* p) { return *reinterpret_cast<const pm_bf16x8*>(p); }
 
-// forward.  One wave = 32 output pixels x all output channels; 4 waves per block, no LDS.
+// forward.  One wave = 32 output pixels x all output channels; blockDim.x / 64 waves per block (4 on large
+// maps, 1 on small ones so that the few pixel groups still spread over the chip), no LDS.
 template <int NCT>   // output-channel tiles of 32 (Cout <= 32 NCT)
 __global__ __launch_bounds__(256) void pm_conv_fwd_mfma_kernel(PmConvGeom g, const bf16_t* __restrict__ x,
                                                                PmWLoc<bf16_t> wloc, PmShortcut<bf16_t> sc,
@@ -305,7 +306,7 @@ __global__ __launch_bounds__(256) void pm_conv_fwd_mfma_kernel(PmConvGeom g, con
   const bf16_t* shift = scale + g.Cout;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, pl = lane & 31, kg = lane >> 5;
   const int64_t npix = (int64_t)g.B * g.Ho * g.Wo;
-  const int64_t p = ((int64_t)blockIdx.x * 4 + wave) * 32 + pl;
+  const int64_t p = ((int64_t)blockIdx.x * (blockDim.x >> 6) + wave) * 32 + pl;
   const bool pv = p < npix;
   const int ox = (int)(p % g.Wo), oy = (int)((p / g.Wo) % g.Ho), b = (int)(p / ((int64_t)g.Wo * g.Ho));
   pm_f32x16 acc[NCT];
@@ -359,18 +360,18 @@ __global__ __launch_bounds__(256) void pm_conv_dgrad_mfma_kernel(PmConvGeom g, c
   {
     const bf16_t* Wt = wloc.get();
     const int chunks = g.Cout * (K9 / 8);
-    for (int c = threadIdx.x; c < chunks; c += 256) {
+    for (int c = threadIdx.x; c < chunks; c += blockDim.x) {
       const int r = c / (K9 / 8), col = (c % (K9 / 8)) * 8;
       *reinterpret_cast<uint4*>(sW + r * WS + col) = *reinterpret_cast<const uint4*>(Wt + (int64_t)r * K9 + col);
     }
     // fragment reads of a channel tile wider than Cin run past a row's end into the next row (those
     // MFMA rows are discarded); the 16 tail rows keep such reads of the last row inside the array
-    for (int c = threadIdx.x; c < 16 * WS / 8; c += 256) *reinterpret_cast<uint4*>(sW + g.Cout * WS + c * 8) = make_uint4(0, 0, 0, 0);
+    for (int c = threadIdx.x; c < 16 * WS / 8; c += blockDim.x) *reinterpret_cast<uint4*>(sW + g.Cout * WS + c * 8) = make_uint4(0, 0, 0, 0);
   }
   __syncthreads();
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, pl = lane & 31, kg = lane >> 5;
   const int64_t npix = (int64_t)g.B * g.H * g.W;
-  const int64_t p = ((int64_t)blockIdx.x * 4 + wave) * 32 + pl;
+  const int64_t p = ((int64_t)blockIdx.x * (blockDim.x >> 6) + wave) * 32 + pl;
   const bool pv = p < npix;
   const int ix = (int)(p % g.W), iy = (int)((p / g.W) % g.H), b = (int)(p / ((int64_t)g.W * g.H));
   pm_f32x16 acc[NCT];
@@ -641,7 +642,8 @@ inline void pm_conv_fwd_launch(hipStream_t st, const PmConvGeom& g, const T* x, 
   const int64_t npix = (int64_t)g.B * g.Ho * g.Wo;
   if constexpr (sizeof(T) == 2) {
     if (pm_conv_mfma_fits(g.Cin, g.Cout)) {
-      const dim3 grid((unsigned)((npix + 127) / 128)), blk(256);
+      const int wpb = npix >= 256 * 128 ? 4 : 1;          // waves (of 32 pixels) per block
+      const dim3 grid((unsigned)((npix + 32 * wpb - 1) / (32 * wpb))), blk(64 * wpb);
       if (g.Cout <= 32) hipLaunchKernelGGL((pm_conv_fwd_mfma_kernel<1>), grid, blk, 0, st, g, x, w, sc, z, y);
       else hipLaunchKernelGGL((pm_conv_fwd_mfma_kernel<2>), grid, blk, 0, st, g, x, w, sc, z, y);
       return;
@@ -657,6 +659,7 @@ inline void pm_conv_dgrad_launch(hipStream_t st, const PmConvGeom& g, const T* d
   const int64_t npix = (int64_t)g.B * g.H * g.W;
   if constexpr (sizeof(T) == 2) {
     if (pm_conv_mfma_fits(g.Cin, g.Cout)) {
+      // (fewer waves per block on small maps were measured slower here: every block first loads the kernel tensor)
       const dim3 grid((unsigned)((npix + 127) / 128)), blk(256);
 #define PM_CD(A, B) hipLaunchKernelGGL((pm_conv_dgrad_mfma_kernel<A, B>), grid, blk, 0, st, g, dz, w, sb, dx)
       if (g.Cout <= 32 && g.Cin <= 32) PM_CD(1, 1);
