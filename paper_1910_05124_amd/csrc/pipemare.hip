@@ -709,6 +709,35 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
     PmEpiBwdData<T> e{zprev, out, n_in, act};
     launch_gemm<T>(c, Tk, n_in, n_out, dz, n_out, 1, Wb(u, 0), 1, n_in, e);
   };
+  // query, key and value projections of units u+1 .. u+3 (same input): one launch when the shapes suit
+  auto qkv_fwd = [&](int u, const T* n1, T* q, T* k, T* v) {
+    if constexpr (sizeof(T) == 2) {
+      T* outs[3] = {q, k, v};
+      PmGemmProb<PmEpiFwd<T>> pr[3];
+      for (int p = 0; p < 3; ++p) {
+        PmEpiFwd<T> epi;
+        epi.bias = Wf(u + 1 + p, U(u + 1 + p).boff);
+        epi.z = nullptr; epi.a = outs[p]; epi.z32 = nullptr; epi.ld = d; epi.act = PM_ACT_NONE; epi.b_ = nullptr;
+        pr[p] = PmGemmProb<PmEpiFwd<T>>{Tk, d, d, n1, d, Wf(u + 1 + p, 0), d, epi};
+      }
+      if (pm_gemm_multi3_try(st, pr)) return;
+    }
+    lin_fwd(u + 1, n1, d, d, nullptr, q, PM_ACT_NONE);
+    lin_fwd(u + 2, n1, d, d, nullptr, k, PM_ACT_NONE);
+    lin_fwd(u + 3, n1, d, d, nullptr, v, PM_ACT_NONE);
+  };
+  // out = dzq Wq + dzk Wk + dzv Wv (backward weights): one product over the concatenated contraction
+  auto qkv_dgrad = [&](int u, const T* dzq, const T* dzk, const T* dzv, float* out) {
+    if constexpr (sizeof(T) == 2) {
+      const T* const A[3] = {dzq, dzk, dzv};
+      const PmWLoc<T> Bw[3] = {Wb(u + 1, 0), Wb(u + 2, 0), Wb(u + 3, 0)};
+      PmEpiF32 e{out, d, 0};
+      if (pm_gemm_kseg3_try(st, Tk, d, d, A, d, Bw, d, e)) return;
+    }
+    dgrad_f32(u + 1, dzq, d, d, d, out, 0);
+    dgrad_f32(u + 2, dzk, d, d, d, out, 1);
+    dgrad_f32(u + 3, dzv, d, d, d, out, 1);
+  };
   auto ln_fwd = [&](int u, const float* x, T* out, float* mu, float* rs) {
     pm_ln_fwd_launch<T>(st, x, Wf(u, 0), (int)U(u).boff, out, mu, rs, Tk, d);
   };
@@ -735,9 +764,7 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
     float* x = F(b.x);
     float* y = F(l + 1 < nl ? lay.tl[l + 1].x : lay.t_xf);
     ln_fwd(u, x, TT(b.n1), F(b.mu1), F(b.rs1));
-    lin_fwd(u + 1, TT(b.n1), d, d, nullptr, TT(b.q), PM_ACT_NONE);
-    lin_fwd(u + 2, TT(b.n1), d, d, nullptr, TT(b.k), PM_ACT_NONE);
-    lin_fwd(u + 3, TT(b.n1), d, d, nullptr, TT(b.v), PM_ACT_NONE);
+    qkv_fwd(u, TT(b.n1), TT(b.q), TT(b.k), TT(b.v));
     if (!pm_attn_fwd_launch<T>(st, B, S, H, dh, TT(b.q), TT(b.k), TT(b.v), TT(b.o), F(b.lse)))
       return fail(PM_EINVAL, "attention shape not supported");
     lin_fwd_res(u + 4, TT(b.o), d, d, x, F(b.h));
@@ -794,9 +821,7 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
     wg(u + 1, TT(b.dzq), d, TT(b.n1), d, d);
     wg(u + 2, TT(b.dzk), d, TT(b.n1), d, d);
     wg(u + 3, TT(b.dzv), d, TT(b.n1), d, d);
-    dgrad_f32(u + 1, TT(b.dzq), d, d, d, dn, 0);
-    dgrad_f32(u + 2, TT(b.dzk), d, d, d, dn, 1);
-    dgrad_f32(u + 3, TT(b.dzv), d, d, d, dn, 1);
+    qkv_dgrad(u, TT(b.dzq), TT(b.dzk), TT(b.dzv), dn);
     ln_bwd(u, dn, F(b.x), F(b.mu1), F(b.rs1), dx, dx, l ? TT(lay.tl[l - 1].dz2) : nullptr);   // dx is now d loss / d x
   }
   if constexpr (sizeof(T) == 2) {

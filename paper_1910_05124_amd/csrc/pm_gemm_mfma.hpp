@@ -421,9 +421,23 @@ struct PmBigLds {
 // the register set that slab kt came from, and slab kt + 1 (loaded one iteration earlier) moves from
 // the other register set into the other LDS stage, a part behind each k-step.  A load therefore has
 // more than a slab of MFMA time to arrive before it is waited for; one barrier per slab.
-template <class Cfg, bool AKC, bool BKC, bool CHECK, class Epi>
+//
+// Seg: PmNoSeg, or PmKSeg3 = the contraction runs over three operand pairs of Kseg indices each
+// (out = A0 B0 + A1 B1 + A2 B2 as ONE product with K = 3 Kseg: the slab loader switches base pointers
+// at the segment boundaries, which fall on slab boundaries since Kseg is a multiple of 64).
+struct PmNoSeg {
+  static constexpr bool on = false;
+};
+struct PmKSeg3 {                     // pair 0 is the problem's own A and B
+  static constexpr bool on = true;
+  const bf16_t* A1;
+  const bf16_t* A2;
+  PmWLoc<bf16_t> B1, B2;
+  int Kseg;
+};
+template <class Cfg, bool AKC, bool BKC, bool CHECK, class Epi, class Seg = PmNoSeg>
 __device__ __forceinline__ void pm_gemm_big_body(const PmGemmProb<Epi>& pr, int id, int tiles_i, int tiles_j, bf16_t* smem,
-                                                 bool xcd_remap = true) {
+                                                 bool xcd_remap = true, const Seg& sg = Seg()) {
   constexpr int BI = Cfg::BI, BJ = Cfg::BJ, WI = Cfg::WI, WJ = Cfg::WJ, NT = Cfg::NT, BK = 64;
   constexpr int TI = BI / WI / 32, TJ = BJ / WJ / 32;
   using SA = PmBigTile<BI, AKC>;
@@ -467,28 +481,56 @@ __device__ __forceinline__ void pm_gemm_big_body(const PmGemmProb<Epi>& pr, int 
   LA la0, la1;
   LB lb0, lb1;
   const int nk = (K + BK - 1) / BK;
-  la0.template load<CHECK>(A, lda, i0, 0, I, K);
-  lb0.template load<CHECK>(B, ldb, j0, 0, J, K);
+  // segment p > 0 is addressed with the running contraction index through a base pointer moved back by
+  // p * Kseg contraction steps, so the loader's address arithmetic is the same as for a single pair
+  const bf16_t* As1 = A;
+  const bf16_t* As2 = A;
+  const bf16_t* Bs1 = B;
+  const bf16_t* Bs2 = B;
+  int Kseg = K;
+  if constexpr (Seg::on) {
+    Kseg = sg.Kseg;
+    const int64_t ka = AKC ? 1 : lda, kb = BKC ? 1 : ldb;
+    As1 = sg.A1 - (int64_t)Kseg * ka;
+    As2 = sg.A2 - 2 * (int64_t)Kseg * ka;
+    Bs1 = sg.B1.get() - (int64_t)Kseg * kb;
+    Bs2 = sg.B2.get() - 2 * (int64_t)Kseg * kb;
+  }
+  // global loads of slab kt into a register set
+  // global loads of slab kt into a register set.  (The selects work on copies of the pointers: a
+  // conditional between the captured variables themselves is a conditional between their addresses,
+  // which keeps every captured variable in memory.)
+  auto load_slab = [&](LA& sa, LB& sb, int kt_) __attribute__((always_inline)) {
+    const int k_ = kt_ * BK;
+    const bf16_t* Xa_ = A;
+    const bf16_t* Xb_ = B;
+    if constexpr (Seg::on) {
+      const bf16_t *a1_ = As1, *a2_ = As2, *b1_ = Bs1, *b2_ = Bs2;
+      const int ks_ = Kseg;
+      if (k_ >= ks_) Xa_ = a1_, Xb_ = b1_;
+      if (k_ >= 2 * ks_) Xa_ = a2_, Xb_ = b2_;
+    }
+    sa.template load<CHECK>(Xa_, lda, i0, k_, I, K);
+    sb.template load<CHECK>(Xb_, ldb, j0, k_, J, K);
+  };
+  load_slab(la0, lb0, 0);
   la0.store(smem);
   lb0.store(smem + SA::elems);
-  if (nk > 1) {
-    la1.template load<CHECK>(A, lda, i0, BK, I, K);
-    lb1.template load<CHECK>(B, ldb, j0, BK, J, K);
-  }
+  if (nk > 1) load_slab(la1, lb1, 1);
   __syncthreads();
 
   // one slab: fa / fb = register set that is free (refilled with slab kt + 2), na / nb = register set
   // holding slab kt + 1 (moved to the other LDS stage).  steady (compile-time): slabs kt + 1 and
   // kt + 2 exist, so the loads and stores are unconditional and the compiler's wait counts before
   // the LDS stores cover exactly the older register set.
-  auto slab = [&](auto steady, int kt, LA& fa_set, LB& fb_set, const LA& na_set, const LB& nb_set) {
+  auto slab = [&](auto steady, int kt, LA& fa_set, LB& fb_set, const LA& na_set, const LB& nb_set)
+                  __attribute__((always_inline)) {
     constexpr bool STEADY = decltype(steady)::value;
     const int cur = kt & 1;
     const bf16_t* cA = smem + cur * STAGE;
     const bf16_t* cB = cA + SA::elems;
     if (STEADY || kt + 2 < nk) {
-      fa_set.template load<CHECK>(A, lda, i0, (kt + 2) * BK, I, K);
-      fb_set.template load<CHECK>(B, ldb, j0, (kt + 2) * BK, J, K);
+      load_slab(fa_set, fb_set, kt + 2);
       // keep the loads here, ahead of the slab's MFMAs (the instruction scheduler otherwise sinks
       // them to the end of the slab to shorten register live ranges, which costs the latency cover)
       __builtin_amdgcn_sched_barrier(0);
@@ -596,6 +638,24 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WP
   pm_gemm_big_body<Cfg, AKC, BKC, CHECK, Epi>(pr, blockIdx.x, tiles_i, tiles_j, smem);
 }
 
+// Three products of equal shape in one launch (the query / key / value projections share their
+// input): block b works on problem b / (tiles_i * tiles_j).  One launch instead of three keeps the
+// chip filled across the problems' first and last waves of tiles.
+template <class Cfg, bool AKC, bool BKC, bool CHECK, class Epi>
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WPE, Cfg::WPE))) void pm_gemm_big_multi3_kernel(PmGemmProb<Epi> p0, PmGemmProb<Epi> p1, PmGemmProb<Epi> p2, int tiles_i, int tiles_j) {
+  __shared__ __attribute__((aligned(16))) bf16_t smem[PmBigLds<Cfg, AKC, BKC>::elems];
+  const int nt = tiles_i * tiles_j;
+  const int p = blockIdx.x / nt, id = blockIdx.x - p * nt;      // uniform over the block
+  pm_gemm_big_body<Cfg, AKC, BKC, CHECK, Epi>(p == 0 ? p0 : p == 1 ? p1 : p2, id, tiles_i, tiles_j, smem);
+}
+
+// One product whose contraction runs over three operand pairs (PmKSeg3); pr.K = 3 * Kseg, pr.A / pr.B = pair 0.
+template <class Cfg, bool AKC, bool BKC, bool CHECK, class Epi>
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WPE, Cfg::WPE))) void pm_gemm_big_kseg3_kernel(PmGemmProb<Epi> pr, PmKSeg3 sg, int tiles_i, int tiles_j) {
+  __shared__ __attribute__((aligned(16))) bf16_t smem[PmBigLds<Cfg, AKC, BKC>::elems];
+  pm_gemm_big_body<Cfg, AKC, BKC, CHECK, Epi, PmKSeg3>(pr, blockIdx.x, tiles_i, tiles_j, smem, true, sg);
+}
+
 // Many problems in one launch, scheduled per XCD.  Consecutive block ids land on consecutive XCDs
 // (8 of them, each with its own L2), so block b works for XCD b % 8 at position b / 8 of that XCD's
 // own work list: a list of segments (problem, first tile, tile count) built by the host so that the
@@ -678,5 +738,68 @@ inline bool pm_big_try(hipStream_t st, const PmGemmProb<Epi>& pr) {
     if (!(tiles >= 32 && pr.K >= 2048)) return false;
   }
   pm_big_launch<PmBig128, AKC, BKC>(st, pr);
+  return true;
+}
+
+
+// Which pipelined block tile a problem with `tiles128` / `tiles64` block tiles in total gets: 0 none, 128, 64.
+inline int pm_big_choice(long tiles128, long tiles64, int K) {
+  if (K < 256) return 0;
+  if (tiles128 >= 200) return 128;
+  if (tiles64 >= 256) return 64;
+  return 0;
+}
+
+// Three products of equal shape and layout (A row-major over the contraction, B likewise) in one launch.
+// False (nothing launched) if the shapes do not suit the pipelined kernels.
+template <class Epi>
+inline bool pm_gemm_multi3_try(hipStream_t st, const PmGemmProb<Epi> (&pr)[3]) {
+  const int I = pr[0].I, J = pr[0].J, K = pr[0].K;
+  for (int p = 0; p < 3; ++p) {
+    if (pr[p].I != I || pr[p].J != J || pr[p].K != K) return false;
+    if (!pm_mfma_fits(I, J, K, pr[p].A, pr[p].lda, 1, pr[p].B.base, pr[p].B.stride, pr[p].ldb, 1)) return false;
+  }
+  const long t128 = (long)((I + 127) / 128) * ((J + 127) / 128), t64 = (long)((I + 63) / 64) * ((J + 63) / 64);
+  const int pick = pm_big_choice(3 * t128, 3 * t64, K);
+  auto go = [&](auto cfg) {
+    using Cfg = decltype(cfg);
+    const int ti = (I + Cfg::BI - 1) / Cfg::BI, tj = (J + Cfg::BJ - 1) / Cfg::BJ;
+    if (pm_big_aligned<Cfg>(I, J, K))
+      hipLaunchKernelGGL((pm_gemm_big_multi3_kernel<Cfg, true, true, false, Epi>), dim3(3 * ti * tj), dim3(Cfg::NT), 0, st,
+                         pr[0], pr[1], pr[2], ti, tj);
+    else
+      hipLaunchKernelGGL((pm_gemm_big_multi3_kernel<Cfg, true, true, true, Epi>), dim3(3 * ti * tj), dim3(Cfg::NT), 0, st,
+                         pr[0], pr[1], pr[2], ti, tj);
+  };
+  if (pick == 128) go(PmBig128());
+  else if (pick == 64) go(PmBig64());
+  else return false;
+  return true;
+}
+
+// out = sum over p of A_p B_p with A_p (I x Kseg, row-major) and B_p (Kseg x J, row-major) as one product.
+template <class Epi>
+inline bool pm_gemm_kseg3_try(hipStream_t st, int I, int J, int Kseg, const bf16_t* const (&A)[3], int64_t lda,
+                              const PmWLoc<bf16_t> (&B)[3], int64_t ldb, const Epi& epi) {
+  if (Kseg % 64) return false;
+  for (int p = 0; p < 3; ++p)
+    if (!pm_mfma_fits(I, J, Kseg, A[p], lda, 1, B[p].base, B[p].stride, 1, ldb)) return false;
+  const long t128 = (long)((I + 127) / 128) * ((J + 127) / 128), t64 = (long)((I + 63) / 64) * ((J + 63) / 64);
+  const int pick = pm_big_choice(t128, t64, 3 * Kseg);
+  PmGemmProb<Epi> pr{I, J, 3 * Kseg, A[0], lda, B[0], ldb, epi};
+  PmKSeg3 sg{A[1], A[2], B[1], B[2], Kseg};
+  auto go = [&](auto cfg) {
+    using Cfg = decltype(cfg);
+    const int ti = (I + Cfg::BI - 1) / Cfg::BI, tj = (J + Cfg::BJ - 1) / Cfg::BJ;
+    if (pm_big_aligned<Cfg>(I, J, Kseg))
+      hipLaunchKernelGGL((pm_gemm_big_kseg3_kernel<Cfg, true, false, false, Epi>), dim3(ti * tj), dim3(Cfg::NT), 0, st, pr,
+                         sg, ti, tj);
+    else
+      hipLaunchKernelGGL((pm_gemm_big_kseg3_kernel<Cfg, true, false, true, Epi>), dim3(ti * tj), dim3(Cfg::NT), 0, st, pr,
+                         sg, ti, tj);
+  };
+  if (pick == 128) go(PmBig128());
+  else if (pick == 64) go(PmBig64());
+  else return false;
   return true;
 }

@@ -226,3 +226,21 @@ def test_small_bf16_transformer_mfma_path(torch_cuda, opt):
     assert err <= TOL["bf16"], errs
     assert max(m for u, m in enumerate(mvs) if u not in key_bias_entries(w)) <= 0.15, mvs
     g.close()
+
+
+def test_ragged_bf16_transformer_grouped_projections(torch_cuda):
+    """3360 tokens of width 320 (five heads of 64): the query / key / value projections go out as one
+    three-problem launch and their data gradients as one product over the concatenated contraction,
+    both with ragged last tiles (3360 = 52.5 * 64 = 26.25 * 128, 320 = 2.5 * 128)."""
+    w = wl.transformer(1, 320, 5, 640, 512, 96, 35, dtype="bf16", K=4,
+                       sched=dict(kind="warmup_invsqrt", base=2e-5, init=1e-7, warmup=4))
+    kw = dict(opt="sgdm", lr=0.002, beta=0.9, D=0.5, K=4)
+    g, o, losses = run_pair(torch_cuda, w, 6, **kw)
+    for lo, lg in losses:
+        assert lg == pytest.approx(lo, rel=2e-2)
+    err, errs = max_rel_err(g.weights(), o.weights(), skip=key_bias_entries(w))
+    mv, mvs = movement_rel_l2(g.weights(), o.weights(), wl.init_params(w))
+    print("ragged grouped projections", "max-rel", err, "movement rel-L2", mv, np.round(mvs, 3))
+    assert err <= TOL["bf16"], errs
+    assert max(m for u, m in enumerate(mvs) if u not in key_bias_entries(w)) <= 0.15, mvs
+    g.close()
