@@ -49,7 +49,7 @@ __device__ __forceinline__ pm_bf16x8 pm_at_frag_tr(const bf16_t* s, int r32, int
 __device__ __forceinline__ pm_bf16x8 pm_at_pack8(const float* x) {
   union { pm_bf16x8 v; uint32_t w[4]; } u;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) u.w[e] = (uint32_t)f32_to_bf16(x[2 * e]) | ((uint32_t)f32_to_bf16(x[2 * e + 1]) << 16);
+  for (int e = 0; e < 4; ++e) u.w[e] = pm_pack_bf16(x[2 * e], x[2 * e + 1]);
   return u.v;
 }
 __device__ __forceinline__ pm_bf16x8 pm_at_zero8() {
@@ -66,8 +66,8 @@ __device__ __forceinline__ void pm_at_store_t(bf16_t* out_row, const pm_f32x16* 
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
       uint2 w;
-      w.x = (uint32_t)f32_to_bf16(acc[dt][4 * a] * mul) | ((uint32_t)f32_to_bf16(acc[dt][4 * a + 1] * mul) << 16);
-      w.y = (uint32_t)f32_to_bf16(acc[dt][4 * a + 2] * mul) | ((uint32_t)f32_to_bf16(acc[dt][4 * a + 3] * mul) << 16);
+      w.x = pm_pack_bf16(acc[dt][4 * a] * mul, acc[dt][4 * a + 1] * mul);
+      w.y = pm_pack_bf16(acc[dt][4 * a + 2] * mul, acc[dt][4 * a + 3] * mul);
       *reinterpret_cast<uint2*>(out_row + dt * 32 + 8 * a + 4 * g) = w;
     }
 }

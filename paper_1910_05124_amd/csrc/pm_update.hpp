@@ -200,10 +200,10 @@ template <bool NT> struct PmAccSplit {
   }
   static __device__ __forceinline__ void st(bf16_t* p, const float* x) {
     uint2 a, b;
-    a.x = (uint32_t)f32_to_bf16(x[0]) | ((uint32_t)f32_to_bf16(x[1]) << 16);
-    a.y = (uint32_t)f32_to_bf16(x[2]) | ((uint32_t)f32_to_bf16(x[3]) << 16);
-    b.x = (uint32_t)f32_to_bf16(x[4]) | ((uint32_t)f32_to_bf16(x[5]) << 16);
-    b.y = (uint32_t)f32_to_bf16(x[6]) | ((uint32_t)f32_to_bf16(x[7]) << 16);
+    a.x = pm_pack_bf16(x[0], x[1]);
+    a.y = pm_pack_bf16(x[2], x[3]);
+    b.x = pm_pack_bf16(x[4], x[5]);
+    b.y = pm_pack_bf16(x[6], x[7]);
     s2(reinterpret_cast<uint2*>(p), a);
     s2(reinterpret_cast<uint2*>(p + 1024), b);
   }
