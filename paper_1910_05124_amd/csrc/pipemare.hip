@@ -551,8 +551,8 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
   {
     const Unit& u = lay.units[L - 1];
     if (c->o.loss == PM_LOSS_XENT)
-      hipLaunchKernelGGL((pm_xent_kernel<T>), dim3((M + 3) / 4), dim3(256), 0, st, c->at<float>(u.z32_off),
-                         (const int32_t*)y_dev, c->at<T>(u.dz_off), M, u.d.n_out, u.ld_out, c->hdr());
+      pm_xent_launch<T>(st, c->at<float>(u.z32_off), (const int32_t*)y_dev, c->at<T>(u.dz_off), M, u.d.n_out, u.ld_out,
+                        c->hdr());
     else {
       const int64_t tot = (int64_t)M * u.ld_out;
       hipLaunchKernelGGL((pm_mse_kernel<T>), dim3((unsigned)std::min<int64_t>(256, (tot + 255) / 256)), dim3(256), 0, st,
@@ -779,8 +779,7 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
     epi.z = nullptr; epi.a = nullptr; epi.z32 = F(lay.t_logits); epi.ld = ldV; epi.act = PM_ACT_NONE; epi.b_ = nullptr;
     launch_gemm<T>(c, Tk, V, d, TT(lay.t_nf), d, 1, Wf(L - 1, 0), d, 1, epi);
   }
-  hipLaunchKernelGGL((pm_xent_kernel<T>), dim3((Tk + 3) / 4), dim3(256), 0, st, F(lay.t_logits), (const int32_t*)y_dev,
-                     TT(lay.t_dlogits), Tk, V, ldV, c->hdr());
+  pm_xent_launch<T>(st, F(lay.t_logits), (const int32_t*)y_dev, TT(lay.t_dlogits), Tk, V, ldV, c->hdr());
   prof_mark(c, 1);
   {
     pm_status qs = quiesce(c);
@@ -899,8 +898,7 @@ pm_status launch_resnet(pm_ctx* c, const void* x_dev, const void* y_dev, int acc
     epi.z = nullptr; epi.a = nullptr; epi.z32 = c->at<float>(lay.r_logits); epi.ld = ldc; epi.act = PM_ACT_NONE; epi.b_ = nullptr;
     launch_gemm<T>(c, B, ncls, C, TT(lay.r_pool), C, 1, Wf(fc, 0), C, 1, epi);
   }
-  hipLaunchKernelGGL((pm_xent_kernel<T>), dim3((B + 3) / 4), dim3(256), 0, st, c->at<float>(lay.r_logits),
-                     (const int32_t*)y_dev, TT(lay.r_dlogits), B, ncls, ldc, c->hdr());
+  pm_xent_launch<T>(st, c->at<float>(lay.r_logits), (const int32_t*)y_dev, TT(lay.r_dlogits), B, ncls, ldc, c->hdr());
   prof_mark(c, 1);
   {
     pm_status qs = quiesce(c);

@@ -103,18 +103,25 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_fwd_kernel(const bf16_t* __r
   float m = -3.0e38f, lsum = 0.f;
 
   const int lrow = threadIdx.x >> 3, lcol = (threadIdx.x & 7) * 8;       // loader: 32 rows x 8 pieces of 16 bytes
-  uint4 rk = *reinterpret_cast<const uint4*>(k + base + (int64_t)lrow * d + lcol);
-  uint4 rv = *reinterpret_cast<const uint4*>(v + base + (int64_t)lrow * d + lcol);
-  *reinterpret_cast<uint4*>(&sK[0][lrow * PM_AT_ST + lcol]) = rk;
-  *reinterpret_cast<uint4*>(&sV[0][lrow * PM_AT_ST + lcol]) = rv;
+  // Two register sets: while tile jt is consumed from LDS, tile jt + 1 (loaded an iteration earlier) waits
+  // in one set for its LDS store at the end of the iteration and tile jt + 2 is being loaded into the other,
+  // so a load has more than a whole iteration to arrive.
+  uint4 rk0, rv0, rk1 = make_uint4(0, 0, 0, 0), rv1 = rk1;
+  auto gload = [&](int t, uint4& rk, uint4& rv) __attribute__((always_inline)) {
+    rk = *reinterpret_cast<const uint4*>(k + base + (int64_t)(t * 32 + lrow) * d + lcol);
+    rv = *reinterpret_cast<const uint4*>(v + base + (int64_t)(t * 32 + lrow) * d + lcol);
+  };
+  auto sstore = [&](int buf, const uint4& rk, const uint4& rv) __attribute__((always_inline)) {
+    *reinterpret_cast<uint4*>(&sK[buf][lrow * PM_AT_ST + lcol]) = rk;
+    *reinterpret_cast<uint4*>(&sV[buf][lrow * PM_AT_ST + lcol]) = rv;
+  };
+  gload(0, rk0, rv0);
+  sstore(0, rk0, rv0);
+  if (1 < n_tiles) gload(1, rk1, rv1);
   __syncthreads();
   const int prow = pm_at_perm(ql);
-  for (int jt = 0; jt < n_tiles; ++jt) {
-    const int cur = jt & 1;
-    if (jt + 1 < n_tiles) {
-      rk = *reinterpret_cast<const uint4*>(k + base + (int64_t)((jt + 1) * 32 + lrow) * d + lcol);
-      rv = *reinterpret_cast<const uint4*>(v + base + (int64_t)((jt + 1) * 32 + lrow) * d + lcol);
-    }
+  const float c2 = scale * 1.44269504f;            // scores in base-2 units: exp(x) = exp2(x log2 e)
+  auto tile = [&](int jt, int cur) __attribute__((always_inline)) {
     if (active && jt <= my_last) {
       pm_f32x16 s;
 #pragma unroll
@@ -124,26 +131,33 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_fwd_kernel(const bf16_t* __r
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pm_at_frag(sK[cur], prow, kk * 16, lane), fq[kk], s, 0, 0, 0);
       float p[16], mx = -3.0e38f;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int kidx = jt * 32 + 16 * (e >> 3) + 8 * g + (e & 7);
-        p[e] = (jt == my_last && kidx > q0 + ql) ? -3.0e38f : s[e] * scale;
-        mx = fmaxf(mx, p[e]);
+      for (int e = 0; e < 16; ++e) p[e] = s[e] * c2;
+      if (jt == my_last) {                        // the diagonal tile (uniform over the wave): causal mask
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int kidx = jt * 32 + 16 * (e >> 3) + 8 * g + (e & 7);
+          if (kidx > q0 + ql) p[e] = -3.0e38f;
+        }
       }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, p[e]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float mn = fmaxf(m, mx);            // finite: key jt * 32 <= query for every tile visited
-      const float corr = __expf(m - mn);
+      const float corr = __builtin_amdgcn_exp2f(m - mn);
       float ps = 0.f;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        p[e] = __expf(p[e] - mn);               // masked entries: exp(-huge) = 0
+        p[e] = __builtin_amdgcn_exp2f(p[e] - mn);              // masked entries: exp2(-huge) = 0
         ps += p[e];
       }
       lsum = lsum * corr + ps;
+      if (__builtin_amdgcn_ballot_w64(mn != m) != 0) {      // some row's maximum moved (rare after the first tiles)
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[dt][e] *= corr;
+      }
       m = mn;
-#pragma unroll
-      for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[dt][e] *= corr;
       const pm_bf16x8 pb0 = pm_at_pack8(p), pb1 = pm_at_pack8(p + 8);
 #pragma unroll
       for (int dt = 0; dt < 2; ++dt) {
@@ -151,16 +165,23 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_fwd_kernel(const bf16_t* __r
         acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pm_at_frag_tr(sV[cur], dt * 32, 16, lane), pb1, acc[dt], 0, 0, 0);
       }
     }
-    if (jt + 1 < n_tiles) {
-      *reinterpret_cast<uint4*>(&sK[cur ^ 1][lrow * PM_AT_ST + lcol]) = rk;
-      *reinterpret_cast<uint4*>(&sV[cur ^ 1][lrow * PM_AT_ST + lcol]) = rv;
-    }
+  };
+  for (int jt = 0; jt < n_tiles; jt += 2) {
+    if (jt + 2 < n_tiles) gload(jt + 2, rk0, rv0);
+    tile(jt, 0);
+    if (jt + 1 < n_tiles) sstore(1, rk1, rv1);
     __syncthreads();
+    if (jt + 1 < n_tiles) {
+      if (jt + 3 < n_tiles) gload(jt + 3, rk1, rv1);
+      tile(jt + 1, 1);
+      if (jt + 2 < n_tiles) sstore(0, rk0, rv0);
+      __syncthreads();
+    }
   }
   if (active) {
     lsum += __shfl_xor(lsum, 32, 64);
     pm_at_store_t(o + base + (int64_t)(q0 + ql) * d, acc, 1.f / lsum, lane);
-    if (g == 0) lse[((int64_t)b * H + h) * S + q0 + ql] = m + __logf(lsum);
+    if (g == 0) lse[((int64_t)b * H + h) * S + q0 + ql] = m * 0.693147181f + __logf(lsum);   // m is in base-2 units
   }
 }
 
@@ -213,18 +234,23 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_dq_kernel(const bf16_t* __re
     for (int e = 0; e < 16; ++e) acc[dt][e] = 0.f;
 
   const int lrow = threadIdx.x >> 3, lcol = (threadIdx.x & 7) * 8;
-  uint4 rk = *reinterpret_cast<const uint4*>(k + base + (int64_t)lrow * d + lcol);
-  uint4 rv = *reinterpret_cast<const uint4*>(v + base + (int64_t)lrow * d + lcol);
-  *reinterpret_cast<uint4*>(&sK[0][lrow * PM_AT_ST + lcol]) = rk;
-  *reinterpret_cast<uint4*>(&sV[0][lrow * PM_AT_ST + lcol]) = rv;
+  // two register sets as in the forward kernel: a tile is loaded two iterations before its use
+  uint4 rk0, rv0, rk1 = make_uint4(0, 0, 0, 0), rv1 = rk1;
+  auto gload = [&](int t, uint4& rk, uint4& rv) __attribute__((always_inline)) {
+    rk = *reinterpret_cast<const uint4*>(k + base + (int64_t)(t * 32 + lrow) * d + lcol);
+    rv = *reinterpret_cast<const uint4*>(v + base + (int64_t)(t * 32 + lrow) * d + lcol);
+  };
+  auto sstore = [&](int buf, const uint4& rk, const uint4& rv) __attribute__((always_inline)) {
+    *reinterpret_cast<uint4*>(&sK[buf][lrow * PM_AT_ST + lcol]) = rk;
+    *reinterpret_cast<uint4*>(&sV[buf][lrow * PM_AT_ST + lcol]) = rv;
+  };
+  gload(0, rk0, rv0);
+  sstore(0, rk0, rv0);
+  if (1 < n_tiles) gload(1, rk1, rv1);
   __syncthreads();
   const int prow = pm_at_perm(ql);
-  for (int jt = 0; jt < n_tiles; ++jt) {
-    const int cur = jt & 1;
-    if (jt + 1 < n_tiles) {
-      rk = *reinterpret_cast<const uint4*>(k + base + (int64_t)((jt + 1) * 32 + lrow) * d + lcol);
-      rv = *reinterpret_cast<const uint4*>(v + base + (int64_t)((jt + 1) * 32 + lrow) * d + lcol);
-    }
+  const float c2 = scale * 1.44269504f, lq2 = lq * 1.44269504f;       // base-2 units: exp(x) = exp2(x log2 e)
+  auto tile = [&](int jt, int cur) __attribute__((always_inline)) {
     if (active && jt <= my_last) {
       pm_f32x16 s, dp;
 #pragma unroll
@@ -239,10 +265,13 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_dq_kernel(const bf16_t* __re
       }
       float ds[16];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int kidx = jt * 32 + 16 * (e >> 3) + 8 * g + (e & 7);
-        const float p = (jt == my_last && kidx > q0 + ql) ? 0.f : __expf(s[e] * scale - lq);
-        ds[e] = p * (dp[e] - Dq) * scale;
+      for (int e = 0; e < 16; ++e) ds[e] = __builtin_amdgcn_exp2f(fmaf(s[e], c2, -lq2)) * ((dp[e] - Dq) * scale);
+      if (jt == my_last) {                        // the diagonal tile (uniform over the wave): causal mask
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int kidx = jt * 32 + 16 * (e >> 3) + 8 * g + (e & 7);
+          if (kidx > q0 + ql) ds[e] = 0.f;
+        }
       }
       const pm_bf16x8 b0 = pm_at_pack8(ds), b1 = pm_at_pack8(ds + 8);
 #pragma unroll
@@ -251,11 +280,18 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_dq_kernel(const bf16_t* __re
         acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pm_at_frag_tr(sK[cur], dt * 32, 16, lane), b1, acc[dt], 0, 0, 0);
       }
     }
-    if (jt + 1 < n_tiles) {
-      *reinterpret_cast<uint4*>(&sK[cur ^ 1][lrow * PM_AT_ST + lcol]) = rk;
-      *reinterpret_cast<uint4*>(&sV[cur ^ 1][lrow * PM_AT_ST + lcol]) = rv;
-    }
+  };
+  for (int jt = 0; jt < n_tiles; jt += 2) {
+    if (jt + 2 < n_tiles) gload(jt + 2, rk0, rv0);
+    tile(jt, 0);
+    if (jt + 1 < n_tiles) sstore(1, rk1, rv1);
     __syncthreads();
+    if (jt + 1 < n_tiles) {
+      if (jt + 3 < n_tiles) gload(jt + 3, rk1, rv1);
+      tile(jt + 1, 1);
+      if (jt + 2 < n_tiles) sstore(0, rk0, rv0);
+      __syncthreads();
+    }
   }
   if (active) pm_at_store_t(dq + base + (int64_t)(q0 + ql) * d, acc, 1.f, lane);
 }
@@ -300,37 +336,45 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_dkv_kernel(const bf16_t* __r
     }
 
   const int lrow = threadIdx.x >> 3, lcol = (threadIdx.x & 7) * 8;
-  uint4 rq, rdo;
-  float rD, rL = 0.f;
-  auto gload = [&](int it) {
+  // two register sets (a query tile is loaded two iterations before its use); D of the tile's rows is
+  // computed when the set moves to LDS
+  struct Regs {
+    uint4 q, dO, o;
+    float L;
+  };
+  Regs r0, r1;
+  r1.q = r1.dO = r1.o = make_uint4(0, 0, 0, 0);
+  r0.L = r1.L = 0.f;
+  auto gload = [&](int it, Regs& r) __attribute__((always_inline)) {
     const int64_t ro = base + (int64_t)(it * 32 + lrow) * d + lcol;
-    rq = *reinterpret_cast<const uint4*>(q + ro);
-    rdo = *reinterpret_cast<const uint4*>(dO + ro);
-    float a[8], c[8];
-    pm_ld8(dO + ro, a);
-    pm_ld8(o + ro, c);
+    r.q = *reinterpret_cast<const uint4*>(q + ro);
+    r.dO = *reinterpret_cast<const uint4*>(dO + ro);
+    r.o = *reinterpret_cast<const uint4*>(o + ro);
+    if (threadIdx.x < 32) r.L = lse[lbase + it * 32 + threadIdx.x] * 1.44269504f;       // base-2 units
+  };
+  auto sstore = [&](int buf, const Regs& r) __attribute__((always_inline)) {
+    *reinterpret_cast<uint4*>(&sQ[buf][lrow * PM_AT_ST + lcol]) = r.q;
+    *reinterpret_cast<uint4*>(&sO[buf][lrow * PM_AT_ST + lcol]) = r.dO;
+    const uint32_t a[4] = {r.dO.x, r.dO.y, r.dO.z, r.dO.w}, c[4] = {r.o.x, r.o.y, r.o.z, r.o.w};
     float part = 0.f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) part += a[e] * c[e];
+    for (int e = 0; e < 4; ++e) {
+      part = fmaf(__uint_as_float(a[e] << 16), __uint_as_float(c[e] << 16), part);
+      part = fmaf(__uint_as_float(a[e] & 0xffff0000u), __uint_as_float(c[e] & 0xffff0000u), part);
+    }
     part += __shfl_xor(part, 1, 64);
     part += __shfl_xor(part, 2, 64);
     part += __shfl_xor(part, 4, 64);
-    rD = part;
-    if (threadIdx.x < 32) rL = lse[lbase + it * 32 + threadIdx.x];
+    if ((threadIdx.x & 7) == 0) sD[buf][lrow] = part;
+    if (threadIdx.x < 32) sL[buf][threadIdx.x] = r.L;
   };
-  auto sstore = [&](int buf) {
-    *reinterpret_cast<uint4*>(&sQ[buf][lrow * PM_AT_ST + lcol]) = rq;
-    *reinterpret_cast<uint4*>(&sO[buf][lrow * PM_AT_ST + lcol]) = rdo;
-    if ((threadIdx.x & 7) == 0) sD[buf][lrow] = rD;
-    if (threadIdx.x < 32) sL[buf][threadIdx.x] = rL;
-  };
-  gload(first);
-  sstore(0);
+  gload(first, r0);
+  sstore(0, r0);
+  if (first + 1 < n_tiles) gload(first + 1, r1);
   __syncthreads();
   const int prow = pm_at_perm(kl);
-  for (int it = first; it < n_tiles; ++it) {
-    const int cur = (it - first) & 1;
-    if (it + 1 < n_tiles) gload(it + 1);
+  const float c2 = scale * 1.44269504f;
+  auto tile = [&](int it, int cur) __attribute__((always_inline)) {
     if (active && it >= my_first) {
       pm_f32x16 s, dp;
 #pragma unroll
@@ -354,11 +398,16 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_dkv_kernel(const bf16_t* __r
         Dv[4 * c4] = d4.x; Dv[4 * c4 + 1] = d4.y; Dv[4 * c4 + 2] = d4.z; Dv[4 * c4 + 3] = d4.w;
       }
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int qidx = it * 32 + 16 * (e >> 3) + 8 * g + (e & 7);
-        p[e] = (it == my_first && qidx < k0 + kl) ? 0.f : __expf(s[e] * scale - lv[e]);
-        ds[e] = p[e] * (dp[e] - Dv[e]) * scale;
+      for (int e = 0; e < 16; ++e) p[e] = __builtin_amdgcn_exp2f(fmaf(s[e], c2, -lv[e]));
+      if (it == my_first) {                       // the diagonal tile (uniform over the wave): causal mask
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int qidx = it * 32 + 16 * (e >> 3) + 8 * g + (e & 7);
+          if (qidx < k0 + kl) p[e] = 0.f;
+        }
       }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) ds[e] = p[e] * ((dp[e] - Dv[e]) * scale);
       const pm_bf16x8 p0 = pm_at_pack8(p), p1 = pm_at_pack8(p + 8), s0 = pm_at_pack8(ds), s1 = pm_at_pack8(ds + 8);
 #pragma unroll
       for (int dt = 0; dt < 2; ++dt) {
@@ -368,8 +417,18 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_dkv_kernel(const bf16_t* __r
         ak[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pm_at_frag_tr(sQ[cur], dt * 32, 16, lane), s1, ak[dt], 0, 0, 0);
       }
     }
-    if (it + 1 < n_tiles) sstore(cur ^ 1);
+  };
+  for (int it = first; it < n_tiles; it += 2) {
+    if (it + 2 < n_tiles) gload(it + 2, r0);
+    tile(it, 0);
+    if (it + 1 < n_tiles) sstore(1, r1);
     __syncthreads();
+    if (it + 1 < n_tiles) {
+      if (it + 3 < n_tiles) gload(it + 3, r1);
+      tile(it + 1, 1);
+      if (it + 2 < n_tiles) sstore(0, r0);
+      __syncthreads();
+    }
   }
   if (active) {
     pm_at_store_t(dk + base + (int64_t)(k0 + kl) * d, ak, 1.f, lane);

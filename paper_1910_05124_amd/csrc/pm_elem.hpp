@@ -61,6 +61,86 @@ __global__ __launch_bounds__(256) void pm_xent_kernel(const float* __restrict__ 
   if (lane == 0 && label_ok) atomicAdd(&hdr->loss, (logf(se) + mall - z[label]) * invM);
 }
 
+// The same for wide rows (thousands of classes): one block of 512 threads per row keeps the whole row
+// in registers (up to NV float4 per thread), so the logits are read from memory once instead of once
+// per pass; maximum, then sum of exponentials (block reductions through LDS), then the gradient.
+template <typename T, int NV>
+__global__ __launch_bounds__(512) void pm_xent_row_kernel(const float* __restrict__ logits, const int32_t* __restrict__ y,
+                                                          T* __restrict__ dz, int M, int C, int ld, PmStepHdr* hdr) {
+  __shared__ float red[2][8];
+  const int row = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const float* z = logits + (int64_t)row * ld;
+  const int ld4 = ld >> 2;
+  float4 v[NV];
+  float mx = -3.0e38f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c4 = i * 512 + tid;
+    v[i] = make_float4(-3.0e38f, -3.0e38f, -3.0e38f, -3.0e38f);
+    if (c4 < ld4) {
+      const float4 t = reinterpret_cast<const float4*>(z)[c4];
+      const int c = 4 * c4;                      // pad columns (c >= C) take no part
+      v[i].x = c < C ? t.x : -3.0e38f;
+      v[i].y = c + 1 < C ? t.y : -3.0e38f;
+      v[i].z = c + 2 < C ? t.z : -3.0e38f;
+      v[i].w = c + 3 < C ? t.w : -3.0e38f;
+    }
+    mx = fmaxf(mx, fmaxf(fmaxf(v[i].x, v[i].y), fmaxf(v[i].z, v[i].w)));
+  }
+  mx = pm_wave_max(mx);
+  if (lane == 0) red[0][wave] = mx;
+  __syncthreads();
+  float mall = red[0][0];
+#pragma unroll
+  for (int w = 1; w < 8; ++w) mall = fmaxf(mall, red[0][w]);
+  float se = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    if (i * 512 < ld4) {                         // uniform over the block
+      v[i].x = __expf(v[i].x - mall);            // masked entries: exp(-huge) = 0
+      v[i].y = __expf(v[i].y - mall);
+      v[i].z = __expf(v[i].z - mall);
+      v[i].w = __expf(v[i].w - mall);
+      se += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    }
+  }
+  se = pm_wave_sum(se);
+  if (lane == 0) red[1][wave] = se;
+  __syncthreads();
+  se = 0.f;
+#pragma unroll
+  for (int w = 0; w < 8; ++w) se += red[1][w];
+  const int label = y[row];
+  const bool label_ok = label >= 0 && label < C;      // an out-of-range label contributes nothing
+  const float inv = 1.f / se, invM = 1.f / (float)M, k = inv * invM;
+  const int lab = label_ok ? label : -1;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c4 = i * 512 + tid;
+    if (c4 < ld4) {
+      const int c = 4 * c4;
+      float4 o;
+      o.x = v[i].x * k - (c == lab ? invM : 0.f);
+      o.y = v[i].y * k - (c + 1 == lab ? invM : 0.f);
+      o.z = v[i].z * k - (c + 2 == lab ? invM : 0.f);
+      o.w = v[i].w * k - (c + 3 == lab ? invM : 0.f);
+      pm_st4(dz + (int64_t)row * ld + c, o);
+    }
+  }
+  if (tid == 0 && label_ok) atomicAdd(&hdr->loss, (logf(se) + mall - z[label]) * invM);
+}
+
+// softmax cross-entropy of M rows: row-resident kernel for wide rows, one wavefront per row otherwise
+template <typename T>
+inline void pm_xent_launch(hipStream_t st, const float* logits, const int32_t* y, T* dz, int M, int C, int ld,
+                           PmStepHdr* hdr) {
+  constexpr int NV = 16;
+  if (C >= 2048 && (ld >> 2) <= NV * 512)
+    hipLaunchKernelGGL((pm_xent_row_kernel<T, NV>), dim3(M), dim3(512), 0, st, logits, y, dz, M, C, ld, hdr);
+  else
+    hipLaunchKernelGGL((pm_xent_kernel<T>), dim3((M + 3) / 4), dim3(256), 0, st, logits, y, dz, M, C, ld, hdr);
+}
+
 // Mean squared error over all M*C outputs: dz = 2 (out - y) / (M C).
 template <typename T>
 __global__ __launch_bounds__(256) void pm_mse_kernel(const float* __restrict__ out, const float* __restrict__ y,

@@ -166,10 +166,12 @@ def movement_rel_l2(gpu_w, oracle_w, w0):
 
 
 @pytest.mark.parametrize("case", ["pipemare_f32", "sgdm_bf16", "adamw_bf16", "t2_off", "pipedream", "gpipe", "sgdm_clip",
-                                  "microbatches", "sync_warmup", "gelu_ragged_vocab"])
+                                  "microbatches", "sync_warmup", "gelu_ragged_vocab", "wide_vocab", "wide_vocab_bf16"])
 def test_tiny_transformer_modes(torch_cuda, case):
     dtype = "bf16" if case.endswith("bf16") else "f32"
     V = 61 if case != "gelu_ragged_vocab" else 45
+    if case.startswith("wide_vocab"):
+        V = 2501                   # rows wide enough for the row-resident loss kernel, ragged last group of 4
     w = wl.transformer(2, 32, 4, 64, V, 10, 3, dtype=dtype, K=6,
                        sched=dict(kind="warmup_invsqrt", base=1e-3, init=1e-5, warmup=5))
     kw = _kw(w)
@@ -196,6 +198,8 @@ def test_tiny_transformer_modes(torch_cuda, case):
         N = 2
     elif case == "sync_warmup":
         kw["sync_warmup"] = 4
+    elif case == "wide_vocab_bf16":
+        kw = dict(opt="sgdm", lr=0.004, beta=0.9, D=0.5, K=6)
     g, o, losses = run_pair(torch_cuda, w, 12, tau=tau, N=N, **kw)
     for lo, lg in losses:
         assert lg == pytest.approx(lo, rel=3e-2 if dtype == "bf16" else 1e-4)
