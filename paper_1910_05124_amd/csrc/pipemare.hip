@@ -378,6 +378,7 @@ struct pm_ctx {
   int dw_nprob = 0, dw_ntiles = 0;   // Transformer: problems and grid size (8 x the longest XCD list) of the grouped launch
   int dw_max_segs = 0;
   bool dw_aligned = false;           // no tile of the grouped launch needs a bounds test
+  int dw_tile = 128;                 // block tile of the grouped launch (128 or 256)
   // overlap of the update of step t with the forward of step t+1 (second stream owned by the library)
   bool overlap = false;
   int32_t min_tau_f = 0;
@@ -826,7 +827,11 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
   if constexpr (sizeof(T) == 2) {
     if (grouped) {
       const auto* tab = c->at<PmGemmProb<PmEpiBwdWeight>>(lay.t_wprobs) + (accumulate ? c->dw_nprob : 0);
-      if (c->dw_aligned)
+      if (c->dw_tile == 256)
+        hipLaunchKernelGGL((pm_gemm_big_grouped_kernel<PmBig256, false, false, false, PmEpiBwdWeight>), dim3(c->dw_ntiles),
+                           dim3(PmBig256::NT), 0, st, tab, c->at<PmXcdSeg>(lay.t_wsegs), c->at<int32_t>(lay.t_wtiles),
+                           c->dw_max_segs);
+      else if (c->dw_aligned)
         hipLaunchKernelGGL((pm_gemm_big_grouped_kernel<PmBig128, false, false, false, PmEpiBwdWeight>), dim3(c->dw_ntiles),
                            dim3(PmBig128::NT), 0, st, tab, c->at<PmXcdSeg>(lay.t_wsegs), c->at<int32_t>(lay.t_wtiles),
                            c->dw_max_segs);
@@ -1255,9 +1260,21 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
         wp.push_back({u + 6, c->at<bf16_t>(b.dz1), lay.units[u + 6].d.n_out, c->at<bf16_t>(b.n2)});
         wp.push_back({u + 7, c->at<bf16_t>(b.dz2), d, c->at<bf16_t>(b.f)});
       }
+      // 256 x 256 block tiles (half the LDS traffic per MFMA) when every problem is a whole number of
+      // them and there are enough to balance 256 compute units; else 128 x 128
+      int TB = 256;
+      {
+        int64_t t256 = 0;
+        for (const WP& w : wp) {
+          const pm_layer_desc& dd = lay.units[w.u].d;
+          if (!pm_big_aligned<PmBig256>(dd.n_out, dd.n_in, Tk)) TB = 128;
+          t256 += (int64_t)((dd.n_out + 255) / 256) * ((dd.n_in + 255) / 256);
+        }
+        if (t256 < 2000) TB = 128;
+      }
       auto tiles_of = [&](const WP& w) {
         const pm_layer_desc& dd = lay.units[w.u].d;
-        return (int64_t)((dd.n_out + 127) / 128) * ((dd.n_in + 127) / 128);
+        return (int64_t)((dd.n_out + TB - 1) / TB) * ((dd.n_in + TB - 1) / TB);
       };
       std::stable_sort(wp.begin(), wp.end(), [&](const WP& a, const WP& b) { return tiles_of(a) > tiles_of(b); });
       const int np = (int)wp.size();
@@ -1289,7 +1306,7 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
       };
       for (int i = 0; i < np; ++i) {
         const pm_layer_desc& dd = lay.units[wp[i].u].d;
-        const int ti = (dd.n_out + 127) / 128, tj = (dd.n_in + 127) / 128;
+        const int ti = (dd.n_out + TB - 1) / TB, tj = (dd.n_in + TB - 1) / TB;
         if ((int64_t)ti * tj * 8 > total_tiles && ti >= 16) {
           const int panels = (ti + 7) / 8;                       // panels of 8 tile rows (the body's walking order)
           int p0 = 0;
@@ -1311,6 +1328,7 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
       const int32_t longest = *std::max_element(load, load + 8);
       c->dw_grouped = fits;
       c->dw_aligned = aligned;
+      c->dw_tile = TB;
       c->dw_nprob = np;
       c->dw_ntiles = longest * 8;
       c->dw_max_segs = max_segs;
