@@ -4,25 +4,43 @@ import subprocess
 import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(PKG, "csrc", "pipemare.hip")
+CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libpipemare.so")
+OBJ = os.path.join(PKG, "_build")
 
-FLAGS = ["-std=c++17", "-O3", "--offload-arch=gfx950", "-fPIC", "-shared",
+FLAGS = ["-std=c++17", "-O3", "--offload-arch=gfx950", "-fPIC",
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# translation units and their extra flags.  The attention kernels keep the accumulators of the matrix
+# instructions in ordinary vector registers (no copies between the two register files around the
+# softmax arithmetic); the GEMMs with 256 accumulator registers per lane need the second file.
+UNITS = [("pipemare.hip", []),
+         ("pm_attn.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form=1"])]
 
 
 def build(verbose: bool = True) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + [SRC, "-o", LIB + ".tmp"]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in r.stdout.splitlines() if "not a recognized feature" not in l)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out)
+    os.makedirs(OBJ, exist_ok=True)
+
+    def run(cmd):
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        out = "\n".join(l for l in r.stdout.splitlines() if "not a recognized feature" not in l)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + out)
+        if verbose and out.strip():
+            print(out)
+
+    objs = []
+    procs = []
+    for src, extra in UNITS:
+        obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+        objs.append(obj)
+        procs.append([hipcc] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj])
+    for cmd in procs:
+        run(cmd)
+    run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB + ".tmp"])
     os.replace(LIB + ".tmp", LIB)
     return LIB
 

@@ -22,8 +22,9 @@
 // scores; D_i = sum_c dO[i, c] O[i, c].  Two backward kernels (dQ; dK and dV) so that every output
 // has one owner and no atomics are needed.
 #pragma once
+#include "pm_attn_api.hpp"
 #include "pm_common.hpp"
-#include "pm_gemm_mfma.hpp"
+#include "pm_mfma_types.hpp"
 
 constexpr int PM_AT_ST = 72;          // LDS row stride (elements) of a [32][64] tile: 144 B, 16-byte aligned rows
 
@@ -50,11 +51,6 @@ __device__ __forceinline__ pm_bf16x8 pm_at_pack8(const float* x) {
   union { pm_bf16x8 v; uint32_t w[4]; } u;
 #pragma unroll
   for (int e = 0; e < 4; ++e) u.w[e] = pm_pack_bf16(x[2 * e], x[2 * e + 1]);
-  return u.v;
-}
-__device__ __forceinline__ pm_bf16x8 pm_at_zero8() {
-  union { pm_bf16x8 v; uint32_t w[4]; } u;
-  u.w[0] = u.w[1] = u.w[2] = u.w[3] = 0u;
   return u.v;
 }
 // result tile [64 x 32] held as two accumulators (MFMA rows = head dimension, column = owned row):
@@ -166,13 +162,26 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_fwd_kernel(const bf16_t* __r
       }
     }
   };
-  for (int jt = 0; jt < n_tiles; jt += 2) {
+  // steady part: the loads are unconditional, so the compiler counts outstanding loads exactly and the
+  // wait before an LDS store covers only the older register set (a load under a condition would force a
+  // wait for everything in flight, the fresh loads included)
+  int jt = 0;
+  for (; jt + 3 < n_tiles; jt += 2) {
+    gload(jt + 2, rk0, rv0);
+    tile(jt, 0);
+    sstore(1, rk1, rv1);
+    __syncthreads();
+    gload(jt + 3, rk1, rv1);
+    tile(jt + 1, 1);
+    sstore(0, rk0, rv0);
+    __syncthreads();
+  }
+  for (; jt < n_tiles; jt += 2) {           // the last one to three tiles
     if (jt + 2 < n_tiles) gload(jt + 2, rk0, rv0);
     tile(jt, 0);
     if (jt + 1 < n_tiles) sstore(1, rk1, rv1);
     __syncthreads();
     if (jt + 1 < n_tiles) {
-      if (jt + 3 < n_tiles) gload(jt + 3, rk1, rv1);
       tile(jt + 1, 1);
       if (jt + 2 < n_tiles) sstore(0, rk0, rv0);
       __syncthreads();
@@ -265,7 +274,7 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_dq_kernel(const bf16_t* __re
       }
       float ds[16];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) ds[e] = __builtin_amdgcn_exp2f(fmaf(s[e], c2, -lq2)) * ((dp[e] - Dq) * scale);
+      for (int e = 0; e < 16; ++e) ds[e] = __builtin_amdgcn_exp2f(fmaf(s[e], c2, -lq2)) * (dp[e] - Dq);   // 1 / sqrt(dh): final store
       if (jt == my_last) {                        // the diagonal tile (uniform over the wave): causal mask
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
@@ -281,19 +290,32 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_dq_kernel(const bf16_t* __re
       }
     }
   };
-  for (int jt = 0; jt < n_tiles; jt += 2) {
+  // steady part: the loads are unconditional, so the compiler counts outstanding loads exactly and the
+  // wait before an LDS store covers only the older register set (a load under a condition would force a
+  // wait for everything in flight, the fresh loads included)
+  int jt = 0;
+  for (; jt + 3 < n_tiles; jt += 2) {
+    gload(jt + 2, rk0, rv0);
+    tile(jt, 0);
+    sstore(1, rk1, rv1);
+    __syncthreads();
+    gload(jt + 3, rk1, rv1);
+    tile(jt + 1, 1);
+    sstore(0, rk0, rv0);
+    __syncthreads();
+  }
+  for (; jt < n_tiles; jt += 2) {           // the last one to three tiles
     if (jt + 2 < n_tiles) gload(jt + 2, rk0, rv0);
     tile(jt, 0);
     if (jt + 1 < n_tiles) sstore(1, rk1, rv1);
     __syncthreads();
     if (jt + 1 < n_tiles) {
-      if (jt + 3 < n_tiles) gload(jt + 3, rk1, rv1);
       tile(jt + 1, 1);
       if (jt + 2 < n_tiles) sstore(0, rk0, rv0);
       __syncthreads();
     }
   }
-  if (active) pm_at_store_t(dq + base + (int64_t)(q0 + ql) * d, acc, 1.f, lane);
+  if (active) pm_at_store_t(dq + base + (int64_t)(q0 + ql) * d, acc, scale, lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -350,7 +372,7 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_dkv_kernel(const bf16_t* __r
     r.q = *reinterpret_cast<const uint4*>(q + ro);
     r.dO = *reinterpret_cast<const uint4*>(dO + ro);
     r.o = *reinterpret_cast<const uint4*>(o + ro);
-    if (threadIdx.x < 32) r.L = lse[lbase + it * 32 + threadIdx.x] * 1.44269504f;       // base-2 units
+    r.L = lse[lbase + it * 32 + (threadIdx.x & 31)];       // every thread (no load under a condition)
   };
   auto sstore = [&](int buf, const Regs& r) __attribute__((always_inline)) {
     *reinterpret_cast<uint4*>(&sQ[buf][lrow * PM_AT_ST + lcol]) = r.q;
@@ -366,7 +388,7 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_dkv_kernel(const bf16_t* __r
     part += __shfl_xor(part, 2, 64);
     part += __shfl_xor(part, 4, 64);
     if ((threadIdx.x & 7) == 0) sD[buf][lrow] = part;
-    if (threadIdx.x < 32) sL[buf][threadIdx.x] = r.L;
+    if (threadIdx.x < 32) sL[buf][threadIdx.x] = r.L * 1.44269504f;       // base-2 units
   };
   gload(first, r0);
   sstore(0, r0);
@@ -407,7 +429,7 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_dkv_kernel(const bf16_t* __r
         }
       }
 #pragma unroll
-      for (int e = 0; e < 16; ++e) ds[e] = p[e] * ((dp[e] - Dv[e]) * scale);
+      for (int e = 0; e < 16; ++e) ds[e] = p[e] * (dp[e] - Dv[e]);       // the factor 1 / sqrt(dh) goes into the final store
       const pm_bf16x8 p0 = pm_at_pack8(p), p1 = pm_at_pack8(p + 8), s0 = pm_at_pack8(ds), s1 = pm_at_pack8(ds + 8);
 #pragma unroll
       for (int dt = 0; dt < 2; ++dt) {
@@ -418,36 +440,31 @@ __global__ __launch_bounds__(256) void pm_attn_mfma_dkv_kernel(const bf16_t* __r
       }
     }
   };
-  for (int it = first; it < n_tiles; it += 2) {
+  int it = first;
+  for (; it + 3 < n_tiles; it += 2) {        // steady part: unconditional loads (see the forward kernel)
+    gload(it + 2, r0);
+    tile(it, 0);
+    sstore(1, r1);
+    __syncthreads();
+    gload(it + 3, r1);
+    tile(it + 1, 1);
+    sstore(0, r0);
+    __syncthreads();
+  }
+  for (; it < n_tiles; it += 2) {            // the last one to three tiles
     if (it + 2 < n_tiles) gload(it + 2, r0);
     tile(it, 0);
     if (it + 1 < n_tiles) sstore(1, r1);
     __syncthreads();
     if (it + 1 < n_tiles) {
-      if (it + 3 < n_tiles) gload(it + 3, r1);
       tile(it + 1, 1);
       if (it + 2 < n_tiles) sstore(0, r0);
       __syncthreads();
     }
   }
   if (active) {
-    pm_at_store_t(dk + base + (int64_t)(k0 + kl) * d, ak, 1.f, lane);
+    pm_at_store_t(dk + base + (int64_t)(k0 + kl) * d, ak, scale, lane);
     pm_at_store_t(dv + base + (int64_t)(k0 + kl) * d, av, 1.f, lane);
   }
 }
 
-inline bool pm_attn_mfma_fits(int S, int dh) { return dh == 64 && S >= 32 && (S % 32) == 0; }
-
-inline void pm_attn_mfma_fwd(hipStream_t st, int B, int S, int H, const bf16_t* q, const bf16_t* k, const bf16_t* v,
-                             bf16_t* o, float* lse) {
-  const int qblocks = (S + 127) / 128;
-  hipLaunchKernelGGL(pm_attn_mfma_fwd_kernel, dim3(B * H * qblocks), dim3(256), 0, st, q, k, v, o, lse, S, H, B * H, 0.125f);
-}
-inline void pm_attn_mfma_bwd(hipStream_t st, int B, int S, int H, const bf16_t* q, const bf16_t* k, const bf16_t* v,
-                             const bf16_t* o, const bf16_t* dO, const float* lse, bf16_t* dq, bf16_t* dk, bf16_t* dv) {
-  const int qblocks = (S + 127) / 128;
-  hipLaunchKernelGGL(pm_attn_mfma_dq_kernel, dim3(B * H * qblocks), dim3(256), 0, st, q, k, v, o, dO, lse, dq, S, H, B * H,
-                     0.125f);
-  hipLaunchKernelGGL(pm_attn_mfma_dkv_kernel, dim3(B * H * qblocks), dim3(256), 0, st, q, k, v, o, dO, lse, dk, dv, S, H,
-                     B * H, 0.125f);
-}

@@ -22,7 +22,7 @@
 // input convolution) use the plain kernels below.
 #pragma once
 #include "pm_common.hpp"
-#include "pm_attn_mfma.hpp"
+#include "pm_mfma_types.hpp"
 
 struct PmConvGeom {
   int B, H, W, Cin, Cout, stride, Ho, Wo;   // input H x W, output Ho x Wo

@@ -33,9 +33,8 @@
 
 #include "pm_common.hpp"
 #include "pm_elem.hpp"
+#include "pm_mfma_types.hpp"
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 pm_bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float pm_f32x16;
 
 template <int ROWS, bool KC, int BK>
 struct PmTileShape {                       // how a (ROWS x BK) operand tile lies in LDS
@@ -83,7 +82,6 @@ struct PmTileLoader {
   }
 };
 
-typedef short pm_v4s __attribute__((ext_vector_type(4)));
 
 // MFMA operand fragment of the 32-row tile starting at tile row r32 for contraction indices
 // kb .. kb+15 (kb a multiple of 16): lane l holds row r32 + l%32, k = kb + 8*(l/32) .. +7.

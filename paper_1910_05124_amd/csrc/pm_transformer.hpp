@@ -10,7 +10,7 @@
 #pragma once
 #include "pm_common.hpp"
 #include "pm_update.hpp"
-#include "pm_attn_mfma.hpp"
+#include "pm_attn_api.hpp"
 
 constexpr float PM_LN_EPS = 1e-5f;
 
