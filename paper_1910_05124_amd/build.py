@@ -22,25 +22,30 @@ def build(verbose: bool = True) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ, exist_ok=True)
 
-    def run(cmd):
-        if verbose:
-            print(" ".join(cmd), flush=True)
-        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-        out = "\n".join(l for l in r.stdout.splitlines() if "not a recognized feature" not in l)
-        if r.returncode != 0:
-            raise RuntimeError("hipcc failed:\n" + out)
+    def finish(cmd, r_out, rc):
+        out = "\n".join(l for l in r_out.splitlines() if "not a recognized feature" not in l)
+        if rc != 0:
+            raise RuntimeError("hipcc failed (" + " ".join(cmd[-3:]) + "):\n" + out)
         if verbose and out.strip():
             print(out)
 
-    objs = []
-    procs = []
+    # the translation units compile side by side
+    objs, procs = [], []
     for src, extra in UNITS:
         obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
         objs.append(obj)
-        procs.append([hipcc] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj])
-    for cmd in procs:
-        run(cmd)
-    run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB + ".tmp"])
+        cmd = [hipcc] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    for cmd, pr in procs:
+        out, _ = pr.communicate()
+        finish(cmd, out, pr.returncode)
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB + ".tmp"]
+    if verbose:
+        print(" ".join(link), flush=True)
+    r = subprocess.run(link, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    finish(link, r.stdout, r.returncode)
     os.replace(LIB + ".tmp", LIB)
     return LIB
 
