@@ -488,9 +488,9 @@ pm_status quiesce(pm_ctx* c) {
 
 template <typename T, class Epi>
 void launch_gemm_on(hipStream_t st, int I, int J, int K, const T* A, int64_t sai, int64_t sak, PmWLoc<T> B, int64_t sbj,
-                    int64_t sbk, const Epi& epi) {
+                    int64_t sbk, const Epi& epi, const PmPrefetch* pf = nullptr) {
   if constexpr (sizeof(T) == 2) {
-    if (pm_mfma_gemm_try(st, I, J, K, A, sai, sak, B, sbj, sbk, epi)) return;
+    if (pm_mfma_gemm_try(st, I, J, K, A, sai, sak, B, sbj, sbk, epi, pf)) return;
   }
   dim3 grid((J + 15) / 16, (I + 15) / 16);
   hipLaunchKernelGGL((pm_gemm_plain_kernel<T, T, Epi>), grid, dim3(256), 0, st, I, J, K, A, sai, sak, B, sbj, sbk, epi);
@@ -510,8 +510,28 @@ void launch_bias_grad(hipStream_t st, const T* dz, float* db, int M, int N, int 
 
 template <typename T, class Epi>
 void launch_gemm(pm_ctx* c, int I, int J, int K, const T* A, int64_t sai, int64_t sak, PmWLoc<T> B, int64_t sbj,
-                 int64_t sbk, const Epi& epi) {
-  launch_gemm_on<T>(c->stream, I, J, K, A, sai, sak, B, sbj, sbk, epi);
+                 int64_t sbk, const Epi& epi, const PmPrefetch* pf = nullptr) {
+  launch_gemm_on<T>(c->stream, I, J, K, A, sai, sak, B, sbj, sbk, epi, pf);
+}
+
+// What the extra blocks of a small product should read ahead: the weight matrix W [n_out, n_in] of a
+// later product of the chain.  forward: the consumer is Z = A W^T (its column tiles are rows of W);
+// else the data gradient dA = dZ W (its column tiles are column ranges of W).
+template <typename T>
+PmPrefetch prefetch_of(const PmWLoc<T>& W, int n_out, int n_in, bool forward) {
+  PmPrefetch pf{nullptr, nullptr, 0, 0, 0, 0, 0, 0};
+  if (sizeof(T) != 2) return pf;
+  const int tiles = ((forward ? n_out : n_in) + 31) / 32;       // the consumer's column tiles (32 wide)
+  if (tiles % 8) return pf;
+  pf.base = reinterpret_cast<const unsigned char*>(W.base);
+  pf.slot = W.slot;
+  pf.stride_bytes = W.stride * (int64_t)sizeof(T);
+  pf.rows = n_out;
+  pf.row_bytes = n_in * (int)sizeof(T);
+  pf.ld_bytes = (int64_t)n_in * sizeof(T);
+  pf.by_rows = forward ? 1 : 0;
+  pf.share = forward ? tiles / 8 * 32 : tiles / 8 * 32 * (int)sizeof(T);
+  return pf;
 }
 
 // Forward on the tau_fwd-stale ring slots, loss, backward on the corrected weights.
@@ -545,8 +565,14 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
     epi.ld = u.ld_out;
     epi.act = u.d.act;
     epi.b_ = nullptr;
+    // while this product runs, its idle blocks read ahead the next unit's forward weights
+    PmPrefetch pf{nullptr, nullptr, 0, 0, 0, 0, 0, 0};
+    if (l + 1 < L) {
+      const Unit& un = lay.units[l + 1];
+      pf = prefetch_of<T>(PmWLoc<T>{ring + un.ring_off, &c->ld(par)[l + 1].fwd_slot, un.n_pad}, un.d.n_out, un.d.n_in, true);
+    }
     // Z[M, n_out] = A[M, n_in] . W[n_out, n_in]^T
-    launch_gemm<T>(c, M, u.d.n_out, u.d.n_in, a_in, u.ld_in, 1, W, u.d.n_in, 1, epi);
+    launch_gemm<T>(c, M, u.d.n_out, u.d.n_in, a_in, u.ld_in, 1, W, u.d.n_in, 1, epi, &pf);
   }
   // ---- loss and d(loss)/d(z_last)   (the last unit's activation must be PM_ACT_NONE)
   {
@@ -578,7 +604,14 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
     PmWLoc<T> Wb = u.corr ? PmWLoc<T>{ub + u.off, nullptr, 0}
                           : PmWLoc<T>{ring + u.ring_off, &c->ld(par)[l].bkwd_slot, u.n_pad};
     PmEpiBwdData<T> ed{c->at<T>(up.z_off), c->at<T>(up.dz_off), up.ld_out, up.d.act};
-    launch_gemm<T>(c, M, u.d.n_in, u.d.n_out, dz, u.ld_out, 1, Wb, 1, u.d.n_in, ed);
+    // idle blocks read ahead the backward weights of the unit below (the next product of the chain)
+    PmPrefetch pf{nullptr, nullptr, 0, 0, 0, 0, 0, 0};
+    if (l >= 2) {
+      const PmWLoc<T> Wn = up.corr ? PmWLoc<T>{ub + up.off, nullptr, 0}
+                                   : PmWLoc<T>{ring + up.ring_off, &c->ld(par)[l - 1].bkwd_slot, up.n_pad};
+      pf = prefetch_of<T>(Wn, up.d.n_out, up.d.n_in, false);
+    }
+    launch_gemm<T>(c, M, u.d.n_in, u.d.n_out, dz, u.ld_out, 1, Wb, 1, u.d.n_in, ed, &pf);
   };
   if (!lay.recompute) {
     for (int l = L - 1; l >= 1; --l) bwd_data(l);

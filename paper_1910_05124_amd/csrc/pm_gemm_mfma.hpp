@@ -238,11 +238,60 @@ __device__ __forceinline__ void pm_gemm_body(const PmGemmProb<Epi>& pr, Epi epi,
   }
 }
 
-// one problem, passed by value
+// Weights of the NEXT product of a chain of small products, to be pulled towards the compute units while
+// this one runs.  A 128 x 1024 x 1024 product keeps only half the chip busy and is bound by the latency
+// of its weight matrix, which was last touched many steps ago (a ring slot) and, in the data gradient,
+// is read in 64-byte pieces one row apart.  Extra blocks of the launch (grid rows beyond the real tile
+// rows) read the next matrix in dense pieces; block x of any launch runs on XCD x % 8 and the tile
+// order below gives XCD k the k-th eighth of the column tiles, so each XCD's extra blocks read exactly
+// the part its own L2 will be asked for.
+struct PmPrefetch {
+  const unsigned char* base;   // nullptr: nothing to prefetch
+  const int32_t* slot;         // ring slot index in the device step table, or nullptr
+  int64_t stride_bytes;        // bytes between ring slots
+  int rows;                    // matrix rows
+  int row_bytes;               // useful bytes per row (a multiple of 16)
+  int64_t ld_bytes;            // bytes between rows
+  int by_rows;                 // 1: an XCD's share is a range of rows (the consumer's column tiles are rows of the
+                               // matrix: forward); 0: a range of bytes of every row (data gradient)
+  int share;                   // rows (by_rows) or bytes of a row (else) per XCD
+};
+
+__device__ __forceinline__ void pm_prefetch_block(const PmPrefetch& pf, int bx, int py, int gx, int npy) {
+  const unsigned char* base = pf.base + (pf.slot ? (int64_t)(*pf.slot) * pf.stride_bytes : 0);
+  const int xcd = bx & 7, q = (bx >> 3) + (gx >> 3) * py, nq = (gx >> 3) * npy;
+  int r0 = 0, nr = pf.rows, c0 = 0, nb = pf.row_bytes;
+  if (pf.by_rows) {
+    r0 = xcd * pf.share;
+    nr = pf.rows - r0 < pf.share ? pf.rows - r0 : pf.share;
+  } else {
+    c0 = xcd * pf.share;
+    nb = pf.row_bytes - c0 < pf.share ? pf.row_bytes - c0 : pf.share;
+  }
+  if (nr <= 0 || nb <= 0) return;
+  const int per_row = (nb + 63) >> 6;                     // one 4-byte read per 64 bytes brings the line in
+  const int total = nr * per_row;
+  uint32_t acc = 0;
+  for (int c = q * 256 + (int)threadIdx.x; c < total; c += nq * 256) {
+    const int r = c / per_row, piece = c - r * per_row;
+    acc |= *reinterpret_cast<const uint32_t*>(base + (int64_t)(r0 + r) * pf.ld_bytes + c0 + piece * 64);
+  }
+  asm volatile("" ::"v"(acc));                            // the reads have no other use: keep them
+}
+
+// one problem, passed by value.  Grid (column tiles, row tiles + extra rows of prefetching blocks).
 template <class Cfg, bool AKC, bool BKC, class Epi>
-__global__ __launch_bounds__(Cfg::NT) void pm_gemm_mfma_kernel(PmGemmProb<Epi> pr) {
+__global__ __launch_bounds__(Cfg::NT) void pm_gemm_mfma_kernel(PmGemmProb<Epi> pr, PmPrefetch pf, int tiles_i) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[PmGemmLds<Cfg, AKC, BKC>::bytes];
-  pm_gemm_body<Cfg, AKC, BKC, Epi>(pr, pr.epi, blockIdx.x, blockIdx.y, smem);
+  if ((int)blockIdx.y >= tiles_i) {
+    pm_prefetch_block(pf, blockIdx.x, blockIdx.y - tiles_i, gridDim.x, gridDim.y - tiles_i);
+    return;
+  }
+  // XCD k (blocks with x % 8 == k) takes the k-th eighth of the column tiles: its L2 then holds one
+  // contiguous part of the B operand
+  int bx = blockIdx.x;
+  if ((gridDim.x & 7) == 0) bx = (bx & 7) * (gridDim.x >> 3) + (bx >> 3);
+  pm_gemm_body<Cfg, AKC, BKC, Epi>(pr, pr.epi, bx, blockIdx.y, smem);
 }
 
 // a table of problems in device memory, one per blockIdx.z
@@ -254,9 +303,14 @@ __global__ __launch_bounds__(Cfg::NT) void pm_gemm_mfma_grouped_kernel(const PmG
 }
 
 template <class Cfg, bool AKC, bool BKC, class Epi>
-inline void pm_mfma_launch(hipStream_t st, const PmGemmProb<Epi>& pr) {
+inline void pm_mfma_launch(hipStream_t st, const PmGemmProb<Epi>& pr, const PmPrefetch* pf = nullptr) {
   dim3 grid((pr.J + Cfg::BJ - 1) / Cfg::BJ, (pr.I + Cfg::BI - 1) / Cfg::BI);
-  hipLaunchKernelGGL((pm_gemm_mfma_kernel<Cfg, AKC, BKC, Epi>), grid, dim3(Cfg::NT), 0, st, pr);
+  const int tiles_i = (int)grid.y;
+  PmPrefetch none{nullptr, nullptr, 0, 0, 0, 0, 0, 0};
+  // prefetching blocks only where the product leaves compute units idle, as many as are idle
+  if (pf && pf->base && (grid.x & 7) == 0 && grid.x * grid.y < 256) grid.y += (256 - grid.x * grid.y) / grid.x;
+  else pf = &none;
+  hipLaunchKernelGGL((pm_gemm_mfma_kernel<Cfg, AKC, BKC, Epi>), grid, dim3(Cfg::NT), 0, st, pr, *pf, tiles_i);
 }
 
 using PmCfgBig = PmGemmCfg<128, 128, 2, 2, 1, 64>;      // MFMA-bound shapes
@@ -274,7 +328,7 @@ template <bool AKC, bool BKC, class Epi>
 inline bool pm_mid_try(hipStream_t st, const PmGemmProb<Epi>& pr);
 
 template <bool AKC, bool BKC, class Epi>
-inline void pm_mfma_pick(hipStream_t st, const PmGemmProb<Epi>& pr) {
+inline void pm_mfma_pick(hipStream_t st, const PmGemmProb<Epi>& pr, const PmPrefetch* pf = nullptr) {
   if (pm_big_try<AKC, BKC>(st, pr)) return;
   const long tiles128 = (long)((pr.I + 127) / 128) * ((pr.J + 127) / 128);
   const long tiles64 = (long)((pr.I + 63) / 64) * ((pr.J + 63) / 64);
@@ -282,9 +336,9 @@ inline void pm_mfma_pick(hipStream_t st, const PmGemmProb<Epi>& pr) {
   if (tiles128 >= 512) pm_mfma_launch<PmCfgBig, AKC, BKC>(st, pr);
   else if (pr.K <= 128) pm_mfma_launch<PmCfgShortK, AKC, BKC>(st, pr);
   else if (tiles64 >= 192 || pr.K <= 256) pm_mfma_launch<PmCfgMid, AKC, BKC>(st, pr);
-  else if (pr.K >= 768) pm_mfma_launch<PmCfgSkinny1K, AKC, BKC>(st, pr);
-  else if (pr.K >= 384) pm_mfma_launch<PmCfgSkinny512, AKC, BKC>(st, pr);
-  else pm_mfma_launch<PmCfgSkinny256, AKC, BKC>(st, pr);
+  else if (pr.K >= 768) pm_mfma_launch<PmCfgSkinny1K, AKC, BKC>(st, pr, pf);
+  else if (pr.K >= 384) pm_mfma_launch<PmCfgSkinny512, AKC, BKC>(st, pr, pf);
+  else pm_mfma_launch<PmCfgSkinny256, AKC, BKC>(st, pr, pf);
 }
 
 // Alignment rules of the MFMA path for one problem given element strides (exactly one of
@@ -307,14 +361,14 @@ inline bool pm_mfma_fits(int I, int J, int K, const void* A, int64_t sai, int64_
 // not fit, in which case the caller uses the plain kernel.
 template <class Epi>
 inline bool pm_mfma_gemm_try(hipStream_t st, int I, int J, int K, const bf16_t* A, int64_t sai, int64_t sak,
-                             PmWLoc<bf16_t> B, int64_t sbj, int64_t sbk, const Epi& epi) {
+                             PmWLoc<bf16_t> B, int64_t sbj, int64_t sbk, const Epi& epi, const PmPrefetch* pf = nullptr) {
   if (!pm_mfma_fits(I, J, K, A, sai, sak, B.base, B.stride, sbj, sbk)) return false;
   const bool akc = sak == 1, bkc = sbk == 1;
   PmGemmProb<Epi> pr{I, J, K, A, akc ? sai : sak, B, bkc ? sbj : sbk, epi};
-  if (akc && bkc) pm_mfma_pick<true, true>(st, pr);
-  else if (akc && !bkc) pm_mfma_pick<true, false>(st, pr);
-  else if (!akc && bkc) pm_mfma_pick<false, true>(st, pr);
-  else pm_mfma_pick<false, false>(st, pr);
+  if (akc && bkc) pm_mfma_pick<true, true>(st, pr, pf);
+  else if (akc && !bkc) pm_mfma_pick<true, false>(st, pr, pf);
+  else if (!akc && bkc) pm_mfma_pick<false, true>(st, pr, pf);
+  else pm_mfma_pick<false, false>(st, pr, pf);
   return true;
 }
 
