@@ -334,8 +334,8 @@ inline void pm_mfma_pick(hipStream_t st, const PmGemmProb<Epi>& pr, const PmPref
   const long tiles64 = (long)((pr.I + 63) / 64) * ((pr.J + 63) / 64);
   if (pm_mid_try<AKC, BKC>(st, pr)) return;
   if (tiles128 >= 512) pm_mfma_launch<PmCfgBig, AKC, BKC>(st, pr);
-  else if (pr.K <= 128) pm_mfma_launch<PmCfgShortK, AKC, BKC>(st, pr);
-  else if (tiles64 >= 192 || pr.K <= 256) pm_mfma_launch<PmCfgMid, AKC, BKC>(st, pr);
+  else if (pr.K <= 128) pm_mfma_launch<PmCfgShortK, AKC, BKC>(st, pr, pf);
+  else if (tiles64 >= 192 || pr.K <= 256) pm_mfma_launch<PmCfgMid, AKC, BKC>(st, pr, pf);
   else if (pr.K >= 768) pm_mfma_launch<PmCfgSkinny1K, AKC, BKC>(st, pr, pf);
   else if (pr.K >= 384) pm_mfma_launch<PmCfgSkinny512, AKC, BKC>(st, pr, pf);
   else pm_mfma_launch<PmCfgSkinny256, AKC, BKC>(st, pr, pf);
@@ -456,8 +456,6 @@ struct PmBigCfg {
   // waves per SIMD the register budget is sized for: the 128 x 128 wave tile holds 256 accumulator
   // registers and needs the whole 512-entry file (its LDS footprint allows one block per CU anyway)
   static constexpr int WPE = (BI_ / WI_) * (BJ_ / WJ_) >= 128 * 128 ? 1 : (BI_ / WI_) * (BJ_ / WJ_) <= 32 * 32 ? 4 : 2;
-  // first k-step (of 4) behind which the staged next slab is written to LDS
-  static constexpr int STORE_FROM = (BI_ / WI_) * (BJ_ / WJ_) >= 128 * 128 ? 2 : 0;
 };
 
 template <class Cfg, bool AKC, bool BKC>
