@@ -34,7 +34,8 @@ struct PmLayerStep {
   int32_t rec_slot;    // (max(t - tau_recomp, 0)) mod R : version the recomputation reads when it needs no correction
   int32_t ur_slot;     // (max(t + 1 - tau_recomp, 0)) mod R : base of the next corrected recompute weights
   float corr_r_next;   // coefficient of the NEXT step's corrected recompute weights (0 during synchronous warm-up)
-  int32_t pad_[3];
+  int32_t rev;         // t mod 2: direction in which this step's update pass walks the parameter chunks
+  int32_t pad_[2];
 };
 
 // The step table and the per-step scalars exist twice (index = step parity): the update of step t,

@@ -58,7 +58,8 @@ __device__ __forceinline__ void pm_prologue_block(PmStepHdr* hdr, const PmLayerS
     D.rec_slot = (int32_t)(vr % S.R);
     D.ur_slot = (int32_t)(vur % S.R);
     D.corr_r_next = warm_next ? 0.f : S.corr_r;
-    D.pad_[0] = D.pad_[1] = D.pad_[2] = 0;
+    D.rev = (int32_t)(t & 1);
+    D.pad_[0] = D.pad_[1] = 0;
     ld[l] = D;
   }
   __syncthreads();
@@ -214,7 +215,11 @@ template <> struct PmAcc<2> : PmAccSplit<true> {};
 template <typename RT, int OPT, int VAR>
 __global__ __launch_bounds__(256) void pm_fused_update_kernel(PmUpdArgs<RT> a) {
   using X = PmAcc<VAR>;
-  const int c = blockIdx.x;
+  // Chunks are walked in opposite directions on alternate steps: the pass streams more state than the
+  // 256 MB last-level cache holds, so what survives there from the previous pass is its tail, and the
+  // next pass starts with exactly that part instead of evicting it before reaching it.
+  // (the direction comes from this step's table, which is not rewritten while the pass runs)
+  const int c = a.ld[0].rev ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
   const int l = a.chunk_layer[c];
   const PmLayerStatic S = a.ls[l];
   const PmLayerStep D = a.ld[l];
