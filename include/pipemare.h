@@ -327,6 +327,19 @@ pm_status pm_conv3x3_bwd_weight(void* stream, int32_t dtype, int32_t B, int32_t 
  * second stream (overlap_update). */
 pm_status pm_synchronize(pm_ctx* ctx);
 
+/* Checkpoint / resume of the training state (the paper's method has none of its own; the state of
+ * the recurrences of Sec. 2 and Sec. 3.2 is what must survive): step counter, fp32 master weights,
+ * optimizer moments, delta accumulator, every ring slot, the corrected backward (and recompute) weights.
+ * pm_checkpoint_bytes: size in bytes of the image (host, out).
+ * pm_checkpoint_save: writes the image to dst_host (host memory, caller-owned, `bytes` as returned above;
+ *   PM_EINVAL if smaller).  PM_ESTATE in the middle of a minibatch.  Synchronises.
+ * pm_checkpoint_load: restores a context created with the SAME layers, delays, dtype and options from an
+ *   image (PM_EINVAL if the image does not match the context's layout or is truncated).  The next
+ *   pm_step continues bit-identically to the run that saved.  Synchronises. */
+pm_status pm_checkpoint_bytes(pm_ctx* ctx, size_t* bytes);
+pm_status pm_checkpoint_save(pm_ctx* ctx, void* dst_host, size_t bytes);
+pm_status pm_checkpoint_load(pm_ctx* ctx, const void* src_host, size_t bytes);
+
 /* Frees host state only; the arena stays the caller's. */
 void pm_destroy(pm_ctx* ctx);
 

@@ -18,7 +18,7 @@ __all__ = [
     "pm_delays", "pm_slots", "pm_t1_lr", "pm_query_bytes", "pm_create", "pm_step", "pm_weights",
     "pm_state", "pm_device_step_table", "pm_stats", "pm_recompute_delays", "pm_device_recompute_slots", "pm_delay_thresholds", "pm_stochastic_delays", "pm_set_grads", "pm_apply_update", "pm_destroy",
     "pm_linear_fwd", "pm_linear_bwd_data", "pm_linear_bwd_weight", "pm_profile_begin", "pm_profile_end",
-    "pm_synchronize", "PipeMare", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
+    "pm_synchronize", "pm_checkpoint_bytes", "pm_checkpoint_save", "pm_checkpoint_load", "PipeMare", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
     "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight", "pm_conv3x3_bwd_weight_scratch",
     "PM_LINEAR", "PM_KIND", "PM_ARCH", "PM_ACT", "PM_METHOD", "PM_LR", "PM_OPT", "PM_DTYPE", "PM_LOSS", "EXPORTS",
 ]
@@ -53,7 +53,7 @@ EXPORTS = ["pm_status_str", "pm_last_error", "pm_delays", "pm_slots", "pm_t1_lr"
            "pm_set_grads", "pm_apply_update", "pm_profile_begin", "pm_profile_end", "pm_linear_fwd", "pm_linear_bwd_data",
            "pm_linear_bwd_weight", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
            "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight", "pm_conv3x3_bwd_weight_scratch",
-           "pm_synchronize", "pm_destroy"]
+           "pm_checkpoint_bytes", "pm_checkpoint_save", "pm_checkpoint_load", "pm_synchronize", "pm_destroy"]
 
 
 class pm_layer_desc(C.Structure):
@@ -86,6 +86,9 @@ class PmError(RuntimeError):
 
 
 lib.pm_status_str.restype = C.c_char_p
+lib.pm_checkpoint_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
+lib.pm_checkpoint_save.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
+lib.pm_checkpoint_load.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
 lib.pm_status_str.argtypes = [C.c_int]
 lib.pm_last_error.restype = C.c_char_p
 lib.pm_last_error.argtypes = []
@@ -236,6 +239,24 @@ def pm_device_recompute_slots(ctx: int, L: int):
     r = (C.c_int32 * L)()
     _check(lib.pm_device_recompute_slots(ctx, C.byref(t), r))
     return t.value, list(r)
+
+
+def pm_checkpoint_bytes(ctx: int) -> int:
+    n = C.c_size_t()
+    _check(lib.pm_checkpoint_bytes(ctx, C.byref(n)))
+    return n.value
+
+
+def pm_checkpoint_save(ctx: int) -> np.ndarray:
+    """The context's training state as one byte image (host)."""
+    buf = np.empty(pm_checkpoint_bytes(ctx), dtype=np.uint8)
+    _check(lib.pm_checkpoint_save(ctx, buf.ctypes.data_as(C.c_void_p), buf.size))
+    return buf
+
+
+def pm_checkpoint_load(ctx: int, image: np.ndarray):
+    image = np.ascontiguousarray(image, dtype=np.uint8)
+    _check(lib.pm_checkpoint_load(ctx, image.ctypes.data_as(C.c_void_p), image.size))
 
 
 def pm_stats(ctx: int, param_norm: bool = False):
@@ -400,6 +421,12 @@ class PipeMare:
 
     def synchronize(self):
         pm_synchronize(self.ctx)
+
+    def checkpoint(self) -> np.ndarray:
+        return pm_checkpoint_save(self.ctx)
+
+    def restore(self, image: np.ndarray):
+        pm_checkpoint_load(self.ctx, image)
 
     def stats(self, param_norm=False):
         return pm_stats(self.ctx, param_norm)

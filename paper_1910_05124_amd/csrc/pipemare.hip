@@ -1793,6 +1793,109 @@ pm_status pm_synchronize(pm_ctx* c) {
   return PM_OK;
 }
 
+// ---- checkpoint / resume: header + the state arrays as they lie in the arena
+namespace {
+struct CkptHdr {
+  uint64_t magic;
+  uint32_t version, esz;
+  int32_t L, P, opt, has_ur;
+  int64_t n_flat, ring_elems;
+  int64_t t;
+  int32_t diverged;
+  float last_loss;
+};
+constexpr uint64_t CKPT_MAGIC = 0x50697065'4d617265ull;   // "PipeMare"
+
+struct CkptSeg { size_t off, bytes; };
+std::vector<CkptSeg> ckpt_segments(const pm_ctx* c) {
+  const Layout& lay = c->lay;
+  const size_t f32 = (size_t)lay.n_flat * 4, cd = (size_t)lay.n_flat * lay.esz;
+  std::vector<CkptSeg> v{{lay.w_off, f32}, {lay.v_off, f32}};
+  if (c->o.opt == PM_OPT_ADAMW) v.push_back({lay.s_off, f32});
+  v.push_back({lay.d_off, f32});
+  v.push_back({lay.ub_off, cd});
+  if (lay.has_ur) v.push_back({lay.ur_off, cd});
+  v.push_back({lay.ring_off, (size_t)lay.ring_elems * lay.esz});
+  return v;
+}
+CkptHdr ckpt_header(const pm_ctx* c) {
+  CkptHdr h{};
+  h.magic = CKPT_MAGIC;
+  h.version = 1;
+  h.esz = (uint32_t)c->lay.esz;
+  h.L = c->L;
+  h.P = c->P;
+  h.opt = c->o.opt;
+  h.has_ur = c->lay.has_ur ? 1 : 0;
+  h.n_flat = c->lay.n_flat;
+  h.ring_elems = c->lay.ring_elems;
+  h.t = c->t_host;
+  h.diverged = c->diverged ? 1 : 0;
+  h.last_loss = c->last_loss;
+  return h;
+}
+}  // namespace
+
+pm_status pm_checkpoint_bytes(pm_ctx* c, size_t* bytes) {
+  if (!c || !bytes) return fail(PM_EINVAL, "NULL argument");
+  size_t n = sizeof(CkptHdr);
+  for (const CkptSeg& sgm : ckpt_segments(c)) n += sgm.bytes;
+  *bytes = n;
+  return PM_OK;
+}
+
+pm_status pm_checkpoint_save(pm_ctx* c, void* dst, size_t bytes) {
+  size_t need = 0;
+  pm_status s = pm_checkpoint_bytes(c, &need);
+  if (s != PM_OK) return s;
+  if (!dst || bytes < need) return fail(PM_EINVAL, "checkpoint buffer: need %zu bytes", need);
+  if (c->micro != 0) return fail(PM_ESTATE, "checkpoint in the middle of a minibatch");
+  if ((s = pm_synchronize(c)) != PM_OK) return s;
+  char* p = static_cast<char*>(dst);
+  const CkptHdr h = ckpt_header(c);
+  std::memcpy(p, &h, sizeof h);
+  p += sizeof h;
+  for (const CkptSeg& sgm : ckpt_segments(c)) {
+    PM_HIP(hipMemcpy(p, c->arena + sgm.off, sgm.bytes, hipMemcpyDeviceToHost));
+    p += sgm.bytes;
+  }
+  return PM_OK;
+}
+
+pm_status pm_checkpoint_load(pm_ctx* c, const void* src, size_t bytes) {
+  size_t need = 0;
+  pm_status s = pm_checkpoint_bytes(c, &need);
+  if (s != PM_OK) return s;
+  if (!src || bytes < need) return fail(PM_EINVAL, "checkpoint image: need %zu bytes", need);
+  const char* p = static_cast<const char*>(src);
+  CkptHdr h;
+  std::memcpy(&h, p, sizeof h);
+  const CkptHdr w = ckpt_header(c);
+  if (h.magic != CKPT_MAGIC || h.version != w.version || h.esz != w.esz || h.L != w.L || h.P != w.P || h.opt != w.opt ||
+      h.has_ur != w.has_ur || h.n_flat != w.n_flat || h.ring_elems != w.ring_elems || h.t < 0)
+    return fail(PM_EINVAL, "checkpoint image does not match this context");
+  if ((s = pm_synchronize(c)) != PM_OK) return s;
+  p += sizeof h;
+  for (const CkptSeg& sgm : ckpt_segments(c)) {
+    PM_HIP(hipMemcpy(c->arena + sgm.off, p, sgm.bytes, hipMemcpyHostToDevice));
+    p += sgm.bytes;
+  }
+  // the device step counter; the step table is rebuilt from it by the first kernel of the next step
+  PmStepHdr dh;
+  PM_HIP(hipMemcpy(&dh, c->hdr(), sizeof dh, hipMemcpyDeviceToHost));
+  dh.t_next = h.t;
+  dh.t_used = h.t > 0 ? h.t - 1 : 0;
+  dh.diverged = h.diverged;
+  dh.loss = 0.f;
+  PM_HIP(hipMemcpy(c->hdr(), &dh, sizeof dh, hipMemcpyHostToDevice));
+  c->t_host = h.t;
+  c->micro = 0;
+  c->diverged = h.diverged != 0;
+  c->last_loss = h.last_loss;
+  c->upd_pending = false;
+  return PM_OK;
+}
+
 void pm_destroy(pm_ctx* c) {
   if (!c) return;
   if (c->stream_b) {
