@@ -163,7 +163,7 @@ def test_linear_primitives_against_numpy(torch_cuda, dtype, shape):
 
 # ------------------------------------------------------------------------------- whole step, small cases
 def test_config0_fp32_mlp_50_steps(torch_cuda):
-    """BASELINE config 1: 4-stage fp32 MLP, tau_fwd = (7,5,3,1), tau_bkwd = 0, momentum 0.9, lr 0.01, D 0.9."""
+    """The smallest configuration of the task (config 0): 4-stage fp32 MLP, tau_fwd = (7,5,3,1), tau_bkwd = 0, momentum 0.9, lr 0.01, D 0.9."""
     w = wl.config(0)
     o_ = w.opt
     g, o, losses = run_pair(torch_cuda, w, w.steps, check_tables=True, lr=o_["lr"], beta=o_["beta"], D=o_["D"], K=o_["K"])
