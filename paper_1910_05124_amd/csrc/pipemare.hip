@@ -1303,7 +1303,7 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
           if (!pm_big_aligned<PmBig256>(dd.n_out, dd.n_in, Tk)) TB = 128;
           t256 += (int64_t)((dd.n_out + 255) / 256) * ((dd.n_in + 255) / 256);
         }
-        if (t256 < 2000) TB = 128;
+        if (t256 < 256) TB = 128;
       }
       auto tiles_of = [&](const WP& w) {
         const pm_layer_desc& dd = lay.units[w.u].d;

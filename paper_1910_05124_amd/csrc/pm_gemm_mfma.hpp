@@ -742,9 +742,12 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WP
 // other's barriers.  Measured on 8192-row problems (K, N in {1024, 4096}) this beat 256 x 256
 // (8 waves x 128 x 64) and 256 x 128 (4 waves x 128 x 64) blocks in 7 of 9 shape / layout cases.
 using PmBig128 = PmBigCfg<128, 128, 2, 2>;
-// 256 x 256 block, 4 waves x (128 x 128): one block per CU, one wave per SIMD holding 256 accumulator
-// registers; every LDS byte read feeds twice the MFMA work of the 64 x 64 wave tile
-using PmBig256 = PmBigCfg<256, 256, 2, 2>;
+// 256 x 256 block, 8 waves x (128 x 64): one block per CU, two waves per SIMD (128 accumulator registers
+// each).  Per MFMA it reads 3/4 of the LDS bytes of the 64 x 64 wave tile and writes half.  Measured on
+// the 8192-deep weight gradients against 4 waves x (128 x 128) (one wave per SIMD, still less LDS
+// traffic): 2.7 vs 3.5 ms - the second wave per SIMD, which covers the other's LDS and barrier waits,
+// matters more than the traffic.
+using PmBig256 = PmBigCfg<256, 256, 2, 4>;
 // 64 x 64 block, 4 waves x (32 x 32): 37 KB of LDS, four blocks per CU.  For token counts in the low
 // thousands with narrow layers (4096 x 512 x 512 ...): enough tiles to fill the chip, and the same
 // software pipeline hides the memory latency that a load - store - compute loop pays once per slab.
@@ -786,6 +789,12 @@ inline bool pm_big_try(hipStream_t st, const PmGemmProb<Epi>& pr) {
     const long tiles64 = (long)((pr.I + 63) / 64) * ((pr.J + 63) / 64);
     if (tiles64 >= 256) return false;
     if (!(tiles >= 32 && pr.K >= 2048)) return false;
+  }
+  // long contraction and enough 256 x 256 tiles for every compute unit: the larger tile (measured on
+  // 32000 x 1024 x 8192: 735 vs 937 us); with K <= 4096 the 128 x 128 tile is as fast or faster
+  if (pr.K >= 8192 && (long)((pr.I + 255) / 256) * ((pr.J + 255) / 256) >= 256 && pm_big_aligned<PmBig256>(pr.I, pr.J, pr.K)) {
+    pm_big_launch<PmBig256, AKC, BKC>(st, pr);
+    return true;
   }
   pm_big_launch<PmBig128, AKC, BKC>(st, pr);
   return true;
