@@ -928,8 +928,7 @@ pm_status launch_resnet(pm_ctx* c, const void* x_dev, const void* y_dev, int acc
     }
     pm_conv_fwd_launch<T>(st, b.g, input_of(u), Wf(u, 0), sc, TT(b.z), TT(b.y));
   }
-  hipLaunchKernelGGL((pm_pool_fwd_kernel<T>), dim3((B * C + 255) / 256), dim3(256), 0, st, TT(lay.cv[nconv - 1].y),
-                     TT(lay.r_pool), B, HW, C);
+  pm_pool_fwd_launch<T>(st, TT(lay.cv[nconv - 1].y), TT(lay.r_pool), B, HW, C);
   {
     PmEpiFwd<T> epi;
     epi.bias = Wf(fc, U(fc).boff);

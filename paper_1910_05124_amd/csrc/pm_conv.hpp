@@ -98,6 +98,57 @@ __global__ __launch_bounds__(256) void pm_conv_fwd_plain_kernel(PmConvGeom g, co
   }
 }
 
+// Forward of the image layer (3 input channels, 16 output channels): one thread per output pixel
+// computes all 16 channels from the 27 inputs of its window, with the kernel tensor, scale and shift
+// held in LDS as fp32 (every lane reads the same entry: a broadcast); outputs go out as 16-byte pieces.
+// The one-thread-per-output-element kernel above spends 61 us on the 128 x 32 x 32 images of the
+// ResNet workload (2-byte loads, a 27-element stride between the lanes' weights), this one a few.
+template <typename T>
+__global__ __launch_bounds__(256) void pm_conv_fwd_thin_kernel(PmConvGeom g, const T* __restrict__ x, PmWLoc<T> wloc,
+                                                               PmShortcut<T> sc, T* __restrict__ z, T* __restrict__ y) {
+  constexpr int CO = 16, CI = 3, NW = CO * 9 * CI;
+  __shared__ float sw[NW + 2 * CO];                   // W [CO][9][CI], then scale [CO], shift [CO] (as in memory)
+  const T* Wt = wloc.get();
+  for (int i = threadIdx.x; i < NW + 2 * CO; i += blockDim.x) sw[i] = ldf(Wt + i);
+  __syncthreads();
+  const int64_t npix = (int64_t)g.B * g.Ho * g.Wo;
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < npix; p += (int64_t)gridDim.x * blockDim.x) {
+    const int ox = (int)(p % g.Wo), oy = (int)((p / g.Wo) % g.Ho), b = (int)(p / ((int64_t)g.Wo * g.Ho));
+    float acc[CO];
+#pragma unroll
+    for (int co = 0; co < CO; ++co) acc[co] = 0.f;
+#pragma unroll
+    for (int dy = 0; dy < 3; ++dy) {
+      const int iy = oy * g.stride + dy - 1;
+      if (iy < 0 || iy >= g.H) continue;
+#pragma unroll
+      for (int dx = 0; dx < 3; ++dx) {
+        const int ix = ox * g.stride + dx - 1;
+        if (ix < 0 || ix >= g.W) continue;
+        const T* xr = x + (((int64_t)b * g.H + iy) * g.W + ix) * CI;
+        const float x0 = ldf(xr), x1 = ldf(xr + 1), x2 = ldf(xr + 2);
+        const float* w = sw + (dy * 3 + dx) * CI;
+#pragma unroll
+        for (int co = 0; co < CO; ++co) {             // same order of additions as the plain kernel
+          acc[co] = fmaf(x0, w[co * 9 * CI], acc[co]);
+          acc[co] = fmaf(x1, w[co * 9 * CI + 1], acc[co]);
+          acc[co] = fmaf(x2, w[co * 9 * CI + 2], acc[co]);
+        }
+      }
+    }
+    float a[CO];
+#pragma unroll
+    for (int co = 0; co < CO; ++co) {
+      const float v = sw[NW + co] * acc[co] + sw[NW + CO + co] + sc.at(b, oy, ox, co);
+      a[co] = v > 0.f ? v : 0.f;
+    }
+    pm_st8(z + p * CO, acc);
+    pm_st8(z + p * CO + 8, acc + 8);
+    pm_st8(y + p * CO, a);
+    pm_st8(y + p * CO + 8, a + 8);
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void pm_conv_dgrad_plain_kernel(PmConvGeom g, const T* __restrict__ dz, PmWLoc<T> wloc,
                                                                   PmShortcutBwd<T> sb, T* __restrict__ dx) {
@@ -279,6 +330,30 @@ __global__ __launch_bounds__(256) void pm_pool_fwd_kernel(const T* __restrict__ 
   float acc = 0.f;
   for (int p = 0; p < HW; ++p) acc += ldf(y + ((int64_t)b * HW + p) * C + c);
   stf(out + i, acc / (float)HW);
+}
+// The same with one block per image when the channel count divides 256: the block's 256 / C groups of
+// threads each sum a share of the pixels (independent loads, consecutive lanes on consecutive channels),
+// then the shares are added through LDS - instead of one thread walking all pixels of a channel with
+// dependent 2-byte loads (20 us for 64 pixels).
+template <typename T>
+__global__ __launch_bounds__(256) void pm_pool_fwd_block_kernel(const T* __restrict__ y, T* __restrict__ out, int HW, int C) {
+  __shared__ float part[256];
+  const int b = blockIdx.x, c = threadIdx.x % C, grp = threadIdx.x / C, ngrp = 256 / C;
+  float acc = 0.f;
+  for (int p = grp; p < HW; p += ngrp) acc += ldf(y + ((int64_t)b * HW + p) * C + c);
+  part[threadIdx.x] = acc;
+  __syncthreads();
+  if (grp == 0) {
+    for (int q = 1; q < ngrp; ++q) acc += part[q * C + c];
+    stf(out + (int64_t)b * C + c, acc / (float)HW);
+  }
+}
+template <typename T>
+inline void pm_pool_fwd_launch(hipStream_t st, const T* y, T* out, int B, int HW, int C) {
+  if (C <= 256 && 256 % C == 0)
+    hipLaunchKernelGGL((pm_pool_fwd_block_kernel<T>), dim3(B), dim3(256), 0, st, y, out, HW, C);
+  else
+    hipLaunchKernelGGL((pm_pool_fwd_kernel<T>), dim3((B * C + 255) / 256), dim3(256), 0, st, y, out, B, HW, C);
 }
 template <typename T>
 __global__ __launch_bounds__(256) void pm_pool_bwd_kernel(const T* __restrict__ dpool, T* __restrict__ dy, int B, int HW, int C) {
@@ -648,6 +723,11 @@ inline void pm_conv_fwd_launch(hipStream_t st, const PmConvGeom& g, const T* x, 
       else hipLaunchKernelGGL((pm_conv_fwd_mfma_kernel<2>), grid, blk, 0, st, g, x, w, sc, z, y);
       return;
     }
+  }
+  if (g.Cin == 3 && g.Cout == 16) {                     // the image layer
+    hipLaunchKernelGGL((pm_conv_fwd_thin_kernel<T>), dim3((unsigned)std::min<int64_t>(65535, (npix + 255) / 256)), dim3(256),
+                       0, st, g, x, w, sc, z, y);
+    return;
   }
   const int64_t total = npix * g.Cout;
   hipLaunchKernelGGL((pm_conv_fwd_plain_kernel<T>), dim3((unsigned)std::min<int64_t>(65535, (total + 255) / 256)), dim3(256), 0,
