@@ -965,14 +965,17 @@ pm_status launch_resnet(pm_ctx* c, const void* x_dev, const void* y_dev, int acc
     if (!pm_conv_affine_bwd_launch<T>(st, TT(b.dy), TT(b.y), TT(b.z), Wb(u, nw), TT(b.da), TT(b.dz), g + U(u).off + nw,
                                       g + U(u).off + nw + b.g.Cout, tot, b.g.Cout, apart, &sums))
       return fail(PM_EINVAL, "unit %d: channel count not supported", u);
-    pm_conv_wgrad_launch<T>(st, b.g, TT(b.dz), input_of(u), g + U(u).off, accumulate, c->at<float>(lay.r_wscratch), sums);
+    // the reduce that ends the weight gradient rides on the data gradient's launch (none for the first layer)
+    PmReducePending pend{};
+    pm_conv_wgrad_launch<T>(st, b.g, TT(b.dz), input_of(u), g + U(u).off, accumulate, c->at<float>(lay.r_wscratch), sums,
+                            u > 0 ? &pend : nullptr);
     if (u == 0) break;
     PmShortcutBwd<T> sb{nullptr, 0, 0, 0, 1};
     if ((u % 2) == 1) {                               // first convolution of a block: its input also feeds the shortcut
       const PmConvGeom& g2 = lay.cv[u + 1].g;
       sb = PmShortcutBwd<T>{TT(lay.cv[u + 1].da), g2.Ho, g2.Wo, g2.Cout, b.g.stride};
     }
-    pm_conv_dgrad_launch<T>(st, b.g, TT(b.dz), Wb(u, 0), sb, TT(lay.cv[u - 1].dy));
+    pm_conv_dgrad_launch<T>(st, b.g, TT(b.dz), Wb(u, 0), sb, TT(lay.cv[u - 1].dy), &pend);
   }
   PM_HIP(hipGetLastError());
   return PM_OK;

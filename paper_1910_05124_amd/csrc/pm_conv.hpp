@@ -365,6 +365,51 @@ __global__ __launch_bounds__(256) void pm_pool_bwd_kernel(const T* __restrict__ 
   }
 }
 
+struct PmReduceJob {
+  const float* part;
+  int nparts;
+  int64_t n;
+  float* out;
+  int accumulate;
+};
+// work of block `bid` (256 threads) of a reduce over two jobs; blocks0 = blocks of the first job
+__device__ __forceinline__ void pm_conv_reduce_block(const PmReduceJob& j0, const PmReduceJob& j1, int blocks0, int bid) {
+  const bool second = bid >= blocks0;
+  const PmReduceJob jb = second ? j1 : j0;
+  const int el = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int64_t e = (int64_t)(second ? bid - blocks0 : bid) * 16 + el;
+  float acc = 0.f;
+  if (e < jb.n) {
+    int p = sl;
+#pragma unroll 1
+    for (; p + 48 < jb.nparts; p += 64) {
+      const float a0 = jb.part[(int64_t)p * jb.n + e], a1 = jb.part[(int64_t)(p + 16) * jb.n + e];
+      const float a2 = jb.part[(int64_t)(p + 32) * jb.n + e], a3 = jb.part[(int64_t)(p + 48) * jb.n + e];
+      acc += (a0 + a1) + (a2 + a3);
+    }
+    for (; p < jb.nparts; p += 16) acc += jb.part[(int64_t)p * jb.n + e];
+  }
+  __shared__ float s[16][16];
+  s[sl][el] = acc;
+  __syncthreads();
+  if (sl == 0 && e < jb.n) {
+    float v = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) v += s[q][el];
+    jb.out[e] = jb.accumulate ? jb.out[e] + v : v;
+  }
+}
+__global__ __launch_bounds__(256) void pm_conv_wgrad_reduce_kernel(PmReduceJob j0, PmReduceJob j1, int blocks0) {
+  pm_conv_reduce_block(j0, j1, blocks0, blockIdx.x);
+}
+// a reduce that has not been launched yet: it can ride as extra blocks on the next independent launch
+struct PmReducePending {
+  PmReduceJob j0, j1;
+  bool valid;
+  int blocks0() const { return (int)((j0.n + 15) / 16); }
+  int blocks() const { return blocks0() + (j1.part ? (int)((j1.n + 15) / 16) : 0); }
+};
+
 // ---------------------------------------------------------------------------------------------
 // implicit-GEMM kernels (bf16, Cin and Cout multiples of 16, at most 64)
 // ---------------------------------------------------------------------------------------------
@@ -429,8 +474,15 @@ __global__ __launch_bounds__(256) void pm_conv_fwd_mfma_kernel(PmConvGeom g, con
 template <int NCO, int NCT>   // channel tiles of 32: Cout <= 32 NCO, Cin <= 32 NCT
 __global__ __launch_bounds__(256) void pm_conv_dgrad_mfma_kernel(PmConvGeom g, const bf16_t* __restrict__ dz,
                                                                  PmWLoc<bf16_t> wloc, PmShortcutBwd<bf16_t> sb,
-                                                                 bf16_t* __restrict__ dx) {
+                                                                 bf16_t* __restrict__ dx, PmReduceJob r0, PmReduceJob r1,
+                                                                 int rblocks0, int dgrad_blocks) {
   __shared__ __attribute__((aligned(16))) bf16_t sW[(32 * NCO + 16) * (9 * 32 * NCT + 8)];
+  // blocks past the data gradient's own carry the pending reduce of the same layer's weight gradient
+  // (independent work: one launch less per layer on maps where a launch costs as much as the kernel)
+  if ((int)blockIdx.x >= dgrad_blocks) {
+    pm_conv_reduce_block(r0, r1, rblocks0, (int)blockIdx.x - dgrad_blocks);
+    return;
+  }
   const int K9 = 9 * g.Cin, WS = K9 + 8;                 // LDS row stride: 16-byte aligned rows
   {
     const bf16_t* Wt = wloc.get();
@@ -669,39 +721,6 @@ __global__ __launch_bounds__(256) void pm_conv_wgrad_mfma_kernel(PmConvGeom g, c
 // arrays are small; what matters is the latency of the longest chain).  A launch carries up to two
 // jobs: the blocks after the first job's work on the second one (used for the per-channel sums of the
 // affine backward, whose out is always added to).
-struct PmReduceJob {
-  const float* part;
-  int nparts;
-  int64_t n;
-  float* out;
-  int accumulate;
-};
-__global__ __launch_bounds__(256) void pm_conv_wgrad_reduce_kernel(PmReduceJob j0, PmReduceJob j1, int blocks0) {
-  const bool second = (int)blockIdx.x >= blocks0;
-  const PmReduceJob jb = second ? j1 : j0;
-  const int el = threadIdx.x & 15, sl = threadIdx.x >> 4;
-  const int64_t e = (int64_t)(second ? blockIdx.x - blocks0 : blockIdx.x) * 16 + el;
-  float acc = 0.f;
-  if (e < jb.n) {
-    int p = sl;
-#pragma unroll 1
-    for (; p + 48 < jb.nparts; p += 64) {
-      const float a0 = jb.part[(int64_t)p * jb.n + e], a1 = jb.part[(int64_t)(p + 16) * jb.n + e];
-      const float a2 = jb.part[(int64_t)(p + 32) * jb.n + e], a3 = jb.part[(int64_t)(p + 48) * jb.n + e];
-      acc += (a0 + a1) + (a2 + a3);
-    }
-    for (; p < jb.nparts; p += 16) acc += jb.part[(int64_t)p * jb.n + e];
-  }
-  __shared__ float s[16][16];
-  s[sl][el] = acc;
-  __syncthreads();
-  if (sl == 0 && e < jb.n) {
-    float v = 0.f;
-#pragma unroll
-    for (int q = 0; q < 16; ++q) v += s[q][el];
-    jb.out[e] = jb.accumulate ? jb.out[e] + v : v;
-  }
-}
 inline void pm_conv_reduce_launch(hipStream_t st, const PmReduceJob& j0, const PmReduceJob& j1) {
   const int b0 = (int)((j0.n + 15) / 16), b1 = j1.part ? (int)((j1.n + 15) / 16) : 0;
   hipLaunchKernelGGL(pm_conv_wgrad_reduce_kernel, dim3((unsigned)(b0 + b1)), dim3(256), 0, st, j0, j1, b0);
@@ -735,13 +754,19 @@ inline void pm_conv_fwd_launch(hipStream_t st, const PmConvGeom& g, const T* x, 
 }
 
 template <typename T>
-inline void pm_conv_dgrad_launch(hipStream_t st, const PmConvGeom& g, const T* dz, PmWLoc<T> w, PmShortcutBwd<T> sb, T* dx) {
+inline void pm_conv_dgrad_launch(hipStream_t st, const PmConvGeom& g, const T* dz, PmWLoc<T> w, PmShortcutBwd<T> sb, T* dx,
+                                 const PmReducePending* pend = nullptr) {
   const int64_t npix = (int64_t)g.B * g.H * g.W;
+  const bool carry = pend && pend->valid;
   if constexpr (sizeof(T) == 2) {
     if (pm_conv_mfma_fits(g.Cin, g.Cout)) {
       // (fewer waves per block on small maps were measured slower here: every block first loads the kernel tensor)
-      const dim3 grid((unsigned)((npix + 127) / 128)), blk(256);
-#define PM_CD(A, B) hipLaunchKernelGGL((pm_conv_dgrad_mfma_kernel<A, B>), grid, blk, 0, st, g, dz, w, sb, dx)
+      const int nb = (int)((npix + 127) / 128);
+      const PmReduceJob none{nullptr, 0, 0, nullptr, 1};
+      const PmReduceJob r0 = carry ? pend->j0 : none, r1 = carry ? pend->j1 : none;
+      const int rb0 = carry ? pend->blocks0() : 0;
+      const dim3 grid((unsigned)(nb + (carry ? pend->blocks() : 0))), blk(256);
+#define PM_CD(A, B) hipLaunchKernelGGL((pm_conv_dgrad_mfma_kernel<A, B>), grid, blk, 0, st, g, dz, w, sb, dx, r0, r1, rb0, nb)
       if (g.Cout <= 32 && g.Cin <= 32) PM_CD(1, 1);
       else if (g.Cout <= 32) PM_CD(1, 2);
       else if (g.Cin <= 32) PM_CD(2, 1);
@@ -753,6 +778,7 @@ inline void pm_conv_dgrad_launch(hipStream_t st, const PmConvGeom& g, const T* d
   const int64_t total = npix * g.Cin;
   hipLaunchKernelGGL((pm_conv_dgrad_plain_kernel<T>), dim3((unsigned)std::min<int64_t>(65535, (total + 255) / 256)), dim3(256),
                      0, st, g, dz, w, sb, dx);
+  if (carry) pm_conv_reduce_launch(st, pend->j0, pend->j1);
 }
 
 // blocks and chunks per wave (4 on large maps, 1 on small ones) of the MFMA weight-gradient kernel
@@ -787,7 +813,15 @@ inline bool pm_conv_wgrad_has_reduce(const PmConvGeom& g) {
 
 template <typename T>
 inline void pm_conv_wgrad_launch(hipStream_t st, const PmConvGeom& g, const T* dz, const T* x, float* dW, int accumulate,
-                                 float* scratch, PmReduceJob extra = PmReduceJob{nullptr, 0, 0, nullptr, 1}) {
+                                 float* scratch, PmReduceJob extra = PmReduceJob{nullptr, 0, 0, nullptr, 1},
+                                 PmReducePending* pend = nullptr) {
+  // the reduce that ends the MFMA and thin paths is launched here, or handed back in *pend for the caller
+  // to attach to its next launch
+  auto finish = [&](const PmReduceJob& j0) {
+    if (pend) *pend = PmReducePending{j0, extra, true};
+    else pm_conv_reduce_launch(st, j0, extra);
+  };
+  if (pend) pend->valid = false;
   if constexpr (sizeof(T) == 2) {
     if (!pm_conv_thin_fits(g) && pm_conv_wgrad_scratch_elems<T>(g) > 0) {
       int blocks, cpw;
@@ -803,14 +837,14 @@ inline void pm_conv_wgrad_launch(hipStream_t st, const PmConvGeom& g, const T* d
       else PM_CW(2, 2);
 #undef PM_CW
       const int64_t nW = (int64_t)g.Cout * 9 * g.Cin;
-      pm_conv_reduce_launch(st, PmReduceJob{scratch, blocks, nW, dW, accumulate}, extra);
+      finish(PmReduceJob{scratch, blocks, nW, dW, accumulate});
       return;
     }
   }
   if (pm_conv_thin_fits(g)) {
     const int64_t nW = (int64_t)g.Cout * 9 * g.Cin;
     hipLaunchKernelGGL((pm_conv_wgrad_thin_kernel<T, 16, 3>), dim3(PM_CONV_THIN_GROUPS, 9), dim3(256), 0, st, g, dz, x, scratch);
-    pm_conv_reduce_launch(st, PmReduceJob{scratch, PM_CONV_THIN_GROUPS, nW, dW, accumulate}, extra);
+    finish(PmReduceJob{scratch, PM_CONV_THIN_GROUPS, nW, dW, accumulate});
     return;
   }
   hipLaunchKernelGGL((pm_conv_wgrad_plain_kernel<T>), dim3((unsigned)(g.Cout * 9 * g.Cin)), dim3(256), 0, st, g, dz, x, dW,
