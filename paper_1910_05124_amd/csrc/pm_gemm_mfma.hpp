@@ -546,7 +546,6 @@ __device__ __forceinline__ void pm_gemm_big_body(const PmGemmProb<Epi>& pr, int 
     Bs1 = sg.B1.get() - (int64_t)Kseg * kb;
     Bs2 = sg.B2.get() - 2 * (int64_t)Kseg * kb;
   }
-  // global loads of slab kt into a register set
   // global loads of slab kt into a register set.  (The selects work on copies of the pointers: a
   // conditional between the captured variables themselves is a conditional between their addresses,
   // which keeps every captured variable in memory.)
