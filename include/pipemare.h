@@ -105,7 +105,8 @@ typedef struct {
   int32_t dtype;             /* pm_dtype */
   int32_t loss;              /* pm_loss_kind */
   int32_t microbatch;        /* rows M of every batch given to pm_step */
-  int32_t use_graph;         /* 1: replay the step as a captured HIP graph after the first call */
+  int32_t use_graph;         /* 1: replay the step as a captured HIP graph after the first call with a given pair
+                                of batch buffers (one graph per (x_dev, y_dev) pair, up to 64 pairs kept) */
   int64_t sync_warmup_steps; /* E_w >= 0: the first E_w optimizer steps run synchronously (all delays 0,
                                 base step size, no correction: the warm-up of PipeMareW, Sec. 4), then
                                 the delays apply and the T1 step counter starts from 0 */

@@ -354,6 +354,8 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
 
 }  // namespace
 
+constexpr size_t PM_MAX_GRAPHS = 64;   // captured step graphs kept per context
+
 struct pm_ctx {
   int32_t P, L;
   pm_opts o;
@@ -367,11 +369,14 @@ struct pm_ctx {
   int32_t micro = 0;       // microbatches accumulated in the current minibatch
   bool diverged = false;
   float last_loss = 0.f;
-  // captured step
-  hipGraph_t graph = nullptr;
-  hipGraphExec_t graph_exec = nullptr;
-  const void* graph_x = nullptr;
-  const void* graph_y = nullptr;
+  // captured steps: one graph per (x, y) batch-buffer pair seen, oldest dropped beyond PM_MAX_GRAPHS
+  struct StepGraph {
+    const void* x;
+    const void* y;
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+  };
+  std::vector<StepGraph> graphs;
   // all weight-gradient products as one grouped MFMA launch (problem tables live in the arena)
   bool dw_grouped = false;
   int dw_maxI = 0, dw_maxJ = 0;
@@ -1424,21 +1429,35 @@ pm_status pm_step(pm_ctx* c, const void* x_dev, const void* y_dev, float* loss_o
   const bool last = c->micro + 1 == c->o.n_microbatches;
   pm_status s = PM_OK;
   if (c->o.use_graph && c->o.n_microbatches == 1 && !c->prof_on) {
-    if (!c->graph_exec || c->graph_x != x_dev || c->graph_y != y_dev) {
-      // (re)capture: all slot and step-size values are read from the device table inside the
-      // kernels, so one graph serves every step as long as the batch pointers stay the same
-      if (c->graph_exec) { (void)hipGraphExecDestroy(c->graph_exec); c->graph_exec = nullptr; }
-      if (c->graph) { (void)hipGraphDestroy(c->graph); c->graph = nullptr; }
+    // All slot and step-size values are read from the device table inside the kernels, so one graph
+    // serves every step that uses the same batch buffers; a caller cycling through a few resident
+    // batches gets one graph per buffer pair.
+    hipGraphExec_t exec = nullptr;
+    for (const pm_ctx::StepGraph& sg : c->graphs)
+      if (sg.x == x_dev && sg.y == y_dev) exec = sg.exec;
+    if (!exec) {
+      if (c->graphs.size() >= PM_MAX_GRAPHS) {
+        (void)hipGraphExecDestroy(c->graphs.front().exec);
+        (void)hipGraphDestroy(c->graphs.front().graph);
+        c->graphs.erase(c->graphs.begin());
+      }
+      hipGraph_t graph = nullptr;
       PM_HIP(hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
       s = enqueue_step_dt(c, x_dev, y_dev, true, true);
-      hipError_t e = hipStreamEndCapture(c->stream, &c->graph);
-      if (s != PM_OK) return s;
+      hipError_t e = hipStreamEndCapture(c->stream, &graph);
+      if (s != PM_OK) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return s;
+      }
       if (e != hipSuccess) return fail(PM_EHIP, "hipStreamEndCapture: %s", hipGetErrorString(e));
-      PM_HIP(hipGraphInstantiate(&c->graph_exec, c->graph, nullptr, nullptr, 0));
-      c->graph_x = x_dev;
-      c->graph_y = y_dev;
+      e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+      if (e != hipSuccess) {
+        (void)hipGraphDestroy(graph);
+        return fail(PM_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e));
+      }
+      c->graphs.push_back(pm_ctx::StepGraph{x_dev, y_dev, graph, exec});
     }
-    PM_HIP(hipGraphLaunch(c->graph_exec, c->stream));
+    PM_HIP(hipGraphLaunch(exec, c->stream));
   } else {
     s = enqueue_step_dt(c, x_dev, y_dev, first, last);
     if (s != PM_OK) return s;
@@ -1907,8 +1926,10 @@ void pm_destroy(pm_ctx* c) {
   if (c->ev_bwd) (void)hipEventDestroy(c->ev_bwd);
   if (c->ev_upd) (void)hipEventDestroy(c->ev_upd);
   for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
-  if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
-  if (c->graph) (void)hipGraphDestroy(c->graph);
+  for (const pm_ctx::StepGraph& sg : c->graphs) {
+    (void)hipGraphExecDestroy(sg.exec);
+    (void)hipGraphDestroy(sg.graph);
+  }
   delete c;
 }
 
