@@ -1059,7 +1059,7 @@ pm_status linear_bwd_weight_t(hipStream_t st, int M, int n_in, int n_out, const 
   // (for few rows; with many rows the column sums would sit on the critical path of the blocks
   // that own them, and a chunked reduction over the whole chip is faster)
   bool fused_db = false;
-  if constexpr (sizeof(T) == 2) fused_db = M <= 512 && pm_mfma_fits(n_out, n_in, M, dz, 1, n_out, a, 0, 1, n_in);
+  if constexpr (sizeof(T) == 2) fused_db = M <= 512 && pm_mfma_takes(n_out, n_in, M, dz, 1, n_out, a, 0, 1, n_in);
   PmEpiBwdWeight epi{dW, n_in, accumulate, fused_db ? db : nullptr};
   launch_gemm_on<T>(st, n_out, n_in, M, (const T*)dz, 1, n_out, PmWLoc<T>{(const T*)a, nullptr, 0}, 1, n_in, epi);
   if (db && !fused_db) launch_bias_grad<T>(st, (const T*)dz, db, M, n_out, n_out, accumulate);

@@ -360,12 +360,20 @@ inline bool pm_mfma_fits(int I, int J, int K, const void* A, int64_t sai, int64_
   return true;
 }
 
+// Whether pm_mfma_gemm_try takes a single product: the alignment rules, and a contraction longer than
+// one MFMA depth (K <= 16, e.g. the data gradient through a 10-class head, goes to the plain kernel,
+// whose single 16-deep step has less latency than staging 64 x 128 tiles of mostly padding).
+inline bool pm_mfma_takes(int I, int J, int K, const void* A, int64_t sai, int64_t sak, const void* Bbase, int64_t Bstride,
+                          int64_t sbj, int64_t sbk) {
+  return K > 16 && pm_mfma_fits(I, J, K, A, sai, sak, Bbase, Bstride, sbj, sbk);
+}
+
 // Try to run the product on MFMA.  Returns false (nothing launched) when the alignment rules do
 // not fit, in which case the caller uses the plain kernel.
 template <class Epi>
 inline bool pm_mfma_gemm_try(hipStream_t st, int I, int J, int K, const bf16_t* A, int64_t sai, int64_t sak,
                              PmWLoc<bf16_t> B, int64_t sbj, int64_t sbk, const Epi& epi, const PmPrefetch* pf = nullptr) {
-  if (!pm_mfma_fits(I, J, K, A, sai, sak, B.base, B.stride, sbj, sbk)) return false;
+  if (!pm_mfma_takes(I, J, K, A, sai, sak, B.base, B.stride, sbj, sbk)) return false;
   const bool akc = sak == 1, bkc = sbk == 1;
   PmGemmProb<Epi> pr{I, J, K, A, akc ? sai : sak, B, bkc ? sbj : sbk, epi};
   if (akc && bkc) pm_mfma_pick<true, true>(st, pr, pf);
