@@ -272,7 +272,8 @@ __device__ __forceinline__ void pm_prefetch_block(const PmPrefetch& pf, int bx, 
   const int per_row = (nb + 63) >> 6;                     // one 4-byte read per 64 bytes brings the line in
   const int total = nr * per_row;
   uint32_t acc = 0;
-  for (int c = q * 256 + (int)threadIdx.x; c < total; c += nq * 256) {
+  const int nt = (int)blockDim.x;
+  for (int c = q * nt + (int)threadIdx.x; c < total; c += nq * nt) {
     const int r = c / per_row, piece = c - r * per_row;
     acc |= *reinterpret_cast<const uint32_t*>(base + (int64_t)(r0 + r) * pf.ld_bytes + c0 + piece * 64);
   }
