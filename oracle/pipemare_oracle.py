@@ -34,7 +34,8 @@ current delta_t.
 Pins (tests/test_oracle_*.py): synchronous special case vs autograd + textbook optimizers,
 equal-delay special case, the stability threshold of Lemma 1 from both sides, the
 momentum and T2 characteristic polynomials as annihilators of the oracle's trajectory,
-T1 closed form, delay tables, hand-worked scalar recurrences, finite differences and an
+T1 closed form, delay tables, hand-worked scalar recurrences (incl. the l2 term and the global
+gradient-norm clip, each also against torch's own routine), finite differences and an
 autograd construction of the two-weight gradient.
 Parity unpinned: the T2 correction with tau_bkwd > 0, and the recompute correction with
 tau_recomp > 0 (in both the paper's text uses the current delta_t while its appendix polynomials

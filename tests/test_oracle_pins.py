@@ -149,6 +149,86 @@ def test_hand_worked_recurrences(golden_dir):
     assert np.allclose(ws, g["C.w"], atol=2e-9) and np.allclose(lrs, g["C.lr"], atol=2e-9)
 
 
+# ----------------------------------------------------------------------------- l2 term and clipping (App. C)
+def test_sgd_weight_decay_hand_worked_and_torch(golden_dir):
+    """The l2 term enters the gradient with the current weights w_t inside v <- beta v - alpha g'
+    (App. B.3 form, App. C's l2 settings): a hand-worked delayed trajectory, then equality with
+    torch.optim.SGD(weight_decay=...) at zero delay and constant step size."""
+    g = read_golden(os.path.join(golden_dir, "scalar_recurrences.txt"))
+    o = scalar_oracle(1, [1], [0], sched=dict(kind="const", base=0.1), beta=0.5, weight_decay=0.5, t1=False, t2=False)
+    ws = []
+    for _ in range(3):
+        o.step(None)
+        ws.append(o.weights(0)[0])
+    assert np.allclose(ws, g["D.w"], atol=1e-12)
+
+    w, params, stream = _mlp_setup("xent", "gelu")
+    P = w.P
+    model = po.MLPModel(w.layers, w.loss)
+    o = po.PipeMareOracle(model, params, [L.stage for L in w.layers], [0] * P, [0] * P,
+                          dict(kind="sgdm", beta=0.9, weight_decay=0.05, sched=dict(kind="const", base=0.05), t1=False))
+    tp = [torch.tensor(p, dtype=torch.float64, requires_grad=True) for p in params]
+    opt = torch.optim.SGD(tp, lr=0.05, momentum=0.9, weight_decay=0.05)
+    for k in range(8):
+        x, y = stream.batch(k)
+        o.step((x, y))
+        opt.zero_grad()
+        _torch_loss(w, _torch_forward(w, tp, x), y).backward()
+        opt.step()
+    for a, b in zip(o.weights(), tp):
+        assert np.allclose(a, b.detach().numpy(), rtol=0, atol=1e-12)
+    # and the decay really moved something: without it the weights differ visibly
+    o0 = po.PipeMareOracle(model, params, [L.stage for L in w.layers], [0] * P, [0] * P,
+                           dict(kind="sgdm", beta=0.9, sched=dict(kind="const", base=0.05), t1=False))
+    for k in range(8):
+        o0.step(stream.batch(k))
+    assert max(np.max(np.abs(a - b)) for a, b in zip(o.weights(), o0.weights())) > 1e-3
+
+
+def test_global_norm_clipping_hand_worked_and_torch(golden_dir):
+    """One threshold over the gradients of ALL stages, applied to the averaged minibatch gradient
+    (App. C, Transformer table): hand-worked two-stage case, then torch's clip_grad_norm_."""
+    g = read_golden(os.path.join(golden_dir, "scalar_recurrences.txt"))
+
+    def two_stage(clip, batch=None):
+        model = po.QuadraticModel(2, 1.0, 0.0)
+        o = po.PipeMareOracle(model, [np.array([3.0]), np.array([4.0])], [1, 2], [0, 0], [0, 0],
+                              dict(sched=dict(kind="const", base=0.1), t1=False, t2=False, clip_norm=clip))
+        o.step(batch)
+        return [o.weights(0)[0], o.weights(1)[0]], o.last_grads
+
+    w1, gr = two_stage(2.5)
+    assert np.allclose(w1, g["E.clipped"], atol=1e-14)
+    assert np.allclose([gr[0][0], gr[1][0]], [1.5, 2.0], atol=1e-14)       # both scaled by exactly 0.5
+    w1, gr = two_stage(10.0)
+    assert np.allclose(w1, g["E.unclipped"], atol=1e-14)
+    assert np.allclose([gr[0][0], gr[1][0]], [3.0, 4.0], atol=1e-14)
+    w1, _ = two_stage(2.5, [np.array([-3.0, -4.0]), np.array([3.0, 4.0])])   # clipped after averaging
+    assert np.allclose(w1, g["E.clipped"], atol=1e-14)
+
+    w, params, stream = _mlp_setup("xent", "gelu")
+    P = w.P
+    model = po.MLPModel(w.layers, w.loss)
+    clip = 0.2
+    o = po.PipeMareOracle(model, params, [L.stage for L in w.layers], [0] * P, [0] * P,
+                          dict(kind="sgdm", beta=0.9, clip_norm=clip, sched=dict(kind="const", base=0.05), t1=False))
+    tp = [torch.tensor(p, dtype=torch.float64, requires_grad=True) for p in params]
+    opt = torch.optim.SGD(tp, lr=0.05, momentum=0.9)
+    clipped_steps = 0
+    for k in range(8):
+        x, y = stream.batch(k)
+        o.step((x, y))
+        opt.zero_grad()
+        _torch_loss(w, _torch_forward(w, tp, x), y).backward()
+        total = float(torch.nn.utils.clip_grad_norm_(tp, clip))
+        clipped_steps += total > clip
+        opt.step()
+    assert clipped_steps >= 4                       # the threshold was active
+    for a, b in zip(o.weights(), tp):
+        # torch divides by (norm + 1e-6): a relative difference of ~1e-5 in the clipped gradient
+        assert np.allclose(a, b.detach().numpy(), rtol=0, atol=2e-6)
+
+
 # ----------------------------------------------------------------------------- Lemma 1 threshold (Sec. 3.1)
 def _amplitude(o, steps):
     tr = trajectory(o, steps)[0]
