@@ -5,12 +5,17 @@ A "step" is one pass of the whole hot path over one microbatch already resident 
 step-size table, forward of all stages on tau_fwd-stale ring weights, loss, backward on corrected
 weights, fused update (T1 + optimizer + delta + ring / corrected-weight write-back).
 
-Workload at N=1: the 16-stage 1024-wide GELU MLP with a 10-class head, bf16 compute with fp32 master
-weights, microbatch 128, PipeMare delays tau_fwd,i = 2(P-i)+1, tau_bkwd = 0.
+Workload at N=1: the largest single-GPU configuration of the task's list (number 5): the fine-grained
+12-layer Transformer, width 1024, 16 heads, feed-forward 4096, vocabulary 32000, 16 sequences of 512
+tokens, every weight unit a pipeline stage of its own (P = 99, tau_fwd = 197 .. 1, tau_bkwd = 0),
+~217 M parameters, 43 GB ring of weight versions; bf16 compute, fp32 master weights, AdamW.
+`--config 1..4` select the other configurations of the list.
 
-Prints ONE JSON line.  `roofline` prices the dominant kernel (the fused update pass, HBM bound)
-with its algorithmic bytes: 32 B per parameter per step (read g, w, v, delta fp32; write w, v, delta
-fp32 + ring slot bf16 + corrected weights bf16).  `cpu_baseline` times the fp64 NumPy oracle on a
+Prints ONE JSON line.  `roofline` prices the fused update pass (HBM bound) with its algorithmic bytes:
+AdamW 40 B per parameter per step (read g, w, m, s, delta fp32; write w, m, s, delta fp32 + ring slot bf16
++ corrected weights bf16), momentum SGD 32 B.  `stage_gemms` prices the stages' matrix products (MFMA
+bound) twice: over the summed duration of the product kernels themselves (event pairs around every such
+launch) and over the whole forward + backward phase.  `cpu_baseline` times the fp64 NumPy oracle on a
 bounded sample of the same workload on the host cores (a reference point, not a target).
 """
 import argparse
@@ -31,16 +36,18 @@ BYTES_PER_PARAM = {("sgdm", "bf16"): 32, ("adamw", "bf16"): 40, ("sgdm", "f32"):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=1,
-                    help="workload index (0: tiny fp32 MLP, 1: 16-stage bf16 MLP (default, the headline workload), "
-                         "2: 6-layer Transformer, 3: ResNet-20, 4: 12-layer Transformer)")
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default per workload: 2000 / 500 / 200 / 300 / 100)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before (default 20; 10 for config 5)")
+    ap.add_argument("--config", type=int, default=5,
+                    help="position in the task's list of configurations (1: tiny fp32 MLP, 2: 16-stage bf16 MLP, "
+                         "3: 6-layer Transformer, 4: ResNet-20, 5: 12-layer Transformer (default, the headline workload))")
     ap.add_argument("--launch", choices=["graph", "eager", "overlap"], default="graph",
                     help="overlap: eager launches, the update of step t on the library's second stream concurrent "
                          "with the forward of step t+1; graph: replay a captured HIP graph; eager: one stream")
     ap.add_argument("--no-graph", action="store_true", help="same as --launch eager")
-    ap.add_argument("--cpu-steps", type=int, default=24, help="oracle steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--cpu-steps", type=int, default=None,
+                    help="oracle steps timed for cpu_baseline (0 = skip; default per workload, about 10-60 s of host work: "
+                         "200 / 24 / 8 / 12 / 1)")
     ap.add_argument("--pool", type=int, default=64, help="distinct device-resident microbatches cycled through")
     ap.add_argument("--recompute", type=int, default=0,
                     help="MLP workloads: S > 0 turns on recomputation with segments of S stages (the backward pass "
@@ -52,6 +59,12 @@ def main():
                     help="also run three plain device-to-device copies of this many MiB after the timed region "
                          "(a kernel of known traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings by)")
     args = ap.parse_args()
+    if args.steps is None:
+        args.steps = {1: 2000, 2: 500, 3: 200, 4: 300, 5: 100}.get(args.config, 100)
+    if args.warmup is None:
+        args.warmup = 10 if args.config == 5 else 20
+    if args.cpu_steps is None:
+        args.cpu_steps = {1: 200, 2: 24, 3: 8, 4: 12, 5: 1}.get(args.config, 1)
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
@@ -116,6 +129,12 @@ def main():
         pm.pm_profile_begin(eng.ctx, args.steps)
         run(args.steps, args.warmup + args.steps)
         prof = pm.pm_profile_end(eng.ctx)
+        # a second, short pass that also brackets every product / attention launch with an event pair
+        ncls = max(1, min(args.steps, 16))
+        pm.pm_profile_begin_classes(eng.ctx, ncls)
+        run(ncls, args.warmup + 2 * args.steps)
+        pm.pm_profile_end(eng.ctx)
+        cls = pm.pm_profile_classes(eng.ctx)
         eng.close()
         if args.calib_copy_mib > 0:
             src = torch.ones(args.calib_copy_mib << 20, dtype=torch.uint8, device="cuda")
@@ -167,6 +186,8 @@ def main():
         if tau_recomp is not None:      # the rebuilt forward of every unit but the head
             gemm_flops += 2.0 * w.microbatch * sum(L.n_in * L.n_out for L in lin[:-1])
     gemm_s = (prof["fwd_ms"] + prof["bwd_ms"]) * 1e-3
+    kern_s = (cls["product_ms"] + cls["attention_ms"]) * 1e-3      # the product (and attention) kernels alone
+    traffic, traffic_src = (measured_traffic(w.name) if tau_recomp is None and stoch is None else (None, None))
     out = {
         "metric": "async pipeline train steps/s",
         "value": round(steps_per_s, 2),
@@ -193,17 +214,23 @@ def main():
                    "launch": launch, "final_loss": round(stats["loss"], 5)},
         "roofline": {"kernel": "pm_fused_update_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic(w.name) if tau_recomp is None and stoch is None else None, "algorithmic_bytes": alg_bytes,
+                     "traffic": traffic, "traffic_source": traffic_src, "algorithmic_bytes": alg_bytes,
                      "bytes_per_param": bpp, "params": n_params,
                      "avg_kernel_ms": round(prof["update_ms"], 5), "launches_timed": prof["n"]},
         "phases_ms": {"forward_loss": round(prof["fwd_ms"], 4), "backward": round(prof["bwd_ms"], 4),
                       "update": round(prof["update_ms"], 4), "note": "serial (non-overlapped) profiling pass"},
-        "stage_gemms": {"algorithmic_tflop_per_step": round(gemm_flops / 1e12, 5),
-                        "achieved_tflops": round(gemm_flops / gemm_s / 1e12, 2) if gemm_s > 0 else None,
-                        "frac_of_bf16_mfma_peak": round(gemm_flops / gemm_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5) if gemm_s > 0 else None,
-                        "note": "flops of the Linear products (and the attention core) over the whole forward + backward "
-                                "phase time of the eager profiling pass: loss, LayerNorm, bias-gradient, embedding kernels "
-                                "and launch gaps are inside that time"},
+        "stage_gemms": {"bound": "mfma", "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "algorithmic_tflop_per_step": round(gemm_flops / 1e12, 5),
+                        "kernels_ms_per_step": round(kern_s * 1e3, 4),
+                        "kernels_achieved": round(gemm_flops / kern_s / 1e12, 2) if kern_s > 0 else None,
+                        "kernels_frac": round(gemm_flops / kern_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5) if kern_s > 0 else None,
+                        "kernels_steps_timed": cls["n"],
+                        "phase_achieved": round(gemm_flops / gemm_s / 1e12, 2) if gemm_s > 0 else None,
+                        "phase_frac": round(gemm_flops / gemm_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5) if gemm_s > 0 else None,
+                        "note": "flops of the stages' matrix / convolution products (and the attention core); kernels_*: "
+                                "over the summed duration of those kernels alone (HIP event pairs around each launch in "
+                                "the eager profiling pass); phase_*: over the whole forward + backward phase (loss, "
+                                "LayerNorm, bias-gradient, embedding kernels and launch gaps inside)"},
     }
     if args.cpu_steps > 0:
         out["cpu_baseline"] = cpu_baseline(w, params, tau_fwd, tau_bkwd, args.cpu_steps, tau_recomp, args.recompute, stoch)
@@ -212,16 +239,22 @@ def main():
 
 def measured_traffic(workload_name):
     """HBM bytes per launch of the update kernel from the committed rocprofv3 counter summary
-    (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a plain copy), or None."""
-    path = os.path.join(ROOT, "profiles", f"update_traffic_{workload_name}.txt")
+    (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a plain copy) and where
+    that number comes from (file and the source revision it was taken at), or (None, None).  Counters
+    cannot be collected inside this process, so the figure is not live: the source string says so."""
+    name = f"update_traffic_{workload_name}.txt"
+    path = os.path.join(ROOT, "profiles", name)
+    val, rev = None, "unknown revision"
     try:
         with open(path) as f:
             for line in f:
+                if line.startswith("# taken at source revision"):
+                    rev = line.split("revision", 1)[1].strip()
                 if line.startswith("traffic_bytes_per_launch pm_fused_update_kernel:"):
-                    return int(float(line.split(":")[1]))
+                    val = int(float(line.split(":")[1]))
     except OSError:
         pass
-    return None
+    return (val, f"profiles/{name} (rocprofv3 counters of a separate run, taken at {rev})") if val is not None else (None, None)
 
 
 def cpu_baseline(w, params, tau_fwd, tau_bkwd, n_steps, tau_recomp=None, segment=0, stochastic=None):
@@ -238,15 +271,17 @@ def cpu_baseline(w, params, tau_fwd, tau_bkwd, n_steps, tau_recomp=None, segment
                       D=o["D"], K=o["K"], weight_decay=o["weight_decay"], sched=o.get("sched"),
                       tau_recomp=tau_recomp, segment=segment, stochastic=stochastic)
     stream = wl.batch_stream(w)
-    batches = [stream.batch(k) for k in range(n_steps + 2)]
-    for k in range(2):
+    pre = 0 if n_steps < 4 else 2
+    batches = [stream.batch(k) for k in range(n_steps + pre)]
+    for k in range(pre):
         orc.step(batches[k])
     t0 = time.perf_counter()
-    for k in range(2, n_steps + 2):
+    for k in range(pre, n_steps + pre):
         orc.step(batches[k])
     dt = time.perf_counter() - t0
-    return {"value": round(n_steps / dt, 3), "unit": "steps/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{n_steps} optimizer steps of the same workload (after 2 untimed), fp64 NumPy, explicit weight histories"}
+    return {"value": round(n_steps / dt, 5), "unit": "steps/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n_steps} whole optimizer step(s) of the same workload (after {pre} untimed), fp64 NumPy, "
+                      f"explicit weight histories, {dt:.1f} s of host time"}
 
 
 if __name__ == "__main__":

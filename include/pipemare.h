@@ -192,11 +192,19 @@ pm_status pm_slots(int32_t tau_fwd, int32_t tau_bkwd, int64_t t,
  * computed on the host in double precision. */
 pm_status pm_t1_lr(const pm_lr_sched* sched, int32_t tau, int64_t k, int32_t t1_enabled, double* lr);
 
-/* Bytes of device arena pm_create needs for this configuration. */
+/* Bytes of device arena pm_create needs for this configuration: fp32 master weights, gradients, optimizer
+ * moments and the delta accumulator of Sec. 3.2 (the "+33 % / +25 %" of weight-plus-optimizer memory the
+ * paper quotes for T2), the corrected backward weights, the ring of tau_fwd,i + 1 weight versions per
+ * stage (sum_i |w_i| (tau_fwd,i + 1) values: what a delay-faithful run on ONE device costs; on a real
+ * pipeline the delayed weights are simply the ones in memory, Sec. 2.2), activations and small tables.
+ * Same argument rules as pm_create; *out_bytes host, out. */
 pm_status pm_query_bytes(int32_t P, int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
                          const pm_opts* opts, size_t* out_bytes);
 
-/* Build a context.
+/* Build a context for the recurrence of Sec. 2.1, w_{t+1} = w_t - alpha grad f_t(u_fwd,t, u_bkwd,t) with
+ * (u_fwd,t)_i = (w_{t - tau_fwd,i})_i and (u_bkwd,t)_i = (w_{t - tau_bkwd,i})_i (delays as in Sec. 2.2 /
+ * Table 1: pm_delays), the step sizes of T1 (Sec. 3.1: sched, sched->K, opts->t1_enabled) and the
+ * corrected backward weights of T2 (Sec. 3.2: opts->D or gamma_override, opts->t2_enabled).
  *   P, L               stages and weight units; layers[L] host
  *   tau_fwd, tau_bkwd  host, P entries, 0 <= tau_bkwd,i <= tau_fwd,i
  *   init_weights_host  L host pointers, unit l in its packed layout (see pm_layer_desc), fp32
@@ -221,8 +229,9 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers,
  * synchronising call. */
 pm_status pm_step(pm_ctx* ctx, const void* x_dev, const void* y_dev, float* loss_out_host);
 
-/* fp32 master weights w_t of unit `layer` into host memory in the unit's packed layout; n must
- * equal the unit's value count.  Synchronises the stream. */
+/* fp32 master weights of unit `layer` - the current iterate w_t of the recurrence of Sec. 2.1 after the t
+ * optimizer steps completed so far, not any delayed version - into host memory in the unit's packed
+ * layout; n must equal the unit's value count.  Synchronises the stream. */
 pm_status pm_weights(pm_ctx* ctx, int32_t layer, float* dst_host, size_t n);
 
 /* Same layout for the delta accumulator (which = 1), the optimizer's first state v or m
@@ -243,9 +252,12 @@ pm_status pm_device_step_table(pm_ctx* ctx, int64_t* t_used, int32_t* fwd_slot, 
  * PM_ESTATE without recomputation.  Synchronises. */
 pm_status pm_device_recompute_slots(pm_ctx* ctx, int64_t* t_used, int32_t* rec_slot);
 
-/* Running numbers: last loss, global gradient L2 norm of the last update (only when clipping is
- * on, else 0), L2 norm of the master weights, number of completed optimizer steps.  Any output
- * may be NULL.  Synchronises. */
+/* Running numbers: mean loss of the most recent MICROBATCH (with n_microbatches > 1 not the mean over the
+ * minibatch), global L2 norm of the averaged minibatch gradient of the last update (only when clipping
+ * is on, else 0; App. C's clipping threshold acts on it), L2 norm of the master weights w_t (the quantity
+ * whose blow-up marks the divergence studied in Sec. 3.1), number t of completed optimizer steps.  Any
+ * output may be NULL.  Synchronises both streams, so a divergence flagged by an overlapped update is seen
+ * here at once, while pm_step's loss read-back (caller's stream only) may report it one step late. */
 pm_status pm_stats(pm_ctx* ctx, double* loss, double* grad_norm, double* param_norm, int64_t* t);
 
 /* Testing / benchmarking of the update pass in isolation (the T1/T2/optimizer/write-back part of
@@ -261,6 +273,15 @@ pm_status pm_apply_update(pm_ctx* ctx);
  * the three phases over the steps recorded (at most max_steps).  n_microbatches must be 1. */
 pm_status pm_profile_begin(pm_ctx* ctx, int32_t max_steps);
 pm_status pm_profile_end(pm_ctx* ctx, double* fwd_ms, double* bwd_ms, double* update_ms, int32_t* n_steps);
+/* A profiling pass (ended by pm_profile_end like the one above) of at most 64 steps that ALSO brackets every
+ * launch of a stage's matrix or convolution product (forward, data gradient, weight gradient: the products
+ * of Sec. 2.1's per-stage forward and backward) and every attention-core launch with an event pair - two
+ * stream markers per launch, which is why the phase times are better taken from a plain pass.
+ * pm_profile_classes returns, for the last such pass that has ended, the mean milliseconds per step summed
+ * over each class and the number of steps measured (zeros if there was none).  Any output may be NULL.
+ * PM_ESTATE while a pass is open. */
+pm_status pm_profile_begin_classes(pm_ctx* ctx, int32_t max_steps);
+pm_status pm_profile_classes(pm_ctx* ctx, double* product_ms, double* attention_ms, int32_t* n_steps);
 
 /* The three matrix products of one Linear unit as stand-alone primitives (the per-stage forward
  * and the two halves of the per-stage backward of Sec. 2.1), on plain device matrices, for

@@ -17,7 +17,7 @@ __all__ = [
     "lib", "PmError", "pm_layer_desc", "pm_lr_sched", "pm_opts",
     "pm_delays", "pm_slots", "pm_t1_lr", "pm_query_bytes", "pm_create", "pm_step", "pm_weights",
     "pm_state", "pm_device_step_table", "pm_stats", "pm_recompute_delays", "pm_device_recompute_slots", "pm_delay_thresholds", "pm_stochastic_delays", "pm_set_grads", "pm_apply_update", "pm_destroy",
-    "pm_linear_fwd", "pm_linear_bwd_data", "pm_linear_bwd_weight", "pm_profile_begin", "pm_profile_end",
+    "pm_linear_fwd", "pm_linear_bwd_data", "pm_linear_bwd_weight", "pm_profile_begin", "pm_profile_end", "pm_profile_classes", "pm_profile_begin_classes",
     "pm_synchronize", "pm_checkpoint_bytes", "pm_checkpoint_save", "pm_checkpoint_load", "PipeMare", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
     "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight", "pm_conv3x3_bwd_weight_scratch",
     "PM_LINEAR", "PM_KIND", "PM_ARCH", "PM_ACT", "PM_METHOD", "PM_LR", "PM_OPT", "PM_DTYPE", "PM_LOSS", "EXPORTS",
@@ -50,7 +50,7 @@ _STATUS = {0: "PM_OK", 1: "PM_EINVAL", 2: "PM_ENOMEM", 3: "PM_EHIP", 4: "PM_ESTA
 EXPORTS = ["pm_status_str", "pm_last_error", "pm_delays", "pm_slots", "pm_t1_lr", "pm_query_bytes",
            "pm_create", "pm_step", "pm_weights", "pm_state", "pm_device_step_table", "pm_stats",
            "pm_recompute_delays", "pm_device_recompute_slots", "pm_delay_thresholds", "pm_stochastic_delays",
-           "pm_set_grads", "pm_apply_update", "pm_profile_begin", "pm_profile_end", "pm_linear_fwd", "pm_linear_bwd_data",
+           "pm_set_grads", "pm_apply_update", "pm_profile_begin", "pm_profile_end", "pm_profile_classes", "pm_profile_begin_classes", "pm_linear_fwd", "pm_linear_bwd_data",
            "pm_linear_bwd_weight", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
            "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight", "pm_conv3x3_bwd_weight_scratch",
            "pm_checkpoint_bytes", "pm_checkpoint_save", "pm_checkpoint_load", "pm_synchronize", "pm_destroy"]
@@ -112,6 +112,8 @@ lib.pm_set_grads.argtypes = [_vp, _i32, _f32p, C.c_size_t]
 lib.pm_apply_update.argtypes = [_vp]
 lib.pm_profile_begin.argtypes = [_vp, _i32]
 lib.pm_profile_end.argtypes = [_vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), _i32p]
+lib.pm_profile_begin_classes.argtypes = [_vp, _i32]
+lib.pm_profile_classes.argtypes = [_vp, C.POINTER(C.c_double), C.POINTER(C.c_double), _i32p]
 lib.pm_linear_fwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _i32, _vp, _vp]
 lib.pm_linear_bwd_data.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _i32, _vp]
 lib.pm_linear_bwd_weight.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _i32]
@@ -282,6 +284,16 @@ def pm_profile_end(ctx: int):
     f, b, u, n = C.c_double(), C.c_double(), C.c_double(), C.c_int32()
     _check(lib.pm_profile_end(ctx, C.byref(f), C.byref(b), C.byref(u), C.byref(n)))
     return dict(fwd_ms=f.value, bwd_ms=b.value, update_ms=u.value, n=n.value)
+
+
+def pm_profile_begin_classes(ctx: int, max_steps: int):
+    _check(lib.pm_profile_begin_classes(ctx, max_steps))
+
+
+def pm_profile_classes(ctx: int):
+    g, a, n = C.c_double(), C.c_double(), C.c_int32()
+    _check(lib.pm_profile_classes(ctx, C.byref(g), C.byref(a), C.byref(n)))
+    return dict(product_ms=g.value, attention_ms=a.value, n=n.value)
 
 
 def pm_synchronize(ctx: int):

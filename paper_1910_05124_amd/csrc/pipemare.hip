@@ -395,6 +395,13 @@ struct pm_ctx {
   std::vector<hipEvent_t> prof_ev;   // 4 per step: start, after forward+loss, after backward, after update
   int32_t prof_cap = 0, prof_n = 0;
   bool prof_on = false;
+  // per-class kernel time of the first steps of a profiling pass: an event pair around every launch of a
+  // matrix / convolution product (class 0) and of an attention-core kernel (class 1)
+  std::vector<hipEvent_t> cls_ev;    // begin, end, begin, end, ...
+  std::vector<int8_t> cls_tag;       // class of each pair
+  int32_t cls_cap = 0;               // steps that record class spans
+  double cls_ms[2] = {0.0, 0.0};     // result of the last pass: mean milliseconds per step
+  int32_t cls_steps = 0;
 
   template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(arena + off); }
   PmStepHdr* hdr() const { return at<PmStepHdr>(lay.hdr_off); }
@@ -430,6 +437,35 @@ inline void prof_mark(pm_ctx* c, int which) {
   if (c->prof_on && c->prof_n < c->prof_cap) (void)hipEventRecord(c->prof_ev[(size_t)c->prof_n * 4 + which], c->stream);
 }
 
+// Event pair around the launches of one kernel class while a profiling pass records classes.
+struct ProfSpan {
+  pm_ctx* c;
+  bool on;
+  ProfSpan(pm_ctx* ctx, int cls) : c(ctx), on(ctx->prof_on && ctx->prof_n < ctx->cls_cap) {
+    if (!on) return;
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) { on = false; return; }
+    (void)hipEventRecord(e, c->stream);
+    c->cls_ev.push_back(e);
+    c->cls_tag.push_back((int8_t)cls);
+  }
+  ~ProfSpan() {
+    if (!on) return;
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) {          // drop the unmatched begin marker
+      (void)hipEventDestroy(c->cls_ev.back());
+      c->cls_ev.pop_back();
+      c->cls_tag.pop_back();
+      return;
+    }
+    (void)hipEventRecord(e, c->stream);
+    c->cls_ev.push_back(e);
+  }
+  ProfSpan(const ProfSpan&) = delete;
+  ProfSpan& operator=(const ProfSpan&) = delete;
+};
+constexpr int PM_CLS_GEMM = 0, PM_CLS_ATTN = 1;
+
 // ---- kernel launches of one microbatch / one update, templated on the compute dtype -------------
 template <typename T>
 pm_status launch_update(pm_ctx* c, hipStream_t st, int par) {
@@ -459,12 +495,12 @@ pm_status launch_update(pm_ctx* c, hipStream_t st, int par) {
   a.beta2 = (float)c->o.beta2;
   a.eps = (float)c->o.eps;
   a.wd = (float)c->o.weight_decay;
-  const dim3 grid((unsigned)lay.n_chunks), blk(256);
   // Streams of up to a few times the 256 MB last-level cache are partly still resident from the
   // previous step (w, v, delta written at step t are read at t+1): cached accesses win there
   // (measured 6.4 vs 5.6 TB/s at 0.5 GB).  Beyond that nothing survives a step and non-temporal
-  // accesses are slightly ahead (5.45 vs 5.23 TB/s at 7 GB).
+  // accesses with one group of four elements per thread are ahead (see PmAcc).
   const bool nontemporal = (size_t)lay.n_flat * 32 > ((size_t)1 << 30);
+  const dim3 grid((unsigned)(lay.n_chunks * (PM_CHUNK / (nontemporal ? PmAcc<2>::PER_BLOCK : PmAcc<1>::PER_BLOCK)))), blk(256);
 #define PM_UPD(OPT, VAR) hipLaunchKernelGGL((pm_fused_update_kernel<T, OPT, VAR>), grid, blk, 0, st, a)
   if (c->o.opt == PM_OPT_SGDM) {
     if (nontemporal) PM_UPD(0, 2); else PM_UPD(0, 1);
@@ -516,6 +552,7 @@ void launch_bias_grad(hipStream_t st, const T* dz, float* db, int M, int N, int 
 template <typename T, class Epi>
 void launch_gemm(pm_ctx* c, int I, int J, int K, const T* A, int64_t sai, int64_t sak, PmWLoc<T> B, int64_t sbj,
                  int64_t sbk, const Epi& epi, const PmPrefetch* pf = nullptr) {
+  ProfSpan span(c, PM_CLS_GEMM);
   launch_gemm_on<T>(c->stream, I, J, K, A, sai, sak, B, sbj, sbk, epi, pf);
 }
 
@@ -666,6 +703,7 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
   bool grouped = false;
   if constexpr (sizeof(T) == 2) {
     if (c->dw_grouped) {
+      ProfSpan span(c, PM_CLS_GEMM);
       const auto* tab = c->at<PmGemmProb<PmEpiBwdWeight>>(lay.probs_off) + (accumulate ? L : 0);
       dim3 grid((c->dw_maxJ + 63) / 64, (c->dw_maxI + 63) / 64, L);
       if (M <= 128)
@@ -759,6 +797,7 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
         epi.z = nullptr; epi.a = outs[p]; epi.z32 = nullptr; epi.ld = d; epi.act = PM_ACT_NONE; epi.b_ = nullptr;
         pr[p] = PmGemmProb<PmEpiFwd<T>>{Tk, d, d, n1, d, Wf(u + 1 + p, 0), d, epi};
       }
+      ProfSpan span(c, PM_CLS_GEMM);
       if (pm_gemm_multi3_try(st, pr)) return;
     }
     lin_fwd(u + 1, n1, d, d, nullptr, q, PM_ACT_NONE);
@@ -771,6 +810,7 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
       const T* const A[3] = {dzq, dzk, dzv};
       const PmWLoc<T> Bw[3] = {Wb(u + 1, 0), Wb(u + 2, 0), Wb(u + 3, 0)};
       PmEpiF32 e{out, d, 0};
+      ProfSpan span(c, PM_CLS_GEMM);
       if (pm_gemm_kseg3_try(st, Tk, d, d, A, d, Bw, d, e)) return;
     }
     dgrad_f32(u + 1, dzq, d, d, d, out, 0);
@@ -804,8 +844,11 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
     float* y = F(l + 1 < nl ? lay.tl[l + 1].x : lay.t_xf);
     ln_fwd(u, x, TT(b.n1), F(b.mu1), F(b.rs1));
     qkv_fwd(u, TT(b.n1), TT(b.q), TT(b.k), TT(b.v));
-    if (!pm_attn_fwd_launch<T>(st, B, S, H, dh, TT(b.q), TT(b.k), TT(b.v), TT(b.o), F(b.lse)))
-      return fail(PM_EINVAL, "attention shape not supported");
+    {
+      ProfSpan span(c, PM_CLS_ATTN);
+      if (!pm_attn_fwd_launch<T>(st, B, S, H, dh, TT(b.q), TT(b.k), TT(b.v), TT(b.o), F(b.lse)))
+        return fail(PM_EINVAL, "attention shape not supported");
+    }
     lin_fwd_res(u + 4, TT(b.o), d, d, x, F(b.h));
     ln_fwd(u + 5, F(b.h), TT(b.n2), F(b.mu2), F(b.rs2));
     lin_fwd(u + 6, TT(b.n2), d, dff, TT(b.z1), TT(b.f), U(u + 6).d.act);
@@ -853,9 +896,12 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
     // h = x + o Wo^T + bo
     wg(u + 4, TT(b.dzo), d, TT(b.o), d, d);
     dgrad_t(u + 4, TT(b.dzo), d, d, nullptr, PM_ACT_NONE, TT(lay.t_do));
-    if (!pm_attn_bwd_launch<T>(st, B, S, H, dh, TT(b.q), TT(b.k), TT(b.v), TT(b.o), TT(lay.t_do), F(b.lse), TT(b.dzq),
-                               TT(b.dzk), TT(b.dzv)))
-      return fail(PM_EINVAL, "attention shape not supported");
+    {
+      ProfSpan span(c, PM_CLS_ATTN);
+      if (!pm_attn_bwd_launch<T>(st, B, S, H, dh, TT(b.q), TT(b.k), TT(b.v), TT(b.o), TT(lay.t_do), F(b.lse), TT(b.dzq),
+                                 TT(b.dzk), TT(b.dzv)))
+        return fail(PM_EINVAL, "attention shape not supported");
+    }
     wg(u + 1, TT(b.dzq), d, TT(b.n1), d, d);
     wg(u + 2, TT(b.dzk), d, TT(b.n1), d, d);
     wg(u + 3, TT(b.dzv), d, TT(b.n1), d, d);
@@ -864,6 +910,7 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
   }
   if constexpr (sizeof(T) == 2) {
     if (grouped) {
+      ProfSpan span(c, PM_CLS_GEMM);
       const auto* tab = c->at<PmGemmProb<PmEpiBwdWeight>>(lay.t_wprobs) + (accumulate ? c->dw_nprob : 0);
       if (c->dw_tile == 256)
         hipLaunchKernelGGL((pm_gemm_big_grouped_kernel<PmBig256, false, false, false, PmEpiBwdWeight>), dim3(c->dw_ntiles),
@@ -931,6 +978,7 @@ pm_status launch_resnet(pm_ctx* c, const void* x_dev, const void* y_dev, int acc
       const PmConvGeom& g1 = lay.cv[u - 1].g;         // geometry of the block's first convolution
       sc = PmShortcut<T>{input_of(u - 1), g1.H, g1.W, g1.Cin, g1.stride};
     }
+    ProfSpan span(c, PM_CLS_GEMM);
     pm_conv_fwd_launch<T>(st, b.g, input_of(u), Wf(u, 0), sc, TT(b.z), TT(b.y));
   }
   pm_pool_fwd_launch<T>(st, TT(lay.cv[nconv - 1].y), TT(lay.r_pool), B, HW, C);
@@ -972,6 +1020,7 @@ pm_status launch_resnet(pm_ctx* c, const void* x_dev, const void* y_dev, int acc
       return fail(PM_EINVAL, "unit %d: channel count not supported", u);
     // the reduce that ends the weight gradient rides on the data gradient's launch (none for the first layer)
     PmReducePending pend{};
+    ProfSpan span(c, PM_CLS_GEMM);      // weight gradient and data gradient of this convolution
     pm_conv_wgrad_launch<T>(st, b.g, TT(b.dz), input_of(u), g + U(u).off, accumulate, c->at<float>(lay.r_wscratch), sums,
                             u > 0 ? &pend : nullptr);
     if (u == 0) break;
@@ -1767,7 +1816,16 @@ pm_status pm_conv3x3_bwd_weight(void* stream, int32_t dtype, int32_t B, int32_t 
   return PM_OK;
 }
 
-pm_status pm_profile_begin(pm_ctx* c, int32_t max_steps) {
+namespace {
+pm_status profile_begin(pm_ctx* c, int32_t max_steps, bool classes);
+}
+pm_status pm_profile_begin(pm_ctx* c, int32_t max_steps) { return profile_begin(c, max_steps, false); }
+pm_status pm_profile_begin_classes(pm_ctx* c, int32_t max_steps) {
+  if (max_steps > 64) return fail(PM_EINVAL, "a pass that records kernel classes takes at most 64 steps");
+  return profile_begin(c, max_steps, true);
+}
+namespace {
+pm_status profile_begin(pm_ctx* c, int32_t max_steps, bool classes) {
   if (!c || max_steps < 1 || max_steps > 65536) return fail(PM_EINVAL, "need a context and 1 <= max_steps <= 65536");
   if (c->o.n_microbatches != 1) return fail(PM_ESTATE, "phase timing supports n_microbatches = 1 only");
   {
@@ -1780,8 +1838,17 @@ pm_status pm_profile_begin(pm_ctx* c, int32_t max_steps) {
   c->prof_cap = max_steps;
   c->prof_n = 0;
   c->prof_on = true;
+  for (hipEvent_t e : c->cls_ev) (void)hipEventDestroy(e);
+  c->cls_ev.clear();
+  c->cls_tag.clear();
+  c->cls_cap = classes ? max_steps : 0;
+  if (classes) {
+    c->cls_ms[0] = c->cls_ms[1] = 0.0;
+    c->cls_steps = 0;
+  }
   return PM_OK;
 }
+}  // namespace
 
 pm_status pm_profile_end(pm_ctx* c, double* fwd_ms, double* bwd_ms, double* update_ms, int32_t* n_steps) {
   if (!c) return fail(PM_EINVAL, "NULL context");
@@ -1799,10 +1866,33 @@ pm_status pm_profile_end(pm_ctx* c, double* fwd_ms, double* bwd_ms, double* upda
   if (bwd_ms) *bwd_ms = acc[1] * inv;
   if (update_ms) *update_ms = acc[2] * inv;
   if (n_steps) *n_steps = c->prof_n;
+  if (c->cls_cap > 0) {
+    double cls[2] = {0.0, 0.0};
+    for (size_t i = 0; i + 1 < c->cls_ev.size(); i += 2) {
+      float ms = 0.f;
+      PM_HIP(hipEventElapsedTime(&ms, c->cls_ev[i], c->cls_ev[i + 1]));
+      cls[c->cls_tag[i / 2]] += ms;
+    }
+    c->cls_steps = std::min(c->prof_n, c->cls_cap);
+    for (int k = 0; k < 2; ++k) c->cls_ms[k] = c->cls_steps ? cls[k] / c->cls_steps : 0.0;
+    for (hipEvent_t e : c->cls_ev) (void)hipEventDestroy(e);
+    c->cls_ev.clear();
+    c->cls_tag.clear();
+    c->cls_cap = 0;
+  }
   for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
   c->prof_ev.clear();
   c->prof_on = false;
   c->prof_cap = c->prof_n = 0;
+  return PM_OK;
+}
+
+pm_status pm_profile_classes(pm_ctx* c, double* product_ms, double* attention_ms, int32_t* n_steps) {
+  if (!c) return fail(PM_EINVAL, "NULL context");
+  if (c->prof_on) return fail(PM_ESTATE, "a profiling pass is still open: call pm_profile_end first");
+  if (product_ms) *product_ms = c->cls_ms[0];
+  if (attention_ms) *attention_ms = c->cls_ms[1];
+  if (n_steps) *n_steps = c->cls_steps;
   return PM_OK;
 }
 
@@ -1926,6 +2016,7 @@ void pm_destroy(pm_ctx* c) {
   if (c->ev_bwd) (void)hipEventDestroy(c->ev_bwd);
   if (c->ev_upd) (void)hipEventDestroy(c->ev_upd);
   for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->cls_ev) (void)hipEventDestroy(e);
   for (const pm_ctx::StepGraph& sg : c->graphs) {
     (void)hipGraphExecDestroy(sg.exec);
     (void)hipGraphDestroy(sg.graph);

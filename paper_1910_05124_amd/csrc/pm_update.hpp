@@ -133,8 +133,8 @@ __global__ void pm_clip_scale_kernel(PmStepHdr* hdr, float clip, int par) {
 //   ur <- round(base_r - (tau_fwd,i - tau_recomp,i) delta_new)        (App. on recompute, "T2 for Recompute":
 //        corrected recompute weights of the NEXT step, only for units that keep such a buffer;
 //        base_r = w_new when tau_recomp = 0, else the stored version t+1-tau_recomp)
-// Each block owns PM_CHUNK consecutive elements, all of one unit (units are padded to the chunk),
-// so the per-unit scalars are wave-uniform; each thread owns 2 x 4 elements (see PmAcc below).
+// Each block owns PM_CHUNK (or half of it, see PmAcc) consecutive elements, all of one unit (units are
+// padded to the chunk), so the per-unit scalars are wave-uniform.
 // ---------------------------------------------------------------------------------------------
 template <typename RT>
 struct PmUpdArgs {
@@ -154,11 +154,17 @@ struct PmUpdArgs {
   float beta1, beta2, eps, wd;
 };
 
-// Element access pattern of one thread inside its 2048-element chunk: two groups of 4 elements
-// 1024 apart, so every load / store instruction of a wave covers one dense 1 KB (fp32) or 512 B
-// (bf16) span.  VAR 1: ordinary accesses; VAR 2: non-temporal loads and stores.
+// Element access pattern of one thread: G groups of 4 elements 1024 apart (a block of 256 threads covers
+// 1024 G consecutive elements: a whole chunk, or half of one), so every load / store instruction of a
+// wave covers one dense 1 KB (fp32) or 512 B (bf16) span.
+// VAR 1: two groups, ordinary accesses (streams small enough to stay partly cached from step to step).
+// VAR 2: ONE group, non-temporal loads and stores (streams of GBs).  Measured on an 8.7 GB pass of this
+//        shape: one group per thread 5.80 TB/s, two 5.50, four 5.57; ordinary accesses 5.27-5.32.
 template <int VAR> struct PmAcc;
-template <bool NT> struct PmAccSplit {
+template <bool NT, int G> struct PmAccSplit {
+  static constexpr int GROUPS = G;
+  static constexpr int PER_BLOCK = 1024 * G;
+  static constexpr int N = 4 * G;       // elements per thread
   static __device__ __forceinline__ int64_t base(int tid) { return tid * 4; }
   typedef float __attribute__((ext_vector_type(4))) f4;
   typedef unsigned int __attribute__((ext_vector_type(2))) u2;
@@ -183,44 +189,57 @@ template <bool NT> struct PmAccSplit {
     __builtin_nontemporal_store(t, reinterpret_cast<u2*>(p));
   }
   static __device__ __forceinline__ void ld(const float* p, float* x) {
-    const float4 a = l4(reinterpret_cast<const float4*>(p));
-    const float4 b = l4(reinterpret_cast<const float4*>(p + 1024));
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+      const float4 a = l4(reinterpret_cast<const float4*>(p + 1024 * k));
+      x[4 * k + 0] = a.x; x[4 * k + 1] = a.y; x[4 * k + 2] = a.z; x[4 * k + 3] = a.w;
+    }
   }
   static __device__ __forceinline__ void ld(const bf16_t* p, float* x) {
-    const uint2 a = l2(reinterpret_cast<const uint2*>(p));
-    const uint2 b = l2(reinterpret_cast<const uint2*>(p + 1024));
-    x[0] = __uint_as_float(a.x << 16); x[1] = __uint_as_float(a.x & 0xffff0000u);
-    x[2] = __uint_as_float(a.y << 16); x[3] = __uint_as_float(a.y & 0xffff0000u);
-    x[4] = __uint_as_float(b.x << 16); x[5] = __uint_as_float(b.x & 0xffff0000u);
-    x[6] = __uint_as_float(b.y << 16); x[7] = __uint_as_float(b.y & 0xffff0000u);
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+      const uint2 a = l2(reinterpret_cast<const uint2*>(p + 1024 * k));
+      x[4 * k + 0] = __uint_as_float(a.x << 16); x[4 * k + 1] = __uint_as_float(a.x & 0xffff0000u);
+      x[4 * k + 2] = __uint_as_float(a.y << 16); x[4 * k + 3] = __uint_as_float(a.y & 0xffff0000u);
+    }
   }
   static __device__ __forceinline__ void st(float* p, const float* x) {
-    s4(reinterpret_cast<float4*>(p), make_float4(x[0], x[1], x[2], x[3]));
-    s4(reinterpret_cast<float4*>(p + 1024), make_float4(x[4], x[5], x[6], x[7]));
+#pragma unroll
+    for (int k = 0; k < G; ++k)
+      s4(reinterpret_cast<float4*>(p + 1024 * k), make_float4(x[4 * k], x[4 * k + 1], x[4 * k + 2], x[4 * k + 3]));
   }
   static __device__ __forceinline__ void st(bf16_t* p, const float* x) {
-    uint2 a, b;
-    a.x = pm_pack_bf16(x[0], x[1]);
-    a.y = pm_pack_bf16(x[2], x[3]);
-    b.x = pm_pack_bf16(x[4], x[5]);
-    b.y = pm_pack_bf16(x[6], x[7]);
-    s2(reinterpret_cast<uint2*>(p), a);
-    s2(reinterpret_cast<uint2*>(p + 1024), b);
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+      uint2 a;
+      a.x = pm_pack_bf16(x[4 * k], x[4 * k + 1]);
+      a.y = pm_pack_bf16(x[4 * k + 2], x[4 * k + 3]);
+      s2(reinterpret_cast<uint2*>(p + 1024 * k), a);
+    }
   }
 };
-template <> struct PmAcc<1> : PmAccSplit<false> {};
-template <> struct PmAcc<2> : PmAccSplit<true> {};
+template <> struct PmAcc<1> : PmAccSplit<false, 2> {};
+template <> struct PmAcc<2> : PmAccSplit<true, 1> {};
 
 template <typename RT, int OPT, int VAR>
 __global__ __launch_bounds__(256) void pm_fused_update_kernel(PmUpdArgs<RT> a) {
   using X = PmAcc<VAR>;
-  // Chunks are walked in opposite directions on alternate steps: the pass streams more state than the
+  constexpr int NE = X::N;
+  static_assert(PM_CHUNK % X::PER_BLOCK == 0, "a block covers a whole chunk or a whole fraction of one");
+  // Blocks are walked in opposite directions on alternate steps: the pass streams more state than the
   // 256 MB last-level cache holds, so what survives there from the previous pass is its tail, and the
   // next pass starts with exactly that part instead of evicting it before reaching it.
   // (the direction comes from this step's table, which is not rewritten while the pass runs)
-  const int c = a.ld[0].rev ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
-  const int l = a.chunk_layer[c];
+  const int64_t blk = a.ld[0].rev ? (int64_t)(gridDim.x - 1 - blockIdx.x) : (int64_t)blockIdx.x;
+  const int64_t e = blk * X::PER_BLOCK + X::base(threadIdx.x);
+  // the streams whose addresses need no table go out first; the table reads overlap their latency
+  float g[NE], w[NE], v[NE], d[NE], s[NE], wn[NE], ubv[NE];
+  X::ld(a.g + e, g);
+  X::ld(a.w + e, w);
+  X::ld(a.v + e, v);
+  X::ld(a.d + e, d);
+  if (OPT == 1) X::ld(a.s + e, s);
+  const int l = a.chunk_layer[blk / (PM_CHUNK / X::PER_BLOCK)];
   const PmLayerStatic S = a.ls[l];
   const PmLayerStep D = a.ld[l];
   // S.corr != 0 says the backward reads the corrected buffer at all; D.corr_next is the coefficient
@@ -228,21 +247,13 @@ __global__ __launch_bounds__(256) void pm_fused_update_kernel(PmUpdArgs<RT> a) {
   const float lr = D.lr, gam = S.gamma, corr = D.corr_next;
   const bool has_ub = S.corr != 0.f;
   const float gs = a.hdr->gscale[a.par];
-  const int64_t e = (int64_t)c * PM_CHUNK + X::base(threadIdx.x);
   const int64_t rel = e - S.off;
-
-  float g[8], w[8], v[8], d[8], s[8], wn[8], ubv[8];
-  X::ld(a.g + e, g);
-  X::ld(a.w + e, w);
-  X::ld(a.v + e, v);
-  X::ld(a.d + e, d);
-  if (OPT == 1) X::ld(a.s + e, s);
   const bool ub_from_ring = (corr != 0.f) && (S.tau_b > 0);
   if (ub_from_ring) X::ld(a.ring + S.ring_off + (int64_t)D.ub_slot * S.n_pad + rel, ubv);
 
   bool bad = false;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
+  for (int j = 0; j < NE; ++j) {
     float gj = g[j] * gs;
     float dw;   // w_{t+1} - w_t, kept as computed (not re-derived by subtraction) so delta keeps its low bits
     if (OPT == 0) {
@@ -267,7 +278,7 @@ __global__ __launch_bounds__(256) void pm_fused_update_kernel(PmUpdArgs<RT> a) {
   X::st(a.ring + S.ring_off + (int64_t)D.write_slot * S.n_pad + rel, wn);
   if (has_ub) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) ubv[j] = (ub_from_ring ? ubv[j] : wn[j]) - corr * d[j];
+    for (int j = 0; j < NE; ++j) ubv[j] = (ub_from_ring ? ubv[j] : wn[j]) - corr * d[j];
     X::st(a.ub + e, ubv);
   }
   if (S.corr_r != 0.f) {        // block-uniform; the ring slot read here is never the one written above (tau_recomp >= 1)
@@ -275,7 +286,7 @@ __global__ __launch_bounds__(256) void pm_fused_update_kernel(PmUpdArgs<RT> a) {
     const bool ur_from_ring = (cr != 0.f) && (S.tau_r > 0);
     if (ur_from_ring) X::ld(a.ring + S.ring_off + (int64_t)D.ur_slot * S.n_pad + rel, ubv);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) ubv[j] = (ur_from_ring ? ubv[j] : wn[j]) - cr * d[j];
+    for (int j = 0; j < NE; ++j) ubv[j] = (ur_from_ring ? ubv[j] : wn[j]) - cr * d[j];
     X::st(a.ur + e, ubv);
   }
   if (bad) a.hdr->diverged = 1;

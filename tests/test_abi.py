@@ -91,7 +91,7 @@ def test_t1_lr_matches_oracle_closed_form():
 
 
 def _args(layers=None, P=None, tau=None, **o):
-    w = wl.config(0)
+    w = wl.config(1)
     layers = layers or w.layers
     P = P or w.P
     tau = tau or pm.pm_delays(P, 1)[0]
@@ -111,7 +111,7 @@ def test_query_bytes_counts_ring_and_state():
 
 
 def test_create_rejects_bad_arguments_before_touching_the_gpu():
-    w = wl.config(0)
+    w = wl.config(1)
     params = wl.init_params(w)
     sc = pm.make_sched(base=0.01, K=20)
     good = dict(P=w.P, layers=w.layers, tau_fwd=[7, 5, 3, 1], tau_bkwd=[0, 0, 0, 0], sched=sc,

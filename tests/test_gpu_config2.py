@@ -20,9 +20,9 @@ pytestmark = pytest.mark.gpu
 
 @pytest.mark.timeout(1500)
 @pytest.mark.parametrize("launch", ["graph", "overlap", "graph_recompute4", "graph_stochastic"])
-def test_config1_bf16_mlp16_500_steps(launch):
+def test_config2_bf16_mlp16_500_steps(launch):
     import torch
-    w = wl.config(1)
+    w = wl.config(2)
     o_ = w.opt
     params = wl.init_params(w)
     tf, tb = po.pipeline_delays(w.P, 1)
@@ -34,6 +34,8 @@ def test_config1_bf16_mlp16_500_steps(launch):
         kw.update(tau_recomp=po.recompute_delays(w.P, 4, 1), segment=4)
         assert kw["tau_recomp"] == [6, 4, 2, 0] * 4
         launch, n_steps = "graph", 200
+    if launch == "overlap":
+        n_steps = 200            # not the default launch mode (and measured slower): a shorter run keeps the suite in budget
     stoch = None
     if launch == "graph_stochastic":
         # the same workload under Hogwild-style stochastic delays (means = the pipeline's delays), 150 steps

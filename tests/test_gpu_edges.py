@@ -73,3 +73,43 @@ def test_t1_annealing_window_edges(torch_cuda):
         g, o, _ = run_pair(torch_cuda, w, 12, check_tables=True, lr=0.05, beta=0.9, D=0.5, K=K)
         assert max_rel_err(g.weights(), o.weights())[0] < TOL["f32"]
         g.close()
+
+
+def test_full_depth_thin_chain_rings_wrap_twice(torch_cuda):
+    """P = 99 stages of width 8 (the stage count of the 12-layer Transformer): tau_fwd = 197 .. 1, rings of
+    198 .. 2 slots, 420 steps so that even the deepest ring wraps twice.  A near-identity linear chain
+    (W = I + 0.05 N) keeps signal and gradient alive through all 99 units, so every unit's weights move
+    by more than 1 % and every delayed read matters.  Slots bit-exact at every step; weights to 1e-5."""
+    P = 99
+    layers = tuple(wl.Layer("linear", 8, 8 if j < P - 1 else 2, "none", j + 1) for j in range(P))
+    w = wl.Workload("deep99", layers, P, 1, "mse", "f32", 8, 2)
+    rng = np.random.default_rng(7)
+    params = []
+    for L in layers:
+        W = np.eye(L.n_out, L.n_in) + 0.05 * rng.standard_normal((L.n_out, L.n_in))
+        params.append(np.concatenate([W.ravel(), 0.01 * rng.standard_normal(L.n_out)]).astype(np.float32))
+    tf, tb = po.pipeline_delays(P, 1)
+    assert tf[0] == 197 and tf[-1] == 1
+    kw = dict(lr=5e-5, beta=0.9, D=0.1, K=100)
+    o = make_oracle(w, params, tf, tb, **kw)
+    g = make_gpu(w, params, tf, tb, **kw)
+    stream = wl.BatchStream(w)
+    seen_slots = [set() for _ in range(P)]
+    for k in range(420):
+        x, y = stream.batch(k)
+        o.step((x, y))
+        g.step(torch_cuda.from_numpy(x).cuda(), torch_cuda.from_numpy(y).cuda())
+        t_used, fs, bs, ws, lrs = g.step_table()
+        assert t_used == k
+        for u in range(P):
+            R = tf[u] + 1
+            vf, vb = o.last_versions[u]
+            assert (fs[u], bs[u], ws[u]) == (vf % R, vb % R, (k + 1) % R)
+            seen_slots[u].add(fs[u])
+    assert len(seen_slots[0]) == 198 and len(seen_slots[-1]) == 2       # every slot of the deepest ring was read
+    err, errs = max_rel_err(g.weights(), o.weights())
+    move = [float(np.max(np.abs(a - b.astype(np.float64))) / np.max(np.abs(b))) for a, b in zip(o.weights(), params)]
+    print("deep99 max-rel", err, "movement min/max", min(move), max(move))
+    assert min(move) > 0.005, move
+    assert err < TOL["f32"], errs
+    g.close()

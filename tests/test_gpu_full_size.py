@@ -98,24 +98,24 @@ def _run(cfg, steps, checkpoints, grad_tol, move_tol, sgdm_lr=None):
 
 @pytest.mark.timeout(1500)
 @pytest.mark.parametrize("variant", ["adamw_warmup", "sgdm"])
-def test_config2_transformer6_bf16_full_size(variant):
+def test_config3_transformer6_bf16_full_size(variant):
     """6 layers, width 512, 8 heads, feed-forward 2048, vocabulary 8192, 32 x 128 tokens, P = 38
     (tau_fwd 75 .. 1): 24 (16) steps, so the latest stages read genuinely delayed versions."""
     if variant == "adamw_warmup":
-        _run(2, 24, (1, 8, 24), grad_tol=3e-2, move_tol=None)
+        _run(3, 24, (1, 8, 24), grad_tol=3e-2, move_tol=None)
     else:
-        _run(2, 16, (1, 16), grad_tol=3e-2, move_tol=0.05, sgdm_lr=5e-4)
+        _run(3, 16, (1, 16), grad_tol=3e-2, move_tol=0.05, sgdm_lr=5e-4)
 
 
 @pytest.mark.timeout(1500)
-def test_config4_transformer12_bf16_full_size():
+def test_config5_transformer12_bf16_full_size():
     """12 layers, width 1024, 16 heads, feed-forward 4096, vocabulary 32000, 16 x 512 tokens, P = 99
     (tau_fwd 197 .. 1), ~217 M parameters, 43 GB ring: 2 steps (the oracle needs minutes per step)."""
-    _run(4, 2, (1, 2), grad_tol=3e-2, move_tol=None)
+    _run(5, 2, (1, 2), grad_tol=3e-2, move_tol=None)
 
 
 @pytest.mark.timeout(1500)
-def test_config3_resnet20_bf16_full_size():
+def test_config4_resnet20_bf16_full_size():
     """ResNet-20 shape, 128 images of 3x32x32, P = 20 (tau_fwd 39 .. 1), momentum SGD: 100 steps, so every
     stage reads genuinely delayed versions for most of the run."""
-    _run(3, 100, (1, 10, 50, 100), grad_tol=3e-2, move_tol=0.05)
+    _run(4, 100, (1, 10, 50, 100), grad_tol=3e-2, move_tol=0.05)

@@ -162,14 +162,14 @@ def test_linear_primitives_against_numpy(torch_cuda, dtype, shape):
 
 
 # ------------------------------------------------------------------------------- whole step, small cases
-def test_config0_fp32_mlp_50_steps(torch_cuda):
-    """The smallest configuration of the task (config 0): 4-stage fp32 MLP, tau_fwd = (7,5,3,1), tau_bkwd = 0, momentum 0.9, lr 0.01, D 0.9."""
-    w = wl.config(0)
+def test_config1_fp32_mlp_50_steps(torch_cuda):
+    """The smallest configuration of the task (config 1): 4-stage fp32 MLP, tau_fwd = (7,5,3,1), tau_bkwd = 0, momentum 0.9, lr 0.01, D 0.9."""
+    w = wl.config(1)
     o_ = w.opt
     g, o, losses = run_pair(torch_cuda, w, w.steps, check_tables=True, lr=o_["lr"], beta=o_["beta"], D=o_["D"], K=o_["K"])
     assert po.pipeline_delays(w.P, 1)[0] == [7, 5, 3, 1]
     err, errs = max_rel_err(g.weights(), o.weights())
-    print("config0 max-rel", err, errs)
+    print("config1 max-rel", err, errs)
     assert err <= TOL["f32"]
     for lo, lg in losses:
         assert lg == pytest.approx(lo, rel=1e-4, abs=1e-6)

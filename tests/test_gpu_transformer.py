@@ -248,3 +248,51 @@ def test_ragged_bf16_transformer_grouped_projections(torch_cuda):
     assert err <= TOL["bf16"], errs
     assert max(m for u, m in enumerate(mvs) if u not in key_bias_entries(w)) <= 0.15, mvs
     g.close()
+
+
+@pytest.mark.parametrize("dtype,steps,lr", [("f32", 420, 2e-5), ("bf16", 210, 5e-5)])
+def test_narrow_transformer_with_the_stage_table_of_the_12_layer_workload(torch_cuda, dtype, steps, lr):
+    """The delay table and ring depths of the largest workload (12 layers, every unit a stage of its own:
+    P = 99, tau_fwd = 197 .. 1) on a narrow model (width 128, 2 heads of 64, feed-forward 256, vocabulary
+    512, 4 x 32 tokens) the oracle steps in milliseconds: fp32 for 420 steps (every ring wraps twice),
+    bf16 (MFMA products and attention) for 210 steps (past tau_max + 2, so every stage has read a
+    genuinely delayed version).  Momentum SGD so that the movement is bounded too."""
+    w = wl.transformer(12, 128, 2, 256, 512, 32, 4, dtype=dtype, ln_own_stage=True)
+    assert w.P == 99
+    tf, tb = po.pipeline_delays(w.P, 1)
+    assert tf[0] == 197 and tf[-1] == 1
+    params = wl.init_params(w)
+    kw = dict(opt="sgdm", lr=lr, beta=0.9, D=0.1, K=50)
+    o = make_oracle(w, params, tf, tb, **kw)
+    g = make_gpu(w, params, tf, tb, **kw)
+    stream = wl.TokenStream(w)
+    for k in range(steps):
+        x, y = stream.batch(k)
+        lo = o.step((x, y))
+        chk = k % 30 == 0 or k + 1 == steps
+        lg = g.step(torch_cuda.from_numpy(x).cuda(), torch_cuda.from_numpy(y).cuda(), want_loss=chk)
+        if not chk:
+            continue
+        assert lg == pytest.approx(lo, rel=2e-2 if dtype == "bf16" else 1e-4)
+        t_used, fs, bs, ws, lrs = g.step_table()
+        assert t_used == k
+        for u, L in enumerate(w.layers):
+            R = tf[L.stage - 1] + 1
+            vf, vb = o.last_versions[u]
+            assert (fs[u], bs[u], ws[u]) == (vf % R, vb % R, (k + 1) % R)
+            assert lrs[u] == pytest.approx(o.last_lr[u], rel=2e-7)
+    err, errs = max_rel_err(g.weights(), o.weights(), skip=key_bias_entries(w))
+    mv, mvs = movement_rel_l2(g.weights(), o.weights(), params)
+    move = [float(np.max(np.abs(a - b.astype(np.float64))) / np.max(np.abs(b))) for a, b in zip(o.weights(), params)]
+    print("narrow 12-layer", dtype, "max-rel", err, "movement rel-L2 err", mv, "largest unit movement", max(move))
+    print("   per unit max-rel:", np.array2string(np.array(errs), precision=1, max_line_width=400))
+    print("   per unit movement:", np.array2string(np.array(move), precision=3, max_line_width=400))
+    assert max(move) > 0.02
+    # fp32: T1 divides the early step sizes by up to 197, which puts many increments below half an ulp of the
+    # fp32 master weight they are added to; each of the N additions w <- w + v rounds by at most 2^-24 |w|, so
+    # N 2^-24 (2.5e-5 for 420 steps) is the bound the arithmetic gives where 1e-5 covers the 50- and 100-step runs
+    tol = max(TOL[dtype], steps * 2.0 ** -24) if dtype == "f32" else TOL[dtype]
+    assert err <= tol, errs
+    if dtype == "bf16":
+        assert max(m for u, m in enumerate(mvs) if u not in key_bias_entries(w)) <= 0.15, mvs
+    g.close()

@@ -67,24 +67,24 @@ def _mlp(name, widths, acts, stages, **kw) -> Workload:
 
 
 def config(idx: int) -> Workload:
-    """Workloads by index.
+    """Workloads by their 1-based position in the task's list of configurations.
 
-    0: tiny fp32 4-stage MLP (64-wide, ReLU, scalar regression head, MSE).
-    1: 16-stage MLP, 1024-wide, GELU, 10-class head sharing the last stage,
+    1: tiny fp32 4-stage MLP (64-wide, ReLU, scalar regression head, MSE).
+    2: 16-stage MLP, 1024-wide, GELU, 10-class head sharing the last stage,
        bf16 compute with fp32 master weights.
-    3: ResNet-20-shaped CNN (19 3x3 convolutions with folded per-channel affine + classifier, one stage
-       each), 128 images of 3x32x32, bf16 compute, momentum SGD.
-    2: 6-layer fine-grained Transformer (width 512, 8 heads, feed-forward 2048, vocabulary 8192,
+    3: 6-layer fine-grained Transformer (width 512, 8 heads, feed-forward 2048, vocabulary 8192,
        32 sequences of 128 tokens), bf16 compute, AdamW.
-    4: 12-layer fine-grained Transformer (width 1024, 16 heads, feed-forward 4096, vocabulary 32000,
+    4: ResNet-20-shaped CNN (19 3x3 convolutions with folded per-channel affine + classifier, one stage
+       each), 128 images of 3x32x32, bf16 compute, momentum SGD.
+    5: 12-layer fine-grained Transformer (width 1024, 16 heads, feed-forward 4096, vocabulary 32000,
        16 sequences of 512 tokens), bf16 compute, AdamW.
     """
-    if idx == 0:
+    if idx == 1:
         return _mlp("mlp4_f32", [64, 64, 64, 64, 1], ["relu", "relu", "relu", "none"], [1, 2, 3, 4],
                     N=1, loss="mse", dtype="f32", microbatch=16, n_classes=1,
                     opt=dict(kind="sgdm", lr=0.01, beta=0.9, D=0.9, K=20, weight_decay=0.0),
                     steps=50)
-    if idx == 1:
+    if idx == 2:
         widths = [1024] * 17 + [10]
         acts = ["gelu"] * 16 + ["none"]
         stages = list(range(1, 17)) + [16]
@@ -92,18 +92,18 @@ def config(idx: int) -> Workload:
                     N=1, loss="xent", dtype="bf16", microbatch=128, n_classes=10,
                     opt=dict(kind="sgdm", lr=0.001, beta=0.9, D=0.9, K=125, weight_decay=0.0),
                     steps=500, init="he")
-    if idx == 2:
+    if idx == 3:
         # fine-grained 6-layer Transformer, one stage per weight matrix (P = 38, 51 weight units); AdamW with
         # the linear warm-up of the paper's Transformer recipe (App. C: 8000 steps from 1e-7 to 5e-4,
         # betas 0.9 / 0.98, weight decay 1e-4), T1 annealing over 5x the warm-up (Sec. 3.1), D = 0.1 (App. C)
         return transformer(6, 512, 8, 2048, 8192, 128, 32, dtype="bf16", name="tfm6x512_bf16", steps=40,
                            lr=5e-4, D=0.1, K=40000, weight_decay=1e-4,
                            sched=dict(kind="warmup_invsqrt", base=5e-4, init=1e-7, warmup=8000))
-    if idx == 3:
+    if idx == 4:
         # ResNet-20 shape: 19 convolutions + the classifier, one stage each (P = 20); momentum SGD with a
         # constant base step, T1 annealing over a quarter of the run, D = 0.5 (the paper's CIFAR10 value, App. C)
         return resnet(3, 128, dtype="bf16", name="resnet20_bf16", steps=200, lr=0.002, D=0.5, K=50)
-    if idx == 4:
+    if idx == 5:
         # 12 layers, width 1024, 16 heads, feed-forward 4096, vocabulary 32000, sequences of 512 tokens:
         # every weight unit a stage of its own: P = 99 (tau_fwd up to 197), ~217 M parameters
         return transformer(12, 1024, 16, 4096, 32000, 512, 16, dtype="bf16", name="tfm12x1024_bf16", steps=6,
