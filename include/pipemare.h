@@ -345,6 +345,21 @@ pm_status pm_conv3x3_bwd_weight(void* stream, int32_t dtype, int32_t B, int32_t 
                                 int32_t stride, const void* dz_dev, const void* x_dev, float* dW_dev, void* scratch_dev,
                                 size_t scratch_bytes);
 
+/* pm_conv3x3_bwd_weight for callers that cannot allocate device memory or bring a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the per-block partial results go
+ * to a fixed array inside the library (pm_static_scratch_bytes: 16 MiB, held once per GPU the library runs
+ * on until the process ends) instead of a caller-provided workspace.  Same arguments, layouts and results as
+ * pm_conv3x3_bwd_weight otherwise (dW overwritten).  Calls no allocating routine.  A shape whose partial
+ * results exceed the array (pm_conv3x3_bwd_weight_scratch reports the need) is rejected with PM_ENOMEM and
+ * nothing is launched.  The device current in the calling thread must be the one the pointers and the
+ * stream belong to; the first call on a device looks up the array's address there (make one call before
+ * capturing a graph).  All calls on one GPU share the array: two calls whose kernels overlap in time (on
+ * different streams) race; calls on one stream are ordered. */
+pm_status pm_static_scratch_bytes(size_t* out_bytes);
+pm_status pm_conv3x3_bwd_weight_static(void* stream, int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t C_in,
+                                       int32_t C_out, int32_t stride, const void* dz_dev, const void* x_dev,
+                                       float* dW_dev);
+
 /* Waits for everything the context has enqueued, on the caller's stream and on the library's
  * second stream (overlap_update). */
 pm_status pm_synchronize(pm_ctx* ctx);

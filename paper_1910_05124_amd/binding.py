@@ -20,6 +20,7 @@ __all__ = [
     "pm_linear_fwd", "pm_linear_bwd_data", "pm_linear_bwd_weight", "pm_profile_begin", "pm_profile_end", "pm_profile_classes", "pm_profile_begin_classes",
     "pm_synchronize", "pm_checkpoint_bytes", "pm_checkpoint_save", "pm_checkpoint_load", "PipeMare", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
     "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight", "pm_conv3x3_bwd_weight_scratch",
+    "pm_conv3x3_bwd_weight_static", "pm_static_scratch_bytes",
     "PM_LINEAR", "PM_KIND", "PM_ARCH", "PM_ACT", "PM_METHOD", "PM_LR", "PM_OPT", "PM_DTYPE", "PM_LOSS", "EXPORTS",
 ]
 
@@ -53,6 +54,7 @@ EXPORTS = ["pm_status_str", "pm_last_error", "pm_delays", "pm_slots", "pm_t1_lr"
            "pm_set_grads", "pm_apply_update", "pm_profile_begin", "pm_profile_end", "pm_profile_classes", "pm_profile_begin_classes", "pm_linear_fwd", "pm_linear_bwd_data",
            "pm_linear_bwd_weight", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
            "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight", "pm_conv3x3_bwd_weight_scratch",
+           "pm_conv3x3_bwd_weight_static", "pm_static_scratch_bytes",
            "pm_checkpoint_bytes", "pm_checkpoint_save", "pm_checkpoint_load", "pm_synchronize", "pm_destroy"]
 
 
@@ -125,6 +127,8 @@ lib.pm_conv3x3_fwd.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _v
 lib.pm_conv3x3_bwd_data.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
 lib.pm_conv3x3_bwd_weight.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, C.c_size_t]
 lib.pm_conv3x3_bwd_weight_scratch.argtypes = [_i32, _i32, _i32, _i32, _i32, _i32, _i32, C.POINTER(C.c_size_t)]
+lib.pm_conv3x3_bwd_weight_static.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
+lib.pm_static_scratch_bytes.argtypes = [C.POINTER(C.c_size_t)]
 lib.pm_synchronize.argtypes = [_vp]
 lib.pm_destroy.argtypes = [_vp]
 lib.pm_destroy.restype = None
@@ -350,6 +354,16 @@ def pm_conv3x3_bwd_weight_scratch(dtype, B, H, W, C_in, C_out, stride) -> int:
 def pm_conv3x3_bwd_weight(stream, dtype, B, H, W, C_in, C_out, stride, dz, x, dW, scratch=None, scratch_bytes=0):
     _check(lib.pm_conv3x3_bwd_weight(_vp(stream), PM_DTYPE[dtype], B, H, W, C_in, C_out, stride, dz, x, dW, scratch,
                                      scratch_bytes))
+
+
+def pm_static_scratch_bytes() -> int:
+    out = C.c_size_t()
+    _check(lib.pm_static_scratch_bytes(C.byref(out)))
+    return out.value
+
+
+def pm_conv3x3_bwd_weight_static(stream, dtype, B, H, W, C_in, C_out, stride, dz, x, dW):
+    _check(lib.pm_conv3x3_bwd_weight_static(_vp(stream), PM_DTYPE[dtype], B, H, W, C_in, C_out, stride, dz, x, dW))
 
 
 def make_sched(kind="const", base=0.01, init=0.0, factor=1.0, interval=1, K=0) -> pm_lr_sched:

@@ -11,6 +11,7 @@
 #include <cstdlib>
 #include <climits>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -1819,6 +1820,63 @@ pm_status pm_conv3x3_bwd_weight(void* stream, int32_t dtype, int32_t B, int32_t 
 namespace {
 pm_status profile_begin(pm_ctx* c, int32_t max_steps, bool classes);
 }
+// ---- the entry point that allocates nothing: the weight gradient of a convolution with its per-block
+// partial results in a fixed device array of this library instead of a caller-provided workspace.
+// Every GPU the library runs on holds its own copy of the array (at its own address) until the process
+// ends; host code reaches it only through the address looked up once per device below.
+constexpr size_t PM_STATIC_SCRATCH_BYTES = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char pm_static_scratch[PM_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int PM_MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[PM_MAX_DEVICES] = {};
+
+// device address of pm_static_scratch on the current device (looked up on the first call per device)
+pm_status static_scratch(void** out) {
+  int dev = -1;
+  PM_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= PM_MAX_DEVICES) return fail(PM_EINVAL, "device index %d outside 0..%d", dev, PM_MAX_DEVICES - 1);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    PM_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(pm_static_scratch)));
+    if (!p) return fail(PM_EHIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return PM_OK;
+}
+}  // namespace
+
+pm_status pm_static_scratch_bytes(size_t* out_bytes) {
+  if (!out_bytes) return fail(PM_EINVAL, "out_bytes is NULL");
+  *out_bytes = PM_STATIC_SCRATCH_BYTES;
+  return PM_OK;
+}
+
+pm_status pm_conv3x3_bwd_weight_static(void* stream, int32_t dtype, int32_t B, int32_t H, int32_t W, int32_t C_in,
+                                       int32_t C_out, int32_t stride, const void* dz_dev, const void* x_dev,
+                                       float* dW_dev) {
+  pm_status s = check_conv(dtype, B, H, W, C_in, C_out, stride);
+  if (s != PM_OK) return s;
+  if (!dz_dev || !x_dev || !dW_dev) return fail(PM_EINVAL, "NULL argument");
+  const PmConvGeom g = conv_geom(B, H, W, C_in, C_out, stride);
+  const size_t need = 4 * (dtype == PM_BF16 ? pm_conv_wgrad_scratch_elems<bf16_t>(g) : pm_conv_wgrad_scratch_elems<float>(g));
+  if (need > PM_STATIC_SCRATCH_BYTES)
+    return fail(PM_ENOMEM, "this shape needs %zu bytes of partial results, the built-in scratch holds %zu: use "
+                           "pm_conv3x3_bwd_weight with a workspace", need, PM_STATIC_SCRATCH_BYTES);
+  void* scratch = nullptr;
+  if ((s = static_scratch(&scratch)) != PM_OK) return s;
+  // every block of the kernels writes all of its slice of the partial results before the reduce reads
+  // it, so nothing left by an earlier call needs clearing
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == PM_BF16) pm_conv_wgrad_launch<bf16_t>(st, g, (const bf16_t*)dz_dev, (const bf16_t*)x_dev, dW_dev, 0, (float*)scratch);
+  else pm_conv_wgrad_launch<float>(st, g, (const float*)dz_dev, (const float*)x_dev, dW_dev, 0, (float*)scratch);
+  PM_HIP(hipGetLastError());
+  return PM_OK;
+}
+
 pm_status pm_profile_begin(pm_ctx* c, int32_t max_steps) { return profile_begin(c, max_steps, false); }
 pm_status pm_profile_begin_classes(pm_ctx* c, int32_t max_steps) {
   if (max_steps > 64) return fail(PM_EINVAL, "a pass that records kernel classes takes at most 64 steps");
