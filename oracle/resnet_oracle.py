@@ -6,8 +6,9 @@ import it; it shares no code with the HIP library).
 
 It plugs into pipemare_oracle.PipeMareOracle as `model`: loss_and_grads(u_fwd, u_bkwd, batch)
 returns the gradient backpropagation produces when the forward pass uses the weights u_fwd and the
-backward pass uses u_bkwd (Sec. 2.1).  Activations, pre-activations and ReLU masks come from the
-forward pass; the backward pass reads a weight only where a gradient flows *through* it:
+backward pass uses u_bkwd (Sec. 2.1); with u_recomp the activations inside every segment of stages are
+rebuilt in the backward pass with a third weight set (see loss_and_grads).  Activations, pre-activations
+and ReLU masks come from the forward pass; the backward pass reads a weight only where a gradient flows *through* it:
   * convolution:        d(input) = transposed convolution of dz with W_bkwd   (dW uses the stored input)
   * per-channel affine: dz = da * scale_bkwd        (d scale = sum da * z_stored, d shift = sum da)
   * fully connected:    d(input) = dlogits @ W_bkwd
@@ -100,7 +101,32 @@ class ResNetModel:
         nw = co * 9 * ci
         return p[:nw].reshape(co, 9 * ci), p[nw:nw + co], p[nw + co:nw + 2 * co]
 
-    def loss_and_grads(self, u_fwd, u_bkwd, batch):
+    def _in_name(self, u):
+        return "img" if u == 0 else f"y{u - 1}"
+
+    def _conv_forward(self, u, p, get):
+        """Convolution unit u from the tensors it reads through get(name): its input (the image or the
+        previous unit's output) and, for the second convolution of a block, the block's input (shortcut).
+        z = conv(inp), a = s z + t (+ shortcut), y = relu(a)."""
+        ci, co, stride = self.specs[u]
+        W, s, t = self._conv_unit(p, u)
+        z = _im2col(get(self._in_name(u)), stride) @ W.T
+        a = z * s + t
+        if u >= 2 and (u - 1) % 2 == 1:          # second convolution of a block: add the shortcut of the block input
+            _, _, stride_block = self.specs[u - 1]
+            a = a + _shortcut(get(self._in_name(u - 1)), co, stride_block)
+        return {f"z{u}": z, f"y{u}": np.maximum(a, 0.0)}
+
+    def loss_and_grads(self, u_fwd, u_bkwd, batch, u_recomp=None, checkpoints=None):
+        """checkpoints (with u_recomp): indices of the units that open a segment (0 is always one).  The forward
+        pass is taken to keep only the tensors that cross a segment boundary; in the backward pass every
+        segment's convolution units first run again, in order, with the weights u_recomp - reading kept
+        forward tensors where the producer sits in an earlier segment and rebuilt ones where it sits in the
+        same segment - and a unit's backward then uses, for every stored tensor it needs (its input, its
+        pre-activation z, its output's ReLU mask), the rebuilt value if that tensor was produced in the unit's
+        own segment and the kept forward value otherwise (App. "Statistical efficiency and recompute").  The
+        classifier is not rebuilt (loss and its gradient come from the forward pass); its pooled input follows
+        the same rule.  Data gradients use u_bkwd as always."""
         x, labels = batch
         x = np.transpose(np.asarray(x, dtype=np.float64), (0, 2, 3, 1))        # NCHW -> NHWC
         labels = np.asarray(labels).astype(np.int64).reshape(-1)
@@ -108,26 +134,12 @@ class ResNetModel:
         F, Bk = u_fwd, u_bkwd
         nconv = len(self.specs)
 
-        # ---------------- forward with u_fwd.  conv u: z = conv(inp), a = s z + t (+ shortcut), y = relu(a)
-        inp, cols, zs, ys = [None] * nconv, [None] * nconv, [None] * nconv, [None] * nconv
-        cur = x
-        block_in = None
+        # ---------------- forward with u_fwd
+        fwd = {"img": x}
         for u in range(nconv):
-            ci, co, stride = self.specs[u]
-            W, s, t = self._conv_unit(F[u], u)
-            inp[u] = cur
-            cols[u] = _im2col(cur, stride)
-            z = cols[u] @ W.T
-            a = z * s + t
-            if u >= 1 and (u - 1) % 2 == 0:          # first convolution of a block
-                block_in = cur
-            if u >= 2 and (u - 1) % 2 == 1:          # second convolution of a block: add the shortcut
-                c_in_block, _, stride_block = self.specs[u - 1]
-                a = a + _shortcut(block_in, co, stride_block)
-            zs[u] = z
-            ys[u] = np.maximum(a, 0.0)
-            cur = ys[u]
-        pooled = cur.mean(axis=(1, 2))                                          # [B, 64]
+            fwd.update(self._conv_forward(u, F[u], fwd.__getitem__))
+        last = f"y{nconv - 1}"
+        pooled = fwd[last].mean(axis=(1, 2))                                    # [B, 64]
         nfc = self.ncls * 64
         Wf, bf = F[nconv][:nfc].reshape(self.ncls, 64), F[nconv][nfc:]
         logits = pooled @ Wf.T + bf
@@ -136,33 +148,52 @@ class ResNetModel:
         prob = ex / ex.sum(axis=1, keepdims=True)
         loss = float(np.mean(np.log(ex.sum(axis=1)) + zmax[:, 0] - logits[np.arange(B), labels]))
 
-        # ---------------- backward: stored forward quantities, weights from u_bkwd on the data path
+        # ---------------- recomputation: every segment's units again with u_recomp
+        if u_recomp is None:
+            def view(c, name):
+                return fwd[name]
+        else:
+            cps = sorted(set([0] + [int(c) for c in (checkpoints or [])]))
+            seg_of = [sum(1 for c in cps if c <= u) - 1 for u in range(nconv + 1)]
+            rebuilt = [dict() for _ in cps]
+            for u in range(nconv):
+                mine = rebuilt[seg_of[u]]
+                mine.update(self._conv_forward(u, u_recomp[u], lambda name, mine=mine: mine[name] if name in mine else fwd[name]))
+
+            def view(c, name):
+                mine = rebuilt[seg_of[c]]
+                return mine[name] if name in mine else fwd[name]
+
+        # ---------------- backward: stored (or rebuilt) quantities, weights from u_bkwd on the data path
         grads = [None] * self.n_units
         dlog = prob
         dlog[np.arange(B), labels] -= 1.0
         dlog = dlog / B
-        grads[nconv] = np.concatenate([(dlog.T @ pooled).ravel(), dlog.sum(axis=0)])
+        y_last = view(nconv, last)
+        grads[nconv] = np.concatenate([(dlog.T @ y_last.mean(axis=(1, 2))).ravel(), dlog.sum(axis=0)])
         Wf_b = Bk[nconv][:nfc].reshape(self.ncls, 64)
         dpool = dlog @ Wf_b
-        hw = cur.shape[1] * cur.shape[2]
-        dy = np.broadcast_to(dpool[:, None, None, :] / hw, cur.shape).copy()
+        hw = y_last.shape[1] * y_last.shape[2]
+        dy = np.broadcast_to(dpool[:, None, None, :] / hw, y_last.shape).copy()
         pending_shortcut = None        # gradient that reaches a block's input through its shortcut
         for u in range(nconv - 1, -1, -1):
             ci, co, stride = self.specs[u]
             W_b, s_b, _ = self._conv_unit(Bk[u], u)
-            da = dy * (ys[u] > 0.0)
+            da = dy * (view(u, f"y{u}") > 0.0)
             if u >= 2 and (u - 1) % 2 == 1:          # second convolution of a block: da also feeds the shortcut
                 pending_shortcut = da
-            ds = (da * zs[u]).sum(axis=(0, 1, 2))
+            ds = (da * view(u, f"z{u}")).sum(axis=(0, 1, 2))
             dt = da.sum(axis=(0, 1, 2))
             dz = da * s_b
             dz2 = dz.reshape(-1, co)
-            dW = dz2.T @ cols[u].reshape(-1, 9 * ci)
+            inp = view(u, self._in_name(u))
+            cols = _im2col(inp, stride)
+            dW = dz2.T @ cols.reshape(-1, 9 * ci)
             grads[u] = np.concatenate([dW.ravel(), ds, dt])
             if u == 0:
                 break
-            dcols = (dz2 @ W_b).reshape(cols[u].shape)
-            dy = _col2im(dcols, inp[u].shape, stride)
+            dcols = (dz2 @ W_b).reshape(cols.shape)
+            dy = _col2im(dcols, inp.shape, stride)
             if (u - 1) % 2 == 0:                      # first convolution of a block: its input is the block input
-                dy = dy + _shortcut_bwd(pending_shortcut, inp[u].shape, stride)
+                dy = dy + _shortcut_bwd(pending_shortcut, inp.shape, stride)
         return loss, grads

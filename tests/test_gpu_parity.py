@@ -111,6 +111,43 @@ def test_update_chunk_boundaries_large_unit(torch_cuda):
     g.close()
 
 
+@pytest.mark.parametrize("opt", ["sgdm", "adamw"])
+def test_update_large_streams_variant_every_element(torch_cuda, opt):
+    """Parameter streams beyond 1 GiB per pass take the update kernel's other access variant (non-temporal,
+    one group of four elements per thread, two blocks per chunk), otherwise reached only by the 12-layer
+    Transformer: 50 M parameters in three units (corrected with tau_bkwd = 0, corrected from a stored ring
+    version, uncorrected), 3 steps on given gradients, EVERY element of weights, delta and corrected weights
+    against the oracle."""
+    layers = (wl.Layer("linear", 4096, 4096, "relu", 1), wl.Layer("linear", 4096, 4097, "relu", 2),
+              wl.Layer("linear", 4097, 4096, "none", 3))
+    w = wl.Workload("upd_big", layers, 3, 1, "mse", "bf16", 4, 4096)
+    rng = np.random.default_rng(5)
+    params = [rng.uniform(-0.05, 0.05, size=wl.n_params(L)).astype(np.float32) for L in layers]
+    assert sum(p.size for p in params) * 32 > 1 << 30
+    tf, tb = [4, 2, 1], [0, 1, 1]
+    kw = dict(opt=opt, lr=0.02 if opt == "sgdm" else 3e-3, beta=0.9, weight_decay=0.01, D=0.3, K=4)
+    o = make_oracle(w, params, tf, tb, model=GivenGrads(), keep_history=True, **kw)
+    g = make_gpu(w, params, tf, tb, **kw)
+    for k in range(3):
+        grads = [(rng.standard_normal(p.size, dtype=np.float32) * 0.1) for p in params]
+        o.step(tuple(grads))
+        g.set_grads(grads)
+        g.apply_update()
+    err, errs = max_rel_err(g.weights(), o.weights())
+    assert err < 2e-6, errs
+    for u in range(len(layers)):
+        d = g.state(1, u)
+        assert np.max(np.abs(d - o.delta[u])) <= 2e-6 * np.max(np.abs(o.delta[u])) + 1e-7 * np.max(np.abs(o.weights(u)))
+        st = layers[u].stage - 1
+        if tf[st] > tb[st]:
+            want = o.hist[u][max(o.t - tb[st], 0)] - (tf[st] - tb[st]) * o.delta[u]
+            assert np.max(np.abs(g.state(3, u) - want)) <= 2.0 ** -7 * np.max(np.abs(want))
+    # the newest ring slot is what the next forward of a tau = 1 stage reads: compare through the step table
+    t_used, fs, bs, ws, lrs = g.step_table()
+    assert t_used == 2 and list(ws) == [3 % 5, 3 % 3, 3 % 2]
+    g.close()
+
+
 # ------------------------------------------------------------------------------- linear primitives
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("shape", [(128, 1024, 1024), (48, 72, 200), (300, 264, 136), (128, 1024, 16), (16, 64, 64),
