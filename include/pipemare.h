@@ -133,13 +133,18 @@ typedef struct {
                                 cross-entropy (loss must be PM_LOSS_XENT).  Channel counts multiples of 8.  pm_step
                                 takes fp32 images [microbatch, c0_in, image_size, image_size] (NCHW) as x and int32
                                 labels [microbatch] as y. */
-  const int32_t* tau_recomp; /* host, P entries or NULL.  Non-NULL turns on recomputation (PM_ARCH_CHAIN only; App.
+  const int32_t* tau_recomp; /* host, P entries or NULL.  Non-NULL turns on recomputation (all architectures; App.
                                 "Statistical efficiency and recompute"): the forward pass is taken to keep only the
-                                input of every segment of `segment_size` consecutive stages; the backward pass rebuilds
-                                the activations inside a segment from that input with the weights of version
-                                max(t - tau_recomp,i, 0), corrected - when t2_enabled - by (tau_fwd,i - tau_recomp,i)
-                                delta_t ("T2 for Recompute").  Needs tau_bkwd,i <= tau_recomp,i <= tau_fwd,i.
-                                pm_recompute_delays gives the delays of PipeMare Recompute. */
+                                tensors that enter a segment of `segment_size` consecutive stages from an earlier
+                                one; the backward pass rebuilds the activations inside a segment from those with the
+                                weights of version max(t - tau_recomp,i, 0), corrected - when t2_enabled - by
+                                (tau_fwd,i - tau_recomp,i) delta_t ("T2 for Recompute").  A unit's backward (and the
+                                rebuild itself) uses the rebuilt value of a tensor produced in the unit's own
+                                segment and the kept forward value of one produced in an earlier segment; a
+                                weight-free operator (attention core, residual add, pooling) belongs to the unit
+                                that consumes its result; the loss gradient comes from the forward pass.  Needs
+                                tau_bkwd,i <= tau_recomp,i <= tau_fwd,i.  pm_recompute_delays gives the delays of
+                                PipeMare Recompute. */
   int32_t segment_size;      /* stages per segment (>= 1) when tau_recomp is given; the last segment may be shorter */
   int32_t stochastic_delays; /* 1: Hogwild-style stochastic delays (App. "Hogwild! asynchrony"): at every optimizer step
                                 each stage i draws a delay from the exponential distribution with mean tau_fwd[i-1]

@@ -196,7 +196,6 @@ pm_status validate(int32_t P, int32_t L, const pm_layer_desc* layers, const int3
     if (o->tau_recomp) return fail(PM_EINVAL, "stochastic delays and recomputation are not combined");
   }
   if (o->tau_recomp) {
-    if (o->arch != PM_ARCH_CHAIN) return fail(PM_EINVAL, "recomputation is implemented for PM_ARCH_CHAIN only");
     if (o->segment_size < 1) return fail(PM_EINVAL, "recomputation needs segment_size >= 1 (stages per segment)");
     for (int i = 0; i < P; ++i) {
       const int tb = tau_bkwd ? tau_bkwd[i] : 0;
@@ -757,19 +756,30 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
     return U(u).corr ? PmWLoc<T>{ub + U(u).off + extra, nullptr, 0}
                      : PmWLoc<T>{ring + U(u).ring_off + extra, &tab[u].bkwd_slot, U(u).n_pad};
   };
+  // the weights that rebuild unit u's activations in a recomputing backward pass: the unit's own corrected
+  // copy, the corrected backward weights where delay and coefficient coincide, else the plain version
+  // max(t - tau_recomp, 0) read in place from the ring
+  T* ur = lay.has_ur ? c->at<T>(lay.ur_off) : nullptr;
+  auto Wr = [&](int u, int64_t extra) {
+    if (U(u).corr_r) return PmWLoc<T>{ur + U(u).off + extra, nullptr, 0};
+    if (U(u).tau_r == U(u).tau_b && U(u).corr) return PmWLoc<T>{ub + U(u).off + extra, nullptr, 0};
+    return PmWLoc<T>{ring + U(u).ring_off + extra, &tab[u].rec_slot, U(u).n_pad};
+  };
+  bool rebuilding = false;     // the forward helpers below read Wr instead of Wf while a segment is rebuilt
+  auto Wx = [&](int u, int64_t extra) { return rebuilding ? Wr(u, extra) : Wf(u, extra); };
   // z = a_in W_fwd^T + b (optional), a = act(z)
   auto lin_fwd = [&](int u, const T* a_in, int n_in, int n_out, T* z, T* a, int act) {
     PmEpiFwd<T> epi;
-    epi.bias = Wf(u, U(u).boff);
+    epi.bias = Wx(u, U(u).boff);
     epi.z = z; epi.a = a; epi.z32 = nullptr; epi.ld = n_out; epi.act = act; epi.b_ = nullptr;
-    launch_gemm<T>(c, Tk, n_out, n_in, a_in, n_in, 1, Wf(u, 0), n_in, 1, epi);
+    launch_gemm<T>(c, Tk, n_out, n_in, a_in, n_in, 1, Wx(u, 0), n_in, 1, epi);
   };
   // out = res + a_in W_fwd^T + b   (fp32 residual stream)
   auto lin_fwd_res = [&](int u, const T* a_in, int n_in, int n_out, const float* res, float* out) {
     PmEpiFwdRes<T> epi;
-    epi.bias = Wf(u, U(u).boff);
+    epi.bias = Wx(u, U(u).boff);
     epi.res = res; epi.out = out; epi.ld = n_out; epi.b_ = nullptr;
-    launch_gemm<T>(c, Tk, n_out, n_in, a_in, n_in, 1, Wf(u, 0), n_in, 1, epi);
+    launch_gemm<T>(c, Tk, n_out, n_in, a_in, n_in, 1, Wx(u, 0), n_in, 1, epi);
   };
   // dW = dz^T a_in, db = column sums of dz
   auto wgrad = [&](int u, const T* dz, int ld_dz, const T* a_in, int n_out, int n_in) {
@@ -819,7 +829,7 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
     dgrad_f32(u + 3, dzv, d, d, d, out, 1);
   };
   auto ln_fwd = [&](int u, const float* x, T* out, float* mu, float* rs) {
-    pm_ln_fwd_launch<T>(st, x, Wf(u, 0), (int)U(u).boff, out, mu, rs, Tk, d);
+    pm_ln_fwd_launch<T>(st, x, Wx(u, 0), (int)U(u).boff, out, mu, rs, Tk, d);
   };
   auto ln_bwd = [&](int u, const float* dy, const float* x, const float* mu, const float* rs, const float* dx_res,
                     float* dx_out, T* dx_t) {
@@ -827,17 +837,26 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
   };
   auto F = [&](size_t off) { return c->at<float>(off); };
   auto TT = [&](size_t off) { return c->at<T>(off); };
+  // Behind a ReLU the pre-activation need not be kept: the derivative mask of z is the mask of a = relu(z).
+  // The first feed-forward product then writes one output instead of two.
+  auto ff_keeps_z = [&](int u6) { return U(u6).d.act != PM_ACT_RELU; };
+  auto ff_mask_src = [&](const Layout::TfmLayer& b, int u6) { return ff_keeps_z(u6) ? TT(b.z1) : TT(b.f); };
 
   prof_mark(c, 0);
   hipLaunchKernelGGL(pm_begin_tokens_kernel, dim3(1), dim3(256), 0, st, c->hdr(), c->ls(), tab, accumulate ? 0 : L,
                      sched_dev(c), par);
   // ---- forward
   float* x0 = F(nl ? lay.tl[0].x : lay.t_xf);
-  {
+  auto embed_fwd = [&]() {
     const int64_t tot = (int64_t)Tk * d;
     hipLaunchKernelGGL((pm_embed_fwd_kernel<T>), dim3((unsigned)std::min<int64_t>(4096, (tot + 255) / 256)), dim3(256), 0,
-                       st, tokens, Wf(0, 0), F(lay.t_pos), x0, Tk, S, d, V);
-  }
+                       st, tokens, Wx(0, 0), F(lay.t_pos), x0, Tk, S, d, V);
+  };
+  auto attn_fwd = [&](const Layout::TfmLayer& b) {
+    ProfSpan span(c, PM_CLS_ATTN);
+    return pm_attn_fwd_launch<T>(st, B, S, H, dh, TT(b.q), TT(b.k), TT(b.v), TT(b.o), F(b.lse));
+  };
+  embed_fwd();
   for (int l = 0; l < nl; ++l) {
     const Layout::TfmLayer& b = lay.tl[l];
     const int u = 1 + 8 * l;
@@ -845,14 +864,10 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
     float* y = F(l + 1 < nl ? lay.tl[l + 1].x : lay.t_xf);
     ln_fwd(u, x, TT(b.n1), F(b.mu1), F(b.rs1));
     qkv_fwd(u, TT(b.n1), TT(b.q), TT(b.k), TT(b.v));
-    {
-      ProfSpan span(c, PM_CLS_ATTN);
-      if (!pm_attn_fwd_launch<T>(st, B, S, H, dh, TT(b.q), TT(b.k), TT(b.v), TT(b.o), F(b.lse)))
-        return fail(PM_EINVAL, "attention shape not supported");
-    }
+    if (!attn_fwd(b)) return fail(PM_EINVAL, "attention shape not supported");
     lin_fwd_res(u + 4, TT(b.o), d, d, x, F(b.h));
     ln_fwd(u + 5, F(b.h), TT(b.n2), F(b.mu2), F(b.rs2));
-    lin_fwd(u + 6, TT(b.n2), d, dff, TT(b.z1), TT(b.f), U(u + 6).d.act);
+    lin_fwd(u + 6, TT(b.n2), d, dff, ff_keeps_z(u + 6) ? TT(b.z1) : nullptr, TT(b.f), U(u + 6).d.act);
     lin_fwd_res(u + 7, TT(b.f), dff, d, F(b.h), y);
   }
   ln_fwd(L - 2, F(lay.t_xf), TT(lay.t_nf), F(lay.t_muf), F(lay.t_rsf));
@@ -882,19 +897,73 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
   auto wg = [&](int u, const T* dz, int ld_dz, const T* a_in, int n_out, int n_in) {
     if (!grouped) wgrad(u, dz, ld_dz, a_in, n_out, n_in);
   };
+  // Recomputation (App. on recompute; "T2 for Recompute"): the forward pass is taken to have kept only the
+  // tensors that cross a segment boundary.  Units are walked backwards; on entering a segment, all its units
+  // first run again in order with the weights Wr, overwriting their outputs in place.  At that moment every
+  // later segment has finished its backward pass, and no earlier one has been rebuilt: so a unit - in the
+  // rebuild and in its backward alike - sees rebuilt tensors exactly where the producer sits in its own segment
+  // and the kept forward tensors where it sits in an earlier one.  Weight gradients go out as soon as their unit
+  // is reached (their inputs may be overwritten by an earlier segment's rebuild).  The head is not rebuilt (the
+  // loss gradient comes from the forward pass).
+  auto seg_of = [&](int u) { return (U(u).d.stage - 1) / c->o.segment_size; };
+  auto rebuild_unit = [&](int u) -> bool {
+    if (u == 0) { embed_fwd(); return true; }
+    if (u == L - 2) { ln_fwd(u, F(lay.t_xf), TT(lay.t_nf), F(lay.t_muf), F(lay.t_rsf)); return true; }
+    const int l = (u - 1) / 8, j = (u - 1) % 8, u0 = 1 + 8 * l;
+    const Layout::TfmLayer& b = lay.tl[l];
+    switch (j) {
+      case 0: ln_fwd(u, F(b.x), TT(b.n1), F(b.mu1), F(b.rs1)); break;
+      case 1: lin_fwd(u, TT(b.n1), d, d, nullptr, TT(b.q), PM_ACT_NONE); break;
+      case 2: lin_fwd(u, TT(b.n1), d, d, nullptr, TT(b.k), PM_ACT_NONE); break;
+      case 3: lin_fwd(u, TT(b.n1), d, d, nullptr, TT(b.v), PM_ACT_NONE); break;
+      case 4:
+        if (!attn_fwd(b)) return false;
+        lin_fwd_res(u, TT(b.o), d, d, F(b.x), F(b.h));
+        break;
+      case 5: ln_fwd(u, F(b.h), TT(b.n2), F(b.mu2), F(b.rs2)); break;
+      case 6: lin_fwd(u, TT(b.n2), d, dff, ff_keeps_z(u) ? TT(b.z1) : nullptr, TT(b.f), U(u).d.act); break;
+      default: lin_fwd_res(u0 + 7, TT(b.f), dff, d, F(b.h), F(l + 1 < nl ? lay.tl[l + 1].x : lay.t_xf)); break;
+    }
+    return true;
+  };
+  auto enter = [&](int u) -> bool {       // called before the backward of unit u
+    if (!lay.recompute || (u < L - 1 && seg_of(u) == seg_of(u + 1))) return true;
+    int lo = u;
+    while (lo > 0 && seg_of(lo - 1) == seg_of(u)) --lo;
+    rebuilding = true;
+    bool ok = true;
+    for (int v = lo; v <= u && ok; ++v)
+      if (v != L - 1) ok = rebuild_unit(v);
+    rebuilding = false;
+    return ok;
+  };
+#define PM_ENTER(u) do { if (!enter(u)) return fail(PM_EINVAL, "attention shape not supported"); } while (0)
+  PM_ENTER(L - 1);
   wg(L - 1, TT(lay.t_dlogits), ldV, TT(lay.t_nf), V, d);
   dgrad_f32(L - 1, TT(lay.t_dlogits), ldV, V, d, dn, 0);
+  PM_ENTER(L - 2);
   ln_bwd(L - 2, dn, F(lay.t_xf), F(lay.t_muf), F(lay.t_rsf), nullptr, dx, nl ? TT(lay.tl[nl - 1].dz2) : nullptr);
   for (int l = nl - 1; l >= 0; --l) {
     const Layout::TfmLayer& b = lay.tl[l];
     const int u = 1 + 8 * l;
-    // y = h + f W2^T + b2
+    // y = h + f W2^T + b2.  The activation derivative of the first feed-forward matrix rides on this product
+    // unless a segment boundary separates the two: then it waits for the rebuilt pre-activations.
+    const bool split_act = lay.recompute && seg_of(u + 6) != seg_of(u + 7) && U(u + 6).d.act != PM_ACT_NONE;
+    PM_ENTER(u + 7);
     wg(u + 7, TT(b.dz2), d, TT(b.f), d, dff);
-    dgrad_t(u + 7, TT(b.dz2), d, dff, TT(b.z1), U(u + 6).d.act, TT(b.dz1));
+    dgrad_t(u + 7, TT(b.dz2), d, dff, ff_mask_src(b, u + 6), split_act ? (int)PM_ACT_NONE : U(u + 6).d.act, TT(b.dz1));
+    PM_ENTER(u + 6);
+    if (split_act) {
+      const int64_t tot = (int64_t)Tk * dff;
+      hipLaunchKernelGGL((pm_act_bwd_apply_kernel<T>), dim3((unsigned)std::min<int64_t>(4096, (tot / 4 + 255) / 256)), dim3(256), 0,
+                         st, TT(b.dz1), ff_mask_src(b, u + 6), U(u + 6).d.act, tot);
+    }
     wg(u + 6, TT(b.dz1), dff, TT(b.n2), dff, d);
     dgrad_f32(u + 6, TT(b.dz1), dff, dff, d, dn, 0);
+    PM_ENTER(u + 5);
     ln_bwd(u + 5, dn, F(b.h), F(b.mu2), F(b.rs2), dx, dx, TT(b.dzo));          // dx is now d loss / d h
     // h = x + o Wo^T + bo
+    PM_ENTER(u + 4);
     wg(u + 4, TT(b.dzo), d, TT(b.o), d, d);
     dgrad_t(u + 4, TT(b.dzo), d, d, nullptr, PM_ACT_NONE, TT(lay.t_do));
     {
@@ -903,12 +972,17 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
                                  TT(b.dzk), TT(b.dzv)))
         return fail(PM_EINVAL, "attention shape not supported");
     }
-    wg(u + 1, TT(b.dzq), d, TT(b.n1), d, d);
-    wg(u + 2, TT(b.dzk), d, TT(b.n1), d, d);
+    PM_ENTER(u + 3);
     wg(u + 3, TT(b.dzv), d, TT(b.n1), d, d);
+    PM_ENTER(u + 2);
+    wg(u + 2, TT(b.dzk), d, TT(b.n1), d, d);
+    PM_ENTER(u + 1);
+    wg(u + 1, TT(b.dzq), d, TT(b.n1), d, d);
     qkv_dgrad(u, TT(b.dzq), TT(b.dzk), TT(b.dzv), dn);
+    PM_ENTER(u);
     ln_bwd(u, dn, F(b.x), F(b.mu1), F(b.rs1), dx, dx, l ? TT(lay.tl[l - 1].dz2) : nullptr);   // dx is now d loss / d x
   }
+#undef PM_ENTER
   if constexpr (sizeof(T) == 2) {
     if (grouped) {
       ProfSpan span(c, PM_CLS_GEMM);
@@ -956,6 +1030,12 @@ pm_status launch_resnet(pm_ctx* c, const void* x_dev, const void* y_dev, int acc
     return U(u).corr ? PmWLoc<T>{ub + U(u).off + extra, nullptr, 0}
                      : PmWLoc<T>{ring + U(u).ring_off + extra, &tab[u].bkwd_slot, U(u).n_pad};
   };
+  T* ur = lay.has_ur ? c->at<T>(lay.ur_off) : nullptr;
+  auto Wr = [&](int u, int64_t extra) {       // the weights that rebuild unit u's activations (see launch_tfm)
+    if (U(u).corr_r) return PmWLoc<T>{ur + U(u).off + extra, nullptr, 0};
+    if (U(u).tau_r == U(u).tau_b && U(u).corr) return PmWLoc<T>{ub + U(u).off + extra, nullptr, 0};
+    return PmWLoc<T>{ring + U(u).ring_off + extra, &tab[u].rec_slot, U(u).n_pad};
+  };
   auto TT = [&](size_t off) { return c->at<T>(off); };
   const int fc = L - 1, C = U(fc).d.n_in, ncls = U(fc).d.n_out, ldc = (int)round_up(ncls, 8);
   const PmConvGeom& gl = lay.cv[nconv - 1].g;
@@ -972,7 +1052,7 @@ pm_status launch_resnet(pm_ctx* c, const void* x_dev, const void* y_dev, int acc
   }
   // ---- forward
   auto input_of = [&](int u) { return u == 0 ? TT(lay.r_x) : TT(lay.cv[u - 1].y); };
-  for (int u = 0; u < nconv; ++u) {
+  auto conv_fwd = [&](int u, PmWLoc<T> W) {
     const Layout::ConvBuf& b = lay.cv[u];
     PmShortcut<T> sc{nullptr, 0, 0, 0, 1};
     if (u >= 2 && (u % 2) == 0) {                     // second convolution of a block: add the block input
@@ -980,8 +1060,9 @@ pm_status launch_resnet(pm_ctx* c, const void* x_dev, const void* y_dev, int acc
       sc = PmShortcut<T>{input_of(u - 1), g1.H, g1.W, g1.Cin, g1.stride};
     }
     ProfSpan span(c, PM_CLS_GEMM);
-    pm_conv_fwd_launch<T>(st, b.g, input_of(u), Wf(u, 0), sc, TT(b.z), TT(b.y));
-  }
+    pm_conv_fwd_launch<T>(st, b.g, input_of(u), W, sc, TT(b.z), TT(b.y));
+  };
+  for (int u = 0; u < nconv; ++u) conv_fwd(u, Wf(u, 0));
   pm_pool_fwd_launch<T>(st, TT(lay.cv[nconv - 1].y), TT(lay.r_pool), B, HW, C);
   {
     PmEpiFwd<T> epi;
@@ -1000,6 +1081,20 @@ pm_status launch_resnet(pm_ctx* c, const void* x_dev, const void* y_dev, int acc
     const unsigned bx = (unsigned)std::max<int64_t>(1, std::min<int64_t>(64, lay.zero_max / 4 / 256));
     hipLaunchKernelGGL(pm_zero_regions_kernel, dim3(bx, lay.n_zero), dim3(256), 0, st, g, c->at<int64_t>(lay.t_zero));
   }
+  // Recomputation: on entering a segment (walking the units backwards) its convolutions run again in order with
+  // the weights Wr, overwriting their outputs in place; a unit then sees rebuilt tensors where the producer sits in
+  // its own segment and kept forward tensors where it sits in an earlier one (see launch_tfm).  The classifier is
+  // not rebuilt; its pooled input is, when the last convolution shares its segment.
+  auto seg_of = [&](int u) { return (U(u).d.stage - 1) / c->o.segment_size; };
+  auto enter = [&](int u) {                 // called before the backward of unit u
+    if (!lay.recompute || (u < L - 1 && seg_of(u) == seg_of(u + 1))) return;
+    int lo = u;
+    while (lo > 0 && seg_of(lo - 1) == seg_of(u)) --lo;
+    for (int v = lo; v <= u; ++v)
+      if (v < nconv) conv_fwd(v, Wr(v, 0));
+    if (u == fc && lo <= nconv - 1) pm_pool_fwd_launch<T>(st, TT(lay.cv[nconv - 1].y), TT(lay.r_pool), B, HW, C);
+  };
+  enter(fc);
   {
     PmEpiBwdWeight ew{g + U(fc).off, C, accumulate, nullptr};
     launch_gemm<T>(c, ncls, C, B, TT(lay.r_dlogits), 1, ldc, PmWLoc<T>{TT(lay.r_pool), nullptr, 0}, 1, C, ew);
@@ -1011,6 +1106,7 @@ pm_status launch_resnet(pm_ctx* c, const void* x_dev, const void* y_dev, int acc
                        TT(lay.r_dpool), TT(lay.cv[nconv - 1].dy), B, HW, C);
   }
   for (int u = nconv - 1; u >= 0; --u) {
+    enter(u);
     const Layout::ConvBuf& b = lay.cv[u];
     const int64_t nw = U(u).nw, tot = (int64_t)B * b.g.Ho * b.g.Wo * b.g.Cout;
     // the per-channel sums of the affine backward ride on the weight gradient's reduce launch when it has one
@@ -1416,7 +1512,7 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
         }
       }
       const int32_t longest = *std::max_element(load, load + 8);
-      c->dw_grouped = fits;
+      c->dw_grouped = fits && !lay.recompute;   // a recomputing backward needs each weight gradient at its unit's turn
       c->dw_aligned = aligned;
       c->dw_tile = TB;
       c->dw_nprob = np;

@@ -201,6 +201,19 @@ __global__ __launch_bounds__(256) void pm_bias_grad_chunked_kernel(const T* __re
     atomicAdd(db + col, part[0][threadIdx.x] + part[1][threadIdx.x] + part[2][threadIdx.x] + part[3][threadIdx.x]);
 }
 
+// dz <- dz * act'(z), element by element (n a multiple of 4): the activation derivative of a unit applied
+// apart from the matrix product that produced dz, for the case where the two belong to different segments
+// of a recomputing backward pass (the derivative must then wait for the rebuilt pre-activations).
+template <typename T>
+__global__ __launch_bounds__(256) void pm_act_bwd_apply_kernel(T* __restrict__ dz, const T* __restrict__ z, int act, int64_t n) {
+  const int64_t n4 = n >> 2;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x) {
+    const float4 g = pm_ld4(dz + 4 * i), zz = pm_ld4(z + 4 * i);
+    pm_st4(dz + 4 * i, make_float4(g.x * pm_act_bwd(zz.x, act), g.y * pm_act_bwd(zz.y, act), g.z * pm_act_bwd(zz.z, act),
+                                   g.w * pm_act_bwd(zz.w, act)));
+  }
+}
+
 __global__ __launch_bounds__(256) void pm_zero_f32_kernel(float* p, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0.f;
 }
