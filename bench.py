@@ -36,7 +36,7 @@ BYTES_PER_PARAM = {("sgdm", "bf16"): 32, ("adamw", "bf16"): 40, ("sgdm", "f32"):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None, help="timed steps (default per workload: 2000 / 500 / 200 / 300 / 100)")
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default per workload: 300 / 500 / 200 / 300 / 100)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps before (default 20; 10 for config 5)")
     ap.add_argument("--config", type=int, default=5,
                     help="position in the task's list of configurations (1: tiny fp32 MLP, 2: 16-stage bf16 MLP, "
@@ -60,7 +60,7 @@ def main():
                          "(a kernel of known traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings by)")
     args = ap.parse_args()
     if args.steps is None:
-        args.steps = {1: 2000, 2: 500, 3: 200, 4: 300, 5: 100}.get(args.config, 100)
+        args.steps = {1: 300, 2: 500, 3: 200, 4: 300, 5: 100}.get(args.config, 100)
     if args.warmup is None:
         args.warmup = 10 if args.config == 5 else 20
     if args.cpu_steps is None:
@@ -169,6 +169,8 @@ def main():
         gemm_flops = 6.0 * tokens * sum(L.n_in * L.n_out for L in lin)
         attn_flops = 6.0 * a["seq"] ** 2 * (a["d_model"] // a["n_heads"]) * w.microbatch * a["n_heads"] * a["n_layers"]
         gemm_flops += attn_flops
+        if tau_recomp is not None:      # the rebuilt forward: every product but the head, and the attention core's forward third
+            gemm_flops += 2.0 * tokens * sum(L.n_in * L.n_out for L in lin[:-1]) + attn_flops / 3.0
         samples = tokens
     elif is_cnn:
         # every convolution: forward, data gradient (not for the first), weight gradient, 2 * pixels_out * C_out * 9 C_in each
@@ -177,7 +179,7 @@ def main():
         for u, L in enumerate(w.layers[:-1]):
             if u > 0 and u % 2 == 1 and L.n_out == 2 * L.n_in:
                 H //= 2
-            gemm_flops += (3.0 if u > 0 else 2.0) * 2.0 * w.microbatch * H * H * L.n_out * 9 * L.n_in
+            gemm_flops += ((3.0 if u > 0 else 2.0) + (1.0 if tau_recomp is not None else 0.0)) * 2.0 * w.microbatch * H * H * L.n_out * 9 * L.n_in
         gemm_flops += 6.0 * w.microbatch * w.layers[-1].n_in * w.layers[-1].n_out
         samples = w.microbatch
     else:
@@ -227,10 +229,12 @@ def main():
                         "kernels_steps_timed": cls["n"],
                         "phase_achieved": round(gemm_flops / gemm_s / 1e12, 2) if gemm_s > 0 else None,
                         "phase_frac": round(gemm_flops / gemm_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5) if gemm_s > 0 else None,
-                        "note": "flops of the stages' matrix / convolution products (and the attention core); kernels_*: "
+                        "note": "flops of the stages' matrix / convolution products (and the attention core; with recomputation also of the rebuilt forward); kernels_*: "
                                 "over the summed duration of those kernels alone (HIP event pairs around each launch in "
                                 "the eager profiling pass); phase_*: over the whole forward + backward phase (loss, "
-                                "LayerNorm, bias-gradient, embedding kernels and launch gaps inside)"},
+                                "LayerNorm, bias-gradient, embedding kernels and launch gaps inside).  Where the products take a few "
+                                "microseconds each (configurations 1, 2, 4) the two markers per launch cost more than the kernels: "
+                                "read phase_* there"},
     }
     if args.cpu_steps > 0:
         out["cpu_baseline"] = cpu_baseline(w, params, tau_fwd, tau_bkwd, args.cpu_steps, tau_recomp, args.recompute, stoch)

@@ -30,7 +30,7 @@ def _rel_l2(a, b):
     return float(np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b), 1e-300))
 
 
-def _run(cfg, steps, checkpoints, grad_tol, move_tol, sgdm_lr=None):
+def _run(cfg, steps, checkpoints, grad_tol, move_tol, sgdm_lr=None, segment=0):
     """sgdm_lr None: the workload's own optimizer (AdamW on the paper's warm-up schedule, which starts at
     1e-7: together with the T1 division by tau the first steps are smaller than half an fp32 ulp of
     the master weights, so the training movement is reported but not bounded).  sgdm_lr given:
@@ -48,6 +48,8 @@ def _run(cfg, steps, checkpoints, grad_tol, move_tol, sgdm_lr=None):
                   weight_decay=o_["weight_decay"], sched=o_["sched"])
     else:
         kw = dict(opt="sgdm", lr=sgdm_lr, beta=0.9, D=o_["D"], K=8, weight_decay=o_["weight_decay"])
+    if segment > 0:        # recomputation in segments of `segment` stages with the delays of PipeMare Recompute
+        kw.update(tau_recomp=po.recompute_delays(w.P, segment, 1, tb), segment=segment)
     stream = wl.batch_stream(w)
     o = make_oracle(w, params, tf, tb, **kw)
     skip = key_bias_entries(w)
@@ -210,6 +212,20 @@ def test_config3_transformer6_bf16_live_oracle_sgdm():
     """6 layers, width 512, 8 heads, feed-forward 2048, vocabulary 8192, 32 x 128 tokens, P = 38 (tau_fwd 75 .. 1):
     16 steps of momentum SGD beside the live oracle, EVERY entry of every unit compared."""
     _run(3, 16, (1, 16), grad_tol=3e-2, move_tol=0.05, sgdm_lr=5e-4)
+
+
+@pytest.mark.timeout(900)
+def test_config3_transformer6_bf16_recompute_live_oracle():
+    """The same workload with recomputation in segments of 6 stages (tau_recomp = 10, 8, ..., 0 inside every
+    segment; "T2 for Recompute"): 8 steps beside the live oracle, every entry compared.  The cuts fall between
+    units of a layer (P = 38 = 1 + 6 per layer + 1), so kept and rebuilt tensors mix inside the layers."""
+    _run(3, 8, (1, 8), grad_tol=3e-2, move_tol=0.05, sgdm_lr=5e-4, segment=6)
+
+
+@pytest.mark.timeout(900)
+def test_config4_resnet20_bf16_recompute_live_oracle():
+    """ResNet-20 shape with recomputation in segments of 4 stages: 12 steps beside the live oracle."""
+    _run(4, 12, (1, 12), grad_tol=3e-2, move_tol=0.05, segment=4)
 
 
 @pytest.mark.timeout(900)

@@ -224,8 +224,9 @@ def test_modes_small(torch_cuda, case):
                                "overlap_gpipe", "overlap_warmup") else "f32"
     width = 72 if case != "ragged_bf16" else 50
     w = wl.small_mlp(width, 5, 6, "gelu", "xent", dtype, 24, layers_per_stage=2)
-    # bf16 contexts: a smaller step keeps 14 steps of rounding noise (activations, ring and
-    # corrected weights are stored in bf16) inside the 2e-3 band relative to max|w|
+    # bf16 contexts: at the fp32 cases' step (0.02) the 10-class head moves by 55 % of its largest entry in
+    # these 14 steps, and bf16's relative error on that movement (activations, ring and corrected weights are
+    # stored in bf16) comes to 3.8e-3 of max|w| (measured); at 0.005 the head moves 14 % and the error is 1.1e-3
     kw = dict(lr=0.02 if dtype == "f32" else 0.005, beta=0.9, D=0.5, K=8)
     tau, N, gpu_kw = None, 1, {}
     if case == "t2_off":

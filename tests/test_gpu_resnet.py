@@ -99,7 +99,7 @@ def test_small_resnet_modes(torch_cuda, case):
     dtype = "bf16" if case.endswith("bf16") else "f32"
     nb = 2 if case == "two_blocks_bf16" else 1
     w = wl.resnet(nb, 6, dtype=dtype, image=8)
-    kw = dict(opt="sgdm", lr=0.01 if dtype == "f32" else 0.005, beta=0.9, D=0.5, K=6)
+    kw = dict(opt="sgdm", lr=0.02, beta=0.9, D=0.5, K=6)
     tau, N = None, 1
     if case == "t2_off":
         kw["t2"] = False

@@ -173,7 +173,7 @@ def test_tiny_transformer_modes(torch_cuda, case):
     if case.startswith("wide_vocab"):
         V = 2501                   # rows wide enough for the row-resident loss kernel, ragged last group of 4
     w = wl.transformer(2, 32, 4, 64, V, 10, 3, dtype=dtype, K=6,
-                       sched=dict(kind="warmup_invsqrt", base=1e-3, init=1e-5, warmup=5))
+                       sched=dict(kind="warmup_invsqrt", base=2e-3, init=1e-5, warmup=5))
     kw = _kw(w)
     tau, N = None, 1
     if case == "sgdm_bf16":

@@ -102,7 +102,7 @@ def config(idx: int) -> Workload:
     if idx == 4:
         # ResNet-20 shape: 19 convolutions + the classifier, one stage each (P = 20); momentum SGD with a
         # constant base step, T1 annealing over a quarter of the run, D = 0.5 (the paper's CIFAR10 value, App. C)
-        return resnet(3, 128, dtype="bf16", name="resnet20_bf16", steps=200, lr=0.002, D=0.5, K=50)
+        return resnet(3, 128, dtype="bf16", name="resnet20_bf16", steps=200, lr=0.01, D=0.5, K=50)
     if idx == 5:
         # 12 layers, width 1024, 16 heads, feed-forward 4096, vocabulary 32000, sequences of 512 tokens:
         # every weight unit a stage of its own: P = 99 (tau_fwd up to 197), ~217 M parameters
