@@ -122,8 +122,12 @@ def _run_golden(name, *, grad_tol, move_tol, min_move=0.0):
     every step; per unit the sampled master weights (max |dw| / max |w| <= 2e-3) and the sampled consumed
     gradient (max |dg| / max |g| <= grad_tol, 4 x after the first step, when each side evaluates the
     gradient at its own slightly different weights); the segment sums of movement and gradient over ALL
-    entries; at the last checkpoint the movement w - w_0 on the samples (relative L2 <= move_tol) and
-    that the largest unit movement exceeds min_move (the weight bound is then not met vacuously)."""
+    entries; at the last checkpoint the movement w - w_0 on the samples and that the largest unit movement
+    exceeds min_move (the weight bound is then not met vacuously).  The movement bound is relative L2 <=
+    move_tol beyond what fp32 master weights cannot hold: an increment far below an entry's ulp is lost or
+    rounded up to one (a LayerNorm scale of 1.0 in a stage whose step size T1 divides by 197 moves by 1e-9 per
+    step, its ulp is 6e-8), so half an ulp per step and entry - steps x 2^-24 x ||w|| over the samples - is
+    allowed on top; at least a third of the units must lie above that floor, or the bound would say nothing."""
     import torch
     gm = _gold_module()
     path = os.path.join(_GOLD, f"full_size_{name}.npz")
@@ -161,7 +165,7 @@ def _run_golden(name, *, grad_tol, move_tol, min_move=0.0):
                 R = tau + 1
                 assert (fs[u], bs[u], ws[u]) == (max(k - tau, 0) % R, max(k - tb[L.stage - 1], 0) % R, (k + 1) % R)
                 assert lrs[u] == pytest.approx(po.t1_lr(po.base_lr(sched, k), tau, k, kw["K"]), rel=2e-7)
-            werrs, gerrs, merrs, moves = [], [], [], []
+            werrs, gerrs, merrs, moves, floored = [], [], [], [], 0
             for u in range(len(w.layers)):
                 key = f"k{k + 1}_u{u}_"
                 idx, gw, gg = gold[key + "idx"], gold[key + "w"].astype(np.float64), gold[key + "g"].astype(np.float64)
@@ -177,7 +181,10 @@ def _run_golden(name, *, grad_tol, move_tol, min_move=0.0):
                 werrs.append(float(np.max(np.abs(W[idx] - gw)[keep]) / maxw))
                 gerrs.append(float(np.max(np.abs(G[idx] - gg)[keep]) / max(maxg, 1e-300)))
                 mvs = gw - w0[idx]
-                merrs.append(float(np.linalg.norm(((W[idx] - w0[idx]) - mvs)[keep]) / max(np.linalg.norm(mvs[keep]), 1e-300)))
+                res = (k + 1) * 2.0 ** -24 * np.linalg.norm(gw[keep])
+                mvn = max(np.linalg.norm(mvs[keep]), 1e-300)
+                merrs.append(float(max(np.linalg.norm(((W[idx] - w0[idx]) - mvs)[keep]) - res, 0.0) / mvn))
+                floored += bool(move_tol is not None and res > move_tol * mvn)
                 moves.append(float(np.max(np.abs(mvs)) / maxw))
                 # every entry, through segment sums: |difference of sums| within a share of the absolute sum plus
                 # the noise of sqrt(n) independent element errors of the size the element bounds allow
@@ -193,7 +200,8 @@ def _run_golden(name, *, grad_tol, move_tol, min_move=0.0):
                 assert not bad_g.any(), (k + 1, u, "gradient segments", np.nonzero(bad_g)[0][:8])
             worst["w"], worst["g"] = max(worst["w"], max(werrs)), max(worst["g"], max(gerrs))
             print(f"after {k + 1} steps ({time.time() - t0:.0f}s): sampled weight max-rel {max(werrs):.3e}, sampled gradient max-rel "
-                  f"{max(gerrs):.3e}, movement rel-L2 {max(merrs):.3e}, largest unit movement {max(moves):.3e}", flush=True)
+                  f"{max(gerrs):.3e}, movement rel-L2 beyond fp32 resolution {max(merrs):.3e} ({floored} units below the floor), "
+                  f"largest unit movement {max(moves):.3e}", flush=True)
             print("   per unit weight max-rel", np.array2string(np.array(werrs), precision=1, max_line_width=250), flush=True)
             print("   per unit gradient max-rel", np.array2string(np.array(gerrs), precision=1, max_line_width=250), flush=True)
             print("   per unit movement rel-L2", np.array2string(np.array(merrs), precision=2, max_line_width=250), flush=True)
@@ -203,6 +211,7 @@ def _run_golden(name, *, grad_tol, move_tol, min_move=0.0):
                 assert max(moves) >= min_move, moves
                 if move_tol is not None:
                     assert max(merrs) <= move_tol, merrs
+                    assert 3 * floored <= 2 * len(w.layers), floored
         g.close()
     return worst
 
