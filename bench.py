@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--stochastic", type=int, default=-1,
                     help="TAU_MAX >= 0 turns on Hogwild-style stochastic delays: every step each stage draws its delay from "
                          "the exponential with the pipeline's delay as mean, truncated at TAU_MAX")
+    ap.add_argument("--chain", action="store_true",
+                    help="MLP workloads: the chained forward / data-gradient launches instead of one launch per product")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run three plain device-to-device copies of this many MiB after the timed region "
                          "(a kernel of known traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings by)")
@@ -99,7 +101,7 @@ def main():
                             overlap_update=(launch == "overlap"), arch=w.arch.get("kind", "chain"),
                             n_heads=w.arch.get("n_heads", 0), seq_len=w.arch.get("seq", 0),
                             image_size=w.arch.get("image", 0), tau_recomp=tau_recomp, segment_size=args.recompute,
-                            stochastic=stoch)
+                            stochastic=stoch, chained_launches=args.chain)
         eng = pm.PipeMare(w.layers, w.P, tau_fwd, tau_bkwd, sched, opts, params, stream=side)
         # Microbatches are resident in HBM before the timed region and handed over by pointer.  A captured
         # graph is bound to its batch buffers and the library keeps one graph per buffer pair, so the pool is

@@ -155,6 +155,13 @@ typedef struct {
                                 with recomputation. */
   int32_t tau_max;           /* stochastic delays: largest delay, 0 .. 65535 */
   uint64_t delay_seed;       /* stochastic delays: seed of the counter-based generator */
+  int32_t chained_launches;  /* 1 (PM_ARCH_CHAIN, bf16, at most 128 rows, a multiple of 32, unit widths multiples of
+                                64): the forward products of all such units (Sec. 2.1: one per stage, each waiting
+                                for the one before) run as ONE persistent launch whose blocks pass the activations
+                                to each other through device memory, likewise the data-gradient products.  Same
+                                results up to the order of the fp32 partial sums.  0 (default): one launch per
+                                product, which measures slightly faster on the 16-layer MLP workload.  Ignored
+                                for other shapes, with recomputation and with overlap_update. */
 } pm_opts;
 
 const char* pm_status_str(pm_status s);
@@ -256,6 +263,12 @@ pm_status pm_device_step_table(pm_ctx* ctx, int64_t* t_used, int32_t* fwd_slot, 
  * step, from the device-resident step table (host array of L entries, may be NULL).
  * PM_ESTATE without recomputation.  Synchronises. */
 pm_status pm_device_recompute_slots(pm_ctx* ctx, int64_t* t_used, int32_t* rec_slot);
+
+/* How many units the chained launches of this context cover (see pm_opts.chained_launches): units 0 ..
+ * *n_forward - 1 run forward as one launch, the data-gradient products of units *n_backward .. 1 as one launch;
+ * 0 = that direction keeps one launch per product (option off, or the shapes do not qualify).  Either output may
+ * be NULL.  No device work. */
+pm_status pm_chained_units(pm_ctx* ctx, int32_t* n_forward, int32_t* n_backward);
 
 /* Running numbers: mean loss of the most recent MICROBATCH (with n_microbatches > 1 not the mean over the
  * minibatch), global L2 norm of the averaged minibatch gradient of the last update (only when clipping

@@ -19,6 +19,7 @@
 #include "pm_elem.hpp"
 #include "pm_gemm_mfma.hpp"
 #include "pm_update.hpp"
+#include "pm_chain.hpp"
 #include "pm_transformer.hpp"
 #include "pm_conv.hpp"
 
@@ -92,6 +93,7 @@ struct Layout {
   size_t esz = 4;         // bytes per element of the compute dtype
   // byte offsets
   size_t w_off, g_off, v_off, s_off, d_off, ub_off, ur_off, cdf_off, ring_off, chunk_off, ls_off, ld_off, hdr_off, probs_off, x_off;
+  size_t chain_f_off, chain_b_off;                         // unit tables of the chained launches
   size_t act_begin, act_end, total;
   // Transformer activations (byte offsets; see launch_tfm).  Per layer: index [layer]
   struct TfmLayer {
@@ -275,6 +277,8 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
   lay.ld_off = take(sizeof(PmLayerStep) * L * 2);
   lay.hdr_off = take(sizeof(PmStepHdr));
   lay.probs_off = take(sizeof(PmGemmProb<PmEpiBwdWeight>) * 2 * L);
+  lay.chain_f_off = take(sizeof(PmChainFwd) * L);
+  lay.chain_b_off = take(sizeof(PmChainBwd) * L);
   const int M = o->microbatch;
   lay.act_begin = p;
   if (o->arch == PM_ARCH_TRANSFORMER) {
@@ -384,6 +388,10 @@ struct pm_ctx {
   int dw_max_segs = 0;
   bool dw_aligned = false;           // no tile of the grouped launch needs a bounds test
   int dw_tile = 128;                 // block tile of the grouped launch (128 or 256)
+  // MLP chain with few rows: units 0 .. chain_nf - 1 run forward as one chained launch, the data gradients of
+  // units chain_hb .. 1 as another (0: the launch-per-product path)
+  int chain_nf = 0, chain_hb = 0, chain_grid = 0;
+  int64_t chain_fill16 = 0;   // 16-byte words from the first unit's z to the last unit's dz (filled before every chained pass)
   // overlap of the update of step t with the forward of step t+1 (second stream owned by the library)
   bool overlap = false;
   int32_t min_tau_f = 0;
@@ -587,15 +595,23 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
   float* g = c->at<float>(lay.g_off);
   const Unit& u0 = lay.units[0];
   prof_mark(c, 0);
+  const bool chained = sizeof(T) == 2 && c->chain_grid > 0 && par == 0;
   {
     // one launch: block 0 also refreshes the slot / step-size table at the start of a minibatch
-    const int64_t tot = (int64_t)M * u0.ld_in;
+    const int64_t tot = std::max<int64_t>((int64_t)M * u0.ld_in, chained ? c->chain_fill16 : 0);
     hipLaunchKernelGGL((pm_begin_step_kernel<T>), dim3((unsigned)std::min<int64_t>(1024, (tot + 255) / 256)), dim3(256),
                        0, st, (const float*)x_dev, c->at<T>(lay.x_off), M, u0.d.n_in, u0.ld_in, c->hdr(), c->ls(),
-                       c->ld(par), accumulate ? 0 : L, sched_dev(c), par);
+                       c->ld(par), accumulate ? 0 : L, sched_dev(c), par,
+                       chained ? c->at<uint4>(lay.units[0].z_off) : nullptr, chained ? c->chain_fill16 : 0);
   }
+  if (chained && c->chain_nf >= 2) {
+    ProfSpan span(c, PM_CLS_GEMM);
+    hipLaunchKernelGGL(pm_chain_fwd_kernel, dim3(c->chain_grid), dim3(PM_CHAIN_NT), 0, st, c->at<PmChainFwd>(lay.chain_f_off),
+                       c->chain_nf, M, c->hdr());
+  }
+  const int fwd_first = chained && c->chain_nf >= 2 ? c->chain_nf : 0;
   // ---- forward: unit l reads W (and b) of version max(t - tau_fwd, 0) in place from its ring slot
-  for (int l = 0; l < L; ++l) {
+  for (int l = fwd_first; l < L; ++l) {
     const Unit& u = lay.units[l];
     const T* a_in = l == 0 ? c->at<T>(lay.x_off) : c->at<T>(lay.units[l - 1].a_off);
     PmWLoc<T> W{ring + u.ring_off, &c->ld(par)[l].fwd_slot, u.n_pad};
@@ -656,7 +672,13 @@ pm_status launch_fwd_bwd(pm_ctx* c, const void* x_dev, const void* y_dev, int ac
     launch_gemm<T>(c, M, u.d.n_in, u.d.n_out, dz, u.ld_out, 1, Wb, 1, u.d.n_in, ed, &pf);
   };
   if (!lay.recompute) {
-    for (int l = L - 1; l >= 1; --l) bwd_data(l);
+    const int hb = chained && c->chain_hb >= 2 ? c->chain_hb : 0;
+    for (int l = L - 1; l > hb; --l) bwd_data(l);
+    if (hb) {
+      ProfSpan span(c, PM_CLS_GEMM);
+      hipLaunchKernelGGL(pm_chain_bwd_kernel, dim3(c->chain_grid), dim3(PM_CHAIN_NT), 0, st, c->at<PmChainBwd>(lay.chain_b_off),
+                         hb, M, c->hdr());
+    }
   } else {
     // Recomputation (App. on recompute): the forward pass is taken to have kept only the input of
     // every segment; before a segment's backward its pre-activations and inner inputs are rebuilt
@@ -1551,6 +1573,58 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
       }
     c->dw_grouped = fits;
     if ((e = hipMemcpyAsync(c->arena + lay.probs_off, probs.data(), probs.size() * sizeof(probs[0]), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy problem table");
+    // chained launches (see pm_chain.hpp): few rows, no recomputation, one step-table set
+    std::vector<PmChainFwd> cf;
+    std::vector<PmChainBwd> cb;
+    if (c->o.chained_launches && M % 32 == 0 && M <= 32 * PM_CHAIN_MAX_ROW_TILES && !lay.recompute && !c->overlap) {
+      bf16_t* ring = c->at<bf16_t>(lay.ring_off);
+      bf16_t* ub = c->at<bf16_t>(lay.ub_off);
+      const PmLayerStep* tab = c->ld(0);
+      int nf = 0;
+      while (nf < L - 1 && nf < PM_CHAIN_MAX_UNITS && lay.units[nf].d.n_in % 64 == 0 && lay.units[nf].d.n_out % 32 == 0) ++nf;   // (the last unit writes fp32 logits for the loss: not chained)
+      int hb = 0;
+      while (hb + 1 < L && hb < PM_CHAIN_MAX_UNITS && lay.units[hb + 1].d.n_out % 64 == 0 && lay.units[hb + 1].d.n_in % 32 == 0) ++hb;
+      int max_tiles = 0;
+      for (int l = 0; l < nf; ++l) {
+        const Unit& u = lay.units[l];
+        PmChainFwd f;
+        f.W = PmWLoc<bf16_t>{ring + u.ring_off, &tab[l].fwd_slot, u.n_pad};
+        f.boff = u.boff;
+        f.in = l == 0 ? c->at<bf16_t>(lay.x_off) : c->at<bf16_t>(lay.units[l - 1].a_off);
+        f.z = c->at<bf16_t>(u.z_off);
+        f.a = c->at<bf16_t>(u.a_off);
+        f.n_in = u.d.n_in; f.n_out = u.d.n_out; f.act = u.d.act;
+        f.in_shared = l > 0;
+        cf.push_back(f);
+        max_tiles = std::max(max_tiles, (M / 32) * (u.d.n_out / 32));
+      }
+      for (int l = hb; l >= 1; --l) {
+        const Unit& u = lay.units[l];
+        const Unit& up = lay.units[l - 1];
+        PmChainBwd b;
+        b.W = u.corr ? PmWLoc<bf16_t>{ub + u.off, nullptr, 0} : PmWLoc<bf16_t>{ring + u.ring_off, &tab[l].bkwd_slot, u.n_pad};
+        b.dz = c->at<bf16_t>(u.dz_off);
+        b.zprev = c->at<bf16_t>(up.z_off);
+        b.dzprev = c->at<bf16_t>(up.dz_off);
+        b.n_in = u.d.n_in; b.n_out = u.d.n_out; b.act_prev = up.d.act;
+        b.dz_shared = l < hb;
+        cb.push_back(b);
+        max_tiles = std::max(max_tiles, (M / 32) * (u.d.n_in / 32));
+      }
+      int cus = 0, dev = 0;
+      if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+      if (cus >= 8 && (nf >= 2 || hb >= 2)) {
+        c->chain_nf = nf >= 2 ? nf : 0;
+        c->chain_hb = hb >= 2 ? hb : 0;
+        // one block per compute unit at most (all blocks must be resident: they wait for each other)
+        c->chain_grid = std::max(8, std::min(cus / 8 * 8, (max_tiles + 7) / 8 * 8));
+        const Unit& ul = lay.units[L - 1];
+        c->chain_fill16 = (int64_t)((ul.dz_off + (size_t)M * ul.ld_out * lay.esz - lay.units[0].z_off + 15) / 16);
+        if (!cf.empty() && (e = hipMemcpyAsync(c->arena + lay.chain_f_off, cf.data(), cf.size() * sizeof(cf[0]), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy chain table");
+        if (!cb.empty() && (e = hipMemcpyAsync(c->arena + lay.chain_b_off, cb.data(), cb.size() * sizeof(cb[0]), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy chain table");
+        if ((e = hipStreamSynchronize(st)) != hipSuccess) return bail(e, "synchronise after chain tables");
+      }
+    }
   }
   if (c->o.dtype == PM_BF16)
     hipLaunchKernelGGL((pm_init_ring_kernel<bf16_t>), dim3((unsigned)lay.n_chunks), dim3(256), 0, st,
@@ -1614,6 +1688,7 @@ pm_status pm_step(pm_ctx* c, const void* x_dev, const void* y_dev, float* loss_o
     PM_HIP(hipMemcpyAsync(&h, c->hdr(), sizeof h, hipMemcpyDeviceToHost, c->stream));
     PM_HIP(hipStreamSynchronize(c->stream));
     *loss_out_host = c->last_loss = h.loss;
+    if (h.chain_err) return fail(PM_EHIP, "a chained launch gave up waiting for its producers (results of this context are invalid)");
     if (h.diverged) { c->diverged = true; return fail(PM_EDIVERGED, "non-finite weight after step %lld", (long long)h.t_used); }
   }
   return PM_OK;
@@ -1693,6 +1768,14 @@ pm_status pm_device_recompute_slots(pm_ctx* c, int64_t* t_used, int32_t* rec_slo
   return PM_OK;
 }
 
+pm_status pm_chained_units(pm_ctx* c, int32_t* n_forward, int32_t* n_backward) {
+  if (!c) return fail(PM_EINVAL, "NULL context");
+  const bool on = c->o.dtype == PM_BF16 && c->chain_grid > 0;
+  if (n_forward) *n_forward = on ? c->chain_nf : 0;
+  if (n_backward) *n_backward = on ? c->chain_hb : 0;
+  return PM_OK;
+}
+
 pm_status pm_stats(pm_ctx* c, double* loss, double* grad_norm, double* param_norm, int64_t* t) {
   if (!c) return fail(PM_EINVAL, "NULL context");
   pm_status qs = quiesce(c);
@@ -1711,6 +1794,7 @@ pm_status pm_stats(pm_ctx* c, double* loss, double* grad_norm, double* param_nor
   if (grad_norm) *grad_norm = c->o.clip_norm > 0.0 ? std::sqrt((double)h.gnorm2[c->last_par]) / c->o.n_microbatches : 0.0;
   if (param_norm) *param_norm = std::sqrt((double)h.pnorm2);
   if (t) *t = h.t_next;
+  if (h.chain_err) return fail(PM_EHIP, "a chained launch gave up waiting for its producers (results of this context are invalid)");
   if (h.diverged) { c->diverged = true; return fail(PM_EDIVERGED, "non-finite weight after step %lld", (long long)h.t_used); }
   return PM_OK;
 }

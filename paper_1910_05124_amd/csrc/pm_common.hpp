@@ -47,7 +47,7 @@ struct PmStepHdr {
   float loss;          // accumulated by the loss kernel
   int32_t diverged;    // set when a non-finite weight is written
   float pnorm2;        // scratch for pm_stats
-  int32_t pad_;
+  int32_t chain_err;   // set (sticky) when a block of a chained launch gave up waiting for its producers
   float gnorm2[2];     // sum of squares of the accumulated gradients (clipping only)
   float gscale[2];     // factor applied to the gradient buffer inside the update
   float bc1[2], bc2[2];  // Adam bias corrections 1/(1-beta^(t+1))

@@ -84,11 +84,16 @@ __global__ void pm_prologue_kernel(PmStepHdr* hdr, const PmLayerStatic* ls, PmLa
 template <typename T>
 __global__ __launch_bounds__(256) void pm_begin_step_kernel(const float* __restrict__ x, T* __restrict__ out, int M,
                                                             int n, int ld_x, PmStepHdr* hdr, const PmLayerStatic* ls,
-                                                            PmLayerStep* ld, int L, PmSchedDev sc, int par) {
+                                                            PmLayerStep* ld, int L, PmSchedDev sc, int par,
+                                                            uint4* shared_fill, int64_t n_shared_fill) {
   if (blockIdx.x == 0) {
     if (L > 0) pm_prologue_block(hdr, ls, ld, L, sc, par);
     if (threadIdx.x == 0) hdr->loss = 0.f;
   }
+  // the tensors that the chained forward / data-gradient launches of this microbatch pass from block to block
+  // start as all-ones words ("not written yet", see pm_chain.hpp)
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_shared_fill; i += (int64_t)gridDim.x * blockDim.x)
+    shared_fill[i] = make_uint4(~0u, ~0u, ~0u, ~0u);
   const int64_t total = (int64_t)M * ld_x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
     const int m = (int)(i / ld_x), c = (int)(i % ld_x);

@@ -148,6 +148,88 @@ def test_update_large_streams_variant_every_element(torch_cuda, opt):
     g.close()
 
 
+# ------------------------------------------------------------------------------- chained launches
+CHAIN_CASES = {
+    # name: (widths, acts, stages, loss, M, steps, extra)
+    "w64_m32": ([64, 64, 64, 64, 64, 10], ["gelu"] * 4 + ["none"], [1, 2, 3, 4, 4], "xent", 32, 16, {}),
+    "w128_m128_relu": ([128] * 7 + [10], ["relu"] * 6 + ["none"], [1, 2, 3, 4, 5, 6, 6], "xent", 128, 16, {}),
+    "mixed_widths_m64": ([64, 128, 64, 256, 192, 64, 5], ["gelu", "relu", "gelu", "none", "gelu", "none"], [1, 2, 3, 4, 5, 6], "xent", 64, 16, {}),
+    "mse_head_in_the_chain_m96": ([128, 64, 128, 64], ["gelu", "gelu", "none"], [1, 2, 3], "mse", 96, 16, {}),
+    "k2048_two_slices_per_wave": ([64, 2048, 2048, 64, 10], ["gelu", "gelu", "gelu", "none"], [1, 2, 3, 4], "xent", 128, 8, {}),
+    "n4096_more_tiles_than_blocks": ([64, 4096, 64, 64, 10], ["gelu", "gelu", "gelu", "none"], [1, 2, 3, 4], "xent", 128, 8, {}),
+    "graph": ([128] * 5 + [10], ["gelu"] * 4 + ["none"], [1, 2, 3, 4, 4], "xent", 64, 16, dict(_gpu=dict(use_graph=True))),
+    "microbatches": ([128] * 5 + [10], ["gelu"] * 4 + ["none"], [1, 2, 3, 4, 4], "xent", 64, 10, dict(_N=2)),
+    "pipedream": ([128] * 5 + [10], ["gelu"] * 4 + ["none"], [1, 2, 3, 4, 4], "xent", 64, 14, dict(_method="pipedream")),
+    "t2_off": ([128] * 5 + [10], ["gelu"] * 4 + ["none"], [1, 2, 3, 4, 4], "xent", 64, 14, dict(t2=False)),
+    # (Adam turns sub-noise-floor gradient entries into full steps: a step size at which 14 of them stay inside the band)
+    "adamw": ([128] * 5 + [10], ["gelu"] * 4 + ["none"], [1, 2, 3, 4, 4], "xent", 64, 14, dict(opt="adamw", lr=2e-5)),
+    "stochastic": ([128] * 5 + [10], ["gelu"] * 4 + ["none"], [1, 2, 3, 4, 4], "xent", 64, 14, dict(stochastic=dict(tau_max=6, seed=3))),
+}
+
+
+@pytest.mark.parametrize("name", list(CHAIN_CASES))
+def test_chained_launches_match_oracle_and_the_launch_per_product_path(torch_cuda, name):
+    """bf16 chains run with the persistent forward / data-gradient launches (an option): weights against the
+    oracle (2e-3), and activations-driven state against the same run with one launch per product (both
+    round to bf16 at the same places; only the order of the fp32 partial sums differs)."""
+    widths, acts, stages, loss, M, steps, extra = CHAIN_CASES[name]
+    extra = dict(extra)
+    gpu_kw = extra.pop("_gpu", None)
+    N = extra.pop("_N", 1)
+    method = extra.pop("_method", "pipemare")
+    layers = tuple(wl.Layer("linear", widths[j], widths[j + 1], acts[j], stages[j]) for j in range(len(acts)))
+    w = wl.Workload("chain_" + name, layers, max(stages), N, loss, "bf16", M, widths[-1], init="he")
+    tau = po.pipeline_delays(w.P, N, method)
+    kw = dict(lr=0.002, beta=0.9, D=0.5, K=6)
+    kw.update(extra)
+    side = torch_cuda.cuda.Stream()
+    with torch_cuda.cuda.stream(side):
+        g, o, losses = run_pair(torch_cuda, w, steps, tau=tau, N=N, gpu_kw=dict(stream=side, chained_launches=True, **(gpu_kw or {})),
+                                check_tables=extra.get("stochastic") is None, **kw)
+        # the chained launches did run: forward every unit but the head (it writes fp32 logits for the loss); backward
+        # the data gradient of every unit, the head's included only where its width allows
+        L = len(layers)
+        assert g.chained_units() == (L - 1, L - 1 if widths[-1] % 64 == 0 else L - 2), g.chained_units()
+        for lo, lg in losses:
+            assert lg == pytest.approx(lo, rel=3e-2, abs=1e-5)
+        err, errs = max_rel_err(g.weights(), o.weights())
+        print(name, "max-rel vs oracle", err)
+        assert err <= 2e-3, errs
+        # the same run with one launch per product
+        params = wl.init_params(w)
+        h = make_gpu(w, params, tau[0], tau[1], N=N, stream=side, **dict(kw, **(gpu_kw or {})))
+        assert h.chained_units() == (0, 0)
+        stream = wl.BatchStream(w)
+        for k in range(steps):
+            for j in range(N):
+                x, y = stream.batch(k * N + j)
+                h.step(torch_cuda.from_numpy(x).cuda(), torch_cuda.from_numpy(y).cuda())
+        d, ds = max_rel_err(g.weights(), [v.astype(np.float64) for v in h.weights()])
+        print(name, "max-rel vs launch-per-product", d)
+        assert d <= 1e-3, ds
+        h.close()
+        g.close()
+
+
+def test_chained_launches_are_left_out_where_the_shapes_do_not_qualify(torch_cuda):
+    """The option asks, the shapes decide: rows not a multiple of 32, fp32, a width that is no multiple of 64."""
+    def units(widths, M, dtype):
+        layers = tuple(wl.Layer("linear", widths[j], widths[j + 1], "gelu" if j + 2 < len(widths) else "none", j + 1)
+                       for j in range(len(widths) - 1))
+        w = wl.Workload("chain_probe", layers, len(layers), 1, "xent", dtype, M, widths[-1], init="he")
+        tau = po.pipeline_delays(w.P, 1, "pipemare")
+        g = make_gpu(w, wl.init_params(w), tau[0], tau[1], chained_launches=True)
+        u = g.chained_units()
+        g.close()
+        return u
+    assert units([64, 64, 64, 64, 10], 32, "bf16") == (3, 2)
+    assert units([64, 64, 64, 64, 10], 48, "bf16") == (0, 0)
+    assert units([64, 64, 64, 64, 10], 32, "f32") == (0, 0)
+    assert units([64, 64, 64, 64, 10], 160, "bf16") == (0, 0)
+    fwd, bwd = units([64, 64, 96, 64, 64, 10], 32, "bf16")      # unit 2 reads 96 columns: the forward chain stops before it
+    assert fwd == 2 and bwd == 0, (fwd, bwd)
+
+
 # ------------------------------------------------------------------------------- linear primitives
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("shape", [(128, 1024, 1024), (48, 72, 200), (300, 264, 136), (128, 1024, 16), (16, 64, 64),
