@@ -19,7 +19,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.timeout(1500)
-@pytest.mark.parametrize("launch", ["graph", "overlap", "graph_recompute4", "graph_stochastic"])
+@pytest.mark.parametrize("launch", ["graph", "overlap", "graph_recompute4", "graph_stochastic", "graph_chain"])
 def test_config2_bf16_mlp16_500_steps(launch):
     import torch
     w = wl.config(2)
@@ -42,6 +42,11 @@ def test_config2_bf16_mlp16_500_steps(launch):
         stoch = dict(tau_max=40, seed=20191005)
         kw.update(stochastic=stoch)
         launch, n_steps = "graph", 150
+    chain = launch == "graph_chain"
+    if chain:
+        # the same 500 steps with the forward products of the 16 wide units in ONE persistent launch and 15 of the
+        # 16 data-gradient products in another (the 10-column head keeps its own launches; an option of the library)
+        launch = "graph"
     stream = wl.BatchStream(w)
     o = make_oracle(w, params, tf, tb, **kw)
     side = torch.cuda.Stream()
@@ -50,7 +55,8 @@ def test_config2_bf16_mlp16_500_steps(launch):
     t0 = time.time()
     with torch.cuda.stream(side):
         g = make_gpu(w, params, tf, tb, use_graph=(launch == "graph"), overlap_update=(launch == "overlap"),
-                     stream=side, **kw)
+                     stream=side, chained_launches=chain, **kw)
+        assert g.chained_units() == ((16, 15) if chain else (0, 0))
         x0, y0 = stream.batch(0)
         xd, yd = torch.from_numpy(x0).cuda(), torch.from_numpy(y0).cuda()
         for k in range(n_steps):
