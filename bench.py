@@ -13,7 +13,10 @@ tokens, every weight unit a pipeline stage of its own (P = 99, tau_fwd = 197 .. 
 
 Prints ONE JSON line.  `roofline` prices the fused update pass (HBM bound) with its algorithmic bytes:
 AdamW 40 B per parameter per step (read g, w, m, s, delta fp32; write w, m, s, delta fp32 + ring slot bf16
-+ corrected weights bf16), momentum SGD 32 B.  `stage_gemms` prices the stages' matrix products (MFMA
++ corrected weights bf16), momentum SGD 32 B.  On the Transformer workloads the weight matrices are updated
+inside the grouped weight-gradient launch and the pass of the timed region covers the other parameters
+(embedding, biases, LayerNorm); `roofline_all_parameters` then gives the same kernel over every parameter,
+from a second context of the same process.  `stage_gemms` prices the stages' matrix products (MFMA
 bound) twice: over the summed duration of the product kernels themselves (event pairs around every such
 launch) and over the whole forward + backward phase.  `cpu_baseline` times the fp64 NumPy oracle on a
 bounded sample of the same workload on the host cores (a reference point, not a target).
@@ -57,6 +60,9 @@ def main():
                          "the exponential with the pipeline's delay as mean, truncated at TAU_MAX")
     ap.add_argument("--chain", action="store_true",
                     help="MLP workloads: the chained forward / data-gradient launches instead of one launch per product")
+    ap.add_argument("--separate-update", action="store_true",
+                    help="Transformer workloads: always the separate update pass over all parameters (default: the "
+                         "weight matrices are updated in the epilogue of the grouped weight-gradient launch)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run three plain device-to-device copies of this many MiB after the timed region "
                          "(a kernel of known traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings by)")
@@ -91,54 +97,70 @@ def main():
     launch = "eager" if args.no_graph else args.launch
     use_graph = launch == "graph"
     side = torch.cuda.Stream()
+    sd = o.get("sched") or dict(kind="const", base=o["lr"])
+    # Microbatches are resident in HBM before the timed region and handed over by pointer.  A captured
+    # graph is bound to its batch buffers and the library keeps one graph per buffer pair, so the pool is
+    # no larger than the warm-up (every pair's graph is captured during the untimed steps).
+    npool = max(1, min(args.pool, args.warmup, 64)) if use_graph else args.pool
     with torch.cuda.stream(side):
-        sd = o.get("sched") or dict(kind="const", base=o["lr"])
-        sched = pm.make_sched(kind=sd["kind"], base=sd["base"], init=sd.get("init", 0.0), factor=sd.get("factor", 1.0),
-                              interval=sd.get("interval", sd.get("warmup", 1)), K=o["K"])
-        opts = pm.make_opts(opt=o["kind"], beta1=o["beta"], beta2=o.get("beta2", 0.98), eps=o.get("eps", 1e-8), D=o["D"],
-                            weight_decay=o["weight_decay"], t1=True, t2=True,
-                            N=w.N, dtype=w.dtype, loss=w.loss, microbatch=w.microbatch, use_graph=use_graph,
-                            overlap_update=(launch == "overlap"), arch=w.arch.get("kind", "chain"),
-                            n_heads=w.arch.get("n_heads", 0), seq_len=w.arch.get("seq", 0),
-                            image_size=w.arch.get("image", 0), tau_recomp=tau_recomp, segment_size=args.recompute,
-                            stochastic=stoch, chained_launches=args.chain)
-        eng = pm.PipeMare(w.layers, w.P, tau_fwd, tau_bkwd, sched, opts, params, stream=side)
-        # Microbatches are resident in HBM before the timed region and handed over by pointer.  A captured
-        # graph is bound to its batch buffers and the library keeps one graph per buffer pair, so the pool is
-        # no larger than the warm-up (every pair's graph is captured during the untimed steps).
-        npool = max(1, min(args.pool, args.warmup, 64)) if use_graph else args.pool
         pool = [stream_data.batch(k) for k in range(npool)]
         xs = [torch.from_numpy(x).cuda() for x, _ in pool]
         ys = [torch.from_numpy(y).cuda() for _, y in pool]
 
-        def run(n, base):
-            for k in range(n):
-                i = (base + k) % npool
-                eng.step(xs[i], ys[i])
+    def measure(separate_update, steps, timed):
+        """One context; `steps` timed steps (if timed), then `steps` eager steps with four events per step, then up
+        to 16 with an event pair around every product / attention launch."""
+        with torch.cuda.stream(side):
+            sched = pm.make_sched(kind=sd["kind"], base=sd["base"], init=sd.get("init", 0.0), factor=sd.get("factor", 1.0),
+                                  interval=sd.get("interval", sd.get("warmup", 1)), K=o["K"])
+            opts = pm.make_opts(opt=o["kind"], beta1=o["beta"], beta2=o.get("beta2", 0.98), eps=o.get("eps", 1e-8), D=o["D"],
+                                weight_decay=o["weight_decay"], t1=True, t2=True,
+                                N=w.N, dtype=w.dtype, loss=w.loss, microbatch=w.microbatch, use_graph=use_graph,
+                                overlap_update=(launch == "overlap"), arch=w.arch.get("kind", "chain"),
+                                n_heads=w.arch.get("n_heads", 0), seq_len=w.arch.get("seq", 0),
+                                image_size=w.arch.get("image", 0), tau_recomp=tau_recomp, segment_size=args.recompute,
+                                stochastic=stoch, chained_launches=args.chain, separate_update=separate_update)
+            eng = pm.PipeMare(w.layers, w.P, tau_fwd, tau_bkwd, sched, opts, params, stream=side)
 
-        run(args.warmup, 0)
-        eng.synchronize()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        run(args.steps, args.warmup)
-        eng.synchronize()          # the caller's stream and the library's second stream
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        stats = eng.stats(param_norm=True)
+            def run(n, base):
+                for k in range(n):
+                    i = (base + k) % npool
+                    eng.step(xs[i], ys[i])
 
-        # per-phase kernel time with HIP events on the engine's stream, same steps, eager launches on one
-        # stream (no overlap, so the update kernel's duration is its own)
-        pm.pm_profile_begin(eng.ctx, args.steps)
-        run(args.steps, args.warmup + args.steps)
-        prof = pm.pm_profile_end(eng.ctx)
-        # a second, short pass that also brackets every product / attention launch with an event pair
-        ncls = max(1, min(args.steps, 16))
-        pm.pm_profile_begin_classes(eng.ctx, ncls)
-        run(ncls, args.warmup + 2 * args.steps)
-        pm.pm_profile_end(eng.ctx)
-        cls = pm.pm_profile_classes(eng.ctx)
-        eng.close()
-        if args.calib_copy_mib > 0:
+            r = {"split": eng.update_split(), "dt": None}
+            run(args.warmup, 0)
+            eng.synchronize()
+            torch.cuda.synchronize()
+            if timed:
+                t0 = time.perf_counter()
+                run(steps, args.warmup)
+                eng.synchronize()          # the caller's stream and the library's second stream
+                torch.cuda.synchronize()
+                r["dt"] = time.perf_counter() - t0
+            r["stats"] = eng.stats(param_norm=True)
+            # per-phase kernel time with HIP events on the engine's stream, same steps, eager launches on one
+            # stream (no overlap, so the update kernel's duration is its own)
+            pm.pm_profile_begin(eng.ctx, steps)
+            run(steps, args.warmup + steps)
+            r["prof"] = pm.pm_profile_end(eng.ctx)
+            # a second, short pass that also brackets every product / attention launch with an event pair
+            ncls = max(1, min(steps, 16))
+            pm.pm_profile_begin_classes(eng.ctx, ncls)
+            run(ncls, args.warmup + 2 * steps)
+            pm.pm_profile_end(eng.ctx)
+            r["cls"] = pm.pm_profile_classes(eng.ctx)
+            eng.close()
+        return r
+
+    m = measure(args.separate_update, args.steps, True)
+    dt, stats, prof, cls = m["dt"], m["stats"], m["prof"], m["cls"]
+    n_epilogue, n_pass = m["split"]
+    # Where the weight matrices are updated inside the weight-gradient launch, the pass of the timed region covers
+    # the remaining parameters only; a second context with the separate pass over ALL parameters gives the pass at
+    # the full footprint and the product kernels without the update work inside (a few untimed steps)
+    m_sep = measure(True, max(4, min(args.steps, 20)), False) if n_epilogue > 0 else None
+    if args.calib_copy_mib > 0:
+        with torch.cuda.stream(side):
             src = torch.ones(args.calib_copy_mib << 20, dtype=torch.uint8, device="cuda")
             dst = torch.empty_like(src)
             for _ in range(3):
@@ -153,7 +175,11 @@ def main():
     upd_s = prof["update_ms"] * 1e-3
     # an embedding has no corrected backward weights (nothing flows through it): one 2- or 4-byte stream less
     esz = 2 if w.dtype == "bf16" else 4
-    alg_bytes = sum(wl.n_params(L) * (bpp - (esz if L.kind == "embed" else 0)) for L in w.layers)
+    # parameters the pass covers: all, or - when the weight matrices are updated in the weight-gradient epilogues -
+    # the rest (embedding, biases, LayerNorm)
+    in_pass = [wl.n_params(L) - (L.n_in * L.n_out if (n_epilogue > 0 and L.kind == "linear") else 0) for L in w.layers]
+    assert n_epilogue == 0 or sum(in_pass) == n_params - n_epilogue
+    alg_bytes = sum(n * (bpp - (esz if L.kind == "embed" else 0)) for n, L in zip(in_pass, w.layers))
     if tau_recomp is not None:
         # units that keep corrected recompute weights of their own (delay or coefficient differs from the
         # backward weights'): one more stored stream, plus a read of the older ring version when tau_recomp > 0
@@ -191,7 +217,8 @@ def main():
             gemm_flops += 2.0 * w.microbatch * sum(L.n_in * L.n_out for L in lin[:-1])
     gemm_s = (prof["fwd_ms"] + prof["bwd_ms"]) * 1e-3
     kern_s = (cls["product_ms"] + cls["attention_ms"]) * 1e-3      # the product (and attention) kernels alone
-    traffic, traffic_src = (measured_traffic(w.name) if tau_recomp is None and stoch is None else (None, None))
+    traffic, traffic_src = (measured_traffic(w.name + ("_separate_update" if args.separate_update and is_tfm else ""))
+                            if tau_recomp is None and stoch is None else (None, None))
     out = {
         "metric": "async pipeline train steps/s",
         "value": round(steps_per_s, 2),
@@ -219,7 +246,7 @@ def main():
         "roofline": {"kernel": "pm_fused_update_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "traffic_source": traffic_src, "algorithmic_bytes": alg_bytes,
-                     "bytes_per_param": bpp, "params": n_params,
+                     "bytes_per_param": bpp, "params": sum(in_pass), "params_updated_in_weight_gradient_epilogues": n_epilogue,
                      "avg_kernel_ms": round(prof["update_ms"], 5), "launches_timed": prof["n"]},
         "phases_ms": {"forward_loss": round(prof["fwd_ms"], 4), "backward": round(prof["bwd_ms"], 4),
                       "update": round(prof["update_ms"], 4), "note": "serial (non-overlapped) profiling pass"},
@@ -238,13 +265,36 @@ def main():
                                 "microseconds each (configurations 1, 2, 4) the two markers per launch cost more than the kernels: "
                                 "read phase_* there"},
     }
+    if m_sep is not None:
+        # the same quantities from the context whose update pass covers every parameter
+        ps, cs = m_sep["prof"], m_sep["cls"]
+        all_bytes = sum(wl.n_params(L) * (bpp - (esz if L.kind == "embed" else 0)) for L in w.layers)
+        a_all = all_bytes / (ps["update_ms"] * 1e-3) / 1e9 if ps["update_ms"] > 0 else 0.0
+        ks = (cs["product_ms"] + cs["attention_ms"]) * 1e-3
+        traffic_all, traffic_all_src = measured_traffic(w.name + "_separate_update")
+        out["roofline"]["note"] = ("the pass of the timed region: the weight matrices (params_updated_in_weight_gradient_epilogues) are "
+                                   "updated by the blocks of the grouped weight-gradient launch, 36 B per parameter there (no "
+                                   "gradient read-back); roofline_all_parameters is the same kernel over every parameter")
+        out["roofline_all_parameters"] = {
+            "kernel": "pm_fused_update_kernel", "bound": "hbm", "achieved": round(a_all, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(a_all / HBM_PEAK_GBS, 4), "traffic": traffic_all, "traffic_source": traffic_all_src,
+            "algorithmic_bytes": all_bytes, "bytes_per_param": bpp, "params": n_params,
+            "avg_kernel_ms": round(ps["update_ms"], 5), "launches_timed": ps["n"],
+            "note": "second context of the same process with pm_opts.separate_update = 1 (untimed for `value`)"}
+        out["stage_gemms"]["separate_update"] = {
+            "kernels_ms_per_step": round(ks * 1e3, 4),
+            "kernels_achieved": round(gemm_flops / ks / 1e12, 2) if ks > 0 else None,
+            "kernels_frac": round(gemm_flops / ks / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5) if ks > 0 else None,
+            "phases_ms": {"forward_loss": round(ps["fwd_ms"], 4), "backward": round(ps["bwd_ms"], 4), "update": round(ps["update_ms"], 4)},
+            "note": "the product kernels without the update work inside the weight-gradient launch (context with the separate pass)"}
     if args.cpu_steps > 0:
         out["cpu_baseline"] = cpu_baseline(w, params, tau_fwd, tau_bkwd, args.cpu_steps, tau_recomp, args.recompute, stoch)
     print(json.dumps(out), flush=True)
 
 
 def measured_traffic(workload_name):
-    """HBM bytes per launch of the update kernel from the committed rocprofv3 counter summary
+    """workload_name: the workload, with "_separate_update" appended for the runs whose pass covers every parameter
+    of a Transformer.  HBM bytes per launch of the update kernel from the committed rocprofv3 counter summary
     (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a plain copy) and where
     that number comes from (file and the source revision it was taken at), or (None, None).  Counters
     cannot be collected inside this process, so the figure is not live: the source string says so."""

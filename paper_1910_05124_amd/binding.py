@@ -16,7 +16,7 @@ import numpy as np
 __all__ = [
     "lib", "PmError", "pm_layer_desc", "pm_lr_sched", "pm_opts",
     "pm_delays", "pm_slots", "pm_t1_lr", "pm_query_bytes", "pm_create", "pm_step", "pm_weights",
-    "pm_state", "pm_device_step_table", "pm_stats", "pm_chained_units", "pm_recompute_delays", "pm_device_recompute_slots", "pm_delay_thresholds", "pm_stochastic_delays", "pm_set_grads", "pm_apply_update", "pm_destroy",
+    "pm_state", "pm_device_step_table", "pm_stats", "pm_chained_units", "pm_update_split", "pm_recompute_delays", "pm_device_recompute_slots", "pm_delay_thresholds", "pm_stochastic_delays", "pm_set_grads", "pm_apply_update", "pm_destroy",
     "pm_linear_fwd", "pm_linear_bwd_data", "pm_linear_bwd_weight", "pm_profile_begin", "pm_profile_end", "pm_profile_classes", "pm_profile_begin_classes",
     "pm_synchronize", "pm_checkpoint_bytes", "pm_checkpoint_save", "pm_checkpoint_load", "PipeMare", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
     "pm_conv3x3_fwd", "pm_conv3x3_bwd_data", "pm_conv3x3_bwd_weight", "pm_conv3x3_bwd_weight_scratch",
@@ -49,7 +49,7 @@ PM_LOSS = {"mse": 0, "xent": 1}
 _STATUS = {0: "PM_OK", 1: "PM_EINVAL", 2: "PM_ENOMEM", 3: "PM_EHIP", 4: "PM_ESTATE", 5: "PM_EDIVERGED"}
 
 EXPORTS = ["pm_status_str", "pm_last_error", "pm_delays", "pm_slots", "pm_t1_lr", "pm_query_bytes",
-           "pm_create", "pm_step", "pm_weights", "pm_state", "pm_device_step_table", "pm_stats", "pm_chained_units",
+           "pm_create", "pm_step", "pm_weights", "pm_state", "pm_device_step_table", "pm_stats", "pm_chained_units", "pm_update_split",
            "pm_recompute_delays", "pm_device_recompute_slots", "pm_delay_thresholds", "pm_stochastic_delays",
            "pm_set_grads", "pm_apply_update", "pm_profile_begin", "pm_profile_end", "pm_profile_classes", "pm_profile_begin_classes", "pm_linear_fwd", "pm_linear_bwd_data",
            "pm_linear_bwd_weight", "pm_layernorm_fwd", "pm_layernorm_bwd", "pm_attention_fwd", "pm_attention_bwd",
@@ -78,7 +78,7 @@ class pm_opts(C.Structure):
                 ("n_heads", C.c_int32), ("seq_len", C.c_int32), ("image_size", C.c_int32),
                 ("tau_recomp", C.POINTER(C.c_int32)), ("segment_size", C.c_int32),
                 ("stochastic_delays", C.c_int32), ("tau_max", C.c_int32), ("delay_seed", C.c_uint64),
-                ("chained_launches", C.c_int32)]
+                ("chained_launches", C.c_int32), ("separate_update", C.c_int32)]
 
 
 class PmError(RuntimeError):
@@ -111,6 +111,7 @@ lib.pm_delay_thresholds.argtypes = [C.c_double, _i32, C.POINTER(C.c_uint32)]
 lib.pm_stochastic_delays.argtypes = [_i32, _i32p, _i32, C.c_uint64, _i64, _i32p]
 lib.pm_device_recompute_slots.argtypes = [_vp, C.POINTER(_i64), _i32p]
 lib.pm_chained_units.argtypes = [_vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+lib.pm_update_split.argtypes = [_vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
 lib.pm_stats.argtypes = [_vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(_i64)]
 lib.pm_set_grads.argtypes = [_vp, _i32, _f32p, C.c_size_t]
 lib.pm_apply_update.argtypes = [_vp]
@@ -273,6 +274,12 @@ def pm_chained_units(ctx: int):
     return nf.value, nb.value
 
 
+def pm_update_split(ctx: int):
+    ne, npass = _i64(), _i64()
+    _check(lib.pm_update_split(ctx, C.byref(ne), C.byref(npass)))
+    return ne.value, npass.value
+
+
 def pm_stats(ctx: int, param_norm: bool = False):
     loss, gn, pn, t = C.c_double(), C.c_double(), C.c_double(), _i64()
     _check(lib.pm_stats(ctx, C.byref(loss), C.byref(gn), C.byref(pn) if param_norm else None, C.byref(t)))
@@ -381,12 +388,13 @@ def make_sched(kind="const", base=0.01, init=0.0, factor=1.0, interval=1, K=0) -
 def make_opts(opt="sgdm", beta1=0.9, beta2=0.98, eps=1e-8, weight_decay=0.0, clip_norm=0.0, D=1.0,
               gamma_override=None, t1=True, t2=True, N=1, dtype="f32", loss="mse", microbatch=1,
               use_graph=False, sync_warmup=0, overlap_update=False, arch="chain", n_heads=0, seq_len=0,
-              image_size=0, tau_recomp=None, segment_size=0, stochastic=None, chained_launches=False) -> pm_opts:
+              image_size=0, tau_recomp=None, segment_size=0, stochastic=None, chained_launches=False,
+              separate_update=False) -> pm_opts:
     o = pm_opts(PM_OPT[opt], beta1, beta2, eps, weight_decay, clip_norm, D, None, int(t1), int(t2), N,
                 PM_DTYPE[dtype], PM_LOSS[loss], microbatch, int(use_graph), int(sync_warmup), int(overlap_update),
                 PM_ARCH[arch], int(n_heads), int(seq_len), int(image_size), None, int(segment_size),
                 0 if stochastic is None else 1, 0 if stochastic is None else int(stochastic["tau_max"]),
-                0 if stochastic is None else int(stochastic["seed"]), int(chained_launches))
+                0 if stochastic is None else int(stochastic["seed"]), int(chained_launches), int(separate_update))
     if tau_recomp is not None:
         arr_r = (C.c_int32 * len(tau_recomp))(*[int(t) for t in tau_recomp])
         o._keep_r = arr_r
@@ -467,6 +475,9 @@ class PipeMare:
 
     def chained_units(self):
         return pm_chained_units(self.ctx)
+
+    def update_split(self):
+        return pm_update_split(self.ctx)
 
     def close(self):
         if self.ctx:

@@ -111,6 +111,7 @@ struct Layout {
   size_t t_xf, t_muf, t_rsf, t_nf, t_logits, t_dlogits;      // final LayerNorm and head
   size_t t_dx, t_dn, t_do;                                   // backward scratch, reused by every layer
   size_t t_pos, t_zero;                                      // positions fp32 [S, d]; zero-region table
+  size_t t_fuse, t_ublocks;                                  // update in the weight-gradient epilogue: problem table of that launch, blocks left to the update pass
   size_t t_wprobs, t_wtiles, t_wsegs;                        // grouped weight-gradient launch: problems (2 sets), tiles per XCD, segments
   int n_zero = 0;
   int64_t zero_max = 0;
@@ -300,6 +301,8 @@ void make_layout(int32_t L, const pm_layer_desc* layers, const int32_t* tau_fwd,
     lay.t_logits = take(Tk * ldV * 4); lay.t_dlogits = take(Tk * ldV * e);
     lay.t_dx = take(Tk * d * 4); lay.t_dn = take(Tk * d * 4); lay.t_do = take(Tk * d * e);
     lay.t_pos = take((size_t)o->seq_len * d * 4);
+    lay.t_fuse = take(sizeof(PmGemmProb<PmEpiBwdWeightUpd>) * L);
+    lay.t_ublocks = take(sizeof(int32_t) * (size_t)lay.n_chunks * (PM_CHUNK / 1024));
     lay.t_wprobs = take(sizeof(PmGemmProb<PmEpiBwdWeight>) * 2 * L);
     lay.t_wtiles = take(sizeof(int32_t) * 8);
     lay.t_wsegs = take(sizeof(PmXcdSeg) * 8 * (size_t)(L + 8));
@@ -383,6 +386,9 @@ struct pm_ctx {
   std::vector<StepGraph> graphs;
   // all weight-gradient products as one grouped MFMA launch (problem tables live in the arena)
   bool dw_grouped = false;
+  bool fuse_upd = false;         // the grouped weight-gradient launch applies the update of its units' weight matrices
+  int upd_nblocks = 0;           // blocks left to the update pass then
+  int64_t upd_fused_params = 0;  // parameters updated in the epilogues
   int dw_maxI = 0, dw_maxJ = 0;
   int dw_nprob = 0, dw_ntiles = 0;   // Transformer: problems and grid size (8 x the longest XCD list) of the grouped launch
   int dw_max_segs = 0;
@@ -476,7 +482,7 @@ constexpr int PM_CLS_GEMM = 0, PM_CLS_ATTN = 1;
 
 // ---- kernel launches of one microbatch / one update, templated on the compute dtype -------------
 template <typename T>
-pm_status launch_update(pm_ctx* c, hipStream_t st, int par) {
+pm_status launch_update(pm_ctx* c, hipStream_t st, int par, bool all_params = false) {
   const Layout& lay = c->lay;
   if (c->o.clip_norm > 0.0) {
     int blocks = (int)std::min<int64_t>(2048, (lay.n_flat / 4 + 255) / 256);
@@ -508,7 +514,13 @@ pm_status launch_update(pm_ctx* c, hipStream_t st, int par) {
   // (measured 6.4 vs 5.6 TB/s at 0.5 GB).  Beyond that nothing survives a step and non-temporal
   // accesses with one group of four elements per thread are ahead (see PmAcc).
   const bool nontemporal = (size_t)lay.n_flat * 32 > ((size_t)1 << 30);
-  const dim3 grid((unsigned)(lay.n_chunks * (PM_CHUNK / (nontemporal ? PmAcc<2>::PER_BLOCK : PmAcc<1>::PER_BLOCK)))), blk(256);
+  // the parameters that the weight-gradient epilogues of this step have already updated are left out
+  // (not when the gradients came from the caller: pm_apply_update)
+  const bool rest_only = c->fuse_upd && !all_params;
+  a.blocks = rest_only ? c->at<int32_t>(lay.t_ublocks) : nullptr;
+  const dim3 grid(rest_only ? (unsigned)c->upd_nblocks
+                            : (unsigned)(lay.n_chunks * (PM_CHUNK / (nontemporal ? PmAcc<2>::PER_BLOCK : PmAcc<1>::PER_BLOCK)))), blk(256);
+  if (grid.x == 0) { prof_mark(c, 3); return PM_OK; }
 #define PM_UPD(OPT, VAR) hipLaunchKernelGGL((pm_fused_update_kernel<T, OPT, VAR>), grid, blk, 0, st, a)
   if (c->o.opt == PM_OPT_SGDM) {
     if (nontemporal) PM_UPD(0, 2); else PM_UPD(0, 1);
@@ -1009,7 +1021,15 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
     if (grouped) {
       ProfSpan span(c, PM_CLS_GEMM);
       const auto* tab = c->at<PmGemmProb<PmEpiBwdWeight>>(lay.t_wprobs) + (accumulate ? c->dw_nprob : 0);
-      if (c->dw_tile == 256)
+      if (c->fuse_upd && c->dw_tile == 256)
+        hipLaunchKernelGGL((pm_gemm_big_grouped_kernel<PmBig256, false, false, false, PmEpiBwdWeightUpd>), dim3(c->dw_ntiles),
+                           dim3(PmBig256::NT), 0, st, c->at<PmGemmProb<PmEpiBwdWeightUpd>>(lay.t_fuse),
+                           c->at<PmXcdSeg>(lay.t_wsegs), c->at<int32_t>(lay.t_wtiles), c->dw_max_segs);
+      else if (c->fuse_upd)
+        hipLaunchKernelGGL((pm_gemm_big_grouped_kernel<PmBig128, false, false, false, PmEpiBwdWeightUpd>), dim3(c->dw_ntiles),
+                           dim3(PmBig128::NT), 0, st, c->at<PmGemmProb<PmEpiBwdWeightUpd>>(lay.t_fuse),
+                           c->at<PmXcdSeg>(lay.t_wsegs), c->at<int32_t>(lay.t_wtiles), c->dw_max_segs);
+      else if (c->dw_tile == 256)
         hipLaunchKernelGGL((pm_gemm_big_grouped_kernel<PmBig256, false, false, false, PmEpiBwdWeight>), dim3(c->dw_ntiles),
                            dim3(PmBig256::NT), 0, st, tab, c->at<PmXcdSeg>(lay.t_wsegs), c->at<int32_t>(lay.t_wtiles),
                            c->dw_max_segs);
@@ -1543,6 +1563,51 @@ pm_status pm_create(int32_t P, int32_t L, const pm_layer_desc* layers, const int
       if ((e = hipMemcpyAsync(c->arena + lay.t_wprobs, probs.data(), probs.size() * sizeof(probs[0]), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy problem table");
       if ((e = hipMemcpyAsync(c->arena + lay.t_wtiles, load, sizeof load, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy tile table");
       if ((e = hipMemcpyAsync(c->arena + lay.t_wsegs, segs.data(), segs.size() * sizeof(PmXcdSeg), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy segment table");
+      // The update inside the weight-gradient epilogue: possible when the gradient a tile holds is final (one
+      // microbatch per step, no clipping by the global norm) and the grouped launch runs last with whole tiles.
+      std::vector<PmGemmProb<PmEpiBwdWeightUpd>> fprobs;
+      std::vector<int32_t> ublocks;
+      if (!c->o.separate_update && c->dw_grouped && aligned && c->o.n_microbatches == 1 && c->o.clip_norm <= 0.0 &&
+          !c->overlap && !lay.has_ur) {
+        const bool nontemporal = (size_t)lay.n_flat * 32 > ((size_t)1 << 30);        // as in launch_update
+        const int per_block = nontemporal ? PmAcc<2>::PER_BLOCK : PmAcc<1>::PER_BLOCK;
+        std::vector<char> fused((size_t)(lay.n_flat / per_block), 0);
+        fprobs.resize(np);
+        for (int i = 0; i < np; ++i) {
+          const Unit& u = lay.units[wp[i].u];
+          const PmGemmProb<PmEpiBwdWeight>& p0 = probs[i];
+          PmGemmProb<PmEpiBwdWeightUpd>& pr = fprobs[i];
+          pr.I = p0.I; pr.J = p0.J; pr.K = p0.K; pr.A = p0.A; pr.lda = p0.lda; pr.B = p0.B; pr.ldb = p0.ldb;
+          PmEpiBwdWeightUpd& ep = pr.epi;
+          std::memset(&ep, 0, sizeof ep);
+          ep.g = p0.epi.g; ep.ld = p0.epi.ld; ep.db = p0.epi.db;
+          ep.f.w = c->at<float>(lay.w_off) + u.off;
+          ep.f.v = c->at<float>(lay.v_off) + u.off;
+          ep.f.s = c->at<float>(lay.s_off) + u.off;
+          ep.f.d = c->at<float>(lay.d_off) + u.off;
+          ep.f.ring = c->at<bf16_t>(lay.ring_off) + u.ring_off;
+          ep.f.ub = c->at<bf16_t>(lay.ub_off) + u.off;
+          ep.f.step = c->ld(0) + wp[i].u;
+          ep.f.hdr = c->hdr();
+          ep.f.n_pad = u.n_pad;
+          ep.f.gamma = (float)u.gamma; ep.f.beta1 = (float)c->o.beta1; ep.f.beta2 = (float)c->o.beta2;
+          ep.f.eps = (float)c->o.eps; ep.f.wd = (float)c->o.weight_decay;
+          ep.f.opt = c->o.opt == PM_OPT_SGDM ? 0 : 1;
+          ep.f.has_ub = u.corr != 0.0 ? 1 : 0;
+          ep.f.tau_b = u.tau_b;
+          // whole update blocks inside the matrix belong to the epilogue; the matrix is a whole number of tiles,
+          // hence of blocks (128 x 128 elements per tile at least)
+          const int64_t nw = (int64_t)u.d.n_out * u.d.n_in;
+          for (int64_t b = u.off / per_block; b < (u.off + nw) / per_block; ++b) fused[(size_t)b] = 1;
+          c->upd_fused_params += nw;
+        }
+        for (size_t b = 0; b < fused.size(); ++b)
+          if (!fused[b]) ublocks.push_back((int32_t)b);
+        c->fuse_upd = true;
+        c->upd_nblocks = (int)ublocks.size();
+        if ((e = hipMemcpyAsync(c->arena + lay.t_fuse, fprobs.data(), fprobs.size() * sizeof(fprobs[0]), hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy fused problem table");
+        if (!ublocks.empty() && (e = hipMemcpyAsync(c->arena + lay.t_ublocks, ublocks.data(), ublocks.size() * 4, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "copy block list");
+      }
       if ((e = hipStreamSynchronize(st)) != hipSuccess) return bail(e, "synchronise after tables");   // host tables go out of scope
       probs.clear();
     }
@@ -1776,6 +1841,13 @@ pm_status pm_chained_units(pm_ctx* c, int32_t* n_forward, int32_t* n_backward) {
   return PM_OK;
 }
 
+pm_status pm_update_split(pm_ctx* c, int64_t* n_epilogue, int64_t* n_pass) {
+  if (!c) return fail(PM_EINVAL, "NULL context");
+  if (n_epilogue) *n_epilogue = c->fuse_upd ? c->upd_fused_params : 0;
+  if (n_pass) *n_pass = c->fuse_upd ? c->lay.n_flat - c->upd_fused_params : c->lay.n_flat;
+  return PM_OK;
+}
+
 pm_status pm_stats(pm_ctx* c, double* loss, double* grad_norm, double* param_norm, int64_t* t) {
   if (!c) return fail(PM_EINVAL, "NULL context");
   pm_status qs = quiesce(c);
@@ -1821,7 +1893,7 @@ pm_status pm_apply_update(pm_ctx* c) {
   const int par = c->par();
   c->last_par = par;
   launch_prologue(c, par);
-  s = c->o.dtype == PM_BF16 ? launch_update<bf16_t>(c, c->stream, par) : launch_update<float>(c, c->stream, par);
+  s = c->o.dtype == PM_BF16 ? launch_update<bf16_t>(c, c->stream, par, true) : launch_update<float>(c, c->stream, par, true);
   if (s == PM_OK) c->t_host += 1;
   return s;
 }

@@ -53,6 +53,24 @@ struct PmStepHdr {
   float bc1[2], bc2[2];  // Adam bias corrections 1/(1-beta^(t+1))
 };
 
+// What the weight-gradient product of a unit needs to apply that unit's update (Sec. 2.1 recurrence with the T1
+// step size of Sec. 3.1, the delta accumulator and the corrected backward weights of Sec. 3.2) in the epilogue of
+// its own tiles.  Pointers address the unit's weight matrix (element 0 = row 0, column 0).
+struct PmFuseUpd {
+  float* w;                   // master weights
+  float* v;                   // momentum, or Adam's first moment
+  float* s;                   // Adam's second moment
+  float* d;                   // delta
+  bf16_t* ring;               // slot 0 of the unit's ring
+  bf16_t* ub;                 // corrected backward weights
+  const PmLayerStep* step;    // the unit's entry of the step table
+  PmStepHdr* hdr;
+  int64_t n_pad;              // ring slot stride
+  float gamma, beta1, beta2, eps, wd;
+  int32_t opt;                // 0: SGD with momentum, 1: AdamW
+  int32_t has_ub, tau_b;
+};
+
 struct PmSchedDev {
   int32_t kind;
   double base, init, factor;

@@ -1,5 +1,7 @@
 // Input staging, loss kernels, bias gradient and the plain (non-MFMA) GEMM used for fp32 contexts.
 #pragma once
+#include <type_traits>
+
 #include "pm_common.hpp"
 
 // x (fp32 [M, n]) -> compute dtype [M, ld]; pad columns zeroed.  Also clears the loss accumulator
@@ -306,6 +308,93 @@ struct PmEpiBwdWeight {
     pm_st8(g + o, out);
   }
 };
+
+// backward weight of a unit whose gradient is final after this product (one microbatch per step, no clipping):
+// g[i, j] = acc as above, and then the block applies the update of its own tile of parameters - the Sec. 2.1
+// recurrence with the T1 step size of Sec. 3.1, the delta accumulator and the corrected backward weights of
+// Sec. 3.2, with the arithmetic of pm_fused_update_kernel - while other tiles of the launch still multiply.
+// The update pass then leaves these parameters out.
+struct PmEpiBwdWeightUpd {
+  static constexpr bool kColSumA = true;
+  static constexpr bool kTileUpdate = true;
+  float* g; int ld;
+  float* db;
+  PmFuseUpd f;
+  __device__ __forceinline__ bool wants_colsum() const { return db != nullptr; }
+  __device__ __forceinline__ void colsum(int i, float s) const { db[i] = s; }
+  __device__ __forceinline__ void begin() {}
+  __device__ __forceinline__ void op8(int i, int j, const float* acc) const { pm_st8(g + (int64_t)i * ld + j, acc); }
+  // single elements are never needed: the launch that uses this epilogue takes whole tiles only
+  __device__ __forceinline__ void operator()(int, int, float) const {}
+
+  // Parameters [i0, i0 + BI) x [j0, j0 + BJ) of the unit's matrix, by a block of NT threads that has stored their
+  // gradients (and passed a barrier since).  A lane takes 8 consecutive parameters of U rows at a time and
+  // requests all their state before it computes: with the accumulators dead there is room to keep 5 U 32-byte
+  // loads per lane in flight, and what bounds this phase is memory latency times the bytes in flight.
+  template <int BI, int BJ, int NT>
+  __device__ __forceinline__ void update_tile(int i0, int j0) const {
+    constexpr int LPR = BJ / 8, RPP = NT / LPR, U = 4;       // lanes per row, rows per pass of the block, rows per lane and pass
+    static_assert(BI % (RPP * U) == 0, "tile rows");
+    const PmLayerStep D = *f.step;
+    const float lr = D.lr, corr = D.corr_next;
+    const float gs = f.hdr->gscale[0], bc1 = f.hdr->bc1[0], bc2 = f.hdr->bc2[0];
+    const bool ub_from_ring = (corr != 0.f) && (f.tau_b > 0);
+    const int64_t wslot = (int64_t)D.write_slot * f.n_pad, ubslot = (int64_t)D.ub_slot * f.n_pad;
+    const int r = (int)threadIdx.x / LPR, c8 = ((int)threadIdx.x % LPR) * 8;
+    bool bad = false;
+    for (int p = 0; p < BI; p += RPP * U) {
+      float gr[U][8], w[U][8], v[U][8], d[U][8], s[U][8];
+      int64_t o[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        o[u] = (int64_t)(i0 + p + u * RPP + r) * ld + j0 + c8;
+        pm_ld8(g + o[u], gr[u]);
+        pm_ld8(f.w + o[u], w[u]);
+        pm_ld8(f.v + o[u], v[u]);
+        pm_ld8(f.d + o[u], d[u]);
+        if (f.opt == 1) pm_ld8(f.s + o[u], s[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float wn[8], ubv[8];
+        if (ub_from_ring) pm_ld8(f.ring + ubslot + o[u], ubv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float ge = gr[u][e] * gs;
+          float dw;
+          if (f.opt == 0) {
+            ge += f.wd * w[u][e];
+            v[u][e] = f.beta1 * v[u][e] - lr * ge;
+            dw = v[u][e];
+          } else {
+            v[u][e] = f.beta1 * v[u][e] + (1.f - f.beta1) * ge;
+            s[u][e] = f.beta2 * s[u][e] + (1.f - f.beta2) * ge * ge;
+            const float mh = v[u][e] * bc1;
+            const float sh = s[u][e] * bc2;
+            dw = -lr * (mh / (sqrtf(sh) + f.eps) + f.wd * w[u][e]);
+          }
+          wn[e] = w[u][e] + dw;
+          d[u][e] = f.gamma * d[u][e] + (1.f - f.gamma) * dw;
+          bad |= !(fabsf(wn[e]) <= 3.0e38f);
+        }
+        pm_st8(f.w + o[u], wn);
+        pm_st8(f.v + o[u], v[u]);
+        pm_st8(f.d + o[u], d[u]);
+        if (f.opt == 1) pm_st8(f.s + o[u], s[u]);
+        pm_st8(f.ring + wslot + o[u], wn);
+        if (f.has_ub) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) ubv[e] = (ub_from_ring ? ubv[e] : wn[e]) - corr * d[u][e];
+          pm_st8(f.ub + o[u], ubv);
+        }
+      }
+    }
+    if (bad) f.hdr->diverged = 1;
+  }
+};
+// true for an epilogue with a tile-wide second phase (update_tile)
+template <class E, class = void> struct pm_has_tile_update : std::false_type {};
+template <class E> struct pm_has_tile_update<E, std::void_t<decltype(E::kTileUpdate)>> : std::true_type {};
 
 // ---------------------------------------------------------------------------------------------
 // Plain tiled GEMM  C[i, j] = sum_k A(i, k) * B(j, k)  with arbitrary strides; fp32 FMA.

@@ -691,6 +691,11 @@ __device__ __forceinline__ void pm_gemm_big_body(const PmGemmProb<Epi>& pr, int 
       }
     }
   }
+  if constexpr (pm_has_tile_update<Epi>::value) {
+    static_assert(!CHECK, "whole tiles only");
+    __syncthreads();      // the block's stores of the tile are visible to all its waves
+    epi.template update_tile<BI, BJ, NT>(i0, j0);
+  }
 }
 
 template <class Cfg, bool AKC, bool BKC, bool CHECK, class Epi>

@@ -152,6 +152,8 @@ struct PmUpdArgs {
   RT* ub;
   RT* ur;     // corrected recompute weights (NULL when no unit keeps any)
   const int32_t* chunk_layer;
+  const int32_t* blocks;   // NULL: block b of the grid takes block b of the flat space (or its mirror image); else the
+                           // list of the blocks to visit (the rest was updated in the weight-gradient epilogues)
   const PmLayerStatic* ls;
   const PmLayerStep* ld;
   PmStepHdr* hdr;
@@ -235,7 +237,8 @@ __global__ __launch_bounds__(256) void pm_fused_update_kernel(PmUpdArgs<RT> a) {
   // 256 MB last-level cache holds, so what survives there from the previous pass is its tail, and the
   // next pass starts with exactly that part instead of evicting it before reaching it.
   // (the direction comes from this step's table, which is not rewritten while the pass runs)
-  const int64_t blk = a.ld[0].rev ? (int64_t)(gridDim.x - 1 - blockIdx.x) : (int64_t)blockIdx.x;
+  const int64_t pos = a.ld[0].rev ? (int64_t)(gridDim.x - 1 - blockIdx.x) : (int64_t)blockIdx.x;
+  const int64_t blk = a.blocks ? (int64_t)a.blocks[pos] : pos;
   const int64_t e = blk * X::PER_BLOCK + X::base(threadIdx.x);
   // the streams whose addresses need no table go out first; the table reads overlap their latency
   float g[NE], w[NE], v[NE], d[NE], s[NE], wn[NE], ubv[NE];

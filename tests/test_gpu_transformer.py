@@ -303,3 +303,69 @@ def test_narrow_transformer_with_the_stage_table_of_the_12_layer_workload(torch_
     if dtype == "bf16":
         assert max(m for u, m in enumerate(mvs) if u not in key_bias_entries(w)) <= 0.15, mvs
     g.close()
+
+
+@pytest.mark.parametrize("opt,tile", [("sgdm", 128), ("adamw", 128), ("adamw", 256)])
+def test_update_in_the_weight_gradient_epilogue_matches_the_separate_pass(torch_cuda, opt, tile):
+    """Where the update is applied (in the epilogue of the grouped weight-gradient launch for the weight matrices,
+    or by the pass over all parameters: pm_opts.separate_update) must not change what is computed: same
+    gradients, same recurrences per parameter.  Two contexts step on the same batches; after every step every
+    state array of every unit is compared, then the second context is given the first one's state (checkpoint
+    image), so that each step starts from identical bits and only the order of the fp32 atomics inside a step
+    (loss, LayerNorm and embedding gradients) can differ.  'tile' picks shapes for the launch's 128 x 128 and
+    256 x 256 block tiles (the latter needs at least 256 such tiles)."""
+    if tile == 128:
+        w = wl.transformer(2, 128, 2, 256, 512, 64, 4, dtype="bf16", K=10,
+                           sched=dict(kind="warmup_invsqrt", base=2e-3, init=1e-5, warmup=10))
+    else:
+        w = wl.transformer(4, 512, 8, 2048, 8192, 64, 4, dtype="bf16", K=10,       # 64 + 4 * 48 = 256 tiles of 256 x 256
+                           sched=dict(kind="warmup_invsqrt", base=2e-3, init=1e-5, warmup=10))
+    kw = _kw(w, weight_decay=0.01) if opt == "adamw" else dict(opt="sgdm", lr=0.002, beta=0.9, D=0.5, K=10, weight_decay=0.01)
+    params = wl.init_params(w)
+    tf, tb = po.pipeline_delays(w.P, 1)
+    ga = make_gpu(w, params, tf, tb, **kw)
+    gb = make_gpu(w, params, tf, tb, separate_update=True, **kw)
+    ne, npass = ga.update_split()
+    n_mat = sum(L.n_in * L.n_out for L in w.layers if L.kind == "linear")
+    assert ne == n_mat and npass > 0, (ne, npass, n_mat)
+    assert gb.update_split()[0] == 0
+    stream = wl.TokenStream(w)
+    steps = 7
+    worst = {True: 0.0, False: 0.0}
+    for k in range(steps):
+        x, y = stream.batch(k)
+        xa, ya = torch_cuda.from_numpy(x).cuda(), torch_cuda.from_numpy(y).cuda()
+        la = ga.step(xa, ya, want_loss=True)
+        lb = gb.step(xa, ya, want_loss=True)
+        assert la == pytest.approx(lb, rel=1e-5)
+        ta, tb_ = ga.step_table(), gb.step_table()
+        assert ta[0] == tb_[0] == k and all(np.array_equal(p, q) for p, q in zip(ta[1:], tb_[1:]))
+        for u, L in enumerate(w.layers):
+            mat = L.kind == "linear"
+            for which in (0, 1, 2, 3, 4):          # master weights, delta, momentum, corrected backward weights, gradient
+                a, b = ga.state(which, u), gb.state(which, u)
+                nm = L.n_in * L.n_out if mat else 0
+                for part, tight in ((slice(0, nm), True), (slice(nm, None), False)):
+                    if a[part].size == 0:
+                        continue
+                    if which == 3:
+                        # stored in bf16: a last-bit difference of the fp32 value before rounding may flip the
+                        # rounding of a few entries by one bf16 step of that entry
+                        # (plus the matrices' own bound where an entry is near zero and its terms cancel)
+                        diff = np.abs(a[part] - b[part])
+                        bound = 2.0 ** -7 * np.abs(b[part]) + 1e-6 * float(np.max(np.abs(b[part])))
+                        assert np.all(diff <= bound) and np.mean(diff > 0) <= 1e-3, (k, u, part, float(np.max(diff - bound)), float(np.mean(diff > 0)))
+                        continue
+                    scale = float(np.max(np.abs(b[part]))) or 1.0
+                    dev = float(np.max(np.abs(a[part] - b[part]))) / scale
+                    worst[tight] = max(worst[tight], dev)
+                    # matrices (same products, same expressions, no atomics): a few times the difference between a
+                    # fused and an unfused multiply-add.  The rest goes through the same pass in both contexts, from
+                    # gradients summed with atomics; where such a sum cancels, the order of its terms decides the low
+                    # bits of an entry whose sign Adam then turns into a full-size step (measured 2.3e-4)
+                    assert dev <= (1e-6 if tight else 2e-3), (k, u, which, part, dev)
+        gb.restore(ga.checkpoint())
+    print("update in the epilogue vs separate pass:", opt, tile, "largest deviation / max: matrices", worst[True],
+          "other parameters", worst[False])
+    ga.close()
+    gb.close()
