@@ -974,9 +974,33 @@ pm_status launch_tfm(pm_ctx* c, const void* x_dev, const void* y_dev, int accumu
 #define PM_ENTER(u) do { if (!enter(u)) return fail(PM_EINVAL, "attention shape not supported"); } while (0)
   PM_ENTER(L - 1);
   wg(L - 1, TT(lay.t_dlogits), ldV, TT(lay.t_nf), V, d);
-  dgrad_f32(L - 1, TT(lay.t_dlogits), ldV, V, d, dn, 0);
+  // The data gradient through the vocabulary projection: Tk x d outputs (few tiles) over a contraction of V.
+  // When 256 x 256 tiles of it cover at most half the chip, the contraction is cut into two halves that run
+  // side by side on such tiles; the second half's output goes to the (still unused) buffer of dx and the
+  // LayerNorm backward that consumes the gradient adds the two.
+  const float* dn2 = nullptr;
+  bool head_split = false;
+  if constexpr (sizeof(T) == 2) {
+    const int t256 = (Tk / 256) * (d / 256);
+    if (Tk % 256 == 0 && d % 256 == 0 && V % 128 == 0 && V >= 16384 && ldV == V && 2 * t256 <= 256 && 2 * t256 >= 128) {
+      const int Kh = V / 2;
+      const T* dl = TT(lay.t_dlogits);
+      const PmWLoc<T> W = Wb(L - 1, 0);
+      PmGemmProb<PmEpiF32> p0{Tk, d, Kh, dl, ldV, W, d, PmEpiF32{dn, d, 0}};
+      PmWLoc<T> W1 = W;
+      W1.base += (int64_t)Kh * d;
+      PmGemmProb<PmEpiF32> p1{Tk, d, Kh, dl + Kh, ldV, W1, d, PmEpiF32{dx, d, 0}};
+      ProfSpan span(c, PM_CLS_GEMM);
+      hipLaunchKernelGGL((pm_gemm_big_khalves_kernel<PmBig256, true, false, PmEpiF32>), dim3(2 * t256), dim3(PmBig256::NT), 0, st,
+                         p0, p1, Tk / 256, d / 256);
+      dn2 = dx;
+      head_split = true;
+    }
+  }
+  if (!head_split) dgrad_f32(L - 1, TT(lay.t_dlogits), ldV, V, d, dn, 0);
   PM_ENTER(L - 2);
-  ln_bwd(L - 2, dn, F(lay.t_xf), F(lay.t_muf), F(lay.t_rsf), nullptr, dx, nl ? TT(lay.tl[nl - 1].dz2) : nullptr);
+  pm_ln_bwd_launch<T>(st, dn, F(lay.t_xf), F(lay.t_muf), F(lay.t_rsf), Wb(L - 2, 0), nullptr, dx, nl ? TT(lay.tl[nl - 1].dz2) : nullptr,
+                      g + U(L - 2).off, g + U(L - 2).off + U(L - 2).boff, Tk, d, dn2);
   for (int l = nl - 1; l >= 0; --l) {
     const Layout::TfmLayer& b = lay.tl[l];
     const int u = 1 + 8 * l;

@@ -715,6 +715,18 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WP
   pm_gemm_big_body<Cfg, AKC, BKC, CHECK, Epi>(p == 0 ? p0 : p == 1 ? p1 : p2, id, tiles_i, tiles_j, smem);
 }
 
+// One product with a very long contraction and too few output tiles to fill the chip, cut into two halves of
+// the contraction that run side by side: block b works on half b / (tiles_i * tiles_j); each half writes its
+// own fp32 output and the consumer adds the two.  (256 x 256 tiles: the only block shape whose main loop gets
+// past 1.1 PFLOP/s needs K >= 8192 to amortise its start and end.)
+template <class Cfg, bool AKC, bool BKC, class Epi>
+__global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WPE, Cfg::WPE))) void pm_gemm_big_khalves_kernel(PmGemmProb<Epi> p0, PmGemmProb<Epi> p1, int tiles_i, int tiles_j) {
+  __shared__ __attribute__((aligned(16))) bf16_t smem[PmBigLds<Cfg, AKC, BKC>::elems];
+  const int nt = tiles_i * tiles_j;
+  const int p = blockIdx.x / nt, id = blockIdx.x - p * nt;      // uniform over the block
+  pm_gemm_big_body<Cfg, AKC, BKC, false, Epi>(p == 0 ? p0 : p1, id, tiles_i, tiles_j, smem);
+}
+
 // One product whose contraction runs over three operand pairs (PmKSeg3); pr.K = 3 * Kseg, pr.A / pr.B = pair 0.
 template <class Cfg, bool AKC, bool BKC, bool CHECK, class Epi>
 __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WPE, Cfg::WPE))) void pm_gemm_big_kseg3_kernel(PmGemmProb<Epi> pr, PmKSeg3 sg, int tiles_i, int tiles_j) {

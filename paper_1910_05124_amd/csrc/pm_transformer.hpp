@@ -176,7 +176,7 @@ __global__ __launch_bounds__(512) void pm_ln_bwd_kernel(const float* __restrict_
                                                         const float* __restrict__ mean, const float* __restrict__ rstd,
                                                         PmWLoc<T> gain_bkwd, const float* dx_res, float* dx_out,
                                                         T* dx_out_t, float* __restrict__ dgain, float* __restrict__ dbias,
-                                                        int rows, int d) {
+                                                        int rows, int d, const float* dy2) {
   __shared__ float4 red[8][2][64 * NC];                       // per wave: gain and bias partial sums
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const T* g = gain_bkwd.get();
@@ -204,6 +204,10 @@ __global__ __launch_bounds__(512) void pm_ln_bwd_kernel(const float* __restrict_
     for (int c = 0; c < NC; ++c) {
       const int j = 256 * c + 4 * lane;
       dyr[r][c] = j < d ? pm_ld4(dy + ro + j) : zero4;
+      if (dy2 && j < d) {       // the gradient arrives as two addends (dy2 may be the buffer dx_out is written to below)
+        const float4 e = pm_ld4(dy2 + ro + j);
+        dyr[r][c].x += e.x; dyr[r][c].y += e.y; dyr[r][c].z += e.z; dyr[r][c].w += e.w;
+      }
       xr[r][c] = j < d ? pm_ld4(x + ro + j) : zero4;
     }
   }
@@ -447,10 +451,10 @@ inline bool pm_ln_fwd_launch(hipStream_t st, const float* x, PmWLoc<T> gb, int b
 template <typename T>
 inline bool pm_ln_bwd_launch(hipStream_t st, const float* dy, const float* x, const float* mean, const float* rstd,
                              PmWLoc<T> gain_bkwd, const float* dx_res, float* dx_out, T* dx_out_t, float* dgain,
-                             float* dbias, int rows, int d) {
+                             float* dbias, int rows, int d, const float* dy2 = nullptr) {
   if (d & 3) return false;
   const dim3 grid((rows + 31) / 32), blk(512);
-#define PM_LNB(NC) hipLaunchKernelGGL((pm_ln_bwd_kernel<T, NC>), grid, blk, 0, st, dy, x, mean, rstd, gain_bkwd, dx_res, dx_out, dx_out_t, dgain, dbias, rows, d)
+#define PM_LNB(NC) hipLaunchKernelGGL((pm_ln_bwd_kernel<T, NC>), grid, blk, 0, st, dy, x, mean, rstd, gain_bkwd, dx_res, dx_out, dx_out_t, dgain, dbias, rows, d, dy2)
   if (d <= 256) PM_LNB(1);
   else if (d <= 512) PM_LNB(2);
   else if (d <= 768) PM_LNB(3);
