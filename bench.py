@@ -61,8 +61,12 @@ def main():
     ap.add_argument("--chain", action="store_true",
                     help="MLP workloads: the chained forward / data-gradient launches instead of one launch per product")
     ap.add_argument("--separate-update", action="store_true",
-                    help="Transformer workloads: always the separate update pass over all parameters (default: the "
-                         "weight matrices are updated in the epilogue of the grouped weight-gradient launch)")
+                    help="Transformer workloads: always the separate update pass over all parameters (default: on the large "
+                         "workload the weight matrices are updated inside the grouped weight-gradient launch)")
+    ap.add_argument("--single-context", action="store_true",
+                    help="skip the second context (separate update pass over all parameters) that the default Transformer "
+                         "run adds after the timed region for roofline_all_parameters: keeps a profiler's kernel list to one "
+                         "launch configuration")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run three plain device-to-device copies of this many MiB after the timed region "
                          "(a kernel of known traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings by)")
@@ -107,7 +111,7 @@ def main():
         xs = [torch.from_numpy(x).cuda() for x, _ in pool]
         ys = [torch.from_numpy(y).cuda() for _, y in pool]
 
-    def measure(separate_update, steps, timed):
+    def measure(placement, steps, timed):
         """One context; `steps` timed steps (if timed), then `steps` eager steps with four events per step, then up
         to 16 with an event pair around every product / attention launch."""
         with torch.cuda.stream(side):
@@ -119,7 +123,7 @@ def main():
                                 overlap_update=(launch == "overlap"), arch=w.arch.get("kind", "chain"),
                                 n_heads=w.arch.get("n_heads", 0), seq_len=w.arch.get("seq", 0),
                                 image_size=w.arch.get("image", 0), tau_recomp=tau_recomp, segment_size=args.recompute,
-                                stochastic=stoch, chained_launches=args.chain, separate_update=separate_update)
+                                stochastic=stoch, chained_launches=args.chain, update_placement=placement)
             eng = pm.PipeMare(w.layers, w.P, tau_fwd, tau_bkwd, sched, opts, params, stream=side)
 
             def run(n, base):
@@ -152,13 +156,13 @@ def main():
             eng.close()
         return r
 
-    m = measure(args.separate_update, args.steps, True)
+    m = measure("pass" if args.separate_update else "auto", args.steps, True)
     dt, stats, prof, cls = m["dt"], m["stats"], m["prof"], m["cls"]
     n_epilogue, n_pass = m["split"]
     # Where the weight matrices are updated inside the weight-gradient launch, the pass of the timed region covers
     # the remaining parameters only; a second context with the separate pass over ALL parameters gives the pass at
     # the full footprint and the product kernels without the update work inside (a few untimed steps)
-    m_sep = measure(True, max(4, min(args.steps, 20)), False) if n_epilogue > 0 else None
+    m_sep = measure("pass", max(4, min(args.steps, 20)), False) if (n_epilogue > 0 and not args.single_context) else None
     if args.calib_copy_mib > 0:
         with torch.cuda.stream(side):
             src = torch.ones(args.calib_copy_mib << 20, dtype=torch.uint8, device="cuda")
@@ -280,7 +284,7 @@ def main():
             "frac": round(a_all / HBM_PEAK_GBS, 4), "traffic": traffic_all, "traffic_source": traffic_all_src,
             "algorithmic_bytes": all_bytes, "bytes_per_param": bpp, "params": n_params,
             "avg_kernel_ms": round(ps["update_ms"], 5), "launches_timed": ps["n"],
-            "note": "second context of the same process with pm_opts.separate_update = 1 (untimed for `value`)"}
+            "note": "second context of the same process with pm_opts.update_placement = 1 (untimed for `value`)"}
         out["stage_gemms"]["separate_update"] = {
             "kernels_ms_per_step": round(ks * 1e3, 4),
             "kernels_achieved": round(gemm_flops / ks / 1e12, 2) if ks > 0 else None,

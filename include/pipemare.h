@@ -162,14 +162,16 @@ typedef struct {
                                 results up to the order of the fp32 partial sums.  0 (default): one launch per
                                 product, which measures slightly faster on the 16-layer MLP workload.  Ignored
                                 for other shapes, with recomputation and with overlap_update. */
-  int32_t separate_update;   /* 0 (default): where the weight gradients of a bf16 Transformer come out of one grouped
-                                launch with whole tiles (one microbatch per step, no clipping, no recomputation, no
-                                overlap_update), a block of that launch, having stored the gradients of its tile,
-                                applies the update of Sec. 2.1 / 3.1 / 3.2 to those parameters at once, and the update
-                                pass covers only the remaining ones (biases, LayerNorm, embedding): the gradient of a
-                                weight matrix is not read back from memory and the pass shrinks to a seventh.  Same
-                                arithmetic per parameter; pm_state still returns the gradient; pm_update_split tells
-                                what applies.  1: always the separate pass over all parameters. */
+  int32_t update_placement;  /* Where the update of Sec. 2.1 / 3.1 / 3.2 is applied to the weight matrices of a bf16
+                                Transformer whose weight gradients come out of one grouped launch with whole tiles
+                                (one microbatch per step, no clipping, no recomputation, no overlap_update).
+                                2: in that launch - a block that has stored the gradients of its tile applies the
+                                update to those parameters at once, and the update pass covers only the remaining
+                                ones (biases, LayerNorm, embedding); the gradient of a weight matrix is not read
+                                back from memory.  1: always the separate pass over all parameters.  0 (default):
+                                2 where the parameter state is too large to stay cached from step to step (the
+                                regime in which it measures faster), else 1.  Same arithmetic per parameter either
+                                way; pm_state still returns the gradient; pm_update_split tells what applies. */
 } pm_opts;
 
 const char* pm_status_str(pm_status s);
@@ -278,7 +280,7 @@ pm_status pm_device_recompute_slots(pm_ctx* ctx, int64_t* t_used, int32_t* rec_s
  * be NULL.  No device work. */
 pm_status pm_chained_units(pm_ctx* ctx, int32_t* n_forward, int32_t* n_backward);
 
-/* Where the update of Sec. 2.1 / 3 is applied in this context (see pm_opts.separate_update): *n_epilogue
+/* Where the update of Sec. 2.1 / 3 is applied in this context (see pm_opts.update_placement): *n_epilogue
  * parameters (weight matrices) are updated in the epilogues of the grouped weight-gradient launch, *n_pass
  * parameters (padding included) by the update pass that follows; *n_epilogue = 0 when the separate pass covers
  * everything.  Either output may be NULL.  No device work. */

@@ -46,6 +46,7 @@ PM_LR = {"const": 0, "step": 1, "warmup_invsqrt": 2}
 PM_OPT = {"sgdm": 0, "adamw": 1}
 PM_DTYPE = {"f32": 0, "bf16": 1}
 PM_LOSS = {"mse": 0, "xent": 1}
+PM_UPDATE_PLACEMENT = {"auto": 0, "pass": 1, "launch": 2}
 _STATUS = {0: "PM_OK", 1: "PM_EINVAL", 2: "PM_ENOMEM", 3: "PM_EHIP", 4: "PM_ESTATE", 5: "PM_EDIVERGED"}
 
 EXPORTS = ["pm_status_str", "pm_last_error", "pm_delays", "pm_slots", "pm_t1_lr", "pm_query_bytes",
@@ -78,7 +79,7 @@ class pm_opts(C.Structure):
                 ("n_heads", C.c_int32), ("seq_len", C.c_int32), ("image_size", C.c_int32),
                 ("tau_recomp", C.POINTER(C.c_int32)), ("segment_size", C.c_int32),
                 ("stochastic_delays", C.c_int32), ("tau_max", C.c_int32), ("delay_seed", C.c_uint64),
-                ("chained_launches", C.c_int32), ("separate_update", C.c_int32)]
+                ("chained_launches", C.c_int32), ("update_placement", C.c_int32)]
 
 
 class PmError(RuntimeError):
@@ -389,12 +390,12 @@ def make_opts(opt="sgdm", beta1=0.9, beta2=0.98, eps=1e-8, weight_decay=0.0, cli
               gamma_override=None, t1=True, t2=True, N=1, dtype="f32", loss="mse", microbatch=1,
               use_graph=False, sync_warmup=0, overlap_update=False, arch="chain", n_heads=0, seq_len=0,
               image_size=0, tau_recomp=None, segment_size=0, stochastic=None, chained_launches=False,
-              separate_update=False) -> pm_opts:
+              update_placement="auto") -> pm_opts:
     o = pm_opts(PM_OPT[opt], beta1, beta2, eps, weight_decay, clip_norm, D, None, int(t1), int(t2), N,
                 PM_DTYPE[dtype], PM_LOSS[loss], microbatch, int(use_graph), int(sync_warmup), int(overlap_update),
                 PM_ARCH[arch], int(n_heads), int(seq_len), int(image_size), None, int(segment_size),
                 0 if stochastic is None else 1, 0 if stochastic is None else int(stochastic["tau_max"]),
-                0 if stochastic is None else int(stochastic["seed"]), int(chained_launches), int(separate_update))
+                0 if stochastic is None else int(stochastic["seed"]), int(chained_launches), PM_UPDATE_PLACEMENT[update_placement])
     if tau_recomp is not None:
         arr_r = (C.c_int32 * len(tau_recomp))(*[int(t) for t in tau_recomp])
         o._keep_r = arr_r

@@ -147,6 +147,43 @@ __device__ __forceinline__ void pm_st8(bf16_t* p, const float* x) {
   o.w = pm_pack_bf16(x[6], x[7]);
   *reinterpret_cast<uint4*>(p) = o;
 }
+// The same through pointers known to address device memory (pointers read from a table in memory are generic to
+// the compiler, which then emits flat accesses: slower to issue, and counted with the LDS operations).
+typedef float __attribute__((ext_vector_type(4))) pm_vf4;
+typedef unsigned int __attribute__((ext_vector_type(4))) pm_vu4;
+#define PM_GLOBAL __attribute__((address_space(1)))
+// A pointer read from a table in device memory is generic to the compiler; sending it through the global address
+// space tells it where the pointer points, so accesses through it (and through pointers derived from it) become
+// global instead of flat ones.  Only for pointers that do address device memory.
+template <typename T>
+__device__ __forceinline__ T* pm_as_global(T* p) { return (T*)(T PM_GLOBAL*)p; }
+__device__ __forceinline__ void pm_ld8_g(const float* p, float* x) {
+  const pm_vf4 PM_GLOBAL* q = (const pm_vf4 PM_GLOBAL*)p;
+  const pm_vf4 a = q[0], b = q[1];
+  x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+__device__ __forceinline__ void pm_ld8_g(const bf16_t* p, float* x) {
+  const pm_vu4 a = *(const pm_vu4 PM_GLOBAL*)p;
+  x[0] = __uint_as_float(a.x << 16); x[1] = __uint_as_float(a.x & 0xffff0000u);
+  x[2] = __uint_as_float(a.y << 16); x[3] = __uint_as_float(a.y & 0xffff0000u);
+  x[4] = __uint_as_float(a.z << 16); x[5] = __uint_as_float(a.z & 0xffff0000u);
+  x[6] = __uint_as_float(a.w << 16); x[7] = __uint_as_float(a.w & 0xffff0000u);
+}
+__device__ __forceinline__ void pm_st8_g(float* p, const float* x) {
+  pm_vf4 PM_GLOBAL* q = (pm_vf4 PM_GLOBAL*)p;
+  pm_vf4 a, b;
+  a.x = x[0]; a.y = x[1]; a.z = x[2]; a.w = x[3]; b.x = x[4]; b.y = x[5]; b.z = x[6]; b.w = x[7];
+  q[0] = a;
+  q[1] = b;
+}
+__device__ __forceinline__ void pm_st8_g(bf16_t* p, const float* x) {
+  pm_vu4 o;
+  o.x = pm_pack_bf16(x[0], x[1]);
+  o.y = pm_pack_bf16(x[2], x[3]);
+  o.z = pm_pack_bf16(x[4], x[5]);
+  o.w = pm_pack_bf16(x[6], x[7]);
+  *(pm_vu4 PM_GLOBAL*)p = o;
+}
 
 // four consecutive elements: one float4 / one uint2
 __device__ __forceinline__ float4 pm_ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }

@@ -241,13 +241,16 @@ struct PmEpiFwd {
     if (z32) z32[o] = zz;
     if (a) stf(a + o, pm_act_fwd(zz, act));
   }
-  // eight consecutive columns j .. j+7 (j a multiple of 8) of row i: 16-byte accesses
-  __device__ __forceinline__ void op8(int i, int j, const float* acc) const {
-    float bb[8], zz[8], aa[8];
-    pm_ld8(b_ + j, bb);
+  // eight consecutive columns j .. j+7 (j a multiple of 8) of row i: 16-byte accesses.  pre8 requests what the
+  // epilogue reads from memory; the caller issues it for several groups before it finishes the first one, so the
+  // loads do not queue behind the stores of the group before (loads and stores complete in issue order).
+  struct Pre { float b[8]; };
+  __device__ __forceinline__ Pre pre8(int, int j) const { Pre p; pm_ld8(b_ + j, p.b); return p; }
+  __device__ __forceinline__ void op8(int i, int j, const float* acc, const Pre& p) const {
+    float zz[8], aa[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      zz[e] = acc[e] + bb[e];
+      zz[e] = acc[e] + p.b[e];
       aa[e] = pm_act_fwd(zz[e], act);
     }
     const int64_t o = (int64_t)i * ld + j;
@@ -268,13 +271,18 @@ struct PmEpiBwdData {
     const int64_t o = (int64_t)i * ld + j;
     stf(dzprev + o, act ? acc * pm_act_bwd(ldf(zprev + o), act) : acc);
   }
-  __device__ __forceinline__ void op8(int i, int j, const float* acc) const {
+  struct Pre { float zp[8]; };
+  __device__ __forceinline__ Pre pre8(int i, int j) const {
+    Pre p;
+    if (act) pm_ld8(zprev + (int64_t)i * ld + j, p.zp);
+    return p;
+  }
+  __device__ __forceinline__ void op8(int i, int j, const float* acc, const Pre& p) const {
     const int64_t o = (int64_t)i * ld + j;
-    float zp[8], out[8];
+    float out[8];
     if (act) {
-      pm_ld8(zprev + o, zp);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) out[e] = acc[e] * pm_act_bwd(zp[e], act);
+      for (int e = 0; e < 8; ++e) out[e] = acc[e] * pm_act_bwd(p.zp[e], act);
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) out[e] = acc[e];
@@ -290,17 +298,23 @@ struct PmEpiBwdWeight {
   __device__ __forceinline__ bool wants_colsum() const { return db != nullptr; }
   __device__ __forceinline__ void colsum(int i, float s) const { db[i] = accumulate ? db[i] + s : s; }
   __device__ __forceinline__ void begin() {}
+  __device__ __forceinline__ void as_global() { g = pm_as_global(g); if (db) db = pm_as_global(db); }
   __device__ __forceinline__ void operator()(int i, int j, float acc) const {
     const int64_t o = (int64_t)i * ld + j;
     g[o] = accumulate ? g[o] + acc : acc;
   }
-  __device__ __forceinline__ void op8(int i, int j, const float* acc) const {
+  struct Pre { float o[8]; };
+  __device__ __forceinline__ Pre pre8(int i, int j) const {
+    Pre p;
+    if (accumulate) pm_ld8(g + (int64_t)i * ld + j, p.o);
+    return p;
+  }
+  __device__ __forceinline__ void op8(int i, int j, const float* acc, const Pre& p) const {
     const int64_t o = (int64_t)i * ld + j;
     float out[8];
     if (accumulate) {
-      pm_ld8(g + o, out);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) out[e] += acc[e];
+      for (int e = 0; e < 8; ++e) out[e] = p.o[e] + acc[e];
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) out[e] = acc[e];
@@ -323,7 +337,13 @@ struct PmEpiBwdWeightUpd {
   __device__ __forceinline__ bool wants_colsum() const { return db != nullptr; }
   __device__ __forceinline__ void colsum(int i, float s) const { db[i] = s; }
   __device__ __forceinline__ void begin() {}
-  __device__ __forceinline__ void op8(int i, int j, const float* acc) const { pm_st8(g + (int64_t)i * ld + j, acc); }
+  __device__ __forceinline__ void as_global() {
+    g = pm_as_global(g); if (db) db = pm_as_global(db);
+    f.step = pm_as_global(f.step); f.hdr = pm_as_global(f.hdr);
+  }
+  struct Pre {};
+  __device__ __forceinline__ Pre pre8(int, int) const { return Pre(); }
+  __device__ __forceinline__ void op8(int i, int j, const float* acc, const Pre&) const { pm_st8(g + (int64_t)i * ld + j, acc); }
   // single elements are never needed: the launch that uses this epilogue takes whole tiles only
   __device__ __forceinline__ void operator()(int, int, float) const {}
 
@@ -348,16 +368,16 @@ struct PmEpiBwdWeightUpd {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         o[u] = (int64_t)(i0 + p + u * RPP + r) * ld + j0 + c8;
-        pm_ld8(g + o[u], gr[u]);
-        pm_ld8(f.w + o[u], w[u]);
-        pm_ld8(f.v + o[u], v[u]);
-        pm_ld8(f.d + o[u], d[u]);
-        if (f.opt == 1) pm_ld8(f.s + o[u], s[u]);
+        pm_ld8_g(g + o[u], gr[u]);
+        pm_ld8_g(f.w + o[u], w[u]);
+        pm_ld8_g(f.v + o[u], v[u]);
+        pm_ld8_g(f.d + o[u], d[u]);
+        if (f.opt == 1) pm_ld8_g(f.s + o[u], s[u]);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         float wn[8], ubv[8];
-        if (ub_from_ring) pm_ld8(f.ring + ubslot + o[u], ubv);
+        if (ub_from_ring) pm_ld8_g(f.ring + ubslot + o[u], ubv);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           float ge = gr[u][e] * gs;
@@ -377,15 +397,15 @@ struct PmEpiBwdWeightUpd {
           d[u][e] = f.gamma * d[u][e] + (1.f - f.gamma) * dw;
           bad |= !(fabsf(wn[e]) <= 3.0e38f);
         }
-        pm_st8(f.w + o[u], wn);
-        pm_st8(f.v + o[u], v[u]);
-        pm_st8(f.d + o[u], d[u]);
-        if (f.opt == 1) pm_st8(f.s + o[u], s[u]);
-        pm_st8(f.ring + wslot + o[u], wn);
+        pm_st8_g(f.w + o[u], wn);
+        pm_st8_g(f.v + o[u], v[u]);
+        pm_st8_g(f.d + o[u], d[u]);
+        if (f.opt == 1) pm_st8_g(f.s + o[u], s[u]);
+        pm_st8_g(f.ring + wslot + o[u], wn);
         if (f.has_ub) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) ubv[e] = (ub_from_ring ? ubv[e] : wn[e]) - corr * d[u][e];
-          pm_st8(f.ub + o[u], ubv);
+          pm_st8_g(f.ub + o[u], ubv);
         }
       }
     }

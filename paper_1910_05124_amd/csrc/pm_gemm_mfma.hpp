@@ -30,6 +30,7 @@
 // contiguous index, holding zeros beyond the logical extent.
 #pragma once
 #include <type_traits>
+#include <utility>
 
 #include "pm_common.hpp"
 #include "pm_elem.hpp"
@@ -116,6 +117,19 @@ struct PmGemmProb {
   int64_t ldb;
   Epi epi;
 };
+
+// A problem read from a table in device memory: its pointers are generic to the compiler, which would emit flat
+// loads for the operands (they count with the LDS operations too, so no wait in the main loop could be counted).
+// Epilogues with table-borne pointers provide as_global().
+template <class E, class = void> struct pm_has_as_global : std::false_type {};
+template <class E> struct pm_has_as_global<E, std::void_t<decltype(std::declval<E&>().as_global())>> : std::true_type {};
+template <class Epi>
+__device__ __forceinline__ void pm_prob_as_global(PmGemmProb<Epi>& pr) {
+  pr.A = pm_as_global(pr.A);
+  pr.B.base = pm_as_global(pr.B.base);
+  if (pr.B.slot) pr.B.slot = pm_as_global(pr.B.slot);
+  if constexpr (pm_has_as_global<Epi>::value) pr.epi.as_global();
+}
 
 template <int BI_, int BJ_, int WI_, int WJ_, int WK_, int BK_>
 struct PmGemmCfg {
@@ -299,7 +313,8 @@ __global__ __launch_bounds__(Cfg::NT) void pm_gemm_mfma_kernel(PmGemmProb<Epi> p
 template <class Cfg, bool AKC, bool BKC, class Epi>
 __global__ __launch_bounds__(Cfg::NT) void pm_gemm_mfma_grouped_kernel(const PmGemmProb<Epi>* __restrict__ probs) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[PmGemmLds<Cfg, AKC, BKC>::bytes];
-  const PmGemmProb<Epi> pr = probs[blockIdx.z];   // by value: the fields become wave-uniform registers
+  PmGemmProb<Epi> pr = probs[blockIdx.z];   // by value: the fields become wave-uniform registers
+  pm_prob_as_global(pr);
   pm_gemm_body<Cfg, AKC, BKC, Epi>(pr, pr.epi, blockIdx.x, blockIdx.y, smem);
 }
 
@@ -674,20 +689,40 @@ __device__ __forceinline__ void pm_gemm_big_body(const PmGemmProb<Epi>& pr, int 
 #pragma unroll
         for (int v = 0; v < 16; ++v)
           es[((a - a0) * 32 + 8 * (v >> 2) + 4 * kg + (v & 3)) * ES + b * 32 + lr] = acc[a][b][v];
-#pragma unroll 4
-    for (int c = lane; c < SR * (WT_J / 8); c += 64) {
-      const int r = c / (WT_J / 8), c8 = (c % (WT_J / 8)) * 8;
-      const int i = wi0 + a0 * 32 + r, j = wj0 + c8;
-      if (CHECK && (i >= I || j >= J)) continue;
-      float vals[8];
-      const float4 v0 = *reinterpret_cast<const float4*>(es + r * ES + c8);
-      const float4 v1 = *reinterpret_cast<const float4*>(es + r * ES + c8 + 4);
-      vals[0] = v0.x; vals[1] = v0.y; vals[2] = v0.z; vals[3] = v0.w;
-      vals[4] = v1.x; vals[5] = v1.y; vals[6] = v1.z; vals[7] = v1.w;
-      if (!CHECK || j + 8 <= J) {
-        epi.op8(i, j, vals);
-      } else {
-        for (int e = 0; e < 8 && j + e < J; ++e) epi(i, j + e, vals[e]);
+    // groups of up to four 8-column pieces per lane: what the epilogue reads from memory is requested for the
+    // whole group first (a load issued behind a store waits for that store to complete)
+    constexpr int ITERS = SR * (WT_J / 8) / 64, GRP = ITERS < 4 ? ITERS : 4;
+    static_assert(SR * (WT_J / 8) % 64 == 0 && ITERS % GRP == 0, "staged pass must split evenly over the lanes");
+#pragma unroll
+    for (int it0 = 0; it0 < ITERS; it0 += GRP) {
+      typename Epi::Pre pre[GRP];
+      int ii[GRP], jj[GRP];
+      bool full[GRP];
+#pragma unroll
+      for (int u = 0; u < GRP; ++u) {
+        const int c = lane + 64 * (it0 + u);
+        const int r = c / (WT_J / 8), c8 = (c % (WT_J / 8)) * 8;
+        ii[u] = wi0 + a0 * 32 + r;
+        jj[u] = wj0 + c8;
+        full[u] = !CHECK || (ii[u] < I && jj[u] + 8 <= J);
+        if (full[u]) pre[u] = epi.pre8(ii[u], jj[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < GRP; ++u) {
+        const int c = lane + 64 * (it0 + u);
+        const int r = c / (WT_J / 8), c8 = (c % (WT_J / 8)) * 8;
+        const int i = ii[u], j = jj[u];
+        if (CHECK && (i >= I || j >= J)) continue;
+        float vals[8];
+        const float4 v0 = *reinterpret_cast<const float4*>(es + r * ES + c8);
+        const float4 v1 = *reinterpret_cast<const float4*>(es + r * ES + c8 + 4);
+        vals[0] = v0.x; vals[1] = v0.y; vals[2] = v0.z; vals[3] = v0.w;
+        vals[4] = v1.x; vals[5] = v1.y; vals[6] = v1.z; vals[7] = v1.w;
+        if (full[u]) {
+          epi.op8(i, j, vals, pre[u]);
+        } else {
+          for (int e = 0; e < 8 && j + e < J; ++e) epi(i, j + e, vals[e]);
+        }
       }
     }
   }
@@ -761,7 +796,8 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WP
     if (list[mid].start <= pos) lo = mid; else hi = mid - 1;
   }
   const PmXcdSeg sg = list[lo];
-  const PmGemmProb<Epi> pr = probs[sg.prob];
+  PmGemmProb<Epi> pr = probs[sg.prob];
+  pm_prob_as_global(pr);
   const int ti = (pr.I + Cfg::BI - 1) / Cfg::BI, tj = (pr.J + Cfg::BJ - 1) / Cfg::BJ;
   pm_gemm_big_body<Cfg, AKC, BKC, CHECK, Epi>(pr, sg.tile0 + (pos - sg.start), ti, tj, smem, false);
 }

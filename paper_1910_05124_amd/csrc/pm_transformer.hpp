@@ -31,13 +31,18 @@ struct PmEpiFwdRes {
     const int64_t o = (int64_t)i * ld + j;
     out[o] = res[o] + acc + ldf(b_ + j);
   }
-  __device__ __forceinline__ void op8(int i, int j, const float* acc) const {
+  struct Pre { float b[8], r[8]; };
+  __device__ __forceinline__ Pre pre8(int i, int j) const {
+    Pre p;
+    pm_ld8(b_ + j, p.b);
+    pm_ld8(res + (int64_t)i * ld + j, p.r);
+    return p;
+  }
+  __device__ __forceinline__ void op8(int i, int j, const float* acc, const Pre& p) const {
     const int64_t o = (int64_t)i * ld + j;
-    float bb[8], rr[8], v[8];
-    pm_ld8(b_ + j, bb);
-    pm_ld8(res + o, rr);
+    float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = rr[e] + acc[e] + bb[e];
+    for (int e = 0; e < 8; ++e) v[e] = p.r[e] + acc[e] + p.b[e];
     pm_st8(out + o, v);
   }
 };
@@ -53,13 +58,18 @@ struct PmEpiF32 {
     const int64_t o = (int64_t)i * ld + j;
     out[o] = accumulate ? out[o] + acc : acc;
   }
-  __device__ __forceinline__ void op8(int i, int j, const float* acc) const {
+  struct Pre { float o[8]; };
+  __device__ __forceinline__ Pre pre8(int i, int j) const {
+    Pre p;
+    if (accumulate) pm_ld8(out + (int64_t)i * ld + j, p.o);
+    return p;
+  }
+  __device__ __forceinline__ void op8(int i, int j, const float* acc, const Pre& p) const {
     const int64_t o = (int64_t)i * ld + j;
     float v[8];
     if (accumulate) {
-      pm_ld8(out + o, v);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] += acc[e];
+      for (int e = 0; e < 8; ++e) v[e] = p.o[e] + acc[e];
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = acc[e];
@@ -191,7 +201,7 @@ __global__ __launch_bounds__(512) void pm_ln_bwd_kernel(const float* __restrict_
   }
   // all loads of the wave's four rows go out first (rows past the end re-read the last row and are
   // masked out below), so the wave pays the memory latency once instead of once per row
-  float4 dyr[4][NC], xr[4][NC];
+  float4 dyr[4][NC], xr[4][NC], rrr[4][NC];
   float mur[4], rsr[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
@@ -209,6 +219,8 @@ __global__ __launch_bounds__(512) void pm_ln_bwd_kernel(const float* __restrict_
         dyr[r][c].x += e.x; dyr[r][c].y += e.y; dyr[r][c].z += e.z; dyr[r][c].w += e.w;
       }
       xr[r][c] = j < d ? pm_ld4(x + ro + j) : zero4;
+      // (requested here, not row by row below: a load issued behind the stores of the row before would wait for them)
+      rrr[r][c] = (dx_res && j < d) ? pm_ld4(dx_res + ro + j) : zero4;
     }
   }
 #pragma unroll
@@ -223,10 +235,9 @@ __global__ __launch_bounds__(512) void pm_ln_bwd_kernel(const float* __restrict_
     for (int c = 0; c < NC; ++c) {
       const int j = 256 * c + 4 * lane;
       float4 dyv = dyr[r][c], xv = zero4;
-      rr[c] = zero4;
+      rr[c] = rrr[r][c];
       if (j < d) {
         xv = xr[r][c];
-        if (dx_res) rr[c] = pm_ld4(dx_res + ro + j);
         xv = make_float4((xv.x - mu) * rs, (xv.y - mu) * rs, (xv.z - mu) * rs, (xv.w - mu) * rs);
       }
       xh[c] = xv;

@@ -38,7 +38,7 @@ def make_oracle(w, params, tau_fwd, tau_bkwd, *, opt="sgdm", lr=0.01, beta=0.9, 
 def make_gpu(w, params, tau_fwd, tau_bkwd, *, opt="sgdm", lr=0.01, beta=0.9, beta2=0.98, eps=1e-8,
              weight_decay=0.0, clip_norm=0.0, D=0.9, K=0, t1=True, t2=True, N=1, sched=None,
              gamma_override=None, use_graph=False, dtype=None, stream=None, sync_warmup=0, overlap_update=False,
-             tau_recomp=None, segment=0, stochastic=None, chained_launches=False, separate_update=False):
+             tau_recomp=None, segment=0, stochastic=None, chained_launches=False, update_placement="auto"):
     import paper_1910_05124_amd as pm
     s = sched or dict(kind="const", base=lr)
     sc = pm.make_sched(kind=s["kind"], base=s["base"], init=s.get("init", 0.0), factor=s.get("factor", 1.0),
@@ -49,7 +49,7 @@ def make_gpu(w, params, tau_fwd, tau_bkwd, *, opt="sgdm", lr=0.01, beta=0.9, bet
                      overlap_update=overlap_update, arch=w.arch.get("kind", "chain"),
                      n_heads=w.arch.get("n_heads", 0), seq_len=w.arch.get("seq", 0),
                      image_size=w.arch.get("image", 0), tau_recomp=tau_recomp, segment_size=segment,
-                     stochastic=stochastic, chained_launches=chained_launches, separate_update=separate_update)
+                     stochastic=stochastic, chained_launches=chained_launches, update_placement=update_placement)
     return pm.PipeMare(w.layers, w.P, tau_fwd, tau_bkwd, sc, o, params, stream=stream)
 
 

@@ -131,6 +131,9 @@ def test_create_rejects_bad_arguments_before_touching_the_gpu():
     assert bad(opts=pm.make_opts(dtype="f32", loss="mse", microbatch=16, D=0.0)).name == "PM_EINVAL"
     assert bad(opts=pm.make_opts(dtype="f32", loss="mse", microbatch=0, D=0.5)).name == "PM_EINVAL"
     assert bad(opts=pm.make_opts(dtype="f32", loss="mse", microbatch=16, D=0.5, N=0)).name == "PM_EINVAL"
+    odd = pm.make_opts(dtype="f32", loss="mse", microbatch=16, D=0.5)
+    odd.update_placement = 3                                          # 0 automatic, 1 separate pass, 2 weight-gradient launch
+    assert bad(opts=odd).name == "PM_EINVAL"
     broken = list(w.layers)
     broken[1] = wl.Layer("linear", 32, 64, "relu", 2)                  # does not chain
     assert bad(layers=broken).name == "PM_EINVAL"

@@ -308,7 +308,7 @@ def test_narrow_transformer_with_the_stage_table_of_the_12_layer_workload(torch_
 @pytest.mark.parametrize("opt,tile", [("sgdm", 128), ("adamw", 128), ("adamw", 256)])
 def test_update_in_the_weight_gradient_epilogue_matches_the_separate_pass(torch_cuda, opt, tile):
     """Where the update is applied (in the epilogue of the grouped weight-gradient launch for the weight matrices,
-    or by the pass over all parameters: pm_opts.separate_update) must not change what is computed: same
+    or by the pass over all parameters: pm_opts.update_placement) must not change what is computed: same
     gradients, same recurrences per parameter.  Two contexts step on the same batches; after every step every
     state array of every unit is compared, then the second context is given the first one's state (checkpoint
     image), so that each step starts from identical bits and only the order of the fp32 atomics inside a step
@@ -323,8 +323,8 @@ def test_update_in_the_weight_gradient_epilogue_matches_the_separate_pass(torch_
     kw = _kw(w, weight_decay=0.01) if opt == "adamw" else dict(opt="sgdm", lr=0.002, beta=0.9, D=0.5, K=10, weight_decay=0.01)
     params = wl.init_params(w)
     tf, tb = po.pipeline_delays(w.P, 1)
-    ga = make_gpu(w, params, tf, tb, **kw)
-    gb = make_gpu(w, params, tf, tb, separate_update=True, **kw)
+    ga = make_gpu(w, params, tf, tb, update_placement="launch", **kw)
+    gb = make_gpu(w, params, tf, tb, update_placement="pass", **kw)
     ne, npass = ga.update_split()
     n_mat = sum(L.n_in * L.n_out for L in w.layers if L.kind == "linear")
     assert ne == n_mat and npass > 0, (ne, npass, n_mat)
