@@ -152,11 +152,12 @@ __device__ __forceinline__ void pm_st8(bf16_t* p, const float* x) {
 typedef float __attribute__((ext_vector_type(4))) pm_vf4;
 typedef unsigned int __attribute__((ext_vector_type(4))) pm_vu4;
 #define PM_GLOBAL __attribute__((address_space(1)))
-// A pointer read from a table in device memory is generic to the compiler; sending it through the global address
-// space tells it where the pointer points, so accesses through it (and through pointers derived from it) become
-// global instead of flat ones.  Only for pointers that do address device memory.
-template <typename T>
-__device__ __forceinline__ T* pm_as_global(T* p) { return (T*)(T PM_GLOBAL*)p; }
+// 16 bytes of bf16 operands through the global address space (see above: a pointer that came out of a table in
+// device memory would otherwise be dereferenced with a flat load)
+__device__ __forceinline__ uint4 pm_ldg16(const bf16_t* p) {
+  const pm_vu4 a = *(const pm_vu4 PM_GLOBAL*)p;
+  return make_uint4(a.x, a.y, a.z, a.w);
+}
 __device__ __forceinline__ void pm_ld8_g(const float* p, float* x) {
   const pm_vf4 PM_GLOBAL* q = (const pm_vf4 PM_GLOBAL*)p;
   const pm_vf4 a = q[0], b = q[1];

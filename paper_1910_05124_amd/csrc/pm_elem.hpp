@@ -291,6 +291,7 @@ struct PmEpiBwdData {
   }
 };
 // backward weight: g[i, j] (+)= acc, fp32; db[i] (+)= column sum of the A operand (MFMA path only)
+// (runs in table-driven launches: its accesses name the global address space, see pm_ldg16)
 struct PmEpiBwdWeight {
   static constexpr bool kColSumA = true;
   float* g; int ld; int accumulate;
@@ -298,7 +299,6 @@ struct PmEpiBwdWeight {
   __device__ __forceinline__ bool wants_colsum() const { return db != nullptr; }
   __device__ __forceinline__ void colsum(int i, float s) const { db[i] = accumulate ? db[i] + s : s; }
   __device__ __forceinline__ void begin() {}
-  __device__ __forceinline__ void as_global() { g = pm_as_global(g); if (db) db = pm_as_global(db); }
   __device__ __forceinline__ void operator()(int i, int j, float acc) const {
     const int64_t o = (int64_t)i * ld + j;
     g[o] = accumulate ? g[o] + acc : acc;
@@ -306,7 +306,7 @@ struct PmEpiBwdWeight {
   struct Pre { float o[8]; };
   __device__ __forceinline__ Pre pre8(int i, int j) const {
     Pre p;
-    if (accumulate) pm_ld8(g + (int64_t)i * ld + j, p.o);
+    if (accumulate) pm_ld8_g(g + (int64_t)i * ld + j, p.o);
     return p;
   }
   __device__ __forceinline__ void op8(int i, int j, const float* acc, const Pre& p) const {
@@ -319,7 +319,7 @@ struct PmEpiBwdWeight {
 #pragma unroll
       for (int e = 0; e < 8; ++e) out[e] = acc[e];
     }
-    pm_st8(g + o, out);
+    pm_st8_g(g + o, out);
   }
 };
 
@@ -337,13 +337,9 @@ struct PmEpiBwdWeightUpd {
   __device__ __forceinline__ bool wants_colsum() const { return db != nullptr; }
   __device__ __forceinline__ void colsum(int i, float s) const { db[i] = s; }
   __device__ __forceinline__ void begin() {}
-  __device__ __forceinline__ void as_global() {
-    g = pm_as_global(g); if (db) db = pm_as_global(db);
-    f.step = pm_as_global(f.step); f.hdr = pm_as_global(f.hdr);
-  }
   struct Pre {};
   __device__ __forceinline__ Pre pre8(int, int) const { return Pre(); }
-  __device__ __forceinline__ void op8(int i, int j, const float* acc, const Pre&) const { pm_st8(g + (int64_t)i * ld + j, acc); }
+  __device__ __forceinline__ void op8(int i, int j, const float* acc, const Pre&) const { pm_st8_g(g + (int64_t)i * ld + j, acc); }
   // single elements are never needed: the launch that uses this epilogue takes whole tiles only
   __device__ __forceinline__ void operator()(int, int, float) const {}
 

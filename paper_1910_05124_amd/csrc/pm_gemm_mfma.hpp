@@ -30,7 +30,6 @@
 // contiguous index, holding zeros beyond the logical extent.
 #pragma once
 #include <type_traits>
-#include <utility>
 
 #include "pm_common.hpp"
 #include "pm_elem.hpp"
@@ -62,10 +61,10 @@ struct PmTileLoader {
         const int lr = c / (S::lds_cols / 8), lc = (c % (S::lds_cols / 8)) * 8;
         if (KC) {
           const int row = r0 + lr, k = k0 + lc;
-          if (row < R && k < K8) v = *reinterpret_cast<const uint4*>(X + (int64_t)row * ld + k);
+          if (row < R && k < K8) v = pm_ldg16(X + (int64_t)row * ld + k);
         } else {
           const int k = k0 + lr, row = r0 + lc;
-          if (k < K && row < R8) v = *reinterpret_cast<const uint4*>(X + (int64_t)k * ld + row);
+          if (k < K && row < R8) v = pm_ldg16(X + (int64_t)k * ld + row);
         }
       }
       r[p] = v;
@@ -117,19 +116,6 @@ struct PmGemmProb {
   int64_t ldb;
   Epi epi;
 };
-
-// A problem read from a table in device memory: its pointers are generic to the compiler, which would emit flat
-// loads for the operands (they count with the LDS operations too, so no wait in the main loop could be counted).
-// Epilogues with table-borne pointers provide as_global().
-template <class E, class = void> struct pm_has_as_global : std::false_type {};
-template <class E> struct pm_has_as_global<E, std::void_t<decltype(std::declval<E&>().as_global())>> : std::true_type {};
-template <class Epi>
-__device__ __forceinline__ void pm_prob_as_global(PmGemmProb<Epi>& pr) {
-  pr.A = pm_as_global(pr.A);
-  pr.B.base = pm_as_global(pr.B.base);
-  if (pr.B.slot) pr.B.slot = pm_as_global(pr.B.slot);
-  if constexpr (pm_has_as_global<Epi>::value) pr.epi.as_global();
-}
 
 template <int BI_, int BJ_, int WI_, int WJ_, int WK_, int BK_>
 struct PmGemmCfg {
@@ -313,8 +299,7 @@ __global__ __launch_bounds__(Cfg::NT) void pm_gemm_mfma_kernel(PmGemmProb<Epi> p
 template <class Cfg, bool AKC, bool BKC, class Epi>
 __global__ __launch_bounds__(Cfg::NT) void pm_gemm_mfma_grouped_kernel(const PmGemmProb<Epi>* __restrict__ probs) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[PmGemmLds<Cfg, AKC, BKC>::bytes];
-  PmGemmProb<Epi> pr = probs[blockIdx.z];   // by value: the fields become wave-uniform registers
-  pm_prob_as_global(pr);
+  const PmGemmProb<Epi> pr = probs[blockIdx.z];   // by value: the fields become wave-uniform registers
   pm_gemm_body<Cfg, AKC, BKC, Epi>(pr, pr.epi, blockIdx.x, blockIdx.y, smem);
 }
 
@@ -435,10 +420,10 @@ struct PmBigLoader {
       uint4 v = make_uint4(0, 0, 0, 0);
       if (KC) {
         const int row = r0 + lr, k = k0 + lc;
-        if (!CHECK || (row < R && k < K8)) v = *reinterpret_cast<const uint4*>(X + (int64_t)row * ld + k);
+        if (!CHECK || (row < R && k < K8)) v = pm_ldg16(X + (int64_t)row * ld + k);
       } else {
         const int k = k0 + lr, row = r0 + lc;
-        if (!CHECK || (k < K && row < R8)) v = *reinterpret_cast<const uint4*>(X + (int64_t)k * ld + row);
+        if (!CHECK || (k < K && row < R8)) v = pm_ldg16(X + (int64_t)k * ld + row);
       }
       r[p] = v;
     }
@@ -796,8 +781,7 @@ __global__ __launch_bounds__(Cfg::NT) __attribute__((amdgpu_waves_per_eu(Cfg::WP
     if (list[mid].start <= pos) lo = mid; else hi = mid - 1;
   }
   const PmXcdSeg sg = list[lo];
-  PmGemmProb<Epi> pr = probs[sg.prob];
-  pm_prob_as_global(pr);
+  const PmGemmProb<Epi> pr = probs[sg.prob];
   const int ti = (pr.I + Cfg::BI - 1) / Cfg::BI, tj = (pr.J + Cfg::BJ - 1) / Cfg::BJ;
   pm_gemm_big_body<Cfg, AKC, BKC, CHECK, Epi>(pr, sg.tile0 + (pos - sg.start), ti, tj, smem, false);
 }
