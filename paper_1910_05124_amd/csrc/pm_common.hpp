@@ -152,6 +152,25 @@ __device__ __forceinline__ void pm_st8(bf16_t* p, const float* x) {
 typedef float __attribute__((ext_vector_type(4))) pm_vf4;
 typedef unsigned int __attribute__((ext_vector_type(4))) pm_vu4;
 #define PM_GLOBAL __attribute__((address_space(1)))
+// Eight consecutive elements as they come from memory: requesting and widening are separate steps, so that several
+// requests can be in flight before the first one is waited for (widening bf16 right behind its load would wait).
+template <typename T> struct PmRaw8;
+template <> struct PmRaw8<float> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const float* p) { a = reinterpret_cast<const float4*>(p)[0]; b = reinterpret_cast<const float4*>(p)[1]; }
+  __device__ __forceinline__ void widen(float* x) const { x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w; }
+};
+template <> struct PmRaw8<bf16_t> {
+  uint4 a;
+  __device__ __forceinline__ void load(const bf16_t* p) { a = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void widen(float* x) const {
+    x[0] = __uint_as_float(a.x << 16); x[1] = __uint_as_float(a.x & 0xffff0000u);
+    x[2] = __uint_as_float(a.y << 16); x[3] = __uint_as_float(a.y & 0xffff0000u);
+    x[4] = __uint_as_float(a.z << 16); x[5] = __uint_as_float(a.z & 0xffff0000u);
+    x[6] = __uint_as_float(a.w << 16); x[7] = __uint_as_float(a.w & 0xffff0000u);
+  }
+};
+
 // 16 bytes of bf16 operands through the global address space (see above: a pointer that came out of a table in
 // device memory would otherwise be dereferenced with a flat load)
 __device__ __forceinline__ uint4 pm_ldg16(const bf16_t* p) {
@@ -242,6 +261,30 @@ __device__ __forceinline__ float pm_act_bwd(float z, int act) {
     return cdf + z * e * 0.39894228040143268f;
   }
   return 1.f;
+}
+
+// eight values at once with the (wave-uniform) choice of the activation taken once, not per element
+__device__ __forceinline__ void pm_act_fwd8(const float* z, float* a, int act) {
+  if (act == 1) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] = z[e] > 0.f ? z[e] : 0.f;
+  } else if (act == 2) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] = pm_act_fwd(z[e], 2);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] = z[e];
+  }
+}
+// out[e] = acc[e] * act'(z[e])
+__device__ __forceinline__ void pm_act_bwd8(const float* acc, const float* z, float* out, int act) {
+  if (act == 1) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) out[e] = z[e] > 0.f ? acc[e] : 0.f;
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) out[e] = acc[e] * pm_act_bwd(z[e], act);
+  }
 }
 
 __device__ __forceinline__ float pm_wave_sum(float v) {

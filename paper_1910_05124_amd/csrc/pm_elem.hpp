@@ -244,19 +244,20 @@ struct PmEpiFwd {
   // eight consecutive columns j .. j+7 (j a multiple of 8) of row i: 16-byte accesses.  pre8 requests what the
   // epilogue reads from memory; the caller issues it for several groups before it finishes the first one, so the
   // loads do not queue behind the stores of the group before (loads and stores complete in issue order).
-  struct Pre { float b[8]; };
-  __device__ __forceinline__ Pre pre8(int, int j) const { Pre p; pm_ld8(b_ + j, p.b); return p; }
+  struct Pre { PmRaw8<T> b; };
+  __device__ __forceinline__ Pre pre8(int, int j) const { Pre p; p.b.load(b_ + j); return p; }
   __device__ __forceinline__ void op8(int i, int j, const float* acc, const Pre& p) const {
-    float zz[8], aa[8];
+    float zz[8], aa[8], bb[8];
+    p.b.widen(bb);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      zz[e] = acc[e] + p.b[e];
-      aa[e] = pm_act_fwd(zz[e], act);
-    }
+    for (int e = 0; e < 8; ++e) zz[e] = acc[e] + bb[e];
     const int64_t o = (int64_t)i * ld + j;
     if (z) pm_st8(z + o, zz);
     if (z32) pm_st8(z32 + o, zz);
-    if (a) pm_st8(a + o, aa);
+    if (a) {
+      pm_act_fwd8(zz, aa, act);
+      pm_st8(a + o, aa);
+    }
   }
 };
 // backward data: dz_prev = acc * act'(z_prev)   (act == 0: dz_prev = acc, z_prev is not read)
@@ -271,18 +272,19 @@ struct PmEpiBwdData {
     const int64_t o = (int64_t)i * ld + j;
     stf(dzprev + o, act ? acc * pm_act_bwd(ldf(zprev + o), act) : acc);
   }
-  struct Pre { float zp[8]; };
+  struct Pre { PmRaw8<T> zp; };
   __device__ __forceinline__ Pre pre8(int i, int j) const {
     Pre p;
-    if (act) pm_ld8(zprev + (int64_t)i * ld + j, p.zp);
+    if (act) p.zp.load(zprev + (int64_t)i * ld + j);
     return p;
   }
   __device__ __forceinline__ void op8(int i, int j, const float* acc, const Pre& p) const {
     const int64_t o = (int64_t)i * ld + j;
     float out[8];
     if (act) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) out[e] = acc[e] * pm_act_bwd(p.zp[e], act);
+      float zp[8];
+      p.zp.widen(zp);
+      pm_act_bwd8(acc, zp, out, act);
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) out[e] = acc[e];

@@ -31,18 +31,20 @@ struct PmEpiFwdRes {
     const int64_t o = (int64_t)i * ld + j;
     out[o] = res[o] + acc + ldf(b_ + j);
   }
-  struct Pre { float b[8], r[8]; };
+  struct Pre { PmRaw8<T> b; PmRaw8<float> r; };
   __device__ __forceinline__ Pre pre8(int i, int j) const {
     Pre p;
-    pm_ld8(b_ + j, p.b);
-    pm_ld8(res + (int64_t)i * ld + j, p.r);
+    p.b.load(b_ + j);
+    p.r.load(res + (int64_t)i * ld + j);
     return p;
   }
   __device__ __forceinline__ void op8(int i, int j, const float* acc, const Pre& p) const {
     const int64_t o = (int64_t)i * ld + j;
-    float v[8];
+    float v[8], bb[8], rr[8];
+    p.b.widen(bb);
+    p.r.widen(rr);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = p.r[e] + acc[e] + p.b[e];
+    for (int e = 0; e < 8; ++e) v[e] = rr[e] + acc[e] + bb[e];
     pm_st8(out + o, v);
   }
 };
