@@ -174,8 +174,7 @@ template <> struct PmRaw8<bf16_t> {
 // 16 bytes of bf16 operands through the global address space (see above: a pointer that came out of a table in
 // device memory would otherwise be dereferenced with a flat load)
 __device__ __forceinline__ uint4 pm_ldg16(const bf16_t* p) {
-  const pm_vu4 a = *(const pm_vu4 PM_GLOBAL*)p;
-  return make_uint4(a.x, a.y, a.z, a.w);
+  return __builtin_bit_cast(uint4, *(const pm_vu4 PM_GLOBAL*)p);
 }
 __device__ __forceinline__ void pm_ld8_g(const float* p, float* x) {
   const pm_vf4 PM_GLOBAL* q = (const pm_vf4 PM_GLOBAL*)p;

@@ -61,10 +61,10 @@ struct PmTileLoader {
         const int lr = c / (S::lds_cols / 8), lc = (c % (S::lds_cols / 8)) * 8;
         if (KC) {
           const int row = r0 + lr, k = k0 + lc;
-          if (row < R && k < K8) v = pm_ldg16(X + (int64_t)row * ld + k);
+          if (row < R && k < K8) v = *reinterpret_cast<const uint4*>(X + (int64_t)row * ld + k);
         } else {
           const int k = k0 + lr, row = r0 + lc;
-          if (k < K && row < R8) v = pm_ldg16(X + (int64_t)k * ld + row);
+          if (k < K && row < R8) v = *reinterpret_cast<const uint4*>(X + (int64_t)k * ld + row);
         }
       }
       r[p] = v;
@@ -420,10 +420,14 @@ struct PmBigLoader {
       uint4 v = make_uint4(0, 0, 0, 0);
       if (KC) {
         const int row = r0 + lr, k = k0 + lc;
-        if (!CHECK || (row < R && k < K8)) v = pm_ldg16(X + (int64_t)row * ld + k);
+        // (the explicit global load only where the load is unconditional: under a predicate it came out with a wait
+        // behind every second load)
+        if (!CHECK) v = pm_ldg16(X + (int64_t)row * ld + k);
+        else if (row < R && k < K8) v = *reinterpret_cast<const uint4*>(X + (int64_t)row * ld + k);
       } else {
         const int k = k0 + lr, row = r0 + lc;
-        if (!CHECK || (k < K && row < R8)) v = pm_ldg16(X + (int64_t)k * ld + row);
+        if (!CHECK) v = pm_ldg16(X + (int64_t)k * ld + row);
+        else if (k < K && row < R8) v = *reinterpret_cast<const uint4*>(X + (int64_t)k * ld + row);
       }
       r[p] = v;
     }
