@@ -151,6 +151,11 @@ def _run_golden(name, *, grad_tol, move_tol, min_move=0.0):
     worst = dict(w=0.0, g=0.0)
     with torch.cuda.stream(side):
         g = make_gpu(w, params, tf, tb, use_graph=True, stream=side, **kw)
+        # where the update runs by default (pm_opts.update_placement = 0): inside the weight-gradient launch for the
+        # weight matrices of the 12-layer workload (state beyond the caches), the separate pass everywhere else
+        n_launch, n_pass = g.update_split()
+        n_mat = sum(L.n_in * L.n_out for L in w.layers if L.kind == "linear")
+        assert n_launch == (n_mat if cfg == 5 else 0) and n_pass > 0, (cfg, n_launch, n_pass)
         x0, y0 = stream.batch(0)
         xd, yd = torch.from_numpy(x0).cuda(), torch.from_numpy(y0).cuda()
         for k in range(steps):
