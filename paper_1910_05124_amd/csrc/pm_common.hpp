@@ -147,11 +147,6 @@ __device__ __forceinline__ void pm_st8(bf16_t* p, const float* x) {
   o.w = pm_pack_bf16(x[6], x[7]);
   *reinterpret_cast<uint4*>(p) = o;
 }
-// The same through pointers known to address device memory (pointers read from a table in memory are generic to
-// the compiler, which then emits flat accesses: slower to issue, and counted with the LDS operations).
-typedef float __attribute__((ext_vector_type(4))) pm_vf4;
-typedef unsigned int __attribute__((ext_vector_type(4))) pm_vu4;
-#define PM_GLOBAL __attribute__((address_space(1)))
 // Eight consecutive elements as they come from memory: requesting and widening are separate steps, so that several
 // requests can be in flight before the first one is waited for (widening bf16 right behind its load would wait).
 template <typename T> struct PmRaw8;
@@ -171,8 +166,13 @@ template <> struct PmRaw8<bf16_t> {
   }
 };
 
-// 16 bytes of bf16 operands through the global address space (see above: a pointer that came out of a table in
-// device memory would otherwise be dereferenced with a flat load)
+// Eight elements / 16 bytes of operands through pointers known to address device memory.  A pointer read from a
+// table in device memory is generic to the compiler, which then emits flat accesses: slower to issue, and counted
+// with the LDS operations, so that no wait of a software pipeline can be a counted one.
+typedef float __attribute__((ext_vector_type(4))) pm_vf4;
+typedef unsigned int __attribute__((ext_vector_type(4))) pm_vu4;
+#define PM_GLOBAL __attribute__((address_space(1)))
+// 16 bytes of bf16 operands
 __device__ __forceinline__ uint4 pm_ldg16(const bf16_t* p) {
   return __builtin_bit_cast(uint4, *(const pm_vu4 PM_GLOBAL*)p);
 }
