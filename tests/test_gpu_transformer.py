@@ -369,3 +369,42 @@ def test_update_in_the_weight_gradient_epilogue_matches_the_separate_pass(torch_
           "other parameters", worst[False])
     ga.close()
     gb.close()
+
+
+def test_wide_vocabulary_transformer_large_tile_paths_live_oracle(torch_cuda):
+    """One layer of width 1024 (16 heads) over a vocabulary of 16384, 16 x 256 tokens: the smallest shapes that take
+    every large-tile path of the 12-layer workload - the grouped weight-gradient launch on 256 x 256 tiles with the
+    update of the weight matrices inside it (40 M parameters: the automatic placement chooses it), and the data
+    gradient through the vocabulary projection as two halves of the contraction whose fp32 results the final
+    LayerNorm backward adds.  Every entry of every unit against the live oracle (the stored-value runs of the large
+    workload compare samples and segment sums)."""
+    w = wl.transformer(1, 1024, 16, 1024, 16384, 256, 16, dtype="bf16")
+    kw = dict(opt="sgdm", lr=0.002, beta=0.9, D=0.5, K=4)
+    params = wl.init_params(w)
+    tf, tb = po.pipeline_delays(w.P, 1)
+    o = make_oracle(w, params, tf, tb, **kw)
+    g = make_gpu(w, params, tf, tb, **kw)
+    n_mat = sum(L.n_in * L.n_out for L in w.layers if L.kind == "linear")
+    assert g.update_split()[0] == n_mat            # the update of the matrices runs inside the weight-gradient launch
+    stream = wl.TokenStream(w)
+    steps = 3
+    for k in range(steps):
+        x, y = stream.batch(k)
+        lo = o.step((x, y))
+        lg = g.step(torch_cuda.from_numpy(x).cuda(), torch_cuda.from_numpy(y).cuda(), want_loss=True)
+        assert lg == pytest.approx(lo, rel=2e-2)
+        if k == 0:
+            # consumed gradients of the first step (same weights on both sides), per unit max |dg| / max |g|
+            skip = key_bias_entries(w)
+            for u in range(len(w.layers)):
+                gg, go = g.state(4, u), o.last_grads[u]
+                if u in skip:                      # the matrix part only (the key bias has a zero gradient)
+                    gg, go = gg[:skip[u].start], go[:skip[u].start]
+                rel = float(np.max(np.abs(gg - go)) / max(float(np.max(np.abs(go))), 1e-300))
+                assert rel <= 3e-2, (u, rel)
+    err, errs = max_rel_err(g.weights(), o.weights(), skip=key_bias_entries(w))
+    mv, mvs = movement_rel_l2(g.weights(), o.weights(), params)
+    print("wide vocabulary, large tiles: max-rel", err, "movement rel-L2", mv)
+    assert err <= TOL["bf16"], errs
+    assert max(m for u, m in enumerate(mvs) if u not in key_bias_entries(w)) <= 0.15, mvs
+    g.close()
