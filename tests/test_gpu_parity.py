@@ -233,7 +233,8 @@ def test_chained_launches_are_left_out_where_the_shapes_do_not_qualify(torch_cud
 # ------------------------------------------------------------------------------- linear primitives
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("shape", [(128, 1024, 1024), (48, 72, 200), (300, 264, 136), (128, 1024, 16), (16, 64, 64),
-                                   (2048, 512, 2048), (4096, 1024, 4096), (4000, 1000, 4040), (8192, 512, 1024)])
+                                   (2048, 512, 2048), (4096, 1024, 4096), (4000, 1000, 4040), (8192, 512, 1024),
+                                   (8192, 1024, 1024), (8192, 4096, 1024)])     # the last two: 256 x 128 / 128 x 256 blocks
 def test_linear_primitives_against_numpy(torch_cuda, dtype, shape):
     import paper_1910_05124_amd as pm
     torch = torch_cuda
