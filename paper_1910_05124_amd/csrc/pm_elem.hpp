@@ -410,6 +410,9 @@ struct PmEpiBwdWeightUpd {
     if (bad) f.hdr->diverged = 1;
   }
 };
+// true for the epilogues whose products run faster on the rectangular 8-wave blocks inside a training step too (see
+// PmBigTall / PmBigWide); specialised next to those epilogues
+template <class E> struct pm_rect_tiles : std::false_type {};
 // true for an epilogue with a tile-wide second phase (update_tile)
 template <class E, class = void> struct pm_has_tile_update : std::false_type {};
 template <class E> struct pm_has_tile_update<E, std::void_t<decltype(E::kTileUpdate)>> : std::true_type {};

@@ -808,10 +808,11 @@ using PmBig64 = PmBigCfg<64, 64, 2, 2>;
 // 256 x 128 and 128 x 256 blocks, 8 waves x (64 x 64), one block per compute unit: the operand tile with 256 rows is
 // written to LDS once for two of the other's (a quarter less LDS write traffic and global load issue than two
 // 128 x 128 blocks), with the same eight waves per compute unit.  Measured stand-alone on the token-rich products of
-// the 12-layer workload (8192 rows; one block per compute unit or a few rounds) against 128 x 128: projections
-// in one launch 77 -> 65 us, K = 4096 forward 78 -> 73 us, feed-forward expansion 88 -> 81 us (256 x 128); data
-// gradients 23 -> 21 us (K = 1024), 79 -> 74 us (K = 4096), 92 -> 87 us (4096 columns; 128 x 256); the vocabulary
-// projection (hundreds of rounds, fp32 output) is slower on them and stays on 128 x 128.
+// the 12-layer workload (8192 rows; one block per compute unit or a few rounds, operands warm) against 128 x 128:
+// K = 4096 forward 78 -> 73 us, feed-forward expansion 88 -> 81 us (256 x 128); data gradients 23 -> 21 us (K = 1024),
+// 79 -> 74 us (K = 4096), 92 -> 87 us (4096 columns; 128 x 256); the vocabulary projection (hundreds of rounds, fp32
+// output) is slower on them.  Inside a step only some of these gains remain (pm_rect_tiles says which epilogues
+// take the rectangular blocks).
 using PmBigTall = PmBigCfg<256, 128, 4, 2>;
 using PmBigWide = PmBigCfg<128, 256, 2, 4>;
 // a problem for these blocks: whole tiles, at least one per compute unit and at most a few rounds, K >= 1024
@@ -870,7 +871,7 @@ inline bool pm_big_try(hipStream_t st, const PmGemmProb<Epi>& pr) {
   }
   // activations times weights with whole rectangular tiles: the tall block where the weights are read along the
   // contraction (forward), the wide one where they are read across it (data gradient)
-  if constexpr (AKC) {
+  if constexpr (AKC && pm_rect_tiles<Epi>::value) {
     using Rect = std::conditional_t<BKC, PmBigTall, PmBigWide>;
     if (pm_big_rect_suits<Rect>(pr.I, pr.J, pr.K)) {
       const int ti = pr.I / Rect::BI, tj = pr.J / Rect::BJ;
@@ -901,12 +902,6 @@ inline bool pm_gemm_multi3_try(hipStream_t st, const PmGemmProb<Epi> (&pr)[3]) {
     if (!pm_mfma_fits(I, J, K, pr[p].A, pr[p].lda, 1, pr[p].B.base, pr[p].B.stride, pr[p].ldb, 1)) return false;
   }
   const long t128 = (long)((I + 127) / 128) * ((J + 127) / 128), t64 = (long)((I + 63) / 64) * ((J + 63) / 64);
-  if (pm_big_aligned<PmBigTall>(I, J, K) && K >= 1024 && 3L * (I / 256) * (J / 128) >= 256 && 3L * (I / 256) * (J / 128) <= 2048) {
-    const int ti = I / 256, tj = J / 128;
-    hipLaunchKernelGGL((pm_gemm_big_multi3_kernel<PmBigTall, true, true, false, Epi>), dim3(3 * ti * tj), dim3(PmBigTall::NT), 0, st,
-                       pr[0], pr[1], pr[2], ti, tj);
-    return true;
-  }
   const int pick = pm_big_choice(3 * t128, 3 * t64, K);
   auto go = [&](auto cfg) {
     using Cfg = decltype(cfg);
